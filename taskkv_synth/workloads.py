@@ -1,0 +1,185 @@
+"""Workload table and tensor generators (torch, CPU or GPU generator).
+
+Recipes (all seeded; `seed = 0x7A5C + workload id`, mixed with layer and
+tensor id):
+  gauss   Q, K, V ~ N(0,1); the intended heterogeneous KV heads get
+          V += 3 * u_h with u_h in {+-1}^d.
+  scaled  per-KV-head scale a_h ~ U(0.5, 2) on K and V; Q ~ N(0,1); intended
+          heterogeneous heads get V += 6 * u_h (absolute, not scaled by a_h).
+  zipf    as `scaled`, plus a key-importance profile: a seeded permutation pi
+          of the positions, b_j = -1.1 * ln(pi(j) + 1); a fixed direction
+          q0 in {+-1}^d per KV head; Q = q0 + N(0,1) and
+          K[j] = a_h * N(0,1) + b_j * q0 / sqrt(d), which adds b_j to every
+          logit of key j (Zipf s = 1.1 weights) while entries stay O(1).
+bf16 tensors are rounded to nearest-even from fp32 by torch.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import List, Tuple
+
+import numpy as np
+import torch
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    wid: int
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ctx_len: int
+    dtype: str            # "f32" | "bf16"
+    n_sink: int
+    n_recent: int
+    n_middle: int
+    n_hetero: int
+    decode_steps: int
+    recipe: str
+    n_layers: int = 1
+    obs_window: int = 32
+    top_t: int = 256
+    add_centre_head: int = 0
+    pool_kernel: int = 1
+    offset: float = 6.0
+
+    @property
+    def group(self) -> int:
+        return self.n_q_heads // self.n_kv_heads
+
+    @property
+    def seed(self) -> int:
+        return 0x7A5C + self.wid
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+
+# Middle budgets of the 32-layer workload for 1 / 2 / 3 heterogeneous heads of
+# 8, chosen so that every layer's ragged cache is 40 % of the full cache
+# (8 * 32768 * 0.4 tokens per batch element) with 4 sinks and 128 recent tokens.
+STACK_MIDDLE = {1: 10166, 2: 6421, 3: 1178}
+
+WORKLOADS = {
+    "cfg1": Workload("cfg1", 1, 1, 8, 8, 64, 512, "f32", 4, 32, 32, 2, 1, "gauss", offset=3.0),
+    "cfg2": Workload("cfg2", 2, 1, 32, 8, 128, 8192, "bf16", 4, 128, 256, 2, 128, "scaled"),
+    "cfg3": Workload("cfg3", 3, 4, 32, 8, 128, 32768, "bf16", 4, 128, 0, 0, 256, "scaled", n_layers=32),
+    "cfg4": Workload("cfg4", 4, 1, 32, 8, 128, 65536, "bf16", 4, 256, 1024, 2, 128, "zipf"),
+    "cfg5": Workload("cfg5", 5, 8, 64, 8, 128, 131072, "bf16", 4, 512, 512, 1, 64, "scaled"),
+}
+
+
+def small_workload(name="small", **kw) -> Workload:
+    """A reduced workload for parity sweeps; keyword overrides any field."""
+    base = dict(name=name, wid=100, batch=2, n_q_heads=8, n_kv_heads=4, head_dim=128,
+                ctx_len=1500, dtype="bf16", n_sink=4, n_recent=32, n_middle=64,
+                n_hetero=1, decode_steps=3, recipe="scaled", obs_window=16, top_t=64)
+    base.update(kw)
+    return Workload(**base)
+
+
+def layer_params(wl: Workload, layer: int) -> Tuple[int, int]:
+    """(n_hetero, n_middle) of one layer.  Only the 32-layer workload varies:
+    its heterogeneous fraction is drawn U(0.1, 0.4) per layer."""
+    if wl.name != "cfg3":
+        return wl.n_hetero, wl.n_middle
+    rs = np.random.RandomState(wl.seed * 1000 + layer)
+    frac = rs.uniform(0.1, 0.4)
+    f = int(min(max(math.floor(wl.n_kv_heads * frac + 0.5), 1), 3))
+    return f, STACK_MIDDLE[f]
+
+
+def _gen(device, *key) -> torch.Generator:
+    g = torch.Generator(device=device)
+    s = 0x9E3779B97F4A7C15
+    for x in key:
+        s = (s * 6364136223846793005 + int(x) + 1442695040888963407) % (1 << 63)
+    g.manual_seed(s)
+    return g
+
+
+@dataclasses.dataclass
+class LayerData:
+    wl: Workload
+    layer: int
+    n_hetero: int
+    n_middle: int
+    q_win: torch.Tensor      # [B, H_q, L, d]
+    k: torch.Tensor          # [B, H_kv, N, d]
+    v: torch.Tensor          # [B, H_kv, N, d]
+    hetero_heads: List[List[int]]   # intended heterogeneous KV heads per batch element
+    head_scale: torch.Tensor        # [B, H_kv] fp32
+    head_sign: torch.Tensor         # [B, H_kv, d] fp32 (+-1), V offset direction
+    q_dir: torch.Tensor             # [B, H_kv, d] fp32 (+-1) or zeros
+    is_offset: torch.Tensor         # [B, H_kv] fp32 0/1
+
+    def decode_inputs(self, step: int):
+        """(q [B,H_q,d], k_new [B,H_kv,d], v_new [B,H_kv,d]) of one decode step."""
+        wl, dev = self.wl, self.k.device
+        B, Hq, Hkv, d, G = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.group
+        g = _gen(dev, wl.seed, self.layer, 7, step)
+        q = torch.randn(B, Hq, d, generator=g, device=dev)
+        q = q + self.q_dir.repeat_interleave(G, dim=1)
+        kn = torch.randn(B, Hkv, d, generator=g, device=dev) * self.head_scale[..., None]
+        vn = torch.randn(B, Hkv, d, generator=g, device=dev) * self.head_scale[..., None]
+        vn = vn + wl.offset * self.is_offset[..., None] * self.head_sign
+        dt = wl.torch_dtype
+        return q.to(dt), kn.to(dt), vn.to(dt)
+
+
+def make_layer(wl: Workload, layer: int = 0, device="cpu", seed_bump: int = 0) -> LayerData:
+    """Prefill-time tensors of one layer.  `seed_bump` selects another draw of
+    the same recipe (used when a draw's decision margins are too small to be a
+    well-posed test, see the tests)."""
+    B, Hq, Hkv, d, N, L = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ctx_len, wl.obs_window
+    G = wl.group
+    n_het, n_mid = layer_params(wl, layer)
+    dev = torch.device(device)
+    g = _gen(dev, wl.seed, layer, 1, seed_bump)
+
+    def sign(*shape):
+        return (torch.randint(0, 2, shape, generator=g, device=dev).float() * 2 - 1)
+
+    if wl.recipe == "gauss":
+        scale = torch.ones(B, Hkv, device=dev)
+    else:
+        scale = torch.rand(B, Hkv, generator=g, device=dev) * 1.5 + 0.5
+    head_sign = sign(B, Hkv, d)
+    q_dir = sign(B, Hkv, d) if wl.recipe == "zipf" else torch.zeros(B, Hkv, d, device=dev)
+
+    hetero_heads, is_off = [], torch.zeros(B, Hkv, device=dev)
+    for b in range(B):
+        perm = torch.randperm(Hkv, generator=g, device=dev)[:n_het].tolist()
+        hetero_heads.append(sorted(perm))
+        for h in perm:
+            is_off[b, h] = 1.0
+
+    dt = wl.torch_dtype
+    q_win = torch.randn(B, Hq, L, d, generator=g, device=dev)
+    q_win = (q_win + q_dir.repeat_interleave(G, dim=1)[:, :, None, :]).to(dt)
+
+    k = torch.empty(B, Hkv, N, d, dtype=dt, device=dev)
+    v = torch.empty(B, Hkv, N, d, dtype=dt, device=dev)
+    for b in range(B):                       # one batch element at a time bounds the fp32 temporaries
+        kb = torch.randn(Hkv, N, d, generator=g, device=dev) * scale[b, :, None, None]
+        if wl.recipe == "zipf":
+            pi = torch.randperm(N, generator=g, device=dev).float()
+            bj = -1.1 * torch.log(pi + 1.0)
+            kb = kb + bj[None, :, None] * q_dir[b, :, None, :] / math.sqrt(d)
+        k[b] = kb.to(dt)
+        del kb
+        vb = torch.randn(Hkv, N, d, generator=g, device=dev) * scale[b, :, None, None]
+        vb = vb + wl.offset * is_off[b, :, None, None] * head_sign[b, :, None, :]
+        v[b] = vb.to(dt)
+        del vb
+    return LayerData(wl, layer, n_het, n_mid, q_win, k, v, hetero_heads, scale, head_sign,
+                     q_dir, is_off)
+
+
+def to_numpy(t: torch.Tensor) -> np.ndarray:
+    """Exact fp32 numpy view of a (possibly bf16, possibly GPU) tensor."""
+    return t.detach().float().cpu().numpy()
