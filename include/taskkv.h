@@ -1,0 +1,186 @@
+/*
+ * taskkv.h -- C ABI of the Task-KV hot path on one AMD MI355X (gfx950).
+ *
+ * Task-KV (arXiv 2501.15113) compresses the KV cache of one transformer layer
+ * at the end of prefill: a semantic separator (paper Sec. 4.1) marks the heads
+ * far from the semantic centre as heterogeneous; those keep their full cache,
+ * all other heads keep attention sinks, a recent window and the best-scored
+ * middle tokens ("middle activations", paper Sec. 4.2).  Decoding then runs
+ * attention over the resulting ragged, mixed-budget cache.
+ *
+ * Conventions for every entry point
+ *   - Tensor arguments are DEVICE pointers owned by the caller, contiguous and
+ *     row-major in the stated shape, 16-byte aligned.  Inputs are never
+ *     written unless stated.  Scalars and the cfg struct are host values.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream);
+ *     no entry point synchronises the device or allocates memory, except
+ *     taskkv_create / taskkv_destroy / taskkv_last_async_error.
+ *   - Return value: TASKKV_OK or a negative taskkv_status.  Host-visible
+ *     argument errors are reported before anything is enqueued.  Conditions
+ *     only the device can see (appending to a full cache) set a sticky flag
+ *     read by taskkv_last_async_error.
+ *   - A "unit" is one (batch element, KV head) pair, unit = b * n_kv_heads + h.
+ *   - One ctx serves one stream at a time; calls on one ctx must not overlap.
+ */
+#ifndef TASKKV_H
+#define TASKKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Every unit's region of the ragged cache starts at a multiple of this many
+ * tokens and is a multiple of it long; it is also the split-K granularity of
+ * decode attention. */
+#define TASKKV_CHUNK_TOKENS 512
+
+typedef struct taskkv_ctx taskkv_ctx; /* opaque: workspace + error flag on one device */
+
+typedef enum { TASKKV_F32 = 0, TASKKV_BF16 = 1 } taskkv_dtype;
+
+typedef enum {
+  TASKKV_OK = 0,
+  TASKKV_EINVAL = -1,     /* bad argument (shape, NULL pointer, unsupported size) */
+  TASKKV_ECAPACITY = -2,  /* ragged cache buffer too small for this cfg */
+  TASKKV_EWORKSPACE = -3, /* ctx workspace too small for this cfg */
+  TASKKV_EHIP = -4        /* a HIP runtime call failed */
+} taskkv_status;
+
+/* One layer's problem statement (paper Sec. 4.1-4.2 notation in comments). */
+typedef struct taskkv_layer_cfg {
+  int32_t batch;           /* B */
+  int32_t n_q_heads;       /* H_q; multiple of n_kv_heads, group G = H_q/H_kv <= 64 */
+  int32_t n_kv_heads;      /* H_kv = n of the paper, <= 256 */
+  int32_t head_dim;        /* d, 64 or 128 */
+  int32_t ctx_len;         /* N, prompt length */
+  int32_t obs_window;      /* L, observation window, 1 <= L <= N (paper: 32) */
+  int32_t top_t;           /* t of Eq. 14 (paper: 256); clipped to N */
+  int32_t n_sink;          /* s1 */
+  int32_t n_recent;        /* s2 */
+  int32_t n_middle;        /* k of Eq. 17; clipped to the size of the middle */
+  int32_t n_hetero;        /* f(r): heads farthest from the centre that keep everything */
+  int32_t add_centre_head; /* 1: the remaining head closest to the centre also keeps
+                              everything (last rule of the ranking paragraph, Sec. 4.1) */
+  int32_t pool_kernel;     /* odd width of the average pooling of selection scores
+                              (paper Sec. 5.4 uses 7); 1 = none */
+  int32_t dtype;           /* taskkv_dtype of Q/K/V and of the cache */
+  float softmax_scale;     /* 0 => 1/sqrt(d) */
+} taskkv_layer_cfg;
+
+/* Create a context on `device_id` with `workspace_bytes` of scratch (see
+ * taskkv_workspace_bytes).  Allocates; the only call besides destroy that does. */
+int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes);
+void taskkv_destroy(taskkv_ctx *ctx);
+const char *taskkv_strerror(int status);
+
+/* Host only.  Upper bound of the scratch any of the three hot-path calls needs
+ * for this cfg with `reserve_decode_tokens` of append room per unit. */
+size_t taskkv_workspace_bytes(const taskkv_layer_cfg *cfg, int32_t reserve_decode_tokens);
+
+/* Host only.  Exact token capacity of the ragged cache this cfg produces: the
+ * head counts are fixed by cfg (n_hetero is a count), so the size is known
+ * without reading the mask back.  Each unit gets its kept tokens plus
+ * `reserve_decode_tokens`, rounded up to TASKKV_CHUNK_TOKENS.  Returns < 0 on
+ * a bad cfg. */
+int64_t taskkv_cache_tokens(const taskkv_layer_cfg *cfg, int32_t reserve_decode_tokens);
+
+/* Host helpers for the budget arithmetic.
+ * Eq. 16: heads marked heterogeneous in layer r of R: n*beta - (n*beta-m)/(R-1)*r,
+ * rounded half up, clipped to [0, n].
+ * Eq. 17: middle budget k = (B_layer - N*f)/(n-f) - s1 - s2, floored, clipped at 0. */
+int32_t taskkv_hetero_head_count(int32_t n_heads, double beta, int32_t m_top, int32_t layer, int32_t n_layers);
+int32_t taskkv_middle_budget(int64_t layer_budget_tokens, int32_t ctx_len, int32_t n_heads,
+                             int32_t n_hetero, int32_t n_sink, int32_t n_recent);
+
+/*
+ * Semantic separator (paper Sec. 4.1, Eq. 12-15, Eq. 7-8, ranking paragraph).
+ *   q_win   [B, H_q, L, d]  last L query rows of the prompt (dtype of cfg)
+ *   k, v    [B, H_kv, N, d] key / value states (dtype of cfg)
+ * out
+ *   scores  [B, H_kv, N] f64  C of Eq. 13, averaged over the G*L window rows of
+ *                             the KV head's query group
+ *   sem_vec [B, H_kv, d] f64  v' of Eq. 15 over the top-t tokens of Eq. 14
+ *   dist    [B, H_kv]    f64  L2 distance of v' from the mean over heads (Eq. 7-8)
+ *   hetero_mask [B, H_kv] u8  1 = heterogeneous (keeps its full cache)
+ * Decisions (top-t membership, head ranking) are taken on the f64 values, ties
+ * to the lower index.
+ */
+int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_win, const void *k,
+                    const void *v, double *scores, double *sem_vec, double *dist,
+                    uint8_t *hetero_mask, void *hip_stream);
+
+/*
+ * KV cache allocation (paper Sec. 4.2): build the ragged cache.
+ *   k, v        [B, H_kv, N, d]  as above
+ *   scores      [B, H_kv, N] f64 from taskkv_separate
+ *   hetero_mask [B, H_kv] u8
+ * out
+ *   k_cache, v_cache  capacity_tokens * d elements each (dtype of cfg), library
+ *                     layout (bf16: tiled for the matrix cores; read it back
+ *                     with taskkv_cache_export)
+ *   offsets  [B*H_kv + 1] i64  first token slot of each unit, multiples of
+ *                              TASKKV_CHUNK_TOKENS
+ *   lens     [B*H_kv]     i32  tokens held per unit: N for heterogeneous units (and
+ *                              when s1 + s2 >= N), else s1 + min(k, N-s1-s2) + s2
+ *   kept_idx [B*H_kv, s1+k+s2] i32  original positions kept by each
+ *                              non-heterogeneous unit, ascending, -1 padded;
+ *                              rows of keep-everything units are all -1
+ * capacity_tokens must be >= taskkv_cache_tokens(cfg, reserve_decode_tokens)
+ * (else TASKKV_ECAPACITY).  Middle tokens are the n_middle best of the pooled
+ * scores inside [s1, N - s2), ties to the lower index; rows are copied
+ * bit-for-bit; slots past a unit's length are zero-filled.
+ */
+int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k, const void *v,
+                    const double *scores, const uint8_t *hetero_mask, void *k_cache, void *v_cache,
+                    int64_t capacity_tokens, int32_t reserve_decode_tokens, int64_t *offsets,
+                    int32_t *lens, int32_t *kept_idx, void *hip_stream);
+
+/*
+ * One decode step of attention over the ragged cache (softmax attention of
+ * Eq. 1 for a single new query row, restricted to each head's kept tokens;
+ * the step the paper times in Sec. 5.5.3).
+ *   q            [B, H_q, d]   query of the new token (dtype of cfg)
+ *   k_new, v_new [B, H_kv, d]  its key / value, appended to EVERY unit before
+ *                              attention (lens += 1); both NULL = no append
+ *   k_cache, v_cache, offsets, lens  as produced by taskkv_compress
+ *                              (cache and lens are updated by the append)
+ * out
+ *   out          [B, H_q, d] f32   softmax(scale * q K_c^T) V_c per query head;
+ *                              the G query heads of a group share one read of K_c, V_c
+ * A unit whose region is full cannot append: the token is dropped and the
+ * sticky error flag is set.  The result is independent of launch order
+ * (partials are merged in a fixed order).
+ */
+int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q, const void *k_new,
+                       const void *v_new, void *k_cache, void *v_cache, int64_t capacity_tokens,
+                       const int64_t *offsets, int32_t *lens, float *out, void *hip_stream);
+
+/*
+ * Inspection: copy the cache back to plain rows.  k_rows / v_rows are
+ * [capacity_tokens, d] row-major (dtype of cfg); token p of unit u lands in row
+ * offsets[u] + p.  Rows past a unit's length are written as stored (zeros).
+ */
+int taskkv_cache_export(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k_cache,
+                        const void *v_cache, int64_t capacity_tokens, const int64_t *offsets,
+                        void *k_rows, void *v_rows, void *hip_stream);
+
+/* Synchronises `hip_stream`, returns and clears the sticky device-side flag:
+ * 0 = none, 1 = append to a full unit. */
+int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream);
+
+/*
+ * Timing hooks for the benchmark.  With profiling on, taskkv_decode_attn
+ * brackets its attention kernel with HIP events on the launch stream (up to
+ * 4096 launches are kept).  taskkv_profile_read synchronises, sums the
+ * recorded durations into *total_ms / *launches and clears the record.
+ */
+int taskkv_profile_enable(taskkv_ctx *ctx, int on);
+int taskkv_profile_read(taskkv_ctx *ctx, double *total_ms, int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TASKKV_H */

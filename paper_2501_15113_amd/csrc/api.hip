@@ -1,0 +1,300 @@
+// C ABI entry points of libtaskkv: argument validation, workspace carving and
+// kernel sequencing.  No entry point here synchronises the device or allocates,
+// except create / destroy / last_async_error / profile_read.
+#include <math.h>
+#include <new>
+
+#include "taskkv_internal.h"
+
+namespace taskkv {
+
+static bool resolve(const taskkv_layer_cfg *c, Dims &d) {
+  if (!c) return false;
+  if (c->batch < 1 || c->n_kv_heads < 1 || c->n_kv_heads > 256 || c->n_q_heads < 1) return false;
+  if (c->n_q_heads % c->n_kv_heads) return false;
+  if (c->head_dim != 64 && c->head_dim != 128) return false;
+  if (c->ctx_len < 1 || c->obs_window < 1 || c->obs_window > c->ctx_len) return false;
+  if (c->top_t < 1 || c->n_sink < 0 || c->n_recent < 0 || c->n_middle < 0 || c->n_hetero < 0) return false;
+  if (c->pool_kernel < 1 || c->pool_kernel % 2 == 0) return false;
+  if (c->dtype != TASKKV_F32 && c->dtype != TASKKV_BF16) return false;
+  if (!(c->softmax_scale >= 0.f)) return false;
+  d.B = c->batch; d.Hq = c->n_q_heads; d.Hkv = c->n_kv_heads; d.G = d.Hq / d.Hkv;
+  d.D = c->head_dim; d.N = c->ctx_len; d.L = c->obs_window;
+  d.T = c->top_t < d.N ? c->top_t : d.N;
+  d.s1 = c->n_sink; d.s2 = c->n_recent;
+  d.keep_all = ((int64_t)d.s1 + d.s2 >= d.N) ? 1 : 0;
+  const int64_t middle = d.keep_all ? 0 : (int64_t)d.N - d.s1 - d.s2;
+  d.k = (int)(c->n_middle < middle ? c->n_middle : middle);
+  d.n_het = c->n_hetero; d.add_centre = c->add_centre_head ? 1 : 0; d.pool = c->pool_kernel;
+  d.R = d.G * d.L;
+  d.Rpad = (d.R + ROW_BLK - 1) / ROW_BLK * ROW_BLK;
+  if (d.G > 64 || d.Rpad > 1024) return false;
+  if ((int64_t)d.B * d.Hkv > 65535) return false;
+  d.units = d.B * d.Hkv;
+  const int64_t stride = (int64_t)d.s1 + c->n_middle + d.s2;
+  if (stride > (int64_t)1 << 30) return false;
+  d.row_stride = (int)stride;
+  d.scale = c->softmax_scale > 0.f ? (double)c->softmax_scale : 1.0 / sqrt((double)d.D);
+  return true;
+}
+
+static int score_tiles_per_wg(const Dims &d) {
+  const int64_t n_tiles = (d.N + SCORE_TILE - 1) / SCORE_TILE;
+  int64_t t = (n_tiles * d.units + 4095) / 4096;
+  if (t < 1) t = 1;
+  if (t > 16) t = 16;
+  return (int)t;
+}
+
+static int64_t cache_tokens(const Dims &d, int reserve) {
+  int n_long = d.n_het < d.Hkv ? d.n_het : d.Hkv;
+  if (d.add_centre && n_long < d.Hkv) n_long += 1;
+  if (d.keep_all) n_long = d.Hkv;
+  auto cap = [&](int64_t len) { return (len + reserve + CHUNK - 1) / CHUNK * CHUNK; };
+  const int64_t short_len = (int64_t)d.s1 + d.k + d.s2;
+  return (int64_t)d.B * (n_long * cap(d.N) + (int64_t)(d.Hkv - n_long) * cap(short_len));
+}
+
+static size_t al(size_t b) { return (b + 255) & ~size_t(255); }
+
+static size_t ws_separate(const Dims &d) {
+  const int tpw = score_tiles_per_wg(d);
+  const int n_tiles = (d.N + SCORE_TILE - 1) / SCORE_TILE;
+  const int n_chunks = (n_tiles + tpw - 1) / tpw;
+  size_t b = 0;
+  b += al((size_t)d.units * d.Rpad * d.D * sizeof(double));           // window rows in fp64
+  b += al((size_t)d.units * n_chunks * d.Rpad * 2 * sizeof(double));  // per-chunk row stats
+  b += al((size_t)d.units * d.Rpad * 2 * sizeof(double));             // row stats
+  b += al((size_t)d.units * d.T * sizeof(int32_t));                   // top-t picks
+  return b;
+}
+static size_t ws_compress(const Dims &d) {
+  return d.pool > 1 ? al((size_t)d.units * d.N * sizeof(double)) : 0;
+}
+static size_t ws_decode(const Dims &d, int64_t capacity) {
+  const size_t n_chunks = (size_t)(capacity / CHUNK);
+  return 2 * al(n_chunks * d.G * sizeof(float)) + al(n_chunks * d.G * d.D * sizeof(float));
+}
+
+}  // namespace taskkv
+
+using namespace taskkv;
+
+extern "C" {
+
+const char *taskkv_strerror(int status) {
+  switch (status) {
+    case TASKKV_OK: return "ok";
+    case TASKKV_EINVAL: return "invalid argument";
+    case TASKKV_ECAPACITY: return "cache buffer too small";
+    case TASKKV_EWORKSPACE: return "workspace too small";
+    case TASKKV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
+  if (!out) return TASKKV_EINVAL;
+  *out = nullptr;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device_id < 0 || device_id >= n_dev) return TASKKV_EHIP;
+  if (hipSetDevice(device_id) != hipSuccess) return TASKKV_EHIP;
+  taskkv_ctx *c = new (std::nothrow) taskkv_ctx();
+  if (!c) return TASKKV_EHIP;
+  c->device = device_id;
+  c->ws = nullptr;
+  c->ws_bytes = workspace_bytes;
+  c->d_err = nullptr;
+  c->profiling = 0;
+  c->n_events = 0;
+  c->events_created = 0;
+  if (workspace_bytes && hipMalloc((void **)&c->ws, workspace_bytes) != hipSuccess) {
+    delete c;
+    return TASKKV_EHIP;
+  }
+  if (hipMalloc((void **)&c->d_err, 256) != hipSuccess || hipMemset(c->d_err, 0, 256) != hipSuccess) {
+    if (c->ws) (void)hipFree(c->ws);
+    delete c;
+    return TASKKV_EHIP;
+  }
+  *out = c;
+  return TASKKV_OK;
+}
+
+void taskkv_destroy(taskkv_ctx *ctx) {
+  if (!ctx) return;
+  (void)hipSetDevice(ctx->device);
+  (void)hipDeviceSynchronize();
+  for (int i = 0; i < ctx->events_created; ++i) {
+    (void)hipEventDestroy(ctx->ev_start[i]);
+    (void)hipEventDestroy(ctx->ev_stop[i]);
+  }
+  if (ctx->ws) (void)hipFree(ctx->ws);
+  if (ctx->d_err) (void)hipFree(ctx->d_err);
+  delete ctx;
+}
+
+size_t taskkv_workspace_bytes(const taskkv_layer_cfg *cfg, int32_t reserve_decode_tokens) {
+  Dims d;
+  if (!resolve(cfg, d) || reserve_decode_tokens < 0) return 0;
+  size_t a = ws_separate(d), b = ws_compress(d), c = ws_decode(d, cache_tokens(d, reserve_decode_tokens));
+  size_t m = a > b ? a : b;
+  return (m > c ? m : c) + 4096;
+}
+
+int64_t taskkv_cache_tokens(const taskkv_layer_cfg *cfg, int32_t reserve_decode_tokens) {
+  Dims d;
+  if (!resolve(cfg, d) || reserve_decode_tokens < 0) return TASKKV_EINVAL;
+  return cache_tokens(d, reserve_decode_tokens);
+}
+
+int32_t taskkv_hetero_head_count(int32_t n_heads, double beta, int32_t m_top, int32_t layer, int32_t n_layers) {
+  double f = n_heads * beta;
+  if (n_layers > 1) f -= (n_heads * beta - m_top) / (double)(n_layers - 1) * layer;
+  double r = floor(f + 0.5);
+  if (r < 0) r = 0;
+  if (r > n_heads) r = n_heads;
+  return (int32_t)r;
+}
+
+int32_t taskkv_middle_budget(int64_t layer_budget_tokens, int32_t ctx_len, int32_t n_heads,
+                             int32_t n_hetero, int32_t n_sink, int32_t n_recent) {
+  if (n_heads <= n_hetero) return 0;
+  const int64_t num = layer_budget_tokens - (int64_t)ctx_len * n_hetero;
+  const int64_t den = n_heads - n_hetero;
+  int64_t q = num / den;
+  if (num % den != 0 && num < 0) q -= 1;  // floor division
+  q -= (int64_t)n_sink + n_recent;
+  return (int32_t)(q < 0 ? 0 : q);
+}
+
+int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_win, const void *k,
+                    const void *v, double *scores, double *sem_vec, double *dist,
+                    uint8_t *hetero_mask, void *hip_stream) {
+  Dims d;
+  if (!ctx || !resolve(cfg, d)) return TASKKV_EINVAL;
+  if (!q_win || !k || !v || !scores || !sem_vec || !dist || !hetero_mask) return TASKKV_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int tpw = score_tiles_per_wg(d);
+  const int n_tiles = (d.N + SCORE_TILE - 1) / SCORE_TILE;
+  const int n_chunks = (n_tiles + tpw - 1) / tpw;
+  Carver cv(ctx->ws, ctx->ws_bytes);
+  double *qd = cv.take<double>((size_t)d.units * d.Rpad * d.D);
+  double *part = cv.take<double>((size_t)d.units * n_chunks * d.Rpad * 2);
+  double *stats = cv.take<double>((size_t)d.units * d.Rpad * 2);
+  int32_t *top_idx = cv.take<int32_t>((size_t)d.units * d.T);
+  if (!cv.ok) return TASKKV_EWORKSPACE;
+  int rc = launch_scores_f64(d, cfg->dtype, q_win, k, qd, part, stats, scores, tpw, s);
+  if (rc) return rc;
+  rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, top_idx, d.T, 0, s);
+  if (rc) return rc;
+  return launch_semvec_mask(d, cfg->dtype, scores, v, top_idx, sem_vec, dist, hetero_mask, s);
+}
+
+int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k, const void *v,
+                    const double *scores, const uint8_t *hetero_mask, void *k_cache, void *v_cache,
+                    int64_t capacity_tokens, int32_t reserve_decode_tokens, int64_t *offsets,
+                    int32_t *lens, int32_t *kept_idx, void *hip_stream) {
+  Dims d;
+  if (!ctx || !resolve(cfg, d) || reserve_decode_tokens < 0) return TASKKV_EINVAL;
+  if (!k || !v || !scores || !hetero_mask || !k_cache || !v_cache || !offsets || !lens) return TASKKV_EINVAL;
+  if (d.row_stride > 0 && !kept_idx) return TASKKV_EINVAL;
+  if (capacity_tokens % CHUNK) return TASKKV_EINVAL;
+  if (capacity_tokens < cache_tokens(d, reserve_decode_tokens)) return TASKKV_ECAPACITY;
+  if (capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const double *sel_scores = scores;
+  if (d.pool > 1) {
+    Carver cv(ctx->ws, ctx->ws_bytes);
+    double *pooled = cv.take<double>((size_t)d.units * d.N);
+    if (!cv.ok) return TASKKV_EWORKSPACE;
+    int rc = launch_pool(d, scores, pooled, s);
+    if (rc) return rc;
+    sel_scores = pooled;
+  }
+  int rc = TASKKV_OK;
+  if (d.row_stride > 0) {
+    rc = launch_select(d, sel_scores, hetero_mask, d.s1, d.N - d.s2, d.k, d.s1, d.s2, kept_idx,
+                       d.row_stride, d.keep_all, s);
+    if (rc) return rc;
+  }
+  rc = launch_layout(d, hetero_mask, reserve_decode_tokens, capacity_tokens, offsets, lens, ctx->d_err, s);
+  if (rc) return rc;
+  return launch_pack(d, cfg->dtype, k, v, kept_idx, hetero_mask, offsets, lens, k_cache, v_cache,
+                     capacity_tokens, s);
+}
+
+int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q, const void *k_new,
+                       const void *v_new, void *k_cache, void *v_cache, int64_t capacity_tokens,
+                       const int64_t *offsets, int32_t *lens, float *out, void *hip_stream) {
+  Dims d;
+  if (!ctx || !resolve(cfg, d)) return TASKKV_EINVAL;
+  if (!q || !k_cache || !v_cache || !offsets || !lens || !out) return TASKKV_EINVAL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return TASKKV_EINVAL;
+  if (capacity_tokens <= 0 || capacity_tokens % CHUNK) return TASKKV_EINVAL;
+  if (capacity_tokens / CHUNK > 0x7fffffff) return TASKKV_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const size_t n_chunks = (size_t)(capacity_tokens / CHUNK);
+  Carver cv(ctx->ws, ctx->ws_bytes);
+  float *pm = cv.take<float>(n_chunks * d.G);
+  float *pl = cv.take<float>(n_chunks * d.G);
+  float *po = cv.take<float>(n_chunks * d.G * d.D);
+  if (!cv.ok) return TASKKV_EWORKSPACE;
+  if (k_new) {
+    int rc = launch_append(d, cfg->dtype, k_new, v_new, k_cache, v_cache, offsets, lens, ctx->d_err, s);
+    if (rc) return rc;
+  }
+  return launch_decode(ctx, d, cfg->dtype, q, k_cache, v_cache, capacity_tokens, offsets, lens, pm, pl,
+                       po, out, s);
+}
+
+int taskkv_cache_export(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k_cache,
+                        const void *v_cache, int64_t capacity_tokens, const int64_t *offsets,
+                        void *k_rows, void *v_rows, void *hip_stream) {
+  Dims d;
+  if (!ctx || !resolve(cfg, d)) return TASKKV_EINVAL;
+  if (!k_cache || !v_cache || !offsets || !k_rows || !v_rows) return TASKKV_EINVAL;
+  if (capacity_tokens < 0 || capacity_tokens % CHUNK || capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
+  return launch_export(d, cfg->dtype, k_cache, v_cache, offsets, k_rows, v_rows, capacity_tokens,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream) {
+  if (!ctx) return TASKKV_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int flag = 0;
+  if (hipMemcpyAsync(&flag, ctx->d_err, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return TASKKV_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return TASKKV_EHIP;
+  if (flag && hipMemsetAsync(ctx->d_err, 0, sizeof(int), s) != hipSuccess) return TASKKV_EHIP;
+  return flag;
+}
+
+int taskkv_profile_enable(taskkv_ctx *ctx, int on) {
+  if (!ctx) return TASKKV_EINVAL;
+  if (on && !ctx->events_created) {
+    for (int i = 0; i < MAX_PROFILE_EVENTS; ++i) {
+      if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess) return TASKKV_EHIP;
+      if (hipEventCreate(&ctx->ev_stop[i]) != hipSuccess) return TASKKV_EHIP;
+      ctx->events_created = i + 1;
+    }
+  }
+  ctx->profiling = on ? 1 : 0;
+  return TASKKV_OK;
+}
+
+int taskkv_profile_read(taskkv_ctx *ctx, double *total_ms, int64_t *launches) {
+  if (!ctx || !total_ms || !launches) return TASKKV_EINVAL;
+  double tot = 0.0;
+  for (int i = 0; i < ctx->n_events; ++i) {
+    if (hipEventSynchronize(ctx->ev_stop[i]) != hipSuccess) return TASKKV_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]) != hipSuccess) return TASKKV_EHIP;
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = ctx->n_events;
+  ctx->n_events = 0;
+  return TASKKV_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,254 @@
+// The ragged KV cache (paper Sec. 4.2): region layout, packing, export, append.
+//
+// Token space: unit u owns slots [offsets[u], offsets[u+1]), both multiples of
+// CHUNK; lens[u] of them are filled, the rest are zero.
+//
+// fp32 cache: plain rows, slot p of the token space is row p.
+//
+// bf16 cache: laid out so that a wavefront loads matrix-core operands straight
+// from HBM with one 16-byte read per lane and no shuffling:
+//   K, per block of 16 tokens (16*D*2 bytes): 16-byte piece (kk, g, r) at index
+//      kk*64 + g*16 + r holds K[token r][32*kk + 8*g .. +8]  -- lane g*16+r of
+//      the QK^T MFMA reads piece kk*64 + lane.
+//   V, per page of 32 tokens (32*D*2 bytes): 16-byte piece (mb, g, r) at index
+//      mb*64 + g*16 + r holds, for e = 0..7, V[token tau(g,e)][16*mb + r] with
+//      tau(g,e) = 16*(e/4) + 4*g + e%4 -- exactly the token order in which the
+//      QK^T MFMA leaves its results in lane group g, so the probabilities feed
+//      the PV MFMA without leaving their lane.
+#include "taskkv_internal.h"
+
+namespace taskkv {
+
+// Largest u with offsets[u] <= tok, or -1 if tok is past the last region.
+__device__ __forceinline__ int find_unit(const int64_t *__restrict__ offsets, int n_units, int64_t tok) {
+  if (tok >= offsets[n_units]) return -1;
+  int lo = 0, hi = n_units - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (offsets[mid] <= tok) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+// lens / offsets from the mask (single block; units are few).
+__global__ void layout_kernel(const uint8_t *__restrict__ mask, int64_t *__restrict__ offsets,
+                              int32_t *__restrict__ lens, int *__restrict__ d_err, Dims dm,
+                              int reserve, int64_t capacity) {
+  const int short_len = dm.s1 + dm.k + dm.s2;
+  for (int u = threadIdx.x; u < dm.units; u += blockDim.x)
+    lens[u] = (dm.keep_all || mask[u]) ? dm.N : short_len;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int64_t off = 0;
+    for (int u = 0; u < dm.units; ++u) {
+      offsets[u] = off;
+      const int64_t cap = ((int64_t)lens[u] + reserve + CHUNK - 1) / CHUNK * CHUNK;
+      off += cap;
+    }
+    offsets[dm.units] = off;
+    if (off > capacity) atomicOr(d_err, 2);
+  }
+}
+
+__device__ __forceinline__ int tau_of(int g, int e) { return 16 * (e >> 2) + 4 * g + (e & 3); }
+
+// One block per 32-token page of the token space.
+template <int D>
+__global__ __launch_bounds__(256) void pack_bf16_kernel(
+    const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const int32_t *__restrict__ kept,
+    const uint8_t *__restrict__ mask, const int64_t *__restrict__ offsets,
+    const int32_t *__restrict__ lens, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, Dims dm) {
+  constexpr int CH = D / 8;  // 16-byte pieces per row
+  const int64_t tok0 = (int64_t)blockIdx.x * PAGE;
+  const int u = find_unit(offsets, dm.units, tok0);
+  if (u < 0) return;
+  const int tid = threadIdx.x;
+  const int local0 = (int)(tok0 - offsets[u]);
+  const int len = lens[u];
+  const bool direct = dm.keep_all || mask[u];
+  __shared__ int src[PAGE];
+  __shared__ __align__(16) uint16_t vt[PAGE][D + 8];
+  if (tid < PAGE) {
+    const int p = local0 + tid;
+    src[tid] = p < len ? (direct ? p : kept[(size_t)u * dm.row_stride + p]) : -1;
+  }
+  __syncthreads();
+  const size_t ubase = (size_t)u * dm.N * D;
+  for (int idx = tid; idx < PAGE * CH; idx += 256) {
+    const int row = idx / CH, ci = idx % CH;
+    uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+    if (src[row] >= 0) {
+      const size_t off = ubase + (size_t)src[row] * D + ci * 8;
+      kv = *reinterpret_cast<const uint4 *>(k + off);
+      vv = *reinterpret_cast<const uint4 *>(v + off);
+    }
+    const int sb = row >> 4, r = row & 15;
+    uint16_t *dst = kc + ((size_t)tok0 + sb * 16) * D + (size_t)(ci * 16 + r) * 8;
+    *reinterpret_cast<uint4 *>(dst) = kv;
+    *reinterpret_cast<uint4 *>(&vt[row][ci * 8]) = vv;
+  }
+  __syncthreads();
+  for (int o = tid; o < (D / 16) * 64; o += 256) {
+    const int mb = o >> 6, g = (o >> 4) & 3, r = o & 15;
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const uint32_t a = vt[tau_of(g, 2 * e2)][16 * mb + r];
+      const uint32_t b = vt[tau_of(g, 2 * e2 + 1)][16 * mb + r];
+      w[e2] = a | (b << 16);
+    }
+    *reinterpret_cast<uint4 *>(vc + (size_t)tok0 * D + (size_t)o * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void export_bf16_kernel(const uint16_t *__restrict__ kc,
+                                                          const uint16_t *__restrict__ vc,
+                                                          const int64_t *__restrict__ offsets,
+                                                          uint16_t *__restrict__ k_rows,
+                                                          uint16_t *__restrict__ v_rows, Dims dm) {
+  constexpr int CH = D / 8;
+  const int64_t tok0 = (int64_t)blockIdx.x * PAGE;
+  if (tok0 >= offsets[dm.units]) return;
+  const int tid = threadIdx.x;
+  for (int idx = tid; idx < PAGE * CH; idx += 256) {
+    const int row = idx / CH, ci = idx % CH;
+    const int sb = row >> 4, r = row & 15;
+    const uint16_t *srcp = kc + ((size_t)tok0 + sb * 16) * D + (size_t)(ci * 16 + r) * 8;
+    *reinterpret_cast<uint4 *>(k_rows + ((size_t)tok0 + row) * D + ci * 8) =
+        *reinterpret_cast<const uint4 *>(srcp);
+  }
+  for (int o = tid; o < (D / 16) * 64; o += 256) {
+    const int mb = o >> 6, g = (o >> 4) & 3, r = o & 15;
+    const uint16_t *srcp = vc + (size_t)tok0 * D + (size_t)o * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v_rows[((size_t)tok0 + tau_of(g, e)) * D + 16 * mb + r] = srcp[e];
+  }
+}
+
+// fp32 cache: plain rows.  One block per 32-token page.
+template <int D>
+__global__ __launch_bounds__(256) void pack_f32_kernel(
+    const float *__restrict__ k, const float *__restrict__ v, const int32_t *__restrict__ kept,
+    const uint8_t *__restrict__ mask, const int64_t *__restrict__ offsets,
+    const int32_t *__restrict__ lens, float *__restrict__ kc, float *__restrict__ vc, Dims dm) {
+  constexpr int CH = D / 4;
+  const int64_t tok0 = (int64_t)blockIdx.x * PAGE;
+  const int u = find_unit(offsets, dm.units, tok0);
+  if (u < 0) return;
+  const int tid = threadIdx.x;
+  const int local0 = (int)(tok0 - offsets[u]);
+  const int len = lens[u];
+  const bool direct = dm.keep_all || mask[u];
+  __shared__ int src[PAGE];
+  if (tid < PAGE) {
+    const int p = local0 + tid;
+    src[tid] = p < len ? (direct ? p : kept[(size_t)u * dm.row_stride + p]) : -1;
+  }
+  __syncthreads();
+  const size_t ubase = (size_t)u * dm.N * D;
+  for (int idx = tid; idx < PAGE * CH; idx += 256) {
+    const int row = idx / CH, ci = idx % CH;
+    float4 kv = make_float4(0, 0, 0, 0), vv = kv;
+    if (src[row] >= 0) {
+      const size_t off = ubase + (size_t)src[row] * D + ci * 4;
+      kv = *reinterpret_cast<const float4 *>(k + off);
+      vv = *reinterpret_cast<const float4 *>(v + off);
+    }
+    const size_t dst = ((size_t)tok0 + row) * D + ci * 4;
+    *reinterpret_cast<float4 *>(kc + dst) = kv;
+    *reinterpret_cast<float4 *>(vc + dst) = vv;
+  }
+}
+
+// Append one token to every unit (paper is silent on decode-time policy; every
+// head grows, as in the prefill-compression methods the paper builds on).
+template <typename T, int D, bool TILED>
+__global__ void append_kernel(const T *__restrict__ k_new, const T *__restrict__ v_new,
+                              T *__restrict__ kc, T *__restrict__ vc,
+                              const int64_t *__restrict__ offsets, int32_t *__restrict__ lens,
+                              int *__restrict__ d_err) {
+  const int u = blockIdx.x, c = threadIdx.x;
+  const int p = lens[u];
+  const int64_t base = offsets[u];
+  const int64_t cap = offsets[u + 1] - base;
+  __syncthreads();  // every thread has read lens[u] before it is bumped
+  if (p >= cap) {
+    if (c == 0) atomicOr(d_err, 1);
+    return;
+  }
+  const T kval = k_new[(size_t)u * D + c], vval = v_new[(size_t)u * D + c];
+  if (TILED) {
+    const int64_t page = base + (p / PAGE) * PAGE;
+    const int t32 = p % PAGE, sb = t32 >> 4, r = t32 & 15;
+    kc[((size_t)page + sb * 16) * D + (size_t)((c >> 3) * 16 + r) * 8 + (c & 7)] = kval;
+    const int g = (t32 & 15) >> 2, e = 4 * (t32 >> 4) + (t32 & 3);
+    vc[(size_t)page * D + (size_t)((c >> 4) * 64 + g * 16 + (c & 15)) * 8 + e] = vval;
+  } else {
+    kc[((size_t)base + p) * D + c] = kval;
+    vc[((size_t)base + p) * D + c] = vval;
+  }
+  if (c == 0) lens[u] = p + 1;
+}
+
+int launch_layout(const Dims &dm, const uint8_t *mask, int reserve, int64_t capacity, int64_t *offsets,
+                  int32_t *lens, int *d_err, hipStream_t s) {
+  layout_kernel<<<dim3(1), dim3(256), 0, s>>>(mask, offsets, lens, d_err, dm, reserve, capacity);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_pack(const Dims &dm, int dtype, const void *k, const void *v, const int32_t *kept_idx,
+                const uint8_t *mask, const int64_t *offsets, const int32_t *lens, void *k_cache,
+                void *v_cache, int64_t capacity, hipStream_t s) {
+  const dim3 grid((unsigned)(capacity / PAGE)), block(256);
+  if (grid.x == 0) return TASKKV_OK;
+  if (dtype == TASKKV_F32) {
+    auto kk = static_cast<const float *>(k), vv = static_cast<const float *>(v);
+    auto kc = static_cast<float *>(k_cache), vc = static_cast<float *>(v_cache);
+    if (dm.D == 64) pack_f32_kernel<64><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, kc, vc, dm);
+    else pack_f32_kernel<128><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, kc, vc, dm);
+  } else {
+    auto kk = static_cast<const uint16_t *>(k), vv = static_cast<const uint16_t *>(v);
+    auto kc = static_cast<uint16_t *>(k_cache), vc = static_cast<uint16_t *>(v_cache);
+    if (dm.D == 64) pack_bf16_kernel<64><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, kc, vc, dm);
+    else pack_bf16_kernel<128><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, kc, vc, dm);
+  }
+  return hip_ok(hipGetLastError());
+}
+
+int launch_export(const Dims &dm, int dtype, const void *k_cache, const void *v_cache,
+                  const int64_t *offsets, void *k_rows, void *v_rows, int64_t capacity, hipStream_t s) {
+  if (capacity == 0) return TASKKV_OK;
+  if (dtype == TASKKV_F32) {
+    // plain rows already: two device-to-device copies
+    const size_t bytes = (size_t)capacity * dm.D * sizeof(float);
+    if (hipMemcpyAsync(k_rows, k_cache, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) return TASKKV_EHIP;
+    if (hipMemcpyAsync(v_rows, v_cache, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) return TASKKV_EHIP;
+    return TASKKV_OK;
+  }
+  const dim3 grid((unsigned)(capacity / PAGE)), block(256);
+  auto kc = static_cast<const uint16_t *>(k_cache), vc = static_cast<const uint16_t *>(v_cache);
+  auto kr = static_cast<uint16_t *>(k_rows), vr = static_cast<uint16_t *>(v_rows);
+  if (dm.D == 64) export_bf16_kernel<64><<<grid, block, 0, s>>>(kc, vc, offsets, kr, vr, dm);
+  else export_bf16_kernel<128><<<grid, block, 0, s>>>(kc, vc, offsets, kr, vr, dm);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_append(const Dims &dm, int dtype, const void *k_new, const void *v_new, void *k_cache,
+                  void *v_cache, const int64_t *offsets, int32_t *lens, int *d_err, hipStream_t s) {
+  const dim3 grid(dm.units), block(dm.D);
+  if (dtype == TASKKV_F32) {
+    auto kn = static_cast<const float *>(k_new), vn = static_cast<const float *>(v_new);
+    auto kc = static_cast<float *>(k_cache), vc = static_cast<float *>(v_cache);
+    if (dm.D == 64) append_kernel<float, 64, false><<<grid, block, 0, s>>>(kn, vn, kc, vc, offsets, lens, d_err);
+    else append_kernel<float, 128, false><<<grid, block, 0, s>>>(kn, vn, kc, vc, offsets, lens, d_err);
+  } else {
+    auto kn = static_cast<const uint16_t *>(k_new), vn = static_cast<const uint16_t *>(v_new);
+    auto kc = static_cast<uint16_t *>(k_cache), vc = static_cast<uint16_t *>(v_cache);
+    if (dm.D == 64) append_kernel<uint16_t, 64, true><<<grid, block, 0, s>>>(kn, vn, kc, vc, offsets, lens, d_err);
+    else append_kernel<uint16_t, 128, true><<<grid, block, 0, s>>>(kn, vn, kc, vc, offsets, lens, d_err);
+  }
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace taskkv

@@ -1,0 +1,219 @@
+// Selection and ranking on fp64 scores: top-t of Eq. 14, the middle-activation
+// pick of Sec. 4.2, the semantic vector of Eq. 15, centre / distance (Eq. 7-8)
+// and the head ranking of Sec. 4.1.  All decisions are taken on the fp64 bit
+// patterns (scores are >= 0, so unsigned integer order equals numeric order),
+// ties go to the lower index.
+#include <math.h>
+
+#include "taskkv_internal.h"
+
+namespace taskkv {
+
+__device__ __forceinline__ uint64_t key_of(double x) { return (uint64_t)__double_as_longlong(x); }
+
+// Exclusive scan of one flag per thread over a 1024-thread block.
+__device__ __forceinline__ int block_scan_flag(bool f, int &total, int *s_wave) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const uint64_t bal = __ballot(f);
+  const int excl = __popcll(bal & ((1ull << lane) - 1ull));
+  if (lane == 0) s_wave[wv] = __popcll(bal);
+  __syncthreads();
+  int off = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    const int c = s_wave[w];
+    if (w < wv) off += c;
+    tot += c;
+  }
+  __syncthreads();
+  total = tot;
+  return off + excl;
+}
+
+// Average pooling of the selection scores: stride 1, zero padding, fixed
+// divisor (Sec. 5.4 names only the kernel size).
+__global__ void pool_kernel(const double *__restrict__ c, double *__restrict__ p, int N, int width) {
+  const int unit = blockIdx.y;
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= N) return;
+  const double *row = c + (size_t)unit * N;
+  const int r = (width - 1) / 2;
+  double acc = 0.0;
+  for (int u = -r; u <= r; ++u) {
+    const int jj = j + u;
+    if (jj >= 0 && jj < N) acc += row[jj];
+  }
+  p[(size_t)unit * N + j] = acc / (double)width;
+}
+
+// One block per unit.  Picks the `count` largest scores inside [lo, hi) by
+// (score desc, index asc) with an 8-bit radix select on the 64-bit patterns,
+// then writes  [0, prefix) ++ picks ascending ++ [N - suffix, N)  and pads the
+// row with -1.  Units flagged in `skip` get an all -1 row.
+__global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__ scores,
+                                                      const uint8_t *__restrict__ skip, int skip_all,
+                                                      int N, int lo, int hi, int count, int prefix,
+                                                      int suffix, int32_t *__restrict__ out,
+                                                      int out_stride) {
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  int32_t *orow = out + (size_t)unit * out_stride;
+  if (skip_all || (skip && skip[unit])) {
+    for (int i = tid; i < out_stride; i += 1024) orow[i] = -1;
+    return;
+  }
+  const double *sc = scores + (size_t)unit * N;
+  __shared__ unsigned hist[256];
+  __shared__ int s_bin, s_rem;
+  __shared__ int s_wave[16];
+
+  uint64_t pat = 0, known = 0;
+  int remaining = count;
+  if (count > 0) {
+    for (int pass = 7; pass >= 0; --pass) {
+      const int shift = pass * 8;
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int j = lo + tid; j < hi; j += 1024) {
+        const uint64_t key = key_of(sc[j]);
+        if ((key & known) == pat) atomicAdd(&hist[(key >> shift) & 255], 1u);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int cum = 0, b = 255;
+        for (; b > 0; --b) {
+          const int c = (int)hist[b];
+          if (cum + c >= remaining) break;
+          cum += c;
+        }
+        s_bin = b;
+        s_rem = remaining - cum;
+      }
+      __syncthreads();
+      pat |= (uint64_t)s_bin << shift;
+      known |= 0xffull << shift;
+      remaining = s_rem;
+      __syncthreads();
+    }
+    // pat = the count-th largest score; `remaining` of the entries equal to it
+    // are taken, lowest index first.
+    int eq_base = 0, out_base = 0;
+    for (int base = lo; base < hi; base += 1024) {
+      const int j = base + tid;
+      const bool in = j < hi;
+      const uint64_t key = in ? key_of(sc[j]) : 0;
+      const bool gt = in && key > pat;
+      const bool eq = in && key == pat;
+      int tot_eq, tot_sel;
+      const int eq_rank = eq_base + block_scan_flag(eq, tot_eq, s_wave);
+      const bool sel = gt || (eq && eq_rank < remaining);
+      const int pos = out_base + block_scan_flag(sel, tot_sel, s_wave);
+      if (sel) orow[prefix + pos] = j;
+      eq_base += tot_eq;
+      out_base += tot_sel;
+    }
+  }
+  for (int i = tid; i < prefix; i += 1024) orow[i] = i;
+  for (int i = tid; i < suffix; i += 1024) orow[prefix + count + i] = N - suffix + i;
+  for (int i = prefix + count + suffix + tid; i < out_stride; i += 1024) orow[i] = -1;
+}
+
+__device__ __forceinline__ double elem_to_double(float x) { return (double)x; }
+__device__ __forceinline__ double elem_to_double(uint16_t x) {
+  return (double)__uint_as_float(uint32_t(x) << 16);
+}
+
+// Eq. 15: v'[unit] = sum over the picked tokens of C[j] * V[j, :], fp64,
+// ascending token order.
+template <typename T>
+__global__ void semvec_kernel(const double *__restrict__ scores, const T *__restrict__ v,
+                              const int32_t *__restrict__ top_idx, double *__restrict__ sem, Dims dm) {
+  const int unit = blockIdx.x, c = threadIdx.x;
+  if (c >= dm.D) return;
+  const double *sc = scores + (size_t)unit * dm.N;
+  const T *vb = v + (size_t)unit * dm.N * dm.D;
+  const int32_t *idx = top_idx + (size_t)unit * dm.T;
+  double acc = 0.0;
+  for (int n = 0; n < dm.T; ++n) {
+    const int j = idx[n];
+    acc += sc[j] * elem_to_double(vb[(size_t)j * dm.D + c]);
+  }
+  sem[(size_t)unit * dm.D + c] = acc;
+}
+
+// Eq. 7-8 and the ranking rule: one block per batch element.
+__global__ __launch_bounds__(256) void dist_mask_kernel(const double *__restrict__ sem,
+                                                        double *__restrict__ dist,
+                                                        uint8_t *__restrict__ mask, Dims dm) {
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int H = dm.Hkv, D = dm.D;
+  const double *sb = sem + (size_t)b * H * D;
+  __shared__ double centre[128];
+  __shared__ double sd[256];
+  __shared__ uint8_t smask[256];
+  if (tid < D) {
+    double acc = 0.0;
+    for (int h = 0; h < H; ++h) acc += sb[(size_t)h * D + tid];
+    centre[tid] = acc / (double)H;
+  }
+  __syncthreads();
+  for (int h = wv; h < H; h += 4) {
+    double acc = 0.0;
+    for (int c = lane; c < D; c += 64) {
+      const double dl = sb[(size_t)h * D + c] - centre[c];
+      acc += dl * dl;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0) sd[h] = sqrt(acc);
+  }
+  __syncthreads();
+  if (tid < H) {
+    const double mine = sd[tid];
+    int rank = 0;
+    for (int o = 0; o < H; ++o) {
+      const double other = sd[o];
+      rank += (other > mine) || (other == mine && o < tid);
+    }
+    smask[tid] = rank < dm.n_het ? 1 : 0;
+  }
+  __syncthreads();
+  if (dm.add_centre && tid == 0) {
+    int best = -1;
+    for (int h = 0; h < H; ++h)
+      if (!smask[h] && (best < 0 || sd[h] < sd[best])) best = h;
+    if (best >= 0) smask[best] = 1;
+  }
+  __syncthreads();
+  if (tid < H) {
+    dist[(size_t)b * H + tid] = sd[tid];
+    mask[(size_t)b * H + tid] = smask[tid];
+  }
+}
+
+int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
+                  int count, int prefix, int suffix, int32_t *out, int out_stride, int skip_all,
+                  hipStream_t s) {
+  select_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, skip_mask, skip_all, dm.N, lo, hi, count,
+                                                     prefix, suffix, out, out_stride);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_pool(const Dims &dm, const double *scores, double *pooled, hipStream_t s) {
+  pool_kernel<<<dim3((dm.N + 255) / 256, dm.units), dim3(256), 0, s>>>(scores, pooled, dm.N, dm.pool);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const void *v,
+                       const int32_t *top_idx, double *sem_vec, double *dist, uint8_t *mask,
+                       hipStream_t s) {
+  if (dtype == TASKKV_F32)
+    semvec_kernel<float><<<dim3(dm.units), dim3(128), 0, s>>>(scores, static_cast<const float *>(v),
+                                                             top_idx, sem_vec, dm);
+  else
+    semvec_kernel<uint16_t><<<dim3(dm.units), dim3(128), 0, s>>>(
+        scores, static_cast<const uint16_t *>(v), top_idx, sem_vec, dm);
+  dist_mask_kernel<<<dim3(dm.B), dim3(256), 0, s>>>(sem_vec, dist, mask, dm);
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace taskkv

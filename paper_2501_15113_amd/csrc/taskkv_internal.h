@@ -1,0 +1,90 @@
+// Internal declarations shared by the HIP sources of libtaskkv (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "taskkv.h"
+
+namespace taskkv {
+
+constexpr int CHUNK = TASKKV_CHUNK_TOKENS;  // tokens per split-K work item / region alignment
+constexpr int PAGE = 32;                    // tokens per matrix-core page of the bf16 cache
+constexpr int SCORE_TILE = 256;             // columns (keys) per scoring tile
+constexpr int ROW_BLK = 8;                  // window rows handled together by the f64 scorer
+constexpr int MAX_PROFILE_EVENTS = 4096;
+
+// Resolved problem sizes handed to kernels by value.
+struct Dims {
+  int B, Hq, Hkv, G, D, N, L, T;  // T = min(top_t, N)
+  int s1, s2, k;                  // k already clipped to the middle
+  int n_het, add_centre, pool;
+  int R, Rpad;                    // window rows per unit (G*L) and padded to ROW_BLK
+  int units;                      // B * Hkv
+  int keep_all;                   // s1 + s2 >= N: every unit keeps everything
+  int row_stride;                 // s1 + cfg.n_middle + s2: width of a kept_idx row
+  double scale;                   // softmax scale
+};
+
+}  // namespace taskkv
+
+struct taskkv_ctx {
+  int device;
+  char *ws;
+  size_t ws_bytes;
+  int *d_err;  // sticky device flag
+  int profiling;
+  int n_events;
+  hipEvent_t ev_start[taskkv::MAX_PROFILE_EVENTS];
+  hipEvent_t ev_stop[taskkv::MAX_PROFILE_EVENTS];
+  int events_created;
+};
+
+namespace taskkv {
+
+// Bump allocator over the ctx workspace (256-byte aligned pieces).
+struct Carver {
+  char *base;
+  size_t cap, used;
+  bool ok;
+  Carver(char *b, size_t c) : base(b), cap(c), used(0), ok(true) {}
+  template <typename T>
+  T *take(size_t n) {
+    size_t bytes = (n * sizeof(T) + 255) & ~size_t(255);
+    if (used + bytes > cap) {
+      ok = false;
+      return nullptr;
+    }
+    T *p = reinterpret_cast<T *>(base + used);
+    used += bytes;
+    return p;
+  }
+};
+
+// ---- launchers (each validates nothing; api.hip has checked the arguments) ----
+int launch_scores_f64(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd,
+                      double *stat_part, double *stats, double *scores, int tiles_per_wg,
+                      hipStream_t s);
+int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
+                  int count, int prefix, int suffix, int32_t *out, int out_stride, int skip_all,
+                  hipStream_t s);
+int launch_pool(const Dims &dm, const double *scores, double *pooled, hipStream_t s);
+int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const void *v,
+                       const int32_t *top_idx, double *sem_vec, double *dist, uint8_t *mask,
+                       hipStream_t s);
+int launch_layout(const Dims &dm, const uint8_t *mask, int reserve, int64_t capacity, int64_t *offsets,
+                  int32_t *lens, int *d_err, hipStream_t s);
+int launch_pack(const Dims &dm, int dtype, const void *k, const void *v, const int32_t *kept_idx,
+                const uint8_t *mask, const int64_t *offsets, const int32_t *lens, void *k_cache,
+                void *v_cache, int64_t capacity, hipStream_t s);
+int launch_export(const Dims &dm, int dtype, const void *k_cache, const void *v_cache,
+                  const int64_t *offsets, void *k_rows, void *v_rows, int64_t capacity, hipStream_t s);
+int launch_append(const Dims &dm, int dtype, const void *k_new, const void *v_new, void *k_cache,
+                  void *v_cache, const int64_t *offsets, int32_t *lens, int *d_err, hipStream_t s);
+int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, const void *k_cache,
+                  const void *v_cache, int64_t capacity, const int64_t *offsets, const int32_t *lens,
+                  float *pm, float *pl, float *po, float *out, hipStream_t s);
+
+inline int hip_ok(hipError_t e) { return e == hipSuccess ? TASKKV_OK : TASKKV_EHIP; }
+
+}  // namespace taskkv

@@ -1,0 +1,110 @@
+"""Shared by the GPU parity tests: run one layer through the HIP library and
+compare every output with the CPU oracle on the same seeded inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import taskkv_oracle as orc
+from taskkv_synth import to_numpy
+
+F32_REL_TOL = 1e-5      # max|o - ref| / max|ref| per (batch, query head) vector
+BF16_ABS_TOL = 1e-2     # max|o - ref| for bf16 inputs with fp32 accumulation
+SCORE_RTOL = 1e-9       # fp64 on both sides; differences are summation order and exp ulps
+MIN_MARGIN = 1e-9       # a decision closer than this is not a well-posed test
+
+
+def oracle_layer(ld, b, cfg):
+    """Oracle results for batch element b, plus the relative margin of every
+    discrete decision (top-t boundary, middle boundary, head ranking)."""
+    q, k, v = to_numpy(ld.q_win[b]), to_numpy(ld.k[b]), to_numpy(ld.v[b])
+    scale = cfg.softmax_scale if cfg.softmax_scale > 0 else None
+    sep = orc.separate(q, k, v, cfg.top_t, cfg.n_hetero, bool(cfg.add_centre_head), scale)
+    kept, kc, vc = orc.compress(k, v, sep["scores"], sep["mask"], cfg.n_sink, cfg.n_recent,
+                                cfg.n_middle, cfg.pool_kernel)
+    margins = []
+    C = sep["scores"]
+    N = C.shape[1]
+    P = orc.pool_scores(C, cfg.pool_kernel)
+    for h in range(C.shape[0]):
+        srt = np.sort(C[h])[::-1]
+        t = min(cfg.top_t, N)
+        if t < N and srt[t - 1] != srt[t]:
+            margins.append((srt[t - 1] - srt[t]) / srt[t - 1])
+        lo, hi = cfg.n_sink, N - cfg.n_recent
+        if not sep["mask"][h] and hi - lo > cfg.n_middle > 0:
+            ms = np.sort(P[h, lo:hi])[::-1]
+            if ms[cfg.n_middle - 1] != ms[cfg.n_middle]:
+                margins.append((ms[cfg.n_middle - 1] - ms[cfg.n_middle]) / ms[cfg.n_middle - 1])
+    ds = np.sort(sep["dist"])[::-1]
+    gaps = np.abs(np.diff(ds)) / max(ds[0], 1e-300)
+    gaps = gaps[gaps > 0]          # exact ties are decided by the index rule on both sides
+    if gaps.size:
+        margins.append(gaps.min())
+    sep.update(kept=kept, k_cache=kc, v_cache=vc, margin=min(margins) if margins else 1.0)
+    return sep
+
+
+def check_compression(ld, cfg, bufs, k_rows, v_rows, b, ref):
+    """Scores, vectors, distances, mask, kept indices, lengths, packed rows."""
+    Hkv, N = cfg.n_kv_heads, cfg.ctx_len
+    scores = bufs.scores[b].cpu().numpy()
+    np.testing.assert_allclose(scores, ref["scores"], rtol=SCORE_RTOL, atol=1e-300)
+    np.testing.assert_allclose(bufs.sem_vec[b].cpu().numpy(), ref["sem_vec"], rtol=1e-8, atol=1e-12)
+    np.testing.assert_allclose(bufs.dist[b].cpu().numpy(), ref["dist"], rtol=1e-8, atol=1e-12)
+    assert bufs.mask[b].cpu().numpy().tolist() == ref["mask"].tolist(), "hetero mask differs"
+    lens = bufs.lens.cpu().numpy().reshape(cfg.batch, Hkv)[b]
+    offs = bufs.offsets.cpu().numpy()
+    kept_gpu = bufs.kept_idx.cpu().numpy().reshape(cfg.batch, Hkv, -1)[b]
+    k_src, v_src = ld.k[b], ld.v[b]
+    for h in range(Hkv):
+        kept = ref["kept"][h]
+        assert lens[h] == len(kept), f"len differs for head {h}"
+        keeps_all = bool(ref["mask"][h]) or cfg.n_sink + cfg.n_recent >= N
+        if keeps_all:
+            assert (kept_gpu[h] == -1).all()
+        elif bufs.row > 0:
+            assert kept_gpu[h, :len(kept)].tolist() == kept.tolist(), f"kept indices differ, head {h}"
+            assert (kept_gpu[h, len(kept):] == -1).all()
+        u = b * Hkv + h
+        assert offs[u] % 512 == 0 and offs[u + 1] - offs[u] >= lens[h]
+        sel = torch.as_tensor(kept, device=k_src.device)
+        rows = slice(int(offs[u]), int(offs[u]) + len(kept))
+        assert torch.equal(k_rows[rows].view(torch.uint8), k_src[h][sel].contiguous().view(torch.uint8)), \
+            f"packed K rows differ, head {h}"
+        assert torch.equal(v_rows[rows].view(torch.uint8), v_src[h][sel].contiguous().view(torch.uint8)), \
+            f"packed V rows differ, head {h}"
+        pad = slice(int(offs[u]) + len(kept), int(offs[u + 1]))
+        assert not k_rows[pad].view(torch.uint8).any() and not v_rows[pad].view(torch.uint8).any()
+
+
+def check_output(out_b, ref_out, dtype, what=""):
+    """Attention output of one batch element against the oracle."""
+    out_b = out_b.astype(np.float64)
+    err = np.abs(out_b - ref_out).max(axis=1)
+    if dtype == "f32":
+        rel = err / np.maximum(np.abs(ref_out).max(axis=1), 1e-30)
+        assert rel.max() <= F32_REL_TOL, f"{what}: fp32 relative error {rel.max():.3e}"
+        return rel.max()
+    assert err.max() <= BF16_ABS_TOL, f"{what}: bf16 max-abs error {err.max():.3e}"
+    return err.max()
+
+
+class OracleCache:
+    """The oracle's per-head cache of one batch element, growing with decode."""
+
+    def __init__(self, ref):
+        self.k = [np.asarray(x, dtype=np.float64) for x in ref["k_cache"]]
+        self.v = [np.asarray(x, dtype=np.float64) for x in ref["v_cache"]]
+        self.new_k = [[] for _ in self.k]
+        self.new_v = [[] for _ in self.v]
+
+    def append(self, k_new_b, v_new_b):
+        for h in range(len(self.k)):
+            self.new_k[h].append(np.asarray(k_new_b[h], dtype=np.float64)[None])
+            self.new_v[h].append(np.asarray(v_new_b[h], dtype=np.float64)[None])
+
+    def attend(self, q_b, scale=None):
+        ks = [np.concatenate([a] + n) if n else a for a, n in zip(self.k, self.new_k)]
+        vs = [np.concatenate([a] + n) if n else a for a, n in zip(self.v, self.new_v)]
+        return orc.decode_attention(q_b, ks, vs, scale)

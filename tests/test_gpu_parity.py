@@ -1,0 +1,192 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle,
+element by element, on seeded synthetic inputs."""
+import numpy as np
+import pytest
+import torch
+
+from taskkv_synth import WORKLOADS, make_layer, small_workload, to_numpy
+from tests._harness import (MIN_MARGIN, OracleCache, check_compression, check_output, oracle_layer)
+
+pytestmark = pytest.mark.gpu
+
+
+def _session():
+    from paper_2501_15113_amd import session
+    return session
+
+
+def run_layer(wl, layer=0, check_batches=(0,), steps=None, check_steps=None, reserve=None,
+              append=True, cfg_override=None, mutate=None):
+    """separate -> compress -> export -> decode on the GPU; every output of the
+    chosen batch elements is compared with the oracle."""
+    ses = _session()
+    bump = 0
+    while True:
+        ld = make_layer(wl, layer, "cuda:0", seed_bump=bump)
+        if mutate is not None:
+            mutate(ld)
+        cfg = ses.cfg_from_workload(wl, ld.n_hetero, ld.n_middle, **(cfg_override or {}))
+        refs = {b: oracle_layer(ld, b, cfg) for b in check_batches}
+        worst = min(r["margin"] for r in refs.values())
+        if worst >= MIN_MARGIN or bump >= 3:
+            break
+        print(f"[{wl.name}] decision margin {worst:.2e} < {MIN_MARGIN}: next draw", flush=True)
+        bump += 1
+    assert worst >= MIN_MARGIN
+    steps = wl.decode_steps if steps is None else steps
+    reserve = steps if reserve is None else reserve
+    bufs = ses.LayerBuffers(cfg, reserve)
+    with ses.Context([cfg], reserve) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        bufs.compress(ctx, ld.k, ld.v)
+        k_rows, v_rows = bufs.export(ctx)
+        torch.cuda.synchronize()
+        for b in check_batches:
+            check_compression(ld, cfg, bufs, k_rows, v_rows, b, refs[b])
+        del k_rows, v_rows
+        caches = {b: OracleCache(refs[b]) for b in check_batches}
+        scale = cfg.softmax_scale if cfg.softmax_scale > 0 else None
+        worst_err = 0.0
+        for step in range(steps):
+            q, kn, vn = ld.decode_inputs(step)
+            out = bufs.decode(ctx, q, kn if append else None, vn if append else None)
+            for b in check_batches:
+                if append:
+                    caches[b].append(to_numpy(kn[b]), to_numpy(vn[b]))
+                if check_steps is None or step in check_steps:
+                    ref = caches[b].attend(to_numpy(q[b]), scale)
+                    worst_err = max(worst_err, check_output(out[b].cpu().numpy(), ref, wl.dtype,
+                                                            f"{wl.name} b={b} step={step}"))
+        from paper_2501_15113_amd import taskkv_last_async_error
+        assert taskkv_last_async_error(ctx.handle) == 0
+        lens = bufs.lens.cpu().numpy().reshape(cfg.batch, cfg.n_kv_heads)
+        for b in check_batches:
+            expect = [len(x) + (steps if append else 0) for x in refs[b]["kept"]]
+            assert lens[b].tolist() == expect
+    print(f"[{wl.name}] margin {worst:.2e}, worst attention error {worst_err:.3e}", flush=True)
+    return bufs, refs
+
+
+# ------------------------------------------------------------------ named workloads
+def test_cfg1_fp32_mha():
+    run_layer(WORKLOADS["cfg1"])
+
+
+def test_cfg2_llama_shaped_layer():
+    run_layer(WORKLOADS["cfg2"], check_steps=set(range(0, 128, 9)) | {127})
+
+
+# ------------------------------------------------------------------ small sweeps
+SWEEP = [
+    dict(),                                                            # defaults: bf16, G=2, ragged N
+    dict(dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=4, ctx_len=700, recipe="gauss", offset=3.0),
+    dict(dtype="f32", head_dim=128, n_q_heads=12, n_kv_heads=4, ctx_len=1030, n_hetero=2),
+    dict(head_dim=64, n_q_heads=16, n_kv_heads=4, ctx_len=2100, n_middle=300, n_recent=100),
+    dict(n_q_heads=32, n_kv_heads=2, ctx_len=1111, n_hetero=1),        # G = 16
+    dict(n_q_heads=40, n_kv_heads=2, ctx_len=900, n_hetero=1, obs_window=8),   # G = 20: two head slices
+    dict(n_hetero=0, ctx_len=640),                                     # nobody keeps everything
+    dict(n_hetero=4, ctx_len=640),                                     # everybody keeps everything
+    dict(add_centre_head=1, n_hetero=1, ctx_len=800),
+    dict(n_middle=0, ctx_len=777),                                     # sinks + recent only
+    dict(n_sink=0, n_recent=0, n_middle=50, ctx_len=600),              # middle only
+    dict(n_sink=300, n_recent=300, ctx_len=512, top_t=1000),           # sinks+recent cover N; t > N
+    dict(n_middle=5000, ctx_len=900),                                  # k larger than the middle
+    dict(pool_kernel=7, ctx_len=1300),                                 # pooled selection scores
+    dict(recipe="zipf", ctx_len=3000, n_middle=200, top_t=128),
+    dict(obs_window=1, ctx_len=520),
+    dict(obs_window=50, ctx_len=50, n_sink=2, n_recent=3, n_middle=4, top_t=10),   # L = N
+    dict(batch=3, ctx_len=33, n_sink=1, n_recent=2, n_middle=3, obs_window=5, top_t=7),
+]
+
+
+@pytest.mark.parametrize("i", range(len(SWEEP)))
+def test_small_sweep(i):
+    run_layer(small_workload(name=f"sweep{i}", wid=100 + i, **SWEEP[i]), check_batches=(0, 1))
+
+
+def test_softmax_scale_override():
+    run_layer(small_workload(name="scale", wid=150), cfg_override=dict(softmax_scale=0.05))
+
+
+def test_decode_without_append():
+    run_layer(small_workload(name="noappend", wid=151), append=False, reserve=0)
+
+
+# ------------------------------------------------------------------ ties
+def test_all_equal_scores_take_lowest_positions():
+    """K == 0 makes every score before the window equal: the tie rule alone
+    decides the top-t set and the middle pick."""
+    def zero_k(ld):
+        ld.k.zero_()
+    wl = small_workload(name="ties", wid=152, ctx_len=900, n_hetero=1)
+    bufs, refs = run_layer(wl, mutate=zero_k)
+    kept = bufs.kept_idx.cpu().numpy()
+    h = int(np.flatnonzero(refs[0]["mask"] == 0)[0])
+    assert kept[h, :wl.n_sink + wl.n_middle].tolist() == list(range(wl.n_sink + wl.n_middle))
+
+
+def test_duplicated_keys_tie_to_lower_index():
+    def dup(ld):
+        ld.k[:, :, 200:400] = ld.k[:, :, 0:200]
+    run_layer(small_workload(name="dups", wid=153, ctx_len=1000, n_middle=120), mutate=dup)
+
+
+# ------------------------------------------------------------------ device-side conditions
+def test_append_to_full_unit_sets_flag_and_drops_token():
+    ses = _session()
+    from paper_2501_15113_amd import taskkv_last_async_error
+    wl = small_workload(name="full", wid=154, ctx_len=512, n_hetero=4, batch=1, decode_steps=1)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 0)
+    with ses.Context([cfg], 0) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        bufs.compress(ctx, ld.k, ld.v)
+        q, kn, vn = ld.decode_inputs(0)
+        ref = bufs.decode(ctx, q).clone()
+        assert taskkv_last_async_error(ctx.handle) == 0
+        out = bufs.decode(ctx, q, kn, vn)
+        assert taskkv_last_async_error(ctx.handle) == 1
+        assert taskkv_last_async_error(ctx.handle) == 0          # reading clears it
+        assert torch.equal(out, ref)
+        assert bufs.lens.cpu().tolist() == [512] * 4
+
+
+def test_decode_is_deterministic():
+    ses = _session()
+    wl = small_workload(name="det", wid=155, ctx_len=5000, n_hetero=2)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 4)
+    with ses.Context([cfg], 4) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        bufs.compress(ctx, ld.k, ld.v)
+        mask0, kept0 = bufs.mask.clone(), bufs.kept_idx.clone()
+        q, _, _ = ld.decode_inputs(0)
+        a = bufs.decode(ctx, q).clone()
+        for _ in range(3):
+            assert torch.equal(bufs.decode(ctx, q), a)
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        bufs.compress(ctx, ld.k, ld.v)
+        assert torch.equal(bufs.mask, mask0) and torch.equal(bufs.kept_idx, kept0)
+
+
+def test_argument_errors_are_reported():
+    ses = _session()
+    import paper_2501_15113_amd as tk
+    wl = small_workload(name="err", wid=156, ctx_len=600)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 0)
+    with ses.Context([cfg], 0) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        with pytest.raises(tk.TaskKVError, match="cache buffer too small"):
+            tk.taskkv_compress(ctx.handle, cfg, ld.k, ld.v, bufs.scores, bufs.mask, bufs.k_cache,
+                               bufs.v_cache, bufs.capacity - 512, 0, bufs.offsets, bufs.lens, bufs.kept_idx)
+    small = tk.taskkv_create(0, 1024)
+    try:
+        with pytest.raises(tk.TaskKVError, match="workspace too small"):
+            tk.taskkv_separate(small, cfg, ld.q_win, ld.k, ld.v, bufs.scores, bufs.sem_vec, bufs.dist,
+                               bufs.mask)
+    finally:
+        tk.taskkv_destroy(small)
