@@ -83,7 +83,7 @@ size_t taskkv_workspace_bytes(const taskkv_layer_cfg *cfg, int32_t reserve_decod
 /* Host only.  Exact token capacity of the ragged cache this cfg produces: the
  * head counts are fixed by cfg (n_hetero is a count), so the size is known
  * without reading the mask back.  Each unit gets its kept tokens plus
- * `reserve_decode_tokens`, rounded up to TASKKV_CHUNK_TOKENS.  Returns < 0 on
+ * `reserve_decode_tokens`, rounded up to TASKKV_CHUNK_TOKENS (at least one chunk).  Returns < 0 on
  * a bad cfg. */
 int64_t taskkv_cache_tokens(const taskkv_layer_cfg *cfg, int32_t reserve_decode_tokens);
 

@@ -50,7 +50,10 @@ static int64_t cache_tokens(const Dims &d, int reserve) {
   int n_long = d.n_het < d.Hkv ? d.n_het : d.Hkv;
   if (d.add_centre && n_long < d.Hkv) n_long += 1;
   if (d.keep_all) n_long = d.Hkv;
-  auto cap = [&](int64_t len) { return (len + reserve + CHUNK - 1) / CHUNK * CHUNK; };
+  auto cap = [&](int64_t len) {
+    const int64_t c = (len + reserve + CHUNK - 1) / CHUNK * CHUNK;
+    return c < CHUNK ? (int64_t)CHUNK : c;  // every unit owns at least one chunk
+  };
   const int64_t short_len = (int64_t)d.s1 + d.k + d.s2;
   return (int64_t)d.B * (n_long * cap(d.N) + (int64_t)(d.Hkv - n_long) * cap(short_len));
 }
@@ -73,7 +76,8 @@ static size_t ws_compress(const Dims &d) {
 }
 static size_t ws_decode(const Dims &d, int64_t capacity) {
   const size_t n_chunks = (size_t)(capacity / CHUNK);
-  return 2 * al(n_chunks * d.G * sizeof(float)) + al(n_chunks * d.G * d.D * sizeof(float));
+  return 2 * al(n_chunks * d.G * sizeof(float)) + al(n_chunks * d.G * d.D * sizeof(float)) +
+         al((size_t)d.units * sizeof(int32_t));
 }
 
 }  // namespace taskkv
@@ -239,13 +243,10 @@ int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void 
   float *pm = cv.take<float>(n_chunks * d.G);
   float *pl = cv.take<float>(n_chunks * d.G);
   float *po = cv.take<float>(n_chunks * d.G * d.D);
+  int32_t *eff_len = cv.take<int32_t>((size_t)d.units);
   if (!cv.ok) return TASKKV_EWORKSPACE;
-  if (k_new) {
-    int rc = launch_append(d, cfg->dtype, k_new, v_new, k_cache, v_cache, offsets, lens, ctx->d_err, s);
-    if (rc) return rc;
-  }
-  return launch_decode(ctx, d, cfg->dtype, q, k_cache, v_cache, capacity_tokens, offsets, lens, pm, pl,
-                       po, out, s);
+  return launch_decode(ctx, d, cfg->dtype, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets,
+                       lens, eff_len, pm, pl, po, out, s);
 }
 
 int taskkv_cache_export(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k_cache,

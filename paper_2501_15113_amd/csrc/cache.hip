@@ -42,7 +42,8 @@ __global__ void layout_kernel(const uint8_t *__restrict__ mask, int64_t *__restr
     int64_t off = 0;
     for (int u = 0; u < dm.units; ++u) {
       offsets[u] = off;
-      const int64_t cap = ((int64_t)lens[u] + reserve + CHUNK - 1) / CHUNK * CHUNK;
+      int64_t cap = ((int64_t)lens[u] + reserve + CHUNK - 1) / CHUNK * CHUNK;
+      if (cap < CHUNK) cap = CHUNK;  // every unit owns at least one chunk
       off += cap;
     }
     offsets[dm.units] = off;

@@ -42,21 +42,46 @@ union Frag {
 // bf16 high and low parts so the probabilities keep ~16 bits.
 template <int D>
 __global__ __launch_bounds__(256) void decode_bf16_kernel(
-    const uint16_t *__restrict__ q, const uint4 *__restrict__ kc, const uint4 *__restrict__ vc,
-    const int64_t *__restrict__ offsets, const int32_t *__restrict__ lens, float *__restrict__ pm,
-    float *__restrict__ pl, float *__restrict__ po, int n_units, int Hq, int Hkv, int G,
-    float scale_log2) {
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_new,
+    const uint16_t *__restrict__ v_new, uint4 *kc, uint4 *vc, const int64_t *__restrict__ offsets,
+    const int32_t *__restrict__ lens, int32_t *__restrict__ eff_len, int *__restrict__ d_err,
+    float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ po, int n_units, int Hq,
+    int Hkv, int G, float scale_log2) {
   constexpr int KK = D / 32, MB = D / 16;
   const int chunk = blockIdx.x, hg = blockIdx.y;
   const int64_t tok0 = (int64_t)chunk * CHUNK;
   const int u = find_unit_d(offsets, n_units, tok0);
   if (u < 0) return;
-  const int local0 = (int)(tok0 - offsets[u]);
-  const int len = lens[u];
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 4, c = l & 15;
+  const int64_t base = offsets[u];
+  const int local0 = (int)(tok0 - base);
+  const int len_old = lens[u];
+  // Fused append (only when one head slice covers the group, so that this
+  // block is the sole reader of the page it writes): the new token goes to
+  // slot len_old of the unit; the block that owns that slot stores it before
+  // any wave of the block loads the page.
+  const bool want_app = k_new != nullptr;
+  const bool can_app = want_app && len_old < (int)(offsets[u + 1] - base);
+  const int len = len_old + (can_app ? 1 : 0);
+  if (local0 == 0 && hg == 0 && tid == 0) {
+    eff_len[u] = len;
+    if (want_app && !can_app) atomicOr(d_err, 1);
+  }
   if (local0 >= len) return;
+  if (can_app && len_old >= local0 && len_old < local0 + CHUNK) {
+    if (tid < D) {
+      uint16_t *kc16 = reinterpret_cast<uint16_t *>(kc), *vc16 = reinterpret_cast<uint16_t *>(vc);
+      const int64_t page = base + (len_old / PAGE) * PAGE;
+      const int t32 = len_old % PAGE, sb = t32 >> 4, r = t32 & 15;
+      kc16[((size_t)page + sb * 16) * D + (size_t)((tid >> 3) * 16 + r) * 8 + (tid & 7)] = k_new[(size_t)u * D + tid];
+      const int ga = (t32 & 15) >> 2, ea = 4 * (t32 >> 4) + (t32 & 3);
+      vc16[(size_t)page * D + (size_t)((tid >> 4) * 64 + ga * 16 + (tid & 15)) * 8 + ea] = v_new[(size_t)u * D + tid];
+    }
+    __threadfence_block();
+    __syncthreads();
+  }
   const int n_tok = min(CHUNK, len - local0);
   const int n_pages = (n_tok + PAGE - 1) / PAGE;
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 4, c = l & 15;
   const int b = u / Hkv, h = u % Hkv;
   const int slot = hg * 16 + c;
 
@@ -230,39 +255,84 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(
   }
 }
 
-// Merge a unit's partials in ascending chunk order.  One block per (b, query
-// head), one thread per output channel.
-template <bool LOG2>
-__global__ void combine_kernel(const float *__restrict__ pm, const float *__restrict__ pl,
-                               const float *__restrict__ po, const int64_t *__restrict__ offsets,
-                               const int32_t *__restrict__ lens, float *__restrict__ out, int Hq,
-                               int Hkv, int G, int D) {
-  const int bq = blockIdx.x, dd = threadIdx.x;
+// Merge a unit's partials.  One block per (b, query head); the 256 threads form
+// NCL chunk lanes x D/4 channel lanes: chunk lane c accumulates chunks c,
+// c+NCL, ... (float4 per thread), then the NCL lane sums are added in lane
+// order.  The summation order is fixed by the indices alone, so the result is
+// reproducible.  `len_src` holds the unit lengths valid for this step; when
+// `lens_out` is given the block of the group's first head stores them there
+// (this is how the fused append publishes the new length).
+template <int D, bool LOG2>
+__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ pm,
+                                                      const float *__restrict__ pl,
+                                                      const float *__restrict__ po,
+                                                      const int64_t *__restrict__ offsets,
+                                                      const int32_t *__restrict__ len_src,
+                                                      int32_t *__restrict__ lens_out,
+                                                      float *__restrict__ out, int Hq, int Hkv, int G) {
+  constexpr int DL = D / 4, NCL = 256 / DL;
+  const int bq = blockIdx.x, tid = threadIdx.x;
   const int b = bq / Hq, hq = bq % Hq, h = hq / G, slot = hq % G;
   const int u = b * Hkv + h;
   const int64_t chunk0 = offsets[u] / CHUNK;
-  const int len = lens[u];
+  const int len = len_src[u];
+  if (lens_out != nullptr && slot == 0 && tid == 0) lens_out[u] = len;
   const int nch = (len + CHUNK - 1) / CHUNK;
+  const int dl = tid % DL, cl = tid / DL;
+  __shared__ float red_m[4];
+  __shared__ float4 red_o[NCL][DL];
+  __shared__ float red_l[NCL];
+  if (nch == 0) {
+    if (tid < D) out[(size_t)bq * D + tid] = 0.f;
+    return;
+  }
   float M = -INFINITY;
-  for (int i = 0; i < nch; ++i) M = fmaxf(M, pm[(size_t)(chunk0 + i) * G + slot]);
-  float L = 0.f, O = 0.f;
-  for (int i = 0; i < nch; ++i) {
+  for (int i = tid; i < nch; i += 256) M = fmaxf(M, pm[(size_t)(chunk0 + i) * G + slot]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+  if ((tid & 63) == 0) red_m[tid >> 6] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float lacc = 0.f;
+  for (int i = cl; i < nch; i += NCL) {
     const size_t pi = (size_t)(chunk0 + i) * G + slot;
     const float dlt = pm[pi] - M;
     const float wgt = LOG2 ? __builtin_amdgcn_exp2f(dlt) : expf(dlt);
-    L += pl[pi] * wgt;
-    O += po[pi * D + dd] * wgt;
+    const float4 o = *reinterpret_cast<const float4 *>(po + pi * D + 4 * dl);
+    acc.x += o.x * wgt; acc.y += o.y * wgt; acc.z += o.z * wgt; acc.w += o.w * wgt;
+    if (dl == 0) lacc += pl[pi] * wgt;
   }
-  out[(size_t)bq * D + dd] = nch > 0 ? O / L : 0.f;
+  red_o[cl][dl] = acc;
+  if (dl == 0) red_l[cl] = lacc;
+  __syncthreads();
+  if (tid < DL) {
+    float4 o = red_o[0][tid];
+    float L = red_l[0];
+#pragma unroll
+    for (int c = 1; c < NCL; ++c) {
+      const float4 x = red_o[c][tid];
+      o.x += x.x; o.y += x.y; o.z += x.z; o.w += x.w;
+      L += red_l[c];
+    }
+    const float inv = 1.f / L;
+    *reinterpret_cast<float4 *>(out + (size_t)bq * D + 4 * tid) = make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+  }
 }
 
-int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, const void *k_cache,
-                  const void *v_cache, int64_t capacity, const int64_t *offsets, const int32_t *lens,
-                  float *pm, float *pl, float *po, float *out, hipStream_t s) {
+int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, const void *k_new,
+                  const void *v_new, void *k_cache, void *v_cache, int64_t capacity,
+                  const int64_t *offsets, int32_t *lens, int32_t *eff_len, float *pm, float *pl,
+                  float *po, float *out, hipStream_t s) {
   const dim3 grid((unsigned)(capacity / CHUNK), (dm.G + 15) / 16), block(256);
+  const dim3 cgrid(dm.B * dm.Hq);
   const bool prof = ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS;
-  if (prof) hipEventRecord(ctx->ev_start[ctx->n_events], s);
   if (dtype == TASKKV_F32) {
+    if (k_new) {
+      int rc = launch_append(dm, dtype, k_new, v_new, k_cache, v_cache, offsets, lens, ctx->d_err, s);
+      if (rc) return rc;
+    }
+    if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
     auto qq = static_cast<const float *>(q);
     auto kc = static_cast<const float *>(k_cache), vc = static_cast<const float *>(v_cache);
     const float scale = (float)dm.scale;
@@ -270,24 +340,35 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
       decode_f32_kernel<64><<<grid, block, 0, s>>>(qq, kc, vc, offsets, lens, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale);
     else
       decode_f32_kernel<128><<<grid, block, 0, s>>>(qq, kc, vc, offsets, lens, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale);
-  } else {
-    auto qq = static_cast<const uint16_t *>(q);
-    auto kc = static_cast<const uint4 *>(k_cache), vc = static_cast<const uint4 *>(v_cache);
-    const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
+    if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
     if (dm.D == 64)
-      decode_bf16_kernel<64><<<grid, block, 0, s>>>(qq, kc, vc, offsets, lens, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale_log2);
+      combine_kernel<64, false><<<cgrid, block, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
     else
-      decode_bf16_kernel<128><<<grid, block, 0, s>>>(qq, kc, vc, offsets, lens, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale_log2);
+      combine_kernel<128, false><<<cgrid, block, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
+    return hip_ok(hipGetLastError());
   }
-  if (prof) {
-    hipEventRecord(ctx->ev_stop[ctx->n_events], s);
-    ctx->n_events++;
+  // bf16: the append is fused into the attention kernel when one head slice
+  // covers the query group; otherwise it runs as its own kernel first.
+  const bool fused = k_new != nullptr && grid.y == 1;
+  if (k_new && !fused) {
+    int rc = launch_append(dm, dtype, k_new, v_new, k_cache, v_cache, offsets, lens, ctx->d_err, s);
+    if (rc) return rc;
   }
-  const dim3 cgrid(dm.B * dm.Hq), cblock(dm.D);
-  if (dtype == TASKKV_F32)
-    combine_kernel<false><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, lens, out, dm.Hq, dm.Hkv, dm.G, dm.D);
+  auto qq = static_cast<const uint16_t *>(q);
+  auto kn = fused ? static_cast<const uint16_t *>(k_new) : nullptr;
+  auto vn = fused ? static_cast<const uint16_t *>(v_new) : nullptr;
+  auto kc = static_cast<uint4 *>(k_cache), vc = static_cast<uint4 *>(v_cache);
+  const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
+  if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
+  if (dm.D == 64)
+    decode_bf16_kernel<64><<<grid, block, 0, s>>>(qq, kn, vn, kc, vc, offsets, lens, eff_len, ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale_log2);
   else
-    combine_kernel<true><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, lens, out, dm.Hq, dm.Hkv, dm.G, dm.D);
+    decode_bf16_kernel<128><<<grid, block, 0, s>>>(qq, kn, vn, kc, vc, offsets, lens, eff_len, ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale_log2);
+  if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
+  if (dm.D == 64)
+    combine_kernel<64, true><<<cgrid, block, 0, s>>>(pm, pl, po, offsets, eff_len, fused ? lens : nullptr, out, dm.Hq, dm.Hkv, dm.G);
+  else
+    combine_kernel<128, true><<<cgrid, block, 0, s>>>(pm, pl, po, offsets, eff_len, fused ? lens : nullptr, out, dm.Hq, dm.Hkv, dm.G);
   return hip_ok(hipGetLastError());
 }
 

@@ -81,9 +81,10 @@ int launch_export(const Dims &dm, int dtype, const void *k_cache, const void *v_
                   const int64_t *offsets, void *k_rows, void *v_rows, int64_t capacity, hipStream_t s);
 int launch_append(const Dims &dm, int dtype, const void *k_new, const void *v_new, void *k_cache,
                   void *v_cache, const int64_t *offsets, int32_t *lens, int *d_err, hipStream_t s);
-int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, const void *k_cache,
-                  const void *v_cache, int64_t capacity, const int64_t *offsets, const int32_t *lens,
-                  float *pm, float *pl, float *po, float *out, hipStream_t s);
+int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, const void *k_new,
+                  const void *v_new, void *k_cache, void *v_cache, int64_t capacity,
+                  const int64_t *offsets, int32_t *lens, int32_t *eff_len, float *pm, float *pl,
+                  float *po, float *out, hipStream_t s);
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? TASKKV_OK : TASKKV_EHIP; }
 

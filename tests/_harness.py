@@ -61,9 +61,11 @@ def check_compression(ld, cfg, bufs, k_rows, v_rows, b, ref):
         kept = ref["kept"][h]
         assert lens[h] == len(kept), f"len differs for head {h}"
         keeps_all = bool(ref["mask"][h]) or cfg.n_sink + cfg.n_recent >= N
-        if keeps_all:
+        if bufs.row == 0:
+            pass                                   # no kept_idx rows exist
+        elif keeps_all:
             assert (kept_gpu[h] == -1).all()
-        elif bufs.row > 0:
+        else:
             assert kept_gpu[h, :len(kept)].tolist() == kept.tolist(), f"kept indices differ, head {h}"
             assert (kept_gpu[h, len(kept):] == -1).all()
         u = b * Hkv + h

@@ -96,6 +96,8 @@ SWEEP = [
     dict(obs_window=1, ctx_len=520),
     dict(obs_window=50, ctx_len=50, n_sink=2, n_recent=3, n_middle=4, top_t=10),   # L = N
     dict(batch=3, ctx_len=33, n_sink=1, n_recent=2, n_middle=3, obs_window=5, top_t=7),
+    dict(n_sink=0, n_recent=0, n_middle=0, ctx_len=700, n_hetero=1),   # the other heads keep nothing
+    dict(ctx_len=1536, n_sink=0, n_recent=480, n_middle=32, decode_steps=4),   # append crosses a chunk edge
 ]
 
 
@@ -150,6 +152,28 @@ def test_append_to_full_unit_sets_flag_and_drops_token():
         assert taskkv_last_async_error(ctx.handle) == 0          # reading clears it
         assert torch.equal(out, ref)
         assert bufs.lens.cpu().tolist() == [512] * 4
+
+
+def test_empty_units_give_zero_output():
+    ses = _session()
+    wl = small_workload(name="empty", wid=157, ctx_len=600, n_sink=0, n_recent=0, n_middle=0, n_hetero=1,
+                        batch=1)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 0)
+    with ses.Context([cfg], 0) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        bufs.compress(ctx, ld.k, ld.v)
+        q, _, _ = ld.decode_inputs(0)
+        out = bufs.decode(ctx, q).cpu()
+        mask = bufs.mask.cpu().numpy()[0]
+        lens = bufs.lens.cpu().numpy()
+        G = wl.group
+        for h in range(wl.n_kv_heads):
+            if mask[h]:
+                assert lens[h] == 600 and out[0, h * G:(h + 1) * G].abs().max() > 0
+            else:
+                assert lens[h] == 0 and not out[0, h * G:(h + 1) * G].any()
 
 
 def test_decode_is_deterministic():
