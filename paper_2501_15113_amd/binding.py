@@ -39,7 +39,9 @@ class LayerCfg(C.Structure):
 
 
 def library_path() -> str:
-    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtaskkv.so")
+    """In-tree libtaskkv.so, or the file named by TASKKV_LIBRARY."""
+    return os.environ.get("TASKKV_LIBRARY") or os.path.join(
+        os.path.dirname(os.path.abspath(__file__)), "libtaskkv.so")
 
 
 _LIB = None

@@ -15,6 +15,10 @@
 
 #include "taskkv_internal.h"
 
+#ifndef TASKKV_DEC_NT
+#define TASKKV_DEC_NT 1
+#endif
+
 namespace taskkv {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -30,16 +34,126 @@ __device__ __forceinline__ int find_unit_d(const int64_t *__restrict__ offsets, 
   return lo;
 }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 union Frag {
   uint4 u;
+  u32x4 v;
   bf16x8 b;
 };
+
+// K/V rows are read once per step and never reused by the step: nontemporal
+// loads keep them from displacing useful lines and stream measurably faster
+// from HBM than ordinary loads on this part.
+__device__ __forceinline__ u32x4 stream_load(const uint4 *p) {
+#if TASKKV_DEC_NT
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+#else
+  return *reinterpret_cast<const u32x4 *>(p);
+#endif
+}
+
+// Unit owning token slot `tok` (largest u with offsets[u] <= tok), or -1 past
+// the last region.  Few units (the common case): every lane loads its share of
+// offsets at once and a ballot counts the entries <= tok -- one memory latency
+// instead of a dependent binary-search chain.
+__device__ __forceinline__ int find_unit_fast(const int64_t *__restrict__ offsets, int n_units,
+                                              int64_t tok, int lane) {
+  if (n_units > 256) return find_unit_d(offsets, n_units, tok);
+  int64_t v[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int idx = lane + 64 * r;
+    v[r] = idx <= n_units ? offsets[idx] : INT64_MAX;
+  }
+  int cnt = 0;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) cnt += __popcll(__ballot(v[r] <= tok));
+  // cnt entries of offsets[0..n_units] are <= tok; the last region ends at offsets[n_units]
+  return cnt > n_units ? -1 : cnt - 1;
+}
+
+template <int D>
+struct PageRegs {
+  Frag kr[2][D / 32];
+  Frag vr[D / 16];
+};
+
+template <int D>
+__device__ __forceinline__ void load_page(const uint4 *kp, const uint4 *vp, int l, PageRegs<D> &r) {
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) r.kr[sb][kk].v = stream_load(kp + sb * 2 * D + kk * 64 + l);
+#pragma unroll
+  for (int mb = 0; mb < D / 16; ++mb) r.vr[mb].v = stream_load(vp + mb * 64 + l);
+}
+
+// One 32-token page: S^T = K q^T, online softmax (exp2 domain), O^T += V^T P^T.
+template <int D>
+__device__ __forceinline__ void attend_page(const PageRegs<D> &r, const Frag (&qv)[D / 32], int tok_base,
+                                            int n_tok, int g, float scale_log2, float &m_run,
+                                            float &l_run, floatx4 (&acc)[D / 16]) {
+  constexpr int KK = D / 32, MB = D / 16;
+#ifdef TASKKV_EXP_NOCOMPUTE  // experiment only: touch the data, skip the math
+  unsigned x = 0;
+  for (int sb = 0; sb < 2; ++sb) for (int kk = 0; kk < KK; ++kk) x ^= r.kr[sb][kk].u.x ^ r.kr[sb][kk].u.y ^ r.kr[sb][kk].u.z ^ r.kr[sb][kk].u.w;
+  for (int mb = 0; mb < MB; ++mb) x ^= r.vr[mb].u.x ^ r.vr[mb].u.y ^ r.vr[mb].u.z ^ r.vr[mb].u.w;
+  acc[0][0] += __uint_as_float(x & 0x3fffffffu); m_run = 0.f; l_run = 1.f;
+  return;
+#endif
+  floatx4 s[2];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    s[sb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      s[sb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.kr[sb][kk].b, qv[kk].b, s[sb], 0, 0, 0);
+  }
+  float sv[8];
+  float mloc = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int t = tok_base + 16 * (e >> 2) + 4 * g + (e & 3);
+    sv[e] = t < n_tok ? s[e >> 2][e & 3] * scale_log2 : -INFINITY;
+    mloc = fmaxf(mloc, sv[e]);
+  }
+  mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+  mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+  const float m_new = fmaxf(m_run, mloc);  // finite: the page holds >= 1 token
+  const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+  float lsum = 0.f;
+  Frag ph, plo;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float p = __builtin_amdgcn_exp2f(sv[e] - m_new);
+    lsum += p;
+    const __bf16 hi = (__bf16)p;
+    ph.b[e] = hi;
+    plo.b[e] = (__bf16)(p - (float)hi);
+  }
+  l_run = l_run * alpha + lsum;
+  m_run = m_new;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    acc[mb] *= alpha;
+    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, ph.b, acc[mb], 0, 0, 0);
+    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, plo.b, acc[mb], 0, 0, 0);
+  }
+}
+
+#ifndef TASKKV_DEC_PIPE
+#define TASKKV_DEC_PIPE 1
+#endif
 
 // bf16 cache, matrix-core path.  Block = 4 waves; wave w takes pages w, w+4, ...
 // of its chunk.  Per 32-token page and wave: 2*D/32 MFMAs for S^T = K q^T
 // (rows = tokens, columns = the <=16 query heads of the group), online softmax
 // in the exp2 domain, then 2*D/16 MFMAs for O^T += V^T P^T with P split into
-// bf16 high and low parts so the probabilities keep ~16 bits.
+// bf16 high and low parts so the probabilities keep ~16 bits.  K/V addresses
+// depend only on the block index, so the first page is requested before the
+// block knows which unit it serves; later pages are requested one iteration
+// ahead of their use.
 template <int D>
 __global__ __launch_bounds__(256) void decode_bf16_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_new,
@@ -47,19 +161,24 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
     const int32_t *__restrict__ lens, int32_t *__restrict__ eff_len, int *__restrict__ d_err,
     float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ po, int n_units, int Hq,
     int Hkv, int G, float scale_log2) {
-  constexpr int KK = D / 32, MB = D / 16;
+  constexpr int KK = D / 32, MB = D / 16, PSTRIDE = PAGE * (D / 8);  // uint4 per page
   const int chunk = blockIdx.x, hg = blockIdx.y;
   const int64_t tok0 = (int64_t)chunk * CHUNK;
-  const int u = find_unit_d(offsets, n_units, tok0);
-  if (u < 0) return;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 4, c = l & 15;
+  const uint4 *kbase = kc + (size_t)tok0 * (D / 8);
+  const uint4 *vbase = vc + (size_t)tok0 * (D / 8);
+  PageRegs<D> ra, rb;
+  load_page<D>(kbase + (size_t)w * PSTRIDE, vbase + (size_t)w * PSTRIDE, l, ra);  // in bounds: whole chunks are allocated
+
+  const int u = find_unit_fast(offsets, n_units, tok0, l);
+  if (u < 0) return;
   const int64_t base = offsets[u];
   const int local0 = (int)(tok0 - base);
   const int len_old = lens[u];
   // Fused append (only when one head slice covers the group, so that this
   // block is the sole reader of the page it writes): the new token goes to
-  // slot len_old of the unit; the block that owns that slot stores it before
-  // any wave of the block loads the page.
+  // slot len_old of the unit; the block that owns that slot stores it, and the
+  // wave that had already requested that page requests it again afterwards.
   const bool want_app = k_new != nullptr;
   const bool can_app = want_app && len_old < (int)(offsets[u + 1] - base);
   const int len = len_old + (can_app ? 1 : 0);
@@ -79,6 +198,8 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
     }
     __threadfence_block();
     __syncthreads();
+    if ((len_old - local0) / PAGE == w)
+      load_page<D>(kbase + (size_t)w * PSTRIDE, vbase + (size_t)w * PSTRIDE, l, ra);
   }
   const int n_tok = min(CHUNK, len - local0);
   const int n_pages = (n_tok + PAGE - 1) / PAGE;
@@ -99,56 +220,23 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) acc[mb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  for (int pg = w; pg < n_pages; pg += 4) {
-    const uint4 *kp = kc + ((size_t)tok0 + (size_t)pg * PAGE) * (D / 8);
-    const uint4 *vp = vc + ((size_t)tok0 + (size_t)pg * PAGE) * (D / 8);
-    Frag kr[2][KK], vr[MB];
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) kr[sb][kk].u = kp[sb * 2 * D + kk * 64 + l];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) vr[mb].u = vp[mb * 64 + l];
-
-    floatx4 s[2];
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      s[sb] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        s[sb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kr[sb][kk].b, qv[kk].b, s[sb], 0, 0, 0);
-    }
-    float sv[8];
-    float mloc = -INFINITY;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int t = pg * PAGE + 16 * (e >> 2) + 4 * g + (e & 3);
-      sv[e] = t < n_tok ? s[e >> 2][e & 3] * scale_log2 : -INFINITY;
-      mloc = fmaxf(mloc, sv[e]);
-    }
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-    const float m_new = fmaxf(m_run, mloc);  // finite: the page holds >= 1 token
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    float lsum = 0.f;
-    Frag ph, plo;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float p = __builtin_amdgcn_exp2f(sv[e] - m_new);
-      lsum += p;
-      const __bf16 hi = (__bf16)p;
-      ph.b[e] = hi;
-      plo.b[e] = (__bf16)(p - (float)hi);
-    }
-    l_run = l_run * alpha + lsum;
-    m_run = m_new;
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      acc[mb] *= alpha;
-      acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vr[mb].b, ph.b, acc[mb], 0, 0, 0);
-      acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vr[mb].b, plo.b, acc[mb], 0, 0, 0);
+#if TASKKV_DEC_PIPE
+  for (int pg = w; pg < n_pages; pg += 8) {
+    if (pg + 4 < n_pages)
+      load_page<D>(kbase + (size_t)(pg + 4) * PSTRIDE, vbase + (size_t)(pg + 4) * PSTRIDE, l, rb);
+    attend_page<D>(ra, qv, pg * PAGE, n_tok, g, scale_log2, m_run, l_run, acc);
+    if (pg + 4 < n_pages) {
+      if (pg + 8 < n_pages)
+        load_page<D>(kbase + (size_t)(pg + 8) * PSTRIDE, vbase + (size_t)(pg + 8) * PSTRIDE, l, ra);
+      attend_page<D>(rb, qv, (pg + 4) * PAGE, n_tok, g, scale_log2, m_run, l_run, acc);
     }
   }
+#else
+  for (int pg = w; pg < n_pages; pg += 4) {
+    if (pg != w) load_page<D>(kbase + (size_t)pg * PSTRIDE, vbase + (size_t)pg * PSTRIDE, l, ra);
+    attend_page<D>(ra, qv, pg * PAGE, n_tok, g, scale_log2, m_run, l_run, acc);
+  }
+#endif
 
   // merge the four waves (fixed order) and write the chunk's partial
   __shared__ float sm[4][16], sl[4][16];
@@ -255,22 +343,23 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(
   }
 }
 
-// Merge a unit's partials.  One block per (b, query head); the 256 threads form
-// NCL chunk lanes x D/4 channel lanes: chunk lane c accumulates chunks c,
-// c+NCL, ... (float4 per thread), then the NCL lane sums are added in lane
-// order.  The summation order is fixed by the indices alone, so the result is
-// reproducible.  `len_src` holds the unit lengths valid for this step; when
-// `lens_out` is given the block of the group's first head stores them there
-// (this is how the fused append publishes the new length).
+// Merge a unit's partials.  One block of 1024 threads per (b, query head):
+// NCL chunk lanes x D/4 channel lanes.  Chunk lane c owns chunks c, c+NCL, ...;
+// it requests UN of them at once (the partials sit in L2, the loop is latency
+// bound otherwise), accumulates them in ascending order, and the NCL lane sums
+// are then added in lane order.  The summation order is fixed by indices
+// alone, so the result is reproducible.  `len_src` holds the unit lengths valid
+// for this step; when `lens_out` is given the block of the group's first head
+// stores them there (this is how the fused append publishes the new length).
 template <int D, bool LOG2>
-__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ pm,
-                                                      const float *__restrict__ pl,
-                                                      const float *__restrict__ po,
-                                                      const int64_t *__restrict__ offsets,
-                                                      const int32_t *__restrict__ len_src,
-                                                      int32_t *__restrict__ lens_out,
-                                                      float *__restrict__ out, int Hq, int Hkv, int G) {
-  constexpr int DL = D / 4, NCL = 256 / DL;
+__global__ __launch_bounds__(1024) void combine_kernel(const float *__restrict__ pm,
+                                                       const float *__restrict__ pl,
+                                                       const float *__restrict__ po,
+                                                       const int64_t *__restrict__ offsets,
+                                                       const int32_t *__restrict__ len_src,
+                                                       int32_t *__restrict__ lens_out,
+                                                       float *__restrict__ out, int Hq, int Hkv, int G) {
+  constexpr int DL = D / 4, NCL = 1024 / DL, UN = 8;
   const int bq = blockIdx.x, tid = threadIdx.x;
   const int b = bq / Hq, hq = bq % Hq, h = hq / G, slot = hq % G;
   const int u = b * Hkv + h;
@@ -279,7 +368,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
   if (lens_out != nullptr && slot == 0 && tid == 0) lens_out[u] = len;
   const int nch = (len + CHUNK - 1) / CHUNK;
   const int dl = tid % DL, cl = tid / DL;
-  __shared__ float red_m[4];
+  __shared__ float red_m[16];
   __shared__ float4 red_o[NCL][DL];
   __shared__ float red_l[NCL];
   if (nch == 0) {
@@ -287,21 +376,35 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
     return;
   }
   float M = -INFINITY;
-  for (int i = tid; i < nch; i += 256) M = fmaxf(M, pm[(size_t)(chunk0 + i) * G + slot]);
+  for (int i = tid; i < nch; i += 1024) M = fmaxf(M, pm[(size_t)(chunk0 + i) * G + slot]);
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
   if ((tid & 63) == 0) red_m[tid >> 6] = M;
   __syncthreads();
-  M = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  M = red_m[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) M = fmaxf(M, red_m[r]);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float lacc = 0.f;
-  for (int i = cl; i < nch; i += NCL) {
-    const size_t pi = (size_t)(chunk0 + i) * G + slot;
-    const float dlt = pm[pi] - M;
-    const float wgt = LOG2 ? __builtin_amdgcn_exp2f(dlt) : expf(dlt);
-    const float4 o = *reinterpret_cast<const float4 *>(po + pi * D + 4 * dl);
-    acc.x += o.x * wgt; acc.y += o.y * wgt; acc.z += o.z * wgt; acc.w += o.w * wgt;
-    if (dl == 0) lacc += pl[pi] * wgt;
+  for (int i0 = cl; i0 < nch; i0 += NCL * UN) {
+    float4 o[UN];
+    float pmv[UN], plv[UN];
+#pragma unroll
+    for (int r = 0; r < UN; ++r) {
+      const int i = i0 + r * NCL;
+      const bool ok = i < nch;
+      const size_t pi = (size_t)(chunk0 + (ok ? i : 0)) * G + slot;
+      pmv[r] = ok ? pm[pi] : -INFINITY;
+      plv[r] = ok ? pl[pi] : 0.f;
+      o[r] = ok ? *reinterpret_cast<const float4 *>(po + pi * D + 4 * dl) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int r = 0; r < UN; ++r) {
+      const float dlt = pmv[r] - M;
+      const float wgt = LOG2 ? __builtin_amdgcn_exp2f(dlt) : expf(dlt);
+      acc.x += o[r].x * wgt; acc.y += o[r].y * wgt; acc.z += o[r].z * wgt; acc.w += o[r].w * wgt;
+      lacc += plv[r] * wgt;
+    }
   }
   red_o[cl][dl] = acc;
   if (dl == 0) red_l[cl] = lacc;
@@ -325,7 +428,7 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
                   const int64_t *offsets, int32_t *lens, int32_t *eff_len, float *pm, float *pl,
                   float *po, float *out, hipStream_t s) {
   const dim3 grid((unsigned)(capacity / CHUNK), (dm.G + 15) / 16), block(256);
-  const dim3 cgrid(dm.B * dm.Hq);
+  const dim3 cgrid(dm.B * dm.Hq), cblock(1024);
   const bool prof = ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS;
   if (dtype == TASKKV_F32) {
     if (k_new) {
@@ -342,9 +445,9 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
       decode_f32_kernel<128><<<grid, block, 0, s>>>(qq, kc, vc, offsets, lens, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale);
     if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
     if (dm.D == 64)
-      combine_kernel<64, false><<<cgrid, block, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
+      combine_kernel<64, false><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
     else
-      combine_kernel<128, false><<<cgrid, block, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
+      combine_kernel<128, false><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
     return hip_ok(hipGetLastError());
   }
   // bf16: the append is fused into the attention kernel when one head slice
@@ -366,9 +469,9 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
     decode_bf16_kernel<128><<<grid, block, 0, s>>>(qq, kn, vn, kc, vc, offsets, lens, eff_len, ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale_log2);
   if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
   if (dm.D == 64)
-    combine_kernel<64, true><<<cgrid, block, 0, s>>>(pm, pl, po, offsets, eff_len, fused ? lens : nullptr, out, dm.Hq, dm.Hkv, dm.G);
+    combine_kernel<64, true><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, eff_len, fused ? lens : nullptr, out, dm.Hq, dm.Hkv, dm.G);
   else
-    combine_kernel<128, true><<<cgrid, block, 0, s>>>(pm, pl, po, offsets, eff_len, fused ? lens : nullptr, out, dm.Hq, dm.Hkv, dm.G);
+    combine_kernel<128, true><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, eff_len, fused ? lens : nullptr, out, dm.Hq, dm.Hkv, dm.G);
   return hip_ok(hipGetLastError());
 }
 
