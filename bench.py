@@ -179,7 +179,7 @@ def main():
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "decode_us_per_step": round(dec_ms * 1e3 / (args.steps * steps_dec), 3),
         "compress_ms_per_layer": round(comp_ms / (args.steps * wl.n_layers), 4),
-        "roofline": {"bound": "hbm", "kernel": "decode_bf16_kernel" if wl.dtype == "bf16" else "decode_f32_kernel",
+        "roofline": {"bound": "hbm", "kernel": "decode_stream_kernel" if wl.dtype == "bf16" else "decode_f32_kernel",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(wl.name),
                      "avg_kernel_us": round(avg_kernel_ms * 1e3, 3), "launches_timed": int(launches),

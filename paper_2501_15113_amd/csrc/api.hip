@@ -74,10 +74,17 @@ static size_t ws_separate(const Dims &d) {
 static size_t ws_compress(const Dims &d) {
   return d.pool > 1 ? al((size_t)d.units * d.N * sizeof(double)) : 0;
 }
+// Partial slots a decode call needs: one per chunk for the chunk-grid kernels,
+// one per (wave, unit) staircase step for the streaming kernel.
+static size_t decode_slots(const Dims &d, int64_t capacity) {
+  const size_t chunk_slots = (size_t)(capacity / CHUNK);
+  const size_t stream_slots = (size_t)STREAM_MAX_WG * 4 + d.units;
+  return chunk_slots > stream_slots ? chunk_slots : stream_slots;
+}
 static size_t ws_decode(const Dims &d, int64_t capacity) {
-  const size_t n_chunks = (size_t)(capacity / CHUNK);
-  return 2 * al(n_chunks * d.G * sizeof(float)) + al(n_chunks * d.G * d.D * sizeof(float)) +
-         al((size_t)d.units * sizeof(int32_t));
+  const size_t n = decode_slots(d, capacity);
+  return 2 * al(n * d.G * sizeof(float)) + al(n * d.G * d.D * sizeof(float)) +
+         2 * al(((size_t)d.units + 1) * sizeof(int32_t));
 }
 
 }  // namespace taskkv
@@ -112,6 +119,14 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
   c->profiling = 0;
   c->n_events = 0;
   c->events_created = 0;
+  c->n_cu = 0;
+  for (int i = 0; i < 4; ++i) c->stream_wg[i] = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) {
+    delete c;
+    return TASKKV_EHIP;
+  }
+  c->n_cu = prop.multiProcessorCount;
   if (workspace_bytes && hipMalloc((void **)&c->ws, workspace_bytes) != hipSuccess) {
     delete c;
     return TASKKV_EHIP;
@@ -238,13 +253,18 @@ int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void 
   if (capacity_tokens <= 0 || capacity_tokens % CHUNK) return TASKKV_EINVAL;
   if (capacity_tokens / CHUNK > 0x7fffffff) return TASKKV_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const size_t n_chunks = (size_t)(capacity_tokens / CHUNK);
+  if (capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
+  const size_t n_slots = decode_slots(d, capacity_tokens);
   Carver cv(ctx->ws, ctx->ws_bytes);
-  float *pm = cv.take<float>(n_chunks * d.G);
-  float *pl = cv.take<float>(n_chunks * d.G);
-  float *po = cv.take<float>(n_chunks * d.G * d.D);
-  int32_t *eff_len = cv.take<int32_t>((size_t)d.units);
+  float *pm = cv.take<float>(n_slots * d.G);
+  float *pl = cv.take<float>(n_slots * d.G);
+  float *po = cv.take<float>(n_slots * d.G * d.D);
+  int32_t *eff_len = cv.take<int32_t>((size_t)d.units + 1);
+  int32_t *page_prefix = cv.take<int32_t>((size_t)d.units + 1);
   if (!cv.ok) return TASKKV_EWORKSPACE;
+  if (cfg->dtype == TASKKV_BF16 && d.units <= STREAM_MAX_UNITS)
+    return launch_decode_stream(ctx, d, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens,
+                                eff_len, page_prefix, pm, pl, po, out, s);
   return launch_decode(ctx, d, cfg->dtype, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets,
                        lens, eff_len, pm, pl, po, out, s);
 }

@@ -15,132 +15,9 @@
 
 #include "taskkv_internal.h"
 
-#ifndef TASKKV_DEC_NT
-#define TASKKV_DEC_NT 1
-#endif
+#include "decode_common.h"
 
 namespace taskkv {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
-
-__device__ __forceinline__ int find_unit_d(const int64_t *__restrict__ offsets, int n_units, int64_t tok) {
-  if (tok >= offsets[n_units]) return -1;
-  int lo = 0, hi = n_units - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (offsets[mid] <= tok) lo = mid; else hi = mid - 1;
-  }
-  return lo;
-}
-
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-union Frag {
-  uint4 u;
-  u32x4 v;
-  bf16x8 b;
-};
-
-// K/V rows are read once per step and never reused by the step: nontemporal
-// loads keep them from displacing useful lines and stream measurably faster
-// from HBM than ordinary loads on this part.
-__device__ __forceinline__ u32x4 stream_load(const uint4 *p) {
-#if TASKKV_DEC_NT
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-#else
-  return *reinterpret_cast<const u32x4 *>(p);
-#endif
-}
-
-// Unit owning token slot `tok` (largest u with offsets[u] <= tok), or -1 past
-// the last region.  Few units (the common case): every lane loads its share of
-// offsets at once and a ballot counts the entries <= tok -- one memory latency
-// instead of a dependent binary-search chain.
-__device__ __forceinline__ int find_unit_fast(const int64_t *__restrict__ offsets, int n_units,
-                                              int64_t tok, int lane) {
-  if (n_units > 256) return find_unit_d(offsets, n_units, tok);
-  int64_t v[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int idx = lane + 64 * r;
-    v[r] = idx <= n_units ? offsets[idx] : INT64_MAX;
-  }
-  int cnt = 0;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) cnt += __popcll(__ballot(v[r] <= tok));
-  // cnt entries of offsets[0..n_units] are <= tok; the last region ends at offsets[n_units]
-  return cnt > n_units ? -1 : cnt - 1;
-}
-
-template <int D>
-struct PageRegs {
-  Frag kr[2][D / 32];
-  Frag vr[D / 16];
-};
-
-template <int D>
-__device__ __forceinline__ void load_page(const uint4 *kp, const uint4 *vp, int l, PageRegs<D> &r) {
-#pragma unroll
-  for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk) r.kr[sb][kk].v = stream_load(kp + sb * 2 * D + kk * 64 + l);
-#pragma unroll
-  for (int mb = 0; mb < D / 16; ++mb) r.vr[mb].v = stream_load(vp + mb * 64 + l);
-}
-
-// One 32-token page: S^T = K q^T, online softmax (exp2 domain), O^T += V^T P^T.
-template <int D>
-__device__ __forceinline__ void attend_page(const PageRegs<D> &r, const Frag (&qv)[D / 32], int tok_base,
-                                            int n_tok, int g, float scale_log2, float &m_run,
-                                            float &l_run, floatx4 (&acc)[D / 16]) {
-  constexpr int KK = D / 32, MB = D / 16;
-#ifdef TASKKV_EXP_NOCOMPUTE  // experiment only: touch the data, skip the math
-  unsigned x = 0;
-  for (int sb = 0; sb < 2; ++sb) for (int kk = 0; kk < KK; ++kk) x ^= r.kr[sb][kk].u.x ^ r.kr[sb][kk].u.y ^ r.kr[sb][kk].u.z ^ r.kr[sb][kk].u.w;
-  for (int mb = 0; mb < MB; ++mb) x ^= r.vr[mb].u.x ^ r.vr[mb].u.y ^ r.vr[mb].u.z ^ r.vr[mb].u.w;
-  acc[0][0] += __uint_as_float(x & 0x3fffffffu); m_run = 0.f; l_run = 1.f;
-  return;
-#endif
-  floatx4 s[2];
-#pragma unroll
-  for (int sb = 0; sb < 2; ++sb) {
-    s[sb] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      s[sb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.kr[sb][kk].b, qv[kk].b, s[sb], 0, 0, 0);
-  }
-  float sv[8];
-  float mloc = -INFINITY;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int t = tok_base + 16 * (e >> 2) + 4 * g + (e & 3);
-    sv[e] = t < n_tok ? s[e >> 2][e & 3] * scale_log2 : -INFINITY;
-    mloc = fmaxf(mloc, sv[e]);
-  }
-  mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-  mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-  const float m_new = fmaxf(m_run, mloc);  // finite: the page holds >= 1 token
-  const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-  float lsum = 0.f;
-  Frag ph, plo;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float p = __builtin_amdgcn_exp2f(sv[e] - m_new);
-    lsum += p;
-    const __bf16 hi = (__bf16)p;
-    ph.b[e] = hi;
-    plo.b[e] = (__bf16)(p - (float)hi);
-  }
-  l_run = l_run * alpha + lsum;
-  m_run = m_new;
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    acc[mb] *= alpha;
-    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, ph.b, acc[mb], 0, 0, 0);
-    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, plo.b, acc[mb], 0, 0, 0);
-  }
-}
 
 #ifndef TASKKV_DEC_PIPE
 #define TASKKV_DEC_PIPE 1
@@ -154,7 +31,7 @@ __device__ __forceinline__ void attend_page(const PageRegs<D> &r, const Frag (&q
 // depend only on the block index, so the first page is requested before the
 // block knows which unit it serves; later pages are requested one iteration
 // ahead of their use.
-template <int D>
+template <int D, bool NT>
 __global__ __launch_bounds__(256) void decode_bf16_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_new,
     const uint16_t *__restrict__ v_new, uint4 *kc, uint4 *vc, const int64_t *__restrict__ offsets,
@@ -168,7 +45,7 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
   const uint4 *kbase = kc + (size_t)tok0 * (D / 8);
   const uint4 *vbase = vc + (size_t)tok0 * (D / 8);
   PageRegs<D> ra, rb;
-  load_page<D>(kbase + (size_t)w * PSTRIDE, vbase + (size_t)w * PSTRIDE, l, ra);  // in bounds: whole chunks are allocated
+  load_page<D, NT>(kbase + (size_t)w * PSTRIDE, vbase + (size_t)w * PSTRIDE, l, ra);  // in bounds: whole chunks are allocated
 
   const int u = find_unit_fast(offsets, n_units, tok0, l);
   if (u < 0) return;
@@ -199,7 +76,7 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
     __threadfence_block();
     __syncthreads();
     if ((len_old - local0) / PAGE == w)
-      load_page<D>(kbase + (size_t)w * PSTRIDE, vbase + (size_t)w * PSTRIDE, l, ra);
+      load_page<D, NT>(kbase + (size_t)w * PSTRIDE, vbase + (size_t)w * PSTRIDE, l, ra);
   }
   const int n_tok = min(CHUNK, len - local0);
   const int n_pages = (n_tok + PAGE - 1) / PAGE;
@@ -223,17 +100,17 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
 #if TASKKV_DEC_PIPE
   for (int pg = w; pg < n_pages; pg += 8) {
     if (pg + 4 < n_pages)
-      load_page<D>(kbase + (size_t)(pg + 4) * PSTRIDE, vbase + (size_t)(pg + 4) * PSTRIDE, l, rb);
+      load_page<D, NT>(kbase + (size_t)(pg + 4) * PSTRIDE, vbase + (size_t)(pg + 4) * PSTRIDE, l, rb);
     attend_page<D>(ra, qv, pg * PAGE, n_tok, g, scale_log2, m_run, l_run, acc);
     if (pg + 4 < n_pages) {
       if (pg + 8 < n_pages)
-        load_page<D>(kbase + (size_t)(pg + 8) * PSTRIDE, vbase + (size_t)(pg + 8) * PSTRIDE, l, ra);
+        load_page<D, NT>(kbase + (size_t)(pg + 8) * PSTRIDE, vbase + (size_t)(pg + 8) * PSTRIDE, l, ra);
       attend_page<D>(rb, qv, (pg + 4) * PAGE, n_tok, g, scale_log2, m_run, l_run, acc);
     }
   }
 #else
   for (int pg = w; pg < n_pages; pg += 4) {
-    if (pg != w) load_page<D>(kbase + (size_t)pg * PSTRIDE, vbase + (size_t)pg * PSTRIDE, l, ra);
+    if (pg != w) load_page<D, NT>(kbase + (size_t)pg * PSTRIDE, vbase + (size_t)pg * PSTRIDE, l, ra);
     attend_page<D>(ra, qv, pg * PAGE, n_tok, g, scale_log2, m_run, l_run, acc);
   }
 #endif
@@ -463,10 +340,17 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
   auto kc = static_cast<uint4 *>(k_cache), vc = static_cast<uint4 *>(v_cache);
   const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
   if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
-  if (dm.D == 64)
-    decode_bf16_kernel<64><<<grid, block, 0, s>>>(qq, kn, vn, kc, vc, offsets, lens, eff_len, ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale_log2);
-  else
-    decode_bf16_kernel<128><<<grid, block, 0, s>>>(qq, kn, vn, kc, vc, offsets, lens, eff_len, ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale_log2);
+  const bool nt = (size_t)capacity * dm.D * 4 > NT_THRESHOLD_BYTES;
+#define TASKKV_LAUNCH_CHUNK(DD, NTV)                                                                   \
+  decode_bf16_kernel<DD, NTV><<<grid, block, 0, s>>>(qq, kn, vn, kc, vc, offsets, lens, eff_len,      \
+                                                     ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, \
+                                                     dm.G, scale_log2)
+  if (dm.D == 64) {
+    if (nt) TASKKV_LAUNCH_CHUNK(64, true); else TASKKV_LAUNCH_CHUNK(64, false);
+  } else {
+    if (nt) TASKKV_LAUNCH_CHUNK(128, true); else TASKKV_LAUNCH_CHUNK(128, false);
+  }
+#undef TASKKV_LAUNCH_CHUNK
   if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
   if (dm.D == 64)
     combine_kernel<64, true><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, eff_len, fused ? lens : nullptr, out, dm.Hq, dm.Hkv, dm.G);

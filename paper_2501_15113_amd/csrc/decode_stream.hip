@@ -1,0 +1,354 @@
+// Decode attention over the ragged bf16 cache, balanced streaming form.
+//
+// The decode step must read every kept K and V row once; nothing else matters
+// for its run time.  Measured on MI355X, HBM read bandwidth keeps rising with
+// the number of bytes in flight (about 6.2 TB/s at 256 KB per CU, 7 TB/s at
+// 512 KB per CU), and a kernel whose workgroups finish at different times
+// loses the tail.  Hence:
+//
+//   * the unit of work is the 32-token page; the T pages a step must read are
+//     dealt out evenly, wave i of W takes pages [i*T/W, (i+1)*T/W) of the
+//     concatenated page list of all units, so all waves finish together
+//     whatever the mix of 131072-token and 1028-token units is;
+//   * every wave keeps a ring of NP pages (16 KB each) in flight in its
+//     registers -- the VGPR file is the largest landing zone on the CU;
+//   * a wave whose range crosses unit boundaries writes one online-softmax
+//     partial (m, l, o) per unit it touched, slot = wave + unit, which is unique
+//     because both indices only grow along the page list; the combine kernel
+//     merges the slots of a unit in ascending order.
+//
+// Waves never synchronise with each other after the prologue.
+#include "decode_common.h"
+
+namespace taskkv {
+
+constexpr int MAXU = STREAM_MAX_UNITS;
+
+// Wave that owns page p when T pages are dealt to W waves.
+__device__ __forceinline__ int owner_of_page(int64_t p, int64_t T, int W) {
+  return (int)(((p + 1) * W - 1) / T);
+}
+
+template <int D, int NP, bool NT>
+__global__ __launch_bounds__(256) void decode_stream_kernel(
+    const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_new,
+    const uint16_t *__restrict__ v_new, uint4 *kc, uint4 *vc, const int64_t *__restrict__ offsets,
+    const int32_t *__restrict__ lens, int32_t *__restrict__ eff_len, int32_t *__restrict__ page_prefix,
+    int *__restrict__ d_err, float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ po,
+    int n_units, int Hq, int Hkv, int G, float scale_log2) {
+  constexpr int KK = D / 32, MB = D / 16, PSTRIDE = PAGE * (D / 8);  // uint4 per page
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 4, c = l & 15;
+  const int hg = blockIdx.y;
+  const bool want_app = k_new != nullptr;
+
+  // ---- prologue: page prefix over units, shared by the block's four waves
+  __shared__ int s_pref[MAXU + 1];
+  __shared__ int s_wtot[4];
+  const int upt = (n_units + 255) / 256;
+  const int first = tid * upt;
+  int sum = 0;
+  for (int i = 0; i < upt; ++i) {
+    const int u = first + i;
+    if (u < n_units) {
+      const int len_old = lens[u];
+      const int app = (want_app && len_old < (int)(offsets[u + 1] - offsets[u])) ? 1 : 0;
+      sum += (len_old + app + PAGE - 1) / PAGE;
+    }
+  }
+  int incl = sum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int t = __shfl_up(incl, off);
+    if (l >= off) incl += t;
+  }
+  if (l == 63) s_wtot[w] = incl;
+  __syncthreads();
+  int run = incl - sum;
+  for (int ww = 0; ww < w; ++ww) run += s_wtot[ww];
+  const bool publish = blockIdx.x == 0 && hg == 0;
+  for (int i = 0; i < upt; ++i) {
+    const int u = first + i;
+    if (u < n_units) {
+      const int len_old = lens[u];
+      const bool can = want_app && len_old < (int)(offsets[u + 1] - offsets[u]);
+      const int len = len_old + (can ? 1 : 0);
+      s_pref[u] = run;
+      if (publish) {
+        eff_len[u] = len;
+        page_prefix[u] = run;
+        if (want_app && !can) atomicOr(d_err, 1);
+      }
+      run += (len + PAGE - 1) / PAGE;
+    }
+  }
+  if (tid == 255) {
+    s_pref[n_units] = run;
+    if (publish) page_prefix[n_units] = run;
+  }
+  __syncthreads();
+  const int64_t T = s_pref[n_units];
+  const int W = gridDim.x * 4;
+  const int wid = blockIdx.x * 4 + w;
+  const int p0 = (int)((int64_t)wid * T / W), p1 = (int)((int64_t)(wid + 1) * T / W);
+  if (p0 >= p1) return;
+
+  // first unit of my range: largest u with s_pref[u] <= p0
+  int u0;
+  {
+    int lo = 0, hi = n_units - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (s_pref[mid] <= p0) lo = mid; else hi = mid - 1;
+    }
+    u0 = lo;
+  }
+
+  // ---- fused append: the wave that owns the page receiving a unit's new token
+  // stores it before requesting any page (it is the only reader of that page).
+  if (want_app) {
+    uint16_t *kc16 = reinterpret_cast<uint16_t *>(kc), *vc16 = reinterpret_cast<uint16_t *>(vc);
+    for (int u = u0; u < n_units && s_pref[u] < p1; ++u) {
+      const int len_old = lens[u];
+      const int64_t base = offsets[u];
+      if (len_old >= (int)(offsets[u + 1] - base)) continue;
+      const int ap = s_pref[u] + len_old / PAGE;
+      if (ap < p0 || ap >= p1) continue;
+      const int64_t page = base + (len_old / PAGE) * PAGE;
+      const int t32 = len_old % PAGE, sb = t32 >> 4, r = t32 & 15;
+      const int ga = (t32 & 15) >> 2, ea = 4 * (t32 >> 4) + (t32 & 3);
+      for (int e = l; e < D; e += 64) {
+        kc16[((size_t)page + sb * 16) * D + (size_t)((e >> 3) * 16 + r) * 8 + (e & 7)] = k_new[(size_t)u * D + e];
+        vc16[(size_t)page * D + (size_t)((e >> 4) * 64 + ga * 16 + (e & 15)) * 8 + ea] = v_new[(size_t)u * D + e];
+      }
+    }
+    __threadfence_block();
+  }
+
+  // ---- ring of NP pages in flight
+  PageRegs<D> ring[NP];
+  int u_ld = u0;           // unit of the next page to request
+  auto request = [&](int gp, PageRegs<D> &r) {
+    while (gp >= s_pref[u_ld + 1]) ++u_ld;
+    const size_t tok = (size_t)offsets[u_ld] + (size_t)(gp - s_pref[u_ld]) * PAGE;
+    load_page<D, NT>(kc + tok * (D / 8), vc + tok * (D / 8), l, r);
+  };
+#pragma unroll
+  for (int s = 0; s < NP; ++s)
+    if (p0 + s < p1) request(p0 + s, ring[s]);
+
+  int u_at = -1;           // unit being accumulated
+  int n_valid = 0;         // its token count
+  int pref_at = 0, pref_next = 0;
+  Frag qv[KK];
+  float m_run = -INFINITY, l_run = 0.f;
+  floatx4 acc[MB];
+  const int slot_h = hg * 16 + c;
+
+  auto flush = [&]() {
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (slot_h < G) {
+      const size_t pi = ((size_t)wid + u_at) * G + slot_h;
+      if (g == 0) { pm[pi] = m_run; pl[pi] = l_tot; }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+        *reinterpret_cast<floatx4 *>(po + pi * D + 16 * mb + 4 * g) = acc[mb];
+    }
+  };
+  auto enter_unit = [&](int gp) {
+    int u = u_at < 0 ? u0 : u_at;
+    while (gp >= s_pref[u + 1]) ++u;
+    u_at = u;
+    pref_at = s_pref[u];
+    pref_next = s_pref[u + 1];
+    const int len_old = lens[u];
+    const bool can = want_app && len_old < (int)(offsets[u + 1] - offsets[u]);
+    n_valid = len_old + (can ? 1 : 0);
+    const int b = u / Hkv, h = u % Hkv;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qv[kk].u = make_uint4(0, 0, 0, 0);
+    if (slot_h < G) {
+      const uint16_t *qp = q + ((size_t)b * Hq + (size_t)h * G + slot_h) * D;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) qv[kk].u = *reinterpret_cast<const uint4 *>(qp + 32 * kk + 8 * g);
+    }
+    m_run = -INFINITY;
+    l_run = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb] = floatx4{0.f, 0.f, 0.f, 0.f};
+  };
+
+  for (int gp0 = p0; gp0 < p1; gp0 += NP) {
+#pragma unroll
+    for (int s = 0; s < NP; ++s) {
+      const int gp = gp0 + s;
+      if (gp < p1) {
+        if (u_at < 0 || gp >= pref_next) {
+          if (u_at >= 0) flush();
+          enter_unit(gp);
+        }
+        attend_page<D>(ring[s], qv, (gp - pref_at) * PAGE, n_valid, g, scale_log2, m_run, l_run, acc);
+        if (gp + NP < p1) request(gp + NP, ring[s]);
+      }
+    }
+  }
+  flush();
+}
+
+// Merge the partials of one (batch, query head): slots wave + unit for the waves
+// whose page ranges meet the unit, ascending.  Same lane layout and fixed
+// summation order as the chunk-grid combine.
+template <int D>
+__global__ __launch_bounds__(1024) void combine_stream_kernel(
+    const float *__restrict__ pm, const float *__restrict__ pl, const float *__restrict__ po,
+    const int32_t *__restrict__ page_prefix, const int32_t *__restrict__ eff_len,
+    int32_t *__restrict__ lens_out, float *__restrict__ out, int n_units, int Hq, int Hkv, int G, int W) {
+  constexpr int DL = D / 4, NCL = 1024 / DL, UN = 4;
+  const int bq = blockIdx.x, tid = threadIdx.x;
+  const int b = bq / Hq, hq = bq % Hq, h = hq / G, slot = hq % G;
+  const int u = b * Hkv + h;
+  if (lens_out != nullptr && slot == 0 && tid == 0) lens_out[u] = eff_len[u];
+  const int64_t T = page_prefix[n_units];
+  const int pa = page_prefix[u], pb = page_prefix[u + 1];
+  if (pa >= pb) {
+    if (tid < D) out[(size_t)bq * D + tid] = 0.f;
+    return;
+  }
+  const int wa = owner_of_page(pa, T, W), wb = owner_of_page(pb - 1, T, W);
+  const int nparts = wb - wa + 1;
+  const size_t slot0 = (size_t)wa + u;
+  const int dl = tid % DL, cl = tid / DL;
+  __shared__ float red_m[16];
+  __shared__ float4 red_o[NCL][DL];
+  __shared__ float red_l[NCL];
+  // a wave between the first and last owner wrote a partial unless its page range is empty
+  auto has_pages = [&](int i) {
+    const int64_t wv = wa + i;
+    return i < nparts && wv * T / W < (wv + 1) * T / W;
+  };
+  float M = -INFINITY;
+  for (int i = tid; i < nparts; i += 1024)
+    if (has_pages(i)) M = fmaxf(M, pm[(slot0 + i) * G + slot]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+  if ((tid & 63) == 0) red_m[tid >> 6] = M;
+  __syncthreads();
+  M = red_m[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) M = fmaxf(M, red_m[r]);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float lacc = 0.f;
+  for (int i0 = cl; i0 < nparts; i0 += NCL * UN) {
+    float4 o[UN];
+    float pmv[UN], plv[UN];
+#pragma unroll
+    for (int r = 0; r < UN; ++r) {
+      const int i = i0 + r * NCL;
+      const bool ok = has_pages(i);
+      const size_t pi = (slot0 + (ok ? i : 0)) * G + slot;
+      pmv[r] = ok ? pm[pi] : -INFINITY;
+      plv[r] = ok ? pl[pi] : 0.f;
+      o[r] = ok ? *reinterpret_cast<const float4 *>(po + pi * D + 4 * dl) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int r = 0; r < UN; ++r) {
+      const float wgt = __builtin_amdgcn_exp2f(pmv[r] - M);
+      acc.x += o[r].x * wgt; acc.y += o[r].y * wgt; acc.z += o[r].z * wgt; acc.w += o[r].w * wgt;
+      lacc += plv[r] * wgt;
+    }
+  }
+  red_o[cl][dl] = acc;
+  if (dl == 0) red_l[cl] = lacc;
+  __syncthreads();
+  if (tid < DL) {
+    float4 o = red_o[0][tid];
+    float L = red_l[0];
+#pragma unroll
+    for (int cc = 1; cc < NCL; ++cc) {
+      const float4 x = red_o[cc][tid];
+      o.x += x.x; o.y += x.y; o.z += x.z; o.w += x.w;
+      L += red_l[cc];
+    }
+    const float inv = 1.f / L;
+    *reinterpret_cast<float4 *>(out + (size_t)bq * D + 4 * tid) = make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+  }
+}
+
+// Ring depth.  A wave can have at most 63 vector memory instructions in flight
+// (the hardware counter is 6 bits) and a page is 16 of them, so rings deeper
+// than 3 pages cannot be kept full; 2 pages at two waves per SIMD measured
+// fastest (deeper rings drop to one wave per SIMD).
+#ifndef TASKKV_STREAM_NP
+#define TASKKV_STREAM_NP 2
+#endif
+// Fewest pages worth giving a wave: below this the launch is latency bound and
+// extra waves only add partials for the combine kernel to read.
+#ifndef TASKKV_STREAM_MIN_PAGES
+#define TASKKV_STREAM_MIN_PAGES 4
+#endif
+
+template <int D, bool NT>
+static void run_stream(taskkv_ctx *ctx, const Dims &dm, const uint16_t *q, const uint16_t *kn,
+                       const uint16_t *vn, uint4 *kc, uint4 *vc, const int64_t *offsets, int32_t *lens,
+                       int32_t *eff_len, int32_t *page_prefix, float *pm, float *pl, float *po,
+                       float *out, int n_wg, bool fused, hipStream_t s) {
+  const dim3 grid(n_wg, (dm.G + 15) / 16), block(256);
+  const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
+  const bool prof = ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS;
+  if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
+  decode_stream_kernel<D, TASKKV_STREAM_NP, NT><<<grid, block, 0, s>>>(
+      q, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, ctx->d_err, pm, pl, po, dm.units, dm.Hq,
+      dm.Hkv, dm.G, scale_log2);
+  if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
+  combine_stream_kernel<D><<<dim3(dm.B * dm.Hq), dim3(1024), 0, s>>>(
+      pm, pl, po, page_prefix, eff_len, fused ? lens : nullptr, out, dm.units, dm.Hq, dm.Hkv, dm.G, n_wg * 4);
+}
+
+int launch_decode_stream(taskkv_ctx *ctx, const Dims &dm, const void *q, const void *k_new,
+                         const void *v_new, void *k_cache, void *v_cache, int64_t capacity,
+                         const int64_t *offsets, int32_t *lens, int32_t *eff_len, int32_t *page_prefix,
+                         float *pm, float *pl, float *po, float *out, hipStream_t s) {
+  const bool nt = (size_t)capacity * dm.D * 4 > NT_THRESHOLD_BYTES;
+  const int variant = (dm.D == 64 ? 0 : 2) + (nt ? 1 : 0);
+  if (!ctx->stream_wg[variant]) {
+    // as many blocks as fit on the device at once, so that every wave is resident
+    int per_cu = 0;
+    hipError_t e;
+    if (dm.D == 64)
+      e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, TASKKV_STREAM_NP, true>, 256, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, TASKKV_STREAM_NP, false>, 256, 0);
+    else
+      e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<128, TASKKV_STREAM_NP, true>, 256, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<128, TASKKV_STREAM_NP, false>, 256, 0);
+    if (e != hipSuccess || per_cu < 1) return TASKKV_EHIP;
+    int n = ctx->n_cu * per_cu;
+    ctx->stream_wg[variant] = n > STREAM_MAX_WG ? STREAM_MAX_WG : n;
+  }
+  int n_wg = ctx->stream_wg[variant];
+  {
+    // capacity / PAGE bounds the pages of a step from above
+    const int64_t want = (capacity / PAGE + 4 * TASKKV_STREAM_MIN_PAGES - 1) / (4 * TASKKV_STREAM_MIN_PAGES);
+    if (want < n_wg) n_wg = want < 1 ? 1 : (int)want;
+  }
+  // The append is fused when one head slice covers the query group; otherwise
+  // it runs as its own kernel first.
+  const bool fused = k_new != nullptr && dm.G <= 16;
+  if (k_new && !fused) {
+    int rc = launch_append(dm, TASKKV_BF16, k_new, v_new, k_cache, v_cache, offsets, lens, ctx->d_err, s);
+    if (rc) return rc;
+  }
+  auto qq = static_cast<const uint16_t *>(q);
+  auto kn = fused ? static_cast<const uint16_t *>(k_new) : nullptr;
+  auto vn = fused ? static_cast<const uint16_t *>(v_new) : nullptr;
+  auto kc = static_cast<uint4 *>(k_cache), vc = static_cast<uint4 *>(v_cache);
+  if (dm.D == 64) {
+    if (nt) run_stream<64, true>(ctx, dm, qq, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, pm, pl, po, out, n_wg, fused, s);
+    else run_stream<64, false>(ctx, dm, qq, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, pm, pl, po, out, n_wg, fused, s);
+  } else {
+    if (nt) run_stream<128, true>(ctx, dm, qq, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, pm, pl, po, out, n_wg, fused, s);
+    else run_stream<128, false>(ctx, dm, qq, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, pm, pl, po, out, n_wg, fused, s);
+  }
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace taskkv

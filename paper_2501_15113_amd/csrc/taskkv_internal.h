@@ -13,6 +13,8 @@ constexpr int PAGE = 32;                    // tokens per matrix-core page of th
 constexpr int SCORE_TILE = 256;             // columns (keys) per scoring tile
 constexpr int ROW_BLK = 8;                  // window rows handled together by the f64 scorer
 constexpr int MAX_PROFILE_EVENTS = 4096;
+constexpr int STREAM_MAX_UNITS = 4096;  // units the streaming decode kernel can index in LDS
+constexpr int STREAM_MAX_WG = 1024;     // workgroups (4 waves each) it is ever launched with
 
 // Resolved problem sizes handed to kernels by value.
 struct Dims {
@@ -38,6 +40,8 @@ struct taskkv_ctx {
   hipEvent_t ev_start[taskkv::MAX_PROFILE_EVENTS];
   hipEvent_t ev_stop[taskkv::MAX_PROFILE_EVENTS];
   int events_created;
+  int n_cu;           // compute units of the device
+  int stream_wg[4];   // cached launch width of the streaming decode kernel per (D, NT) variant, 0 = unknown
 };
 
 namespace taskkv {
@@ -85,6 +89,11 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
                   const void *v_new, void *k_cache, void *v_cache, int64_t capacity,
                   const int64_t *offsets, int32_t *lens, int32_t *eff_len, float *pm, float *pl,
                   float *po, float *out, hipStream_t s);
+
+int launch_decode_stream(taskkv_ctx *ctx, const Dims &dm, const void *q, const void *k_new,
+                         const void *v_new, void *k_cache, void *v_cache, int64_t capacity,
+                         const int64_t *offsets, int32_t *lens, int32_t *eff_len, int32_t *page_prefix,
+                         float *pm, float *pl, float *po, float *out, hipStream_t s);
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? TASKKV_OK : TASKKV_EHIP; }
 
