@@ -27,7 +27,7 @@ static bool resolve(const taskkv_layer_cfg *c, Dims &d) {
   d.k = (int)(c->n_middle < middle ? c->n_middle : middle);
   d.n_het = c->n_hetero; d.add_centre = c->add_centre_head ? 1 : 0; d.pool = c->pool_kernel;
   d.R = d.G * d.L;
-  d.Rpad = (d.R + ROW_BLK - 1) / ROW_BLK * ROW_BLK;
+  d.Rpad = (d.R + 31) / 32 * 32;
   if (d.G > 64 || d.Rpad > 1024) return false;
   if ((int64_t)d.B * d.Hkv > 65535) return false;
   d.units = d.B * d.Hkv;
@@ -60,10 +60,25 @@ static int64_t cache_tokens(const Dims &d, int reserve) {
 
 static size_t al(size_t b) { return (b + 255) & ~size_t(255); }
 
-static size_t ws_separate(const Dims &d) {
+// keys are scored in 256-key chunks; a block takes this many of them
+static int score_chunks_per_wg(const Dims &d) {
+  const int64_t n_chunks = (d.N + 255) / 256;
+  int64_t t = (n_chunks * d.units + 4095) / 4096;
+  if (t < 1) t = 1;
+  if (t > 16) t = 16;
+  return (int)t;
+}
+
+// partial row-statistics records per unit, whichever scorer runs
+static int score_parts(const Dims &d) {
+  if (score_mfma64_supported(d)) return score_mfma64_parts(d, score_chunks_per_wg(d));
   const int tpw = score_tiles_per_wg(d);
   const int n_tiles = (d.N + SCORE_TILE - 1) / SCORE_TILE;
-  const int n_chunks = (n_tiles + tpw - 1) / tpw;
+  return (n_tiles + tpw - 1) / tpw;
+}
+
+static size_t ws_separate(const Dims &d) {
+  const int n_chunks = score_parts(d);
   size_t b = 0;
   b += al((size_t)d.units * d.Rpad * d.D * sizeof(double));           // window rows in fp64
   b += al((size_t)d.units * n_chunks * d.Rpad * 2 * sizeof(double));  // per-chunk row stats
@@ -194,16 +209,19 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   if (!ctx || !resolve(cfg, d)) return TASKKV_EINVAL;
   if (!q_win || !k || !v || !scores || !sem_vec || !dist || !hetero_mask) return TASKKV_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const int tpw = score_tiles_per_wg(d);
-  const int n_tiles = (d.N + SCORE_TILE - 1) / SCORE_TILE;
-  const int n_chunks = (n_tiles + tpw - 1) / tpw;
+  const int n_parts = score_parts(d);
   Carver cv(ctx->ws, ctx->ws_bytes);
   double *qd = cv.take<double>((size_t)d.units * d.Rpad * d.D);
-  double *part = cv.take<double>((size_t)d.units * n_chunks * d.Rpad * 2);
+  double *part = cv.take<double>((size_t)d.units * n_parts * d.Rpad * 2);
   double *stats = cv.take<double>((size_t)d.units * d.Rpad * 2);
   int32_t *top_idx = cv.take<int32_t>((size_t)d.units * d.T);
   if (!cv.ok) return TASKKV_EWORKSPACE;
-  int rc = launch_scores_f64(d, cfg->dtype, q_win, k, qd, part, stats, scores, tpw, s);
+  int rc = launch_q_to_f64(d, cfg->dtype, q_win, qd, s);
+  if (rc) return rc;
+  if (score_mfma64_supported(d))
+    rc = launch_scores_mfma64(d, cfg->dtype, k, qd, part, stats, scores, score_chunks_per_wg(d), s);
+  else
+    rc = launch_scores_f64(d, cfg->dtype, k, qd, part, stats, scores, score_tiles_per_wg(d), s);
   if (rc) return rc;
   rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, top_idx, d.T, 0, s);
   if (rc) return rc;

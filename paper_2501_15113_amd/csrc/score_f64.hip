@@ -1,4 +1,5 @@
-// Window scores in fp64 (paper Sec. 4.1, Eq. 12-13): the exact scorer.
+// Window scores in fp64 on the vector ALUs (paper Sec. 4.1, Eq. 12-13): the
+// fallback for window/group sizes the matrix-core scorer does not cover.
 //
 // Two passes over K.  Pass "stats" finds, for every window row, the row maximum
 // and the softmax denominator; pass "mean" recomputes the logits and
@@ -173,10 +174,8 @@ __global__ void merge_stats_kernel(const double *__restrict__ part, double *__re
 }
 
 template <typename T, int D>
-static int run_scores(const Dims &dm, const T *q_win, const T *k, double *qd, double *part,
-                      double *stats, double *scores, int tiles_per_wg, hipStream_t s) {
-  const size_t total = (size_t)dm.units * dm.Rpad * dm.D;
-  q_to_f64_kernel<T><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(q_win, qd, dm);
+static int run_scores(const Dims &dm, const T *k, double *qd, double *part, double *stats,
+                      double *scores, int tiles_per_wg, hipStream_t s) {
   const int n_tiles = (dm.N + SCORE_TILE - 1) / SCORE_TILE;
   const int n_chunks = (n_tiles + tiles_per_wg - 1) / tiles_per_wg;
   dim3 grid(n_chunks, dm.units);
@@ -186,17 +185,31 @@ static int run_scores(const Dims &dm, const T *q_win, const T *k, double *qd, do
   return hip_ok(hipGetLastError());
 }
 
-int launch_scores_f64(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd,
-                      double *stat_part, double *stats, double *scores, int tiles_per_wg,
-                      hipStream_t s) {
+int launch_q_to_f64(const Dims &dm, int dtype, const void *q_win, double *qd, hipStream_t s) {
+  const size_t total = (size_t)dm.units * dm.Rpad * dm.D;
+  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (dtype == TASKKV_F32)
+    q_to_f64_kernel<float><<<grid, block, 0, s>>>(static_cast<const float *>(q_win), qd, dm);
+  else
+    q_to_f64_kernel<uint16_t><<<grid, block, 0, s>>>(static_cast<const uint16_t *>(q_win), qd, dm);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_merge_stats(const double *part, double *stats, int units, int Rpad, int n_parts, hipStream_t s) {
+  merge_stats_kernel<<<dim3(units), dim3(256), 0, s>>>(part, stats, Rpad, n_parts);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_scores_f64(const Dims &dm, int dtype, const void *k, double *qd, double *stat_part,
+                      double *stats, double *scores, int tiles_per_wg, hipStream_t s) {
   if (dtype == TASKKV_F32) {
-    auto q = static_cast<const float *>(q_win), kk = static_cast<const float *>(k);
-    return dm.D == 64 ? run_scores<float, 64>(dm, q, kk, qd, stat_part, stats, scores, tiles_per_wg, s)
-                      : run_scores<float, 128>(dm, q, kk, qd, stat_part, stats, scores, tiles_per_wg, s);
+    auto kk = static_cast<const float *>(k);
+    return dm.D == 64 ? run_scores<float, 64>(dm, kk, qd, stat_part, stats, scores, tiles_per_wg, s)
+                      : run_scores<float, 128>(dm, kk, qd, stat_part, stats, scores, tiles_per_wg, s);
   }
-  auto q = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
-  return dm.D == 64 ? run_scores<uint16_t, 64>(dm, q, kk, qd, stat_part, stats, scores, tiles_per_wg, s)
-                    : run_scores<uint16_t, 128>(dm, q, kk, qd, stat_part, stats, scores, tiles_per_wg, s);
+  auto kk = static_cast<const uint16_t *>(k);
+  return dm.D == 64 ? run_scores<uint16_t, 64>(dm, kk, qd, stat_part, stats, scores, tiles_per_wg, s)
+                    : run_scores<uint16_t, 128>(dm, kk, qd, stat_part, stats, scores, tiles_per_wg, s);
 }
 
 }  // namespace taskkv

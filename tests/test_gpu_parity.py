@@ -96,6 +96,7 @@ SWEEP = [
     dict(obs_window=1, ctx_len=520),
     dict(obs_window=50, ctx_len=50, n_sink=2, n_recent=3, n_middle=4, top_t=10),   # L = N
     dict(batch=3, ctx_len=33, n_sink=1, n_recent=2, n_middle=3, obs_window=5, top_t=7),
+    dict(n_q_heads=40, n_kv_heads=2, ctx_len=600, obs_window=32, batch=1),   # 640 window rows: vector-ALU scorer
     dict(n_sink=0, n_recent=0, n_middle=0, ctx_len=700, n_hetero=1),   # the other heads keep nothing
     dict(ctx_len=1536, n_sink=0, n_recent=480, n_middle=32, decode_steps=4),   # append crosses a chunk edge
 ]
@@ -103,7 +104,8 @@ SWEEP = [
 
 @pytest.mark.parametrize("i", range(len(SWEEP)))
 def test_small_sweep(i):
-    run_layer(small_workload(name=f"sweep{i}", wid=100 + i, **SWEEP[i]), check_batches=(0, 1))
+    wl = small_workload(name=f"sweep{i}", wid=100 + i, **SWEEP[i])
+    run_layer(wl, check_batches=tuple(range(min(2, wl.batch))))
 
 
 def test_softmax_scale_override():
