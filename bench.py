@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the decode attention kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel); None until measured for the
 # default workload -- see profiles/.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {"cfg5": 572.9e6}  # profiles/decode_stream_kernel_cfg5_hbm_traffic.txt
 
 
 def n_long_units(wl, n_het):
@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5 (default cfg5: largest context, "
                     "the load-imbalance stress case)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 1 GiB device copies (a kernel of known traffic against which "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)")
@@ -185,6 +188,13 @@ def main():
                      "avg_kernel_us": round(avg_kernel_ms * 1e3, 3), "launches_timed": int(launches),
                      "value_with_kernel_events": round(pass_bytes * args.steps / (dec_ms_p * 1e-3) / 1e9, 1)},
     }
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, layers)
     ctx.close()
