@@ -26,6 +26,8 @@ namespace taskkv {
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 constexpr int SKC = 256;   // keys per chunk
+constexpr int SNW = 8;     // waves per block: with <= 8 row pairs every pair streams the same K tiles
+                           // at the same time, so K comes from HBM once per pass
 constexpr int MAXP = 16;   // row pairs (32 rows each) one block can hold column sums for
 
 template <int NKK>
@@ -70,7 +72,7 @@ template <> struct RawCount<float> { static constexpr int per16B = 4; };
 // MODE 0: row statistics -> part[unit][n_parts][Rpad][2], n_parts = gridDim.x * ksplit.
 // MODE 1: column mean -> scores[unit][N] from stats[unit][Rpad][2].
 template <typename T, int D, int MODE>
-__global__ __launch_bounds__(256) void score_mfma64_kernel(const T *__restrict__ k,
+__global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restrict__ k,
                                                            const double *__restrict__ qd,
                                                            const double *__restrict__ stats,
                                                            double *__restrict__ part,
@@ -81,7 +83,7 @@ __global__ __launch_bounds__(256) void score_mfma64_kernel(const T *__restrict__
   const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 15, kq = l >> 4;
   const int N = dm.N, L = dm.L, R = dm.R, Rpad = dm.Rpad;
   const int n_pairs = Rpad / 32;
-  const int ksplit = n_pairs >= 4 ? 1 : 4 / n_pairs;
+  const int ksplit = n_pairs >= SNW ? 1 : SNW / n_pairs;
   const int n_items = n_pairs * ksplit;
   const int sub = SKC / ksplit;  // keys per slice of a chunk
   const T *kb = k + (size_t)unit * N * D;
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(256) void score_mfma64_kernel(const T *__restrict__
 
   if (MODE == 0) {
     const int n_parts = gridDim.x * ksplit;
-    for (int item = w; item < n_items; item += 4) {
+    for (int item = w; item < n_items; item += SNW) {
       const int pair = item % n_pairs, ks = item / n_pairs;
       load_a(pair);
       double m[8], ls[8];
@@ -142,13 +144,12 @@ __global__ __launch_bounds__(256) void score_mfma64_kernel(const T *__restrict__
             const int row = 32 * pair + 16 * (s >> 2) + 4 * (s & 3) + kq;
             const bool vis = valid && row < R && j <= N - L + row % L;
             if (vis) {
+              // one exponential per logit, no divergent branch: e = exp(-|t - m|)
               const double t = acc[s >> 2][s & 3] * scale;
-              if (t > m[s]) {
-                ls[s] = ls[s] * exp(m[s] - t) + 1.0;
-                m[s] = t;
-              } else {
-                ls[s] += exp(t - m[s]);
-              }
+              const bool up = t > m[s];
+              const double e = exp(up ? m[s] - t : t - m[s]);
+              ls[s] = up ? ls[s] * e + 1.0 : ls[s] + e;
+              m[s] = up ? t : m[s];
             }
           }
         }
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(256) void score_mfma64_kernel(const T *__restrict__
     for (int ch = 0; ch < chunks_per_wg; ++ch) {
       const int jchunk = (blockIdx.x * chunks_per_wg + ch) * SKC;
       if (jchunk >= N) break;
-      for (int item = w; item < n_items; item += 4) {
+      for (int item = w; item < n_items; item += SNW) {
         const int pair = item % n_pairs, ks = item / n_pairs;
         load_a(pair);
         double mr[8], inv[8];
@@ -224,7 +225,7 @@ int score_mfma64_parts(const Dims &dm, int chunks_per_wg) {
   const int n_chunks = (dm.N + SKC - 1) / SKC;
   const int n_wg = (n_chunks + chunks_per_wg - 1) / chunks_per_wg;
   const int n_pairs = dm.Rpad / 32;
-  return n_wg * (n_pairs >= 4 ? 1 : 4 / n_pairs);
+  return n_wg * (n_pairs >= SNW ? 1 : SNW / n_pairs);
 }
 
 bool score_mfma64_supported(const Dims &dm) { return dm.Rpad % 32 == 0 && dm.Rpad / 32 <= MAXP; }
@@ -233,7 +234,7 @@ template <typename T, int D>
 static int run_mfma64(const Dims &dm, const T *k, const double *qd, double *part, double *stats,
                       double *scores, int chunks_per_wg, hipStream_t s) {
   const int n_chunks = (dm.N + SKC - 1) / SKC;
-  const dim3 grid((n_chunks + chunks_per_wg - 1) / chunks_per_wg, dm.units), block(256);
+  const dim3 grid((n_chunks + chunks_per_wg - 1) / chunks_per_wg, dm.units), block(64 * SNW);
   score_mfma64_kernel<T, D, 0><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, chunks_per_wg);
   launch_merge_stats(part, stats, dm.units, dm.Rpad, score_mfma64_parts(dm, chunks_per_wg), s);
   score_mfma64_kernel<T, D, 1><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, chunks_per_wg);
