@@ -26,9 +26,11 @@ static bool resolve(const taskkv_layer_cfg *c, Dims &d) {
   const int64_t middle = d.keep_all ? 0 : (int64_t)d.N - d.s1 - d.s2;
   d.k = (int)(c->n_middle < middle ? c->n_middle : middle);
   d.n_het = c->n_hetero; d.add_centre = c->add_centre_head ? 1 : 0; d.pool = c->pool_kernel;
-  d.R = d.G * d.L;
-  d.Rpad = (d.R + 31) / 32 * 32;
-  if (d.G > 64 || d.Rpad > 1024) return false;
+  if (d.G > 64 || (int64_t)d.G * d.L > (int64_t)1 << 30) return false;
+  d.Rtot = d.G * d.L;
+  d.R = d.Rtot;
+  d.Rpad = score_rows_padded(d);
+  d.row0 = 0; d.n_keys = d.N; d.accumulate = 0;
   if ((int64_t)d.B * d.Hkv > 65535) return false;
   d.units = d.B * d.Hkv;
   const int64_t stride = (int64_t)d.s1 + c->n_middle + d.s2;
@@ -36,14 +38,6 @@ static bool resolve(const taskkv_layer_cfg *c, Dims &d) {
   d.row_stride = (int)stride;
   d.scale = c->softmax_scale > 0.f ? (double)c->softmax_scale : 1.0 / sqrt((double)d.D);
   return true;
-}
-
-static int score_tiles_per_wg(const Dims &d) {
-  const int64_t n_tiles = (d.N + SCORE_TILE - 1) / SCORE_TILE;
-  int64_t t = (n_tiles * d.units + 4095) / 4096;
-  if (t < 1) t = 1;
-  if (t > 16) t = 16;
-  return (int)t;
 }
 
 static int64_t cache_tokens(const Dims &d, int reserve) {
@@ -59,23 +53,6 @@ static int64_t cache_tokens(const Dims &d, int reserve) {
 }
 
 static size_t al(size_t b) { return (b + 255) & ~size_t(255); }
-
-// keys are scored in 256-key chunks; a block takes this many of them
-static int score_chunks_per_wg(const Dims &d) {
-  const int64_t n_chunks = (d.N + 255) / 256;
-  int64_t t = (n_chunks * d.units + 4095) / 4096;
-  if (t < 1) t = 1;
-  if (t > 16) t = 16;
-  return (int)t;
-}
-
-// partial row-statistics records per unit, whichever scorer runs
-static int score_parts(const Dims &d) {
-  if (score_mfma64_supported(d)) return score_mfma64_parts(d, score_chunks_per_wg(d));
-  const int tpw = score_tiles_per_wg(d);
-  const int n_tiles = (d.N + SCORE_TILE - 1) / SCORE_TILE;
-  return (n_tiles + tpw - 1) / tpw;
-}
 
 static size_t ws_separate(const Dims &d) {
   const int n_chunks = score_parts(d);
@@ -216,12 +193,7 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   double *stats = cv.take<double>((size_t)d.units * d.Rpad * 2);
   int32_t *top_idx = cv.take<int32_t>((size_t)d.units * d.T);
   if (!cv.ok) return TASKKV_EWORKSPACE;
-  int rc = launch_q_to_f64(d, cfg->dtype, q_win, qd, s);
-  if (rc) return rc;
-  if (score_mfma64_supported(d))
-    rc = launch_scores_mfma64(d, cfg->dtype, k, qd, part, stats, scores, score_chunks_per_wg(d), s);
-  else
-    rc = launch_scores_f64(d, cfg->dtype, k, qd, part, stats, scores, score_tiles_per_wg(d), s);
+  int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, s);
   if (rc) return rc;
   rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, top_idx, d.T, 0, s);
   if (rc) return rc;

@@ -210,13 +210,34 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(
     if (lane == 0) { sm[hh] = mx; sl[hh] = sum; }
   }
   __syncthreads();
-  for (int idx = tid; idx < nh * D; idx += 256) {
-    const int hh = idx / D, dd = idx % D;
-    float o = 0.f;
-    for (int t = 0; t < n_tok; ++t) o = fmaf(ps[hh][t], vc[((size_t)tok0 + t) * D + dd], o);
-    const size_t pi = (size_t)chunk * G + hg * 16 + hh;
-    po[pi * D + dd] = o;
-    if (dd == 0) { pm[pi] = sm[hh]; pl[pi] = sl[hh]; }
+  // p.V: NTL token lanes x D/4 channel lanes; every thread walks its tokens with
+  // float4 loads of V (8 in flight), then the token lanes are added in lane order.
+  constexpr int DL = D / 4, NTL = 256 / DL;
+  __shared__ float4 red[NTL][DL];
+  const int dl = tid % DL, tl = tid / DL;
+  for (int hh = 0; hh < nh; ++hh) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+    for (int t = tl; t < n_tok; t += NTL) {
+      const float p = ps[hh][t];
+      const float4 vv = *reinterpret_cast<const float4 *>(vc + ((size_t)tok0 + t) * D + 4 * dl);
+      acc.x = fmaf(p, vv.x, acc.x); acc.y = fmaf(p, vv.y, acc.y);
+      acc.z = fmaf(p, vv.z, acc.z); acc.w = fmaf(p, vv.w, acc.w);
+    }
+    red[tl][dl] = acc;
+    __syncthreads();
+    if (tid < DL) {
+      float4 o = red[0][tid];
+#pragma unroll
+      for (int r = 1; r < NTL; ++r) {
+        const float4 x = red[r][tid];
+        o.x += x.x; o.y += x.y; o.z += x.z; o.w += x.w;
+      }
+      const size_t pi = (size_t)chunk * G + hg * 16 + hh;
+      *reinterpret_cast<float4 *>(po + pi * D + 4 * tid) = o;
+      if (tid == 0) { pm[pi] = sm[hh]; pl[pi] = sl[hh]; }
+    }
+    __syncthreads();
   }
 }
 

@@ -1,7 +1,9 @@
 // Window scores in fp64 on the matrix cores (paper Sec. 4.1, Eq. 12-13).
 //
-// Same two passes as the vector-ALU scorer (row statistics, then column mean),
-// same arithmetic (every product, sum and exponential in fp64), but the
+// Two passes over K.  Pass 0 finds, for every window row, the row maximum and
+// the softmax denominator; pass 1 recomputes the logits and accumulates the
+// column mean C.  Re-reading K (2*d bytes per key) is cheaper than spilling the
+// G*L logits per key.  Every product, sum and exponential is fp64; the
 // Q.K^T contraction runs on v_mfma_f64_16x16x4_f64: a wave keeps two 16-row
 // blocks of the window in registers as A operands (fp64, 2 * d/4 values per
 // lane) and streams 16-key tiles of K as B operand, converting bf16/fp32 to
@@ -17,6 +19,11 @@
 // range and writes one partial per (block, key slice, row); pass 1 writes each
 // (row pair, key) column sum to LDS exactly once and adds the row pairs in index
 // order, so the result does not depend on scheduling.
+//
+// Windows of more than 512 rows per KV head (G*L; the whole prompt when L = N,
+// which turns Eq. 12-13 into the full attention matrix of Eq. 1-2) are handled
+// in groups of 512 rows: each group runs both passes over the keys its rows can
+// see and adds its share to C.
 #include <math.h>
 
 #include "taskkv_internal.h"
@@ -24,6 +31,55 @@
 namespace taskkv {
 
 typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float elem_to_float(float x) { return x; }
+__device__ __forceinline__ float elem_to_float(uint16_t x) { return __uint_as_float(uint32_t(x) << 16); }
+
+// Rows [row0, row0 + R) of the flattened window (row = g*L + i) of every unit
+// -> qd [unit][Rpad][D] fp64, zero padded.
+template <typename T>
+__global__ void q_to_f64_kernel(const T *__restrict__ q, double *__restrict__ qd, Dims dm) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t total = (size_t)dm.units * dm.Rpad * dm.D;
+  if (idx >= total) return;
+  int c = idx % dm.D;
+  size_t rest = idx / dm.D;
+  int r = rest % dm.Rpad;
+  int unit = rest / dm.Rpad;
+  double val = 0.0;
+  if (r < dm.R) {
+    const int rg = dm.row0 + r;
+    int b = unit / dm.Hkv, h = unit % dm.Hkv, g = rg / dm.L, i = rg % dm.L;
+    size_t src = (((size_t)b * dm.Hq + h * dm.G + g) * dm.L + i) * dm.D + c;
+    val = (double)elem_to_float(q[src]);
+  }
+  qd[idx] = val;
+}
+
+// Fixed-order merge of the per-part row statistics.
+__global__ void merge_stats_kernel(const double *__restrict__ part, double *__restrict__ stats,
+                                   int Rpad, int n_parts) {
+  const int unit = blockIdx.x;
+  for (int r = threadIdx.x; r < Rpad; r += blockDim.x) {
+    double m = -INFINITY, l = 0.0;
+    for (int c = 0; c < n_parts; ++c) {
+      const double *pp = part + (((size_t)unit * n_parts + c) * Rpad + r) * 2;
+      const double mc = pp[0], lc = pp[1];
+      if (mc > -INFINITY) {
+        const double mn = fmax(m, mc);
+        l = l * exp(m - mn) + lc * exp(mc - mn);
+        m = mn;
+      }
+    }
+    stats[((size_t)unit * Rpad + r) * 2] = m;
+    stats[((size_t)unit * Rpad + r) * 2 + 1] = l;
+  }
+}
+
+__global__ void zero_f64_kernel(double *p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.0;
+}
 
 constexpr int SKC = 256;   // keys per chunk
 constexpr int SNW = 8;     // waves per block: with <= 8 row pairs every pair streams the same K tiles
@@ -81,7 +137,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
   constexpr int NKK = D / 4;
   constexpr int NRAW = NKK / RawCount<T>::per16B;
   const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 15, kq = l >> 4;
-  const int N = dm.N, L = dm.L, R = dm.R, Rpad = dm.Rpad;
+  const int N = dm.N, NK = dm.n_keys, L = dm.L, R = dm.R, Rpad = dm.Rpad, row0 = dm.row0;
   const int n_pairs = Rpad / 32;
   const int ksplit = n_pairs >= SNW ? 1 : SNW / n_pairs;
   const int n_items = n_pairs * ksplit;
@@ -109,7 +165,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
   // logits of one 16-key tile for the wave's two row blocks
   auto tile_logits = [&](int j0, bool &valid, f64x4 (&acc)[2]) {
     const int j = j0 + c;
-    valid = j < N;
+    valid = j < NK;
     uint4 raw[NRAW];
     fetch_piece<NKK>(kb + (size_t)(valid ? j : 0) * D + NKK * kq, valid, raw);
     double b[NKK];
@@ -133,8 +189,8 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
       for (int s = 0; s < 8; ++s) { m[s] = -INFINITY; ls[s] = 0.0; }
       for (int ch = 0; ch < chunks_per_wg; ++ch) {
         const int jc = (blockIdx.x * chunks_per_wg + ch) * SKC + ks * sub;
-        if (jc >= N) break;
-        for (int j0 = jc; j0 < jc + sub && j0 < N; j0 += 16) {
+        if (jc >= NK) break;
+        for (int j0 = jc; j0 < jc + sub && j0 < NK; j0 += 16) {
           bool valid;
           f64x4 acc[2];
           tile_logits(j0, valid, acc);
@@ -142,7 +198,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
             const int row = 32 * pair + 16 * (s >> 2) + 4 * (s & 3) + kq;
-            const bool vis = valid && row < R && j <= N - L + row % L;
+            const bool vis = valid && row < R && j <= N - L + (row0 + row) % L;
             if (vis) {
               // one exponential per logit, no divergent branch: e = exp(-|t - m|)
               const double t = acc[s >> 2][s & 3] * scale;
@@ -178,7 +234,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
   } else {
     for (int ch = 0; ch < chunks_per_wg; ++ch) {
       const int jchunk = (blockIdx.x * chunks_per_wg + ch) * SKC;
-      if (jchunk >= N) break;
+      if (jchunk >= NK) break;
       for (int item = w; item < n_items; item += SNW) {
         const int pair = item % n_pairs, ks = item / n_pairs;
         load_a(pair);
@@ -190,7 +246,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
           inv[s] = 1.0 / st[2 * row + 1];
         }
         const int jc = jchunk + ks * sub;
-        for (int j0 = jc; j0 < jc + sub && j0 < N; j0 += 16) {
+        for (int j0 = jc; j0 < jc + sub && j0 < NK; j0 += 16) {
           bool valid;
           f64x4 acc[2];
           tile_logits(j0, valid, acc);
@@ -199,7 +255,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
             const int row = 32 * pair + 16 * (s >> 2) + 4 * (s & 3) + kq;
-            const bool vis = valid && row < R && j <= N - L + row % L;
+            const bool vis = valid && row < R && j <= N - L + (row0 + row) % L;
             if (vis) colsum += exp(acc[s >> 2][s & 3] * scale - mr[s]) * inv[s];
           }
           colsum += __shfl_xor(colsum, 16);
@@ -210,10 +266,11 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
       __syncthreads();
       {
         const int j = jchunk + tid;
-        if (tid < SKC && j < N) {
+        if (tid < SKC && j < NK) {
           double sum = 0.0;
           for (int p = 0; p < n_pairs; ++p) sum += cs[p][tid];
-          scores[(size_t)unit * N + j] = sum / (double)R;
+          double *dst = scores + (size_t)unit * N + j;
+          *dst = dm.accumulate ? *dst + sum / (double)dm.Rtot : sum / (double)dm.Rtot;
         }
       }
       __syncthreads();
@@ -221,36 +278,75 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
   }
 }
 
-int score_mfma64_parts(const Dims &dm, int chunks_per_wg) {
+constexpr int ROW_GROUP = 32 * MAXP;  // window rows scored per launch pair
+
+static int chunks_per_wg_for(const Dims &dm) {
+  const int64_t n_chunks = (dm.N + SKC - 1) / SKC;
+  int64_t t = (n_chunks * dm.units + 4095) / 4096;
+  if (t < 1) t = 1;
+  if (t > 16) t = 16;
+  return (int)t;
+}
+
+// Row-statistics partial records per unit (for the workspace size).
+int score_parts(const Dims &dm) {
+  const int cpw = chunks_per_wg_for(dm);
   const int n_chunks = (dm.N + SKC - 1) / SKC;
-  const int n_wg = (n_chunks + chunks_per_wg - 1) / chunks_per_wg;
-  const int n_pairs = dm.Rpad / 32;
+  const int n_wg = (n_chunks + cpw - 1) / cpw;
+  const int rpad = dm.Rtot < ROW_GROUP ? (dm.Rtot + 31) / 32 * 32 : ROW_GROUP;
+  const int n_pairs = rpad / 32;
   return n_wg * (n_pairs >= SNW ? 1 : SNW / n_pairs);
 }
 
-bool score_mfma64_supported(const Dims &dm) { return dm.Rpad % 32 == 0 && dm.Rpad / 32 <= MAXP; }
+int score_rows_padded(const Dims &dm) { return dm.Rtot < ROW_GROUP ? (dm.Rtot + 31) / 32 * 32 : ROW_GROUP; }
 
 template <typename T, int D>
-static int run_mfma64(const Dims &dm, const T *k, const double *qd, double *part, double *stats,
-                      double *scores, int chunks_per_wg, hipStream_t s) {
-  const int n_chunks = (dm.N + SKC - 1) / SKC;
-  const dim3 grid((n_chunks + chunks_per_wg - 1) / chunks_per_wg, dm.units), block(64 * SNW);
-  score_mfma64_kernel<T, D, 0><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, chunks_per_wg);
-  launch_merge_stats(part, stats, dm.units, dm.Rpad, score_mfma64_parts(dm, chunks_per_wg), s);
-  score_mfma64_kernel<T, D, 1><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, chunks_per_wg);
+static int run_scores(const Dims &dm_all, const T *q_win, const T *k, double *qd, double *part,
+                      double *stats, double *scores, hipStream_t s) {
+  const int cpw = chunks_per_wg_for(dm_all);
+  const int n_groups = (dm_all.Rtot + ROW_GROUP - 1) / ROW_GROUP;
+  if (n_groups > 1) {
+    const size_t n = (size_t)dm_all.units * dm_all.N;
+    zero_f64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(scores, n);
+  }
+  for (int grp = 0; grp < n_groups; ++grp) {
+    Dims dm = dm_all;
+    dm.row0 = grp * ROW_GROUP;
+    dm.R = dm_all.Rtot - dm.row0 < ROW_GROUP ? dm_all.Rtot - dm.row0 : ROW_GROUP;
+    dm.Rpad = (dm.R + 31) / 32 * 32;
+    dm.accumulate = n_groups > 1 ? 1 : 0;
+    // keys the rows of this group can see: all of them unless the group lies
+    // inside one query head's window, where the last row bounds it
+    const int last = dm.row0 + dm.R - 1;
+    dm.n_keys = dm.N;
+    if (dm.row0 / dm.L == last / dm.L) {
+      const int64_t vis = (int64_t)dm.N - dm.L + last % dm.L + 1;
+      dm.n_keys = (int)(vis < dm.N ? vis : dm.N);
+    }
+    const size_t total = (size_t)dm.units * dm.Rpad * dm.D;
+    q_to_f64_kernel<T><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(q_win, qd, dm);
+    const int n_chunks = (dm.n_keys + SKC - 1) / SKC;
+    const int n_wg = (n_chunks + cpw - 1) / cpw;
+    const int n_pairs = dm.Rpad / 32;
+    const int n_parts = n_wg * (n_pairs >= SNW ? 1 : SNW / n_pairs);
+    const dim3 grid(n_wg, dm.units), block(64 * SNW);
+    score_mfma64_kernel<T, D, 0><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw);
+    merge_stats_kernel<<<dim3(dm.units), dim3(256), 0, s>>>(part, stats, dm.Rpad, n_parts);
+    score_mfma64_kernel<T, D, 1><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw);
+  }
   return hip_ok(hipGetLastError());
 }
 
-int launch_scores_mfma64(const Dims &dm, int dtype, const void *k, const double *qd, double *part,
-                         double *stats, double *scores, int chunks_per_wg, hipStream_t s) {
+int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
+                  double *stats, double *scores, hipStream_t s) {
   if (dtype == TASKKV_F32) {
-    auto kk = static_cast<const float *>(k);
-    return dm.D == 64 ? run_mfma64<float, 64>(dm, kk, qd, part, stats, scores, chunks_per_wg, s)
-                      : run_mfma64<float, 128>(dm, kk, qd, part, stats, scores, chunks_per_wg, s);
+    auto qq = static_cast<const float *>(q_win), kk = static_cast<const float *>(k);
+    return dm.D == 64 ? run_scores<float, 64>(dm, qq, kk, qd, part, stats, scores, s)
+                      : run_scores<float, 128>(dm, qq, kk, qd, part, stats, scores, s);
   }
-  auto kk = static_cast<const uint16_t *>(k);
-  return dm.D == 64 ? run_mfma64<uint16_t, 64>(dm, kk, qd, part, stats, scores, chunks_per_wg, s)
-                    : run_mfma64<uint16_t, 128>(dm, kk, qd, part, stats, scores, chunks_per_wg, s);
+  auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
+  return dm.D == 64 ? run_scores<uint16_t, 64>(dm, qq, kk, qd, part, stats, scores, s)
+                    : run_scores<uint16_t, 128>(dm, qq, kk, qd, part, stats, scores, s);
 }
 
 }  // namespace taskkv

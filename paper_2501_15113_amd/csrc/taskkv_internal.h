@@ -10,8 +10,6 @@ namespace taskkv {
 
 constexpr int CHUNK = TASKKV_CHUNK_TOKENS;  // tokens per split-K work item / region alignment
 constexpr int PAGE = 32;                    // tokens per matrix-core page of the bf16 cache
-constexpr int SCORE_TILE = 256;             // columns (keys) per scoring tile
-constexpr int ROW_BLK = 8;                  // window rows handled together by the f64 scorer
 constexpr int MAX_PROFILE_EVENTS = 4096;
 constexpr int STREAM_MAX_UNITS = 4096;  // units the streaming decode kernel can index in LDS
 constexpr int STREAM_MAX_WG = 1024;     // workgroups (4 waves each) it is ever launched with
@@ -21,7 +19,9 @@ struct Dims {
   int B, Hq, Hkv, G, D, N, L, T;  // T = min(top_t, N)
   int s1, s2, k;                  // k already clipped to the middle
   int n_het, add_centre, pool;
-  int R, Rpad;                    // window rows per unit (G*L) and padded to 32
+  int Rtot;                       // window rows per unit, G*L
+  int R, Rpad;                    // rows of the group being scored, and padded to 32
+  int row0, n_keys, accumulate;   // first row of the group, keys it can see, add to C instead of storing
   int units;                      // B * Hkv
   int keep_all;                   // s1 + s2 >= N: every unit keeps everything
   int row_stride;                 // s1 + cfg.n_middle + s2: width of a kept_idx row
@@ -66,14 +66,10 @@ struct Carver {
 };
 
 // ---- launchers (each validates nothing; api.hip has checked the arguments) ----
-int launch_q_to_f64(const Dims &dm, int dtype, const void *q_win, double *qd, hipStream_t s);
-int launch_merge_stats(const double *part, double *stats, int units, int Rpad, int n_parts, hipStream_t s);
-int launch_scores_f64(const Dims &dm, int dtype, const void *k, double *qd, double *stat_part,
-                      double *stats, double *scores, int tiles_per_wg, hipStream_t s);
-bool score_mfma64_supported(const Dims &dm);
-int score_mfma64_parts(const Dims &dm, int chunks_per_wg);
-int launch_scores_mfma64(const Dims &dm, int dtype, const void *k, const double *qd, double *part,
-                         double *stats, double *scores, int chunks_per_wg, hipStream_t s);
+int score_parts(const Dims &dm);
+int score_rows_padded(const Dims &dm);
+int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
+                  double *stats, double *scores, hipStream_t s);
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
                   int count, int prefix, int suffix, int32_t *out, int out_stride, int skip_all,
                   hipStream_t s);

@@ -96,7 +96,8 @@ SWEEP = [
     dict(obs_window=1, ctx_len=520),
     dict(obs_window=50, ctx_len=50, n_sink=2, n_recent=3, n_middle=4, top_t=10),   # L = N
     dict(batch=3, ctx_len=33, n_sink=1, n_recent=2, n_middle=3, obs_window=5, top_t=7),
-    dict(n_q_heads=40, n_kv_heads=2, ctx_len=600, obs_window=32, batch=1),   # 640 window rows: vector-ALU scorer
+    dict(n_q_heads=40, n_kv_heads=2, ctx_len=600, obs_window=32, batch=1),   # 640 window rows: two row groups
+    dict(ctx_len=700, obs_window=700, top_t=700, batch=1),             # L = N with G = 2: 1400 rows, 3 groups
     dict(n_sink=0, n_recent=0, n_middle=0, ctx_len=700, n_hetero=1),   # the other heads keep nothing
     dict(ctx_len=1536, n_sink=0, n_recent=480, n_middle=32, decode_steps=4),   # append crosses a chunk edge
 ]
@@ -106,6 +107,25 @@ SWEEP = [
 def test_small_sweep(i):
     wl = small_workload(name=f"sweep{i}", wid=100 + i, **SWEEP[i])
     run_layer(wl, check_batches=tuple(range(min(2, wl.batch))))
+
+
+def test_full_window_reproduces_exact_semantic_vector():
+    """L = N, t = N, one query head per KV head: the separator's vector is the
+    un-approximated definition (Eq. 1-2), computed by the oracle's direct
+    N x N formula."""
+    from oracle import taskkv_oracle as orc
+    ses = _session()
+    wl = small_workload(name="exact", wid=158, batch=1, n_q_heads=4, n_kv_heads=4, ctx_len=1100,
+                        obs_window=1100, top_t=1100, recipe="gauss", offset=3.0)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 0)
+    with ses.Context([cfg], 0) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        sem = bufs.sem_vec[0].cpu().numpy()
+    q, k, v = to_numpy(ld.q_win[0]), to_numpy(ld.k[0]), to_numpy(ld.v[0])
+    for h in range(4):
+        np.testing.assert_allclose(sem[h], orc.full_semantic_vector(q[h], k[h], v[h]), rtol=1e-9, atol=1e-13)
 
 
 def test_softmax_scale_override():
