@@ -38,6 +38,7 @@ __all__ = [
     "centre_and_distances", "hetero_mask", "kept_tokens", "pack_cache",
     "decode_attention", "separate", "compress", "full_semantic_vector",
     "hetero_head_count", "middle_budget", "merge_partials",
+    "kept_tokens_no_cache", "compressed_cache", "round_to_storage",
 ]
 
 
@@ -180,6 +181,70 @@ def pack_cache(k, v, kept):
 
 
 # --------------------------------------------------------------------------- #
+# Alternative compensation methods of the ablation (Sec. 6.2, Fig. 8):
+# "No Cache" and "Compressed Cache"; "Selective Cache" is kept_tokens above.
+# --------------------------------------------------------------------------- #
+def kept_tokens_no_cache(N, is_hetero, n_sink, n_recent, n_extra):
+    """No Cache: only sinks and recent tokens; the cache size that the other
+    methods spend on the middle is added to the recent window."""
+    if is_hetero or n_sink + n_recent + n_extra >= N:
+        return np.arange(N, dtype=np.int64)
+    return np.concatenate([np.arange(0, n_sink), np.arange(N - n_recent - n_extra, N)]).astype(np.int64)
+
+
+def round_to_storage(x, dtype):
+    """fp64 -> storage dtype with one round-to-nearest-even.  "f32": IEEE
+    conversion.  "bf16": returned as float32 holding bf16-representable values
+    (normal range assumed; the means of cached values are)."""
+    x = _f64(x)
+    if dtype == "f32":
+        return x.astype(np.float32)
+    u = x.view(np.uint64) if x.flags["C_CONTIGUOUS"] else np.ascontiguousarray(x).view(np.uint64)
+    sign = (u >> np.uint64(63)).astype(np.uint32)
+    mag = u & np.uint64(0x7FFFFFFFFFFFFFFF)
+    lsb = (mag >> np.uint64(45)) & np.uint64(1)
+    mag = (mag + np.uint64((1 << 44) - 1) + lsb) >> np.uint64(45)        # 11-bit exponent + 7-bit mantissa
+    exp64 = (mag >> np.uint64(7)).astype(np.int64)
+    mant = (mag & np.uint64(0x7F)).astype(np.uint32)
+    exp32 = np.where(exp64 == 0, 0, exp64 - 896).astype(np.uint32)
+    mant = np.where(exp64 == 0, 0, mant).astype(np.uint32)
+    bits = (sign << np.uint32(31)) | (exp32 << np.uint32(23)) | (mant << np.uint32(16))
+    return bits.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def compressed_cache(k, v, is_hetero, n_sink, n_recent, n_groups, dtype):
+    """Compressed Cache: the middle [s1, N-s2) is cut into n_groups contiguous
+    groups of near-equal size (group g covers middle offsets
+    [g*M/n, (g+1)*M/n), integer division) and each group is replaced by one
+    compensation token, the arithmetic mean of its K rows and of its V rows,
+    rounded once to the storage dtype.  The paper gives only "divides the
+    intermediate tokens into groups, one compensation token per group"
+    (reading: contiguous groups, plain mean) -- parity unpinned.
+    Returns (k_cache, v_cache, first_positions): rows = sinks, compensation
+    tokens, recent tokens; first_positions lists the original position of each
+    row (first position of its group for a compensation token)."""
+    k, v = np.asarray(k), np.asarray(v)
+    N = k.shape[0]
+    if is_hetero or n_sink + n_recent >= N:
+        return k.copy(), v.copy(), np.arange(N, dtype=np.int64)
+    lo, hi = n_sink, N - n_recent
+    M = hi - lo
+    n = min(n_groups, M)
+    kk, vv, pos = [k[:lo]], [v[:lo]], list(range(lo))
+    for g in range(n):
+        a, b = lo + (g * M) // n, lo + ((g + 1) * M) // n
+        km = _f64(k[a:b]).sum(axis=0) / float(b - a)
+        vm = _f64(v[a:b]).sum(axis=0) / float(b - a)
+        kk.append(round_to_storage(km, dtype)[None].astype(k.dtype))
+        vv.append(round_to_storage(vm, dtype)[None].astype(v.dtype))
+        pos.append(a)
+    kk.append(k[hi:])
+    vv.append(v[hi:])
+    pos.extend(range(hi, N))
+    return np.concatenate(kk), np.concatenate(vv), np.asarray(pos, dtype=np.int64)
+
+
+# --------------------------------------------------------------------------- #
 # Decode attention over the ragged cache (Sec. 3.1 Eq. 1 restricted to one
 # query row and to the retained keys; Sec. 5.5.3 is where the paper times it)
 # --------------------------------------------------------------------------- #
@@ -228,13 +293,24 @@ def separate(q_win, k, v, top_t, n_hetero, add_centre_head=False, scale=None):
     return dict(scores=C, sem_vec=sem, dist=dist, mask=mask, picks=picks)
 
 
-def compress(k, v, scores, mask, n_sink, n_recent, n_middle, pool_kernel=1):
+def compress(k, v, scores, mask, n_sink, n_recent, n_middle, pool_kernel=1, pack_mode=0, dtype="f32"):
     """Cache allocation for one layer, one batch element.
+    pack_mode 0: selective cache (the method); 1: No Cache; 2: Compressed
+    Cache (dtype names the storage type its means are rounded to).
     Returns (kept list of int64 arrays, k_cache list, v_cache list)."""
     P = pool_scores(scores, pool_kernel)
     kept, kc, vc = [], [], []
     for h in range(len(mask)):
-        idx = kept_tokens(P[h], bool(mask[h]), n_sink, n_recent, n_middle)
+        if pack_mode == 2:
+            kk, vv, idx = compressed_cache(k[h], v[h], bool(mask[h]), n_sink, n_recent, n_middle, dtype)
+            kept.append(idx)
+            kc.append(kk)
+            vc.append(vv)
+            continue
+        if pack_mode == 1:
+            idx = kept_tokens_no_cache(P.shape[1], bool(mask[h]), n_sink, n_recent, n_middle)
+        else:
+            idx = kept_tokens(P[h], bool(mask[h]), n_sink, n_recent, n_middle)
         kk, vv = pack_cache(k[h], v[h], idx)
         kept.append(idx)
         kc.append(kk)

@@ -318,3 +318,56 @@ def test_middle_budget_identity():
         assert 0 <= B - used < (n - f)
     assert orc.middle_budget(100, 50, 4, 4, 1, 1) == 0
     assert orc.middle_budget(10, 50, 4, 1, 1, 1) == 0        # budget too small -> clipped
+
+
+# ----------------------------------------------------------------- Sec. 6.2 ablation modes
+def test_round_to_storage_matches_library_conversion():
+    """Values that are exactly float32: direct fp64 -> bf16 rounding must equal
+    torch's float32 -> bfloat16 conversion (ties to even included)."""
+    x32 = np.concatenate([rand(4000).astype(np.float32) * np.float32(3.0),
+                          np.array([1.0, 1.00390625, 1.01171875, -1.00390625, 0.0, 3.0e-5, 255.5, 256.5],
+                                   dtype=np.float32)])
+    ref = torch.tensor(x32).to(torch.bfloat16).float().numpy()
+    got = orc.round_to_storage(x32.astype(np.float64), "bf16")
+    assert got.dtype == np.float32 and got.tobytes() == ref.tobytes()
+    x = rand(100)
+    assert orc.round_to_storage(x, "f32").tobytes() == x.astype(np.float32).tobytes()
+    # a double just above a bf16 tie must round up although float32 rounding first would land on the tie
+    y = np.array([1.00390625 + 1e-12])
+    assert orc.round_to_storage(y, "bf16")[0] == np.float32(1.0078125)
+
+
+def test_no_cache_mode_keeps_sinks_and_longer_recent_window():
+    assert orc.kept_tokens_no_cache(20, False, 2, 3, 4).tolist() == [0, 1] + list(range(13, 20))
+    assert orc.kept_tokens_no_cache(20, True, 2, 3, 4).tolist() == list(range(20))
+    assert orc.kept_tokens_no_cache(8, False, 2, 3, 4).tolist() == list(range(8))
+
+
+def test_compressed_cache_groups_and_means():
+    N, d, s1, s2, n = 23, 4, 2, 3, 5
+    k = torch.tensor(rand(N, d)).to(torch.bfloat16).float().numpy()
+    v = torch.tensor(rand(N, d)).to(torch.bfloat16).float().numpy()
+    kc, vc, pos = orc.compressed_cache(k, v, False, s1, s2, n, "bf16")
+    assert kc.shape == (s1 + n + s2, d) and pos[:s1].tolist() == [0, 1] and pos[-s2:].tolist() == [20, 21, 22]
+    assert kc[:s1].tobytes() == k[:s1].tobytes() and kc[-s2:].tobytes() == k[-s2:].tobytes()
+    bounds = pos[s1:s1 + n].tolist() + [N - s2]
+    sizes = np.diff(bounds)
+    assert bounds[0] == s1 and sizes.sum() == N - s1 - s2 and sizes.max() - sizes.min() <= 1
+    for g in range(n):                       # each token is the (rounded) mean of its group
+        ref = torch.tensor(k[bounds[g]:bounds[g + 1]].astype(np.float64).mean(axis=0)).to(torch.bfloat16)
+        np.testing.assert_allclose(kc[s1 + g], ref.float().numpy(), rtol=2 ** -7)
+        assert torch.tensor(kc[s1 + g]).to(torch.bfloat16).float().numpy().tobytes() == kc[s1 + g].tobytes()
+    # constant rows compress to themselves; one group per token is the identity
+    const = np.tile(k[5], (N, 1))
+    cc, _, _ = orc.compressed_cache(const, const, False, s1, s2, 4, "bf16")
+    assert (cc == k[5]).all()
+    ident, _, p2 = orc.compressed_cache(k, v, False, s1, s2, 99, "bf16")
+    assert ident.tobytes() == k.tobytes() and p2.tolist() == list(range(N))
+    full, _, _ = orc.compressed_cache(k, v, True, s1, s2, 3, "bf16")
+    assert full.tobytes() == k.tobytes()
+    # fp32 storage: total mass of the middle is preserved by the means
+    k32 = rand(N, d).astype(np.float32)
+    c32, _, p3 = orc.compressed_cache(k32, k32, False, s1, s2, n, "f32")
+    b3 = p3[s1:s1 + n].tolist() + [N - s2]
+    np.testing.assert_allclose((c32[s1:s1 + n].astype(np.float64) * np.diff(b3)[:, None]).sum(axis=0),
+                               k32[s1:N - s2].astype(np.float64).sum(axis=0), rtol=1e-6, atol=1e-6)
