@@ -41,6 +41,15 @@ typedef struct taskkv_ctx taskkv_ctx; /* opaque: workspace + error flag on one d
 
 typedef enum { TASKKV_F32 = 0, TASKKV_BF16 = 1 } taskkv_dtype;
 
+/* How non-heterogeneous heads fill the part of their budget that lies between
+ * sinks and recent window (the compensation methods compared in paper Sec. 6.2). */
+typedef enum {
+  TASKKV_PACK_SELECTIVE = 0,  /* the method: the n_middle best-scored middle tokens (Sec. 4.2) */
+  TASKKV_PACK_NO_CACHE = 1,   /* nothing from the middle; the recent window grows by n_middle */
+  TASKKV_PACK_COMPRESSED = 2  /* the middle is cut into n_middle contiguous groups of near-equal
+                                 size, each replaced by the mean of its K rows and of its V rows */
+} taskkv_pack_mode;
+
 typedef enum {
   TASKKV_OK = 0,
   TASKKV_EINVAL = -1,     /* bad argument (shape, NULL pointer, unsupported size) */
@@ -66,6 +75,7 @@ typedef struct taskkv_layer_cfg {
                               everything (last rule of the ranking paragraph, Sec. 4.1) */
   int32_t pool_kernel;     /* odd width of the average pooling of selection scores
                               (paper Sec. 5.4 uses 7); 1 = none */
+  int32_t pack_mode;       /* taskkv_pack_mode; 0 = the paper's method */
   int32_t dtype;           /* taskkv_dtype of Q/K/V and of the cache */
   float softmax_scale;     /* 0 => 1/sqrt(d) */
 } taskkv_layer_cfg;
@@ -127,11 +137,16 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
  *                              when s1 + s2 >= N), else s1 + min(k, N-s1-s2) + s2
  *   kept_idx [B*H_kv, s1+k+s2] i32  original positions kept by each
  *                              non-heterogeneous unit, ascending, -1 padded;
- *                              rows of keep-everything units are all -1
+ *                              rows of keep-everything units are all -1; in
+ *                              TASKKV_PACK_COMPRESSED mode a compensation token is
+ *                              listed by the first position of its group
  * capacity_tokens must be >= taskkv_cache_tokens(cfg, reserve_decode_tokens)
  * (else TASKKV_ECAPACITY).  Middle tokens are the n_middle best of the pooled
  * scores inside [s1, N - s2), ties to the lower index; rows are copied
- * bit-for-bit; slots past a unit's length are zero-filled.
+ * bit-for-bit; slots past a unit's length are zero-filled.  In
+ * TASKKV_PACK_COMPRESSED mode group g of n covers middle offsets
+ * [g*M/n, (g+1)*M/n) (M = N - s1 - s2, n = min(n_middle, M)); its token is the
+ * fp64 mean of the group's rows rounded once (to nearest even) to the cache dtype.
  */
 int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k, const void *v,
                     const double *scores, const uint8_t *hetero_mask, void *k_cache, void *v_cache,

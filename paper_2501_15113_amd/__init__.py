@@ -3,7 +3,8 @@
 Argument marshalling only -- every step runs in the library's HIP kernels.
 There is no CPU fallback: loading fails loudly when the library is not built.
 """
-from .binding import (LayerCfg, TaskKVError, CHUNK_TOKENS, F32, BF16, library_path, load_library,
+from .binding import (LayerCfg, TaskKVError, CHUNK_TOKENS, F32, BF16, PACK_SELECTIVE, PACK_NO_CACHE,
+                      PACK_COMPRESSED, library_path, load_library,
                       taskkv_create, taskkv_destroy, taskkv_strerror, taskkv_workspace_bytes,
                       taskkv_cache_tokens, taskkv_hetero_head_count, taskkv_middle_budget,
                       taskkv_separate, taskkv_compress, taskkv_decode_attn, taskkv_cache_export,
@@ -11,7 +12,8 @@ from .binding import (LayerCfg, TaskKVError, CHUNK_TOKENS, F32, BF16, library_pa
                       EXPORTED_SYMBOLS)
 
 __all__ = [
-    "LayerCfg", "TaskKVError", "CHUNK_TOKENS", "F32", "BF16", "library_path", "load_library",
+    "LayerCfg", "TaskKVError", "CHUNK_TOKENS", "F32", "BF16", "PACK_SELECTIVE", "PACK_NO_CACHE",
+    "PACK_COMPRESSED", "library_path", "load_library",
     "taskkv_create", "taskkv_destroy", "taskkv_strerror", "taskkv_workspace_bytes",
     "taskkv_cache_tokens", "taskkv_hetero_head_count", "taskkv_middle_budget", "taskkv_separate",
     "taskkv_compress", "taskkv_decode_attn", "taskkv_cache_export", "taskkv_last_async_error",

@@ -6,6 +6,7 @@ import os
 from typing import Optional
 
 F32, BF16 = 0, 1
+PACK_SELECTIVE, PACK_NO_CACHE, PACK_COMPRESSED = 0, 1, 2
 CHUNK_TOKENS = 512
 
 EXPORTED_SYMBOLS = [
@@ -24,7 +25,7 @@ class LayerCfg(C.Structure):
     """Mirror of taskkv_layer_cfg."""
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "ctx_len", "obs_window", "top_t", "n_sink",
-        "n_recent", "n_middle", "n_hetero", "add_centre_head", "pool_kernel", "dtype")] + [
+        "n_recent", "n_middle", "n_hetero", "add_centre_head", "pool_kernel", "pack_mode", "dtype")] + [
         ("softmax_scale", C.c_float)]
 
     def __init__(self, **kw):

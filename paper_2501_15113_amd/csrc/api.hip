@@ -17,14 +17,24 @@ static bool resolve(const taskkv_layer_cfg *c, Dims &d) {
   if (c->top_t < 1 || c->n_sink < 0 || c->n_recent < 0 || c->n_middle < 0 || c->n_hetero < 0) return false;
   if (c->pool_kernel < 1 || c->pool_kernel % 2 == 0) return false;
   if (c->dtype != TASKKV_F32 && c->dtype != TASKKV_BF16) return false;
+  if (c->pack_mode < TASKKV_PACK_SELECTIVE || c->pack_mode > TASKKV_PACK_COMPRESSED) return false;
   if (!(c->softmax_scale >= 0.f)) return false;
   d.B = c->batch; d.Hq = c->n_q_heads; d.Hkv = c->n_kv_heads; d.G = d.Hq / d.Hkv;
   d.D = c->head_dim; d.N = c->ctx_len; d.L = c->obs_window;
   d.T = c->top_t < d.N ? c->top_t : d.N;
   d.s1 = c->n_sink; d.s2 = c->n_recent;
-  d.keep_all = ((int64_t)d.s1 + d.s2 >= d.N) ? 1 : 0;
-  const int64_t middle = d.keep_all ? 0 : (int64_t)d.N - d.s1 - d.s2;
-  d.k = (int)(c->n_middle < middle ? c->n_middle : middle);
+  d.pack_mode = c->pack_mode;
+  if (d.pack_mode == TASKKV_PACK_NO_CACHE) {
+    // the middle budget is spent on a longer recent window
+    const int64_t recent = (int64_t)c->n_recent + c->n_middle;
+    d.keep_all = ((int64_t)d.s1 + recent >= d.N) ? 1 : 0;
+    d.s2 = d.keep_all ? c->n_recent : (int)recent;
+    d.k = 0;
+  } else {
+    d.keep_all = ((int64_t)d.s1 + d.s2 >= d.N) ? 1 : 0;
+    const int64_t middle = d.keep_all ? 0 : (int64_t)d.N - d.s1 - d.s2;
+    d.k = (int)(c->n_middle < middle ? c->n_middle : middle);
+  }
   d.n_het = c->n_hetero; d.add_centre = c->add_centre_head ? 1 : 0; d.pool = c->pool_kernel;
   if (d.G > 64 || (int64_t)d.G * d.L > (int64_t)1 << 30) return false;
   d.Rtot = d.G * d.L;
@@ -33,7 +43,7 @@ static bool resolve(const taskkv_layer_cfg *c, Dims &d) {
   d.row0 = 0; d.n_keys = d.N; d.accumulate = 0;
   if ((int64_t)d.B * d.Hkv > 65535) return false;
   d.units = d.B * d.Hkv;
-  const int64_t stride = (int64_t)d.s1 + c->n_middle + d.s2;
+  const int64_t stride = (int64_t)c->n_sink + c->n_middle + c->n_recent;
   if (stride > (int64_t)1 << 30) return false;
   d.row_stride = (int)stride;
   d.scale = c->softmax_scale > 0.f ? (double)c->softmax_scale : 1.0 / sqrt((double)d.D);
@@ -63,8 +73,11 @@ static size_t ws_separate(const Dims &d) {
   b += al((size_t)d.units * d.T * sizeof(int32_t));                   // top-t picks
   return b;
 }
-static size_t ws_compress(const Dims &d) {
-  return d.pool > 1 ? al((size_t)d.units * d.N * sizeof(double)) : 0;
+static size_t ws_compress(const Dims &d, int dtype) {
+  size_t b = d.pool > 1 ? al((size_t)d.units * d.N * sizeof(double)) : 0;
+  if (d.pack_mode == TASKKV_PACK_COMPRESSED)
+    b += 2 * al((size_t)d.units * d.k * d.D * (dtype == TASKKV_F32 ? 4 : 2));
+  return b;
 }
 // Partial slots a decode call needs: one per chunk for the chunk-grid kernels,
 // one per (wave, unit) staircase step for the streaming kernel.
@@ -148,7 +161,7 @@ void taskkv_destroy(taskkv_ctx *ctx) {
 size_t taskkv_workspace_bytes(const taskkv_layer_cfg *cfg, int32_t reserve_decode_tokens) {
   Dims d;
   if (!resolve(cfg, d) || reserve_decode_tokens < 0) return 0;
-  size_t a = ws_separate(d), b = ws_compress(d), c = ws_decode(d, cache_tokens(d, reserve_decode_tokens));
+  size_t a = ws_separate(d), b = ws_compress(d, cfg->dtype), c = ws_decode(d, cache_tokens(d, reserve_decode_tokens));
   size_t m = a > b ? a : b;
   return (m > c ? m : c) + 4096;
 }
@@ -195,7 +208,7 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   if (!cv.ok) return TASKKV_EWORKSPACE;
   int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, s);
   if (rc) return rc;
-  rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, top_idx, d.T, 0, s);
+  rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, 0, s);
   if (rc) return rc;
   return launch_semvec_mask(d, cfg->dtype, scores, v, top_idx, sem_vec, dist, hetero_mask, s);
 }
@@ -212,25 +225,40 @@ int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k,
   if (capacity_tokens < cache_tokens(d, reserve_decode_tokens)) return TASKKV_ECAPACITY;
   if (capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  Carver cv(ctx->ws, ctx->ws_bytes);
   const double *sel_scores = scores;
-  if (d.pool > 1) {
-    Carver cv(ctx->ws, ctx->ws_bytes);
+  int rc = TASKKV_OK;
+  if (d.pool > 1 && d.pack_mode == TASKKV_PACK_SELECTIVE) {
     double *pooled = cv.take<double>((size_t)d.units * d.N);
     if (!cv.ok) return TASKKV_EWORKSPACE;
-    int rc = launch_pool(d, scores, pooled, s);
+    rc = launch_pool(d, scores, pooled, s);
     if (rc) return rc;
     sel_scores = pooled;
   }
-  int rc = TASKKV_OK;
+  void *comp_k = nullptr, *comp_v = nullptr;
+  if (d.pack_mode == TASKKV_PACK_COMPRESSED && d.k > 0) {
+    const size_t esz = cfg->dtype == TASKKV_F32 ? 4 : 2;
+    comp_k = cv.take<char>((size_t)d.units * d.k * d.D * esz);
+    comp_v = cv.take<char>((size_t)d.units * d.k * d.D * esz);
+    if (!cv.ok) return TASKKV_EWORKSPACE;
+  }
   if (d.row_stride > 0) {
-    rc = launch_select(d, sel_scores, hetero_mask, d.s1, d.N - d.s2, d.k, d.s1, d.s2, kept_idx,
+    // selective: middle pick by score; the other modes take no middle token by
+    // score (count 0) and get sinks + recent from the same kernel
+    const int count = d.pack_mode == TASKKV_PACK_SELECTIVE ? d.k : 0;
+    const int gap = d.pack_mode == TASKKV_PACK_COMPRESSED ? d.k : 0;  // filled with group positions below
+    rc = launch_select(d, sel_scores, hetero_mask, d.s1, d.N - d.s2, count, d.s1, gap, d.s2, kept_idx,
                        d.row_stride, d.keep_all, s);
+    if (rc) return rc;
+  }
+  if (comp_k) {
+    rc = launch_group_means(d, cfg->dtype, k, v, hetero_mask, comp_k, comp_v, kept_idx, s);
     if (rc) return rc;
   }
   rc = launch_layout(d, hetero_mask, reserve_decode_tokens, capacity_tokens, offsets, lens, ctx->d_err, s);
   if (rc) return rc;
-  return launch_pack(d, cfg->dtype, k, v, kept_idx, hetero_mask, offsets, lens, k_cache, v_cache,
-                     capacity_tokens, s);
+  return launch_pack(d, cfg->dtype, k, v, kept_idx, hetero_mask, offsets, lens, comp_k, comp_v, k_cache,
+                     v_cache, capacity_tokens, s);
 }
 
 int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q, const void *k_new,

@@ -19,6 +19,11 @@
 
 namespace taskkv {
 
+__device__ __forceinline__ double elem_as_double(float x) { return (double)x; }
+__device__ __forceinline__ double elem_as_double(uint16_t x) {
+  return (double)__uint_as_float(uint32_t(x) << 16);
+}
+
 // Largest u with offsets[u] <= tok, or -1 if tok is past the last region.
 __device__ __forceinline__ int find_unit(const int64_t *__restrict__ offsets, int n_units, int64_t tok) {
   if (tok >= offsets[n_units]) return -1;
@@ -53,12 +58,59 @@ __global__ void layout_kernel(const uint8_t *__restrict__ mask, int64_t *__restr
 
 __device__ __forceinline__ int tau_of(int g, int e) { return 16 * (e >> 2) + 4 * g + (e & 3); }
 
+// Where slot p of a unit's region comes from: a source row index (>= 0), a
+// compensation token (-2 - g, compressed-cache mode), or nothing (-1: zero fill).
+__device__ __forceinline__ int source_of_slot(int p, int len, bool direct, const int32_t *kept_row,
+                                              bool has_comp, const Dims &dm) {
+  if (p >= len) return -1;
+  if (direct) return p;
+  if (has_comp && p >= dm.s1 && p < dm.s1 + dm.k) return -2 - (p - dm.s1);
+  return kept_row[p];
+}
+
+// fp64 -> storage dtype, one rounding to nearest even.
+__device__ __forceinline__ float round_store(double x, float) { return (float)x; }
+__device__ __forceinline__ uint16_t round_store(double x, uint16_t) {
+  const uint64_t u = (uint64_t)__double_as_longlong(x);
+  const uint32_t sign = (uint32_t)(u >> 63) << 15;
+  uint64_t mag = u & 0x7fffffffffffffffull;
+  mag += ((mag >> 45) & 1ull) + ((1ull << 44) - 1ull);  // ties to even on the 45 dropped bits
+  mag >>= 45;                                           // 11-bit exponent, 7-bit mantissa
+  const uint32_t e64 = (uint32_t)(mag >> 7);
+  if (e64 == 0) return (uint16_t)sign;                  // zero (subnormal doubles do not occur here)
+  return (uint16_t)(sign | ((e64 - 896u) << 7) | (uint32_t)(mag & 0x7full));
+}
+
+// Compressed-cache mode (paper Sec. 6.2): one block per (group, unit); thread c
+// averages channel c of the group's K rows and V rows in fp64.
+template <typename T>
+__global__ void group_mean_kernel(const T *__restrict__ k, const T *__restrict__ v,
+                                  const uint8_t *__restrict__ mask, T *__restrict__ comp_k,
+                                  T *__restrict__ comp_v, int32_t *__restrict__ kept, Dims dm) {
+  const int g = blockIdx.x, u = blockIdx.y, c = threadIdx.x;
+  if (dm.keep_all || mask[u]) return;
+  const int64_t M = (int64_t)dm.N - dm.s1 - dm.s2;
+  const int a = dm.s1 + (int)((int64_t)g * M / dm.k), b = dm.s1 + (int)((int64_t)(g + 1) * M / dm.k);
+  if (c == 0) kept[(size_t)u * dm.row_stride + dm.s1 + g] = a;
+  const T *kb = k + (size_t)u * dm.N * dm.D, *vb = v + (size_t)u * dm.N * dm.D;
+  double sk = 0.0, sv = 0.0;
+  for (int j = a; j < b; ++j) {
+    sk += elem_as_double(kb[(size_t)j * dm.D + c]);
+    sv += elem_as_double(vb[(size_t)j * dm.D + c]);
+  }
+  const double n = (double)(b - a);
+  const size_t o = ((size_t)u * dm.k + g) * dm.D + c;
+  comp_k[o] = round_store(sk / n, T());
+  comp_v[o] = round_store(sv / n, T());
+}
+
 // One block per 32-token page of the token space.
 template <int D>
 __global__ __launch_bounds__(256) void pack_bf16_kernel(
     const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, const int32_t *__restrict__ kept,
     const uint8_t *__restrict__ mask, const int64_t *__restrict__ offsets,
-    const int32_t *__restrict__ lens, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, Dims dm) {
+    const int32_t *__restrict__ lens, const uint16_t *__restrict__ comp_k,
+    const uint16_t *__restrict__ comp_v, uint16_t *__restrict__ kc, uint16_t *__restrict__ vc, Dims dm) {
   constexpr int CH = D / 8;  // 16-byte pieces per row
   const int64_t tok0 = (int64_t)blockIdx.x * PAGE;
   const int u = find_unit(offsets, dm.units, tok0);
@@ -71,7 +123,7 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(
   __shared__ __align__(16) uint16_t vt[PAGE][D + 8];
   if (tid < PAGE) {
     const int p = local0 + tid;
-    src[tid] = p < len ? (direct ? p : kept[(size_t)u * dm.row_stride + p]) : -1;
+    src[tid] = source_of_slot(p, len, direct, kept + (size_t)u * dm.row_stride, comp_k != nullptr, dm);
   }
   __syncthreads();
   const size_t ubase = (size_t)u * dm.N * D;
@@ -82,6 +134,10 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(
       const size_t off = ubase + (size_t)src[row] * D + ci * 8;
       kv = *reinterpret_cast<const uint4 *>(k + off);
       vv = *reinterpret_cast<const uint4 *>(v + off);
+    } else if (src[row] <= -2) {
+      const size_t off = ((size_t)u * dm.k + (size_t)(-2 - src[row])) * D + ci * 8;
+      kv = *reinterpret_cast<const uint4 *>(comp_k + off);
+      vv = *reinterpret_cast<const uint4 *>(comp_v + off);
     }
     const int sb = row >> 4, r = row & 15;
     uint16_t *dst = kc + ((size_t)tok0 + sb * 16) * D + (size_t)(ci * 16 + r) * 8;
@@ -132,7 +188,8 @@ template <int D>
 __global__ __launch_bounds__(256) void pack_f32_kernel(
     const float *__restrict__ k, const float *__restrict__ v, const int32_t *__restrict__ kept,
     const uint8_t *__restrict__ mask, const int64_t *__restrict__ offsets,
-    const int32_t *__restrict__ lens, float *__restrict__ kc, float *__restrict__ vc, Dims dm) {
+    const int32_t *__restrict__ lens, const float *__restrict__ comp_k,
+    const float *__restrict__ comp_v, float *__restrict__ kc, float *__restrict__ vc, Dims dm) {
   constexpr int CH = D / 4;
   const int64_t tok0 = (int64_t)blockIdx.x * PAGE;
   const int u = find_unit(offsets, dm.units, tok0);
@@ -144,7 +201,7 @@ __global__ __launch_bounds__(256) void pack_f32_kernel(
   __shared__ int src[PAGE];
   if (tid < PAGE) {
     const int p = local0 + tid;
-    src[tid] = p < len ? (direct ? p : kept[(size_t)u * dm.row_stride + p]) : -1;
+    src[tid] = source_of_slot(p, len, direct, kept + (size_t)u * dm.row_stride, comp_k != nullptr, dm);
   }
   __syncthreads();
   const size_t ubase = (size_t)u * dm.N * D;
@@ -155,6 +212,10 @@ __global__ __launch_bounds__(256) void pack_f32_kernel(
       const size_t off = ubase + (size_t)src[row] * D + ci * 4;
       kv = *reinterpret_cast<const float4 *>(k + off);
       vv = *reinterpret_cast<const float4 *>(v + off);
+    } else if (src[row] <= -2) {
+      const size_t off = ((size_t)u * dm.k + (size_t)(-2 - src[row])) * D + ci * 4;
+      kv = *reinterpret_cast<const float4 *>(comp_k + off);
+      vv = *reinterpret_cast<const float4 *>(comp_v + off);
     }
     const size_t dst = ((size_t)tok0 + row) * D + ci * 4;
     *reinterpret_cast<float4 *>(kc + dst) = kv;
@@ -198,21 +259,37 @@ int launch_layout(const Dims &dm, const uint8_t *mask, int reserve, int64_t capa
   return hip_ok(hipGetLastError());
 }
 
+int launch_group_means(const Dims &dm, int dtype, const void *k, const void *v, const uint8_t *mask,
+                       void *comp_k, void *comp_v, int32_t *kept_idx, hipStream_t s) {
+  const dim3 grid(dm.k, dm.units), block(dm.D);
+  if (dtype == TASKKV_F32)
+    group_mean_kernel<float><<<grid, block, 0, s>>>(static_cast<const float *>(k), static_cast<const float *>(v),
+                                                   mask, static_cast<float *>(comp_k),
+                                                   static_cast<float *>(comp_v), kept_idx, dm);
+  else
+    group_mean_kernel<uint16_t><<<grid, block, 0, s>>>(
+        static_cast<const uint16_t *>(k), static_cast<const uint16_t *>(v), mask,
+        static_cast<uint16_t *>(comp_k), static_cast<uint16_t *>(comp_v), kept_idx, dm);
+  return hip_ok(hipGetLastError());
+}
+
 int launch_pack(const Dims &dm, int dtype, const void *k, const void *v, const int32_t *kept_idx,
-                const uint8_t *mask, const int64_t *offsets, const int32_t *lens, void *k_cache,
-                void *v_cache, int64_t capacity, hipStream_t s) {
+                const uint8_t *mask, const int64_t *offsets, const int32_t *lens, const void *comp_k,
+                const void *comp_v, void *k_cache, void *v_cache, int64_t capacity, hipStream_t s) {
   const dim3 grid((unsigned)(capacity / PAGE)), block(256);
   if (grid.x == 0) return TASKKV_OK;
   if (dtype == TASKKV_F32) {
     auto kk = static_cast<const float *>(k), vv = static_cast<const float *>(v);
     auto kc = static_cast<float *>(k_cache), vc = static_cast<float *>(v_cache);
-    if (dm.D == 64) pack_f32_kernel<64><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, kc, vc, dm);
-    else pack_f32_kernel<128><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, kc, vc, dm);
+    auto ck = static_cast<const float *>(comp_k), cv = static_cast<const float *>(comp_v);
+    if (dm.D == 64) pack_f32_kernel<64><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, ck, cv, kc, vc, dm);
+    else pack_f32_kernel<128><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, ck, cv, kc, vc, dm);
   } else {
     auto kk = static_cast<const uint16_t *>(k), vv = static_cast<const uint16_t *>(v);
     auto kc = static_cast<uint16_t *>(k_cache), vc = static_cast<uint16_t *>(v_cache);
-    if (dm.D == 64) pack_bf16_kernel<64><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, kc, vc, dm);
-    else pack_bf16_kernel<128><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, kc, vc, dm);
+    auto ck = static_cast<const uint16_t *>(comp_k), cv = static_cast<const uint16_t *>(comp_v);
+    if (dm.D == 64) pack_bf16_kernel<64><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, ck, cv, kc, vc, dm);
+    else pack_bf16_kernel<128><<<grid, block, 0, s>>>(kk, vv, kept_idx, mask, offsets, lens, ck, cv, kc, vc, dm);
   }
   return hip_ok(hipGetLastError());
 }

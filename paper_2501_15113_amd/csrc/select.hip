@@ -48,12 +48,13 @@ __global__ void pool_kernel(const double *__restrict__ c, double *__restrict__ p
 
 // One block per unit.  Picks the `count` largest scores inside [lo, hi) by
 // (score desc, index asc) with an 8-bit radix select on the 64-bit patterns,
-// then writes  [0, prefix) ++ picks ascending ++ [N - suffix, N)  and pads the
-// row with -1.  Units flagged in `skip` get an all -1 row.
+// then writes  [0, prefix) ++ picks ascending ++ (gap slots left for the caller)
+// ++ [N - suffix, N)  and pads the row with -1.  Units flagged in `skip` get an
+// all -1 row.
 __global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__ scores,
                                                       const uint8_t *__restrict__ skip, int skip_all,
                                                       int N, int lo, int hi, int count, int prefix,
-                                                      int suffix, int32_t *__restrict__ out,
+                                                      int gap, int suffix, int32_t *__restrict__ out,
                                                       int out_stride) {
   const int unit = blockIdx.x, tid = threadIdx.x;
   int32_t *orow = out + (size_t)unit * out_stride;
@@ -113,8 +114,8 @@ __global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__
     }
   }
   for (int i = tid; i < prefix; i += 1024) orow[i] = i;
-  for (int i = tid; i < suffix; i += 1024) orow[prefix + count + i] = N - suffix + i;
-  for (int i = prefix + count + suffix + tid; i < out_stride; i += 1024) orow[i] = -1;
+  for (int i = tid; i < suffix; i += 1024) orow[prefix + count + gap + i] = N - suffix + i;
+  for (int i = prefix + count + gap + suffix + tid; i < out_stride; i += 1024) orow[i] = -1;
 }
 
 __device__ __forceinline__ double elem_to_double(float x) { return (double)x; }
@@ -191,10 +192,10 @@ __global__ __launch_bounds__(256) void dist_mask_kernel(const double *__restrict
 }
 
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
-                  int count, int prefix, int suffix, int32_t *out, int out_stride, int skip_all,
+                  int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
                   hipStream_t s) {
   select_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, skip_mask, skip_all, dm.N, lo, hi, count,
-                                                     prefix, suffix, out, out_stride);
+                                                     prefix, gap, suffix, out, out_stride);
   return hip_ok(hipGetLastError());
 }
 

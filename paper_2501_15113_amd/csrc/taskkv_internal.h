@@ -19,6 +19,7 @@ struct Dims {
   int B, Hq, Hkv, G, D, N, L, T;  // T = min(top_t, N)
   int s1, s2, k;                  // k already clipped to the middle
   int n_het, add_centre, pool;
+  int pack_mode;                  // taskkv_pack_mode
   int Rtot;                       // window rows per unit, G*L
   int R, Rpad;                    // rows of the group being scored, and padded to 32
   int row0, n_keys, accumulate;   // first row of the group, keys it can see, add to C instead of storing
@@ -71,7 +72,7 @@ int score_rows_padded(const Dims &dm);
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
                   double *stats, double *scores, hipStream_t s);
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
-                  int count, int prefix, int suffix, int32_t *out, int out_stride, int skip_all,
+                  int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
                   hipStream_t s);
 int launch_pool(const Dims &dm, const double *scores, double *pooled, hipStream_t s);
 int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const void *v,
@@ -80,8 +81,10 @@ int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const vo
 int launch_layout(const Dims &dm, const uint8_t *mask, int reserve, int64_t capacity, int64_t *offsets,
                   int32_t *lens, int *d_err, hipStream_t s);
 int launch_pack(const Dims &dm, int dtype, const void *k, const void *v, const int32_t *kept_idx,
-                const uint8_t *mask, const int64_t *offsets, const int32_t *lens, void *k_cache,
-                void *v_cache, int64_t capacity, hipStream_t s);
+                const uint8_t *mask, const int64_t *offsets, const int32_t *lens, const void *comp_k,
+                const void *comp_v, void *k_cache, void *v_cache, int64_t capacity, hipStream_t s);
+int launch_group_means(const Dims &dm, int dtype, const void *k, const void *v, const uint8_t *mask,
+                       void *comp_k, void *comp_v, int32_t *kept_idx, hipStream_t s);
 int launch_export(const Dims &dm, int dtype, const void *k_cache, const void *v_cache,
                   const int64_t *offsets, void *k_rows, void *v_rows, int64_t capacity, hipStream_t s);
 int launch_append(const Dims &dm, int dtype, const void *k_new, const void *v_new, void *k_cache,

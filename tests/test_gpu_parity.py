@@ -128,6 +128,20 @@ def test_full_window_reproduces_exact_semantic_vector():
         np.testing.assert_allclose(sem[h], orc.full_semantic_vector(q[h], k[h], v[h]), rtol=1e-9, atol=1e-13)
 
 
+# ------------------------------------------------------------------ ablation pack modes (Sec. 6.2)
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("kw", [
+    dict(),                                                            # bf16, ragged N
+    dict(dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=4, ctx_len=900, recipe="gauss", offset=3.0),
+    dict(ctx_len=2000, n_middle=7, n_sink=0),                          # uneven groups, no sinks
+    dict(ctx_len=300, n_middle=5000),                                  # more groups than middle tokens
+    dict(ctx_len=512, n_sink=100, n_recent=300, n_middle=200),         # no-cache mode covers N
+])
+def test_compensation_modes(mode, kw):
+    wl = small_workload(name=f"pack{mode}", wid=170 + mode, **kw)
+    run_layer(wl, check_batches=(0, 1), cfg_override=dict(pack_mode=mode))
+
+
 def test_softmax_scale_override():
     run_layer(small_workload(name="scale", wid=150), cfg_override=dict(softmax_scale=0.05))
 
