@@ -195,15 +195,22 @@ __global__ __launch_bounds__(256) void decode_stream_kernel(
   flush();
 }
 
+#ifndef TASKKV_COMBINE_UN
+#define TASKKV_COMBINE_UN 4
+#endif
+
 // Merge the partials of one (batch, query head): slots wave + unit for the waves
-// whose page ranges meet the unit, ascending.  Same lane layout and fixed
-// summation order as the chunk-grid combine.
+// whose page ranges meet the unit.  One block of 1024 threads = NCL slot lanes x
+// D/4 channel lanes; slot lane c owns slots c, c+NCL, ... and requests UN of
+// them at once (the partials sit in L2; the kernel is latency bound), reduces
+// them with its own running maximum, and the NCL lane results are merged in
+// lane order -- one trip to memory, fixed summation order, reproducible.
 template <int D>
 __global__ __launch_bounds__(1024) void combine_stream_kernel(
     const float *__restrict__ pm, const float *__restrict__ pl, const float *__restrict__ po,
     const int32_t *__restrict__ page_prefix, const int32_t *__restrict__ eff_len,
     int32_t *__restrict__ lens_out, float *__restrict__ out, int n_units, int Hq, int Hkv, int G, int W) {
-  constexpr int DL = D / 4, NCL = 1024 / DL, UN = 4;
+  constexpr int DL = D / 4, NCL = 1024 / DL, UN = TASKKV_COMBINE_UN;
   const int bq = blockIdx.x, tid = threadIdx.x;
   const int b = bq / Hq, hq = bq % Hq, h = hq / G, slot = hq % G;
   const int u = b * Hkv + h;
@@ -218,26 +225,18 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
   const int nparts = wb - wa + 1;
   const size_t slot0 = (size_t)wa + u;
   const int dl = tid % DL, cl = tid / DL;
-  __shared__ float red_m[16];
   __shared__ float4 red_o[NCL][DL];
-  __shared__ float red_l[NCL];
+  __shared__ float red_m[NCL], red_l[NCL];
   // a wave between the first and last owner wrote a partial unless its page range is empty
+  const bool dense = T >= W;   // then every wave owns at least one page (skips the 64-bit divisions)
   auto has_pages = [&](int i) {
+    if (i >= nparts) return false;
+    if (dense) return true;
     const int64_t wv = wa + i;
-    return i < nparts && wv * T / W < (wv + 1) * T / W;
+    return wv * T / W < (wv + 1) * T / W;
   };
-  float M = -INFINITY;
-  for (int i = tid; i < nparts; i += 1024)
-    if (has_pages(i)) M = fmaxf(M, pm[(slot0 + i) * G + slot]);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-  if ((tid & 63) == 0) red_m[tid >> 6] = M;
-  __syncthreads();
-  M = red_m[0];
-#pragma unroll
-  for (int r = 1; r < 16; ++r) M = fmaxf(M, red_m[r]);
+  float m_run = -INFINITY, l_run = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  float lacc = 0.f;
   for (int i0 = cl; i0 < nparts; i0 += NCL * UN) {
     float4 o[UN];
     float pmv[UN], plv[UN];
@@ -250,24 +249,37 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
       plv[r] = ok ? pl[pi] : 0.f;
       o[r] = ok ? *reinterpret_cast<const float4 *>(po + pi * D + 4 * dl) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    float m_new = m_run;
 #pragma unroll
-    for (int r = 0; r < UN; ++r) {
-      const float wgt = __builtin_amdgcn_exp2f(pmv[r] - M);
-      acc.x += o[r].x * wgt; acc.y += o[r].y * wgt; acc.z += o[r].z * wgt; acc.w += o[r].w * wgt;
-      lacc += plv[r] * wgt;
+    for (int r = 0; r < UN; ++r) m_new = fmaxf(m_new, pmv[r]);
+    if (m_new > -INFINITY) {
+      const float a = __builtin_amdgcn_exp2f(m_run - m_new);
+      acc.x *= a; acc.y *= a; acc.z *= a; acc.w *= a;
+      l_run *= a;
+#pragma unroll
+      for (int r = 0; r < UN; ++r) {
+        const float wgt = __builtin_amdgcn_exp2f(pmv[r] - m_new);
+        acc.x += o[r].x * wgt; acc.y += o[r].y * wgt; acc.z += o[r].z * wgt; acc.w += o[r].w * wgt;
+        l_run += plv[r] * wgt;
+      }
+      m_run = m_new;
     }
   }
   red_o[cl][dl] = acc;
-  if (dl == 0) red_l[cl] = lacc;
+  if (dl == 0) { red_m[cl] = m_run; red_l[cl] = l_run; }
   __syncthreads();
   if (tid < DL) {
-    float4 o = red_o[0][tid];
-    float L = red_l[0];
+    float M = red_m[0];
 #pragma unroll
-    for (int cc = 1; cc < NCL; ++cc) {
+    for (int cc = 1; cc < NCL; ++cc) M = fmaxf(M, red_m[cc]);
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    float L = 0.f;
+#pragma unroll
+    for (int cc = 0; cc < NCL; ++cc) {
+      const float wgt = __builtin_amdgcn_exp2f(red_m[cc] - M);   // 0 for lanes that saw no slot
       const float4 x = red_o[cc][tid];
-      o.x += x.x; o.y += x.y; o.z += x.z; o.w += x.w;
-      L += red_l[cc];
+      o.x += x.x * wgt; o.y += x.y * wgt; o.z += x.z * wgt; o.w += x.w * wgt;
+      L += red_l[cc] * wgt;
     }
     const float inv = 1.f / L;
     *reinterpret_cast<float4 *>(out + (size_t)bq * D + 4 * tid) = make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
