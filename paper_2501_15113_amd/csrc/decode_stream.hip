@@ -29,8 +29,13 @@ __device__ __forceinline__ int owner_of_page(int64_t p, int64_t T, int W) {
   return (int)(((p + 1) * W - 1) / T);
 }
 
+#ifndef TASKKV_STREAM_WAVES_PER_SIMD
+#define TASKKV_STREAM_WAVES_PER_SIMD 1
+#endif
+
 template <int D, int NP, bool NT>
-__global__ __launch_bounds__(256) void decode_stream_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TASKKV_STREAM_WAVES_PER_SIMD)))
+void decode_stream_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_new,
     const uint16_t *__restrict__ v_new, uint4 *kc, uint4 *vc, const int64_t *__restrict__ offsets,
     const int32_t *__restrict__ lens, int32_t *__restrict__ eff_len, int32_t *__restrict__ page_prefix,
@@ -126,10 +131,18 @@ __global__ __launch_bounds__(256) void decode_stream_kernel(
 
   // ---- ring of NP pages in flight
   PageRegs<D> ring[NP];
-  int u_ld = u0;           // unit of the next page to request
+  // unit of the next page to request; its first page, end page and token offset
+  // stay in registers so that a request costs no memory access of its own
+  int u_ld = u0, pref_ld = s_pref[u0], next_ld = s_pref[u0 + 1];
+  int64_t off_ld = offsets[u0];
   auto request = [&](int gp, PageRegs<D> &r) {
-    while (gp >= s_pref[u_ld + 1]) ++u_ld;
-    const size_t tok = (size_t)offsets[u_ld] + (size_t)(gp - s_pref[u_ld]) * PAGE;
+    while (gp >= next_ld) {
+      ++u_ld;
+      pref_ld = next_ld;
+      next_ld = s_pref[u_ld + 1];
+      off_ld = offsets[u_ld];
+    }
+    const size_t tok = (size_t)off_ld + (size_t)(gp - pref_ld) * PAGE;
     load_page<D, NT>(kc + tok * (D / 8), vc + tok * (D / 8), l, r);
   };
 #pragma unroll
