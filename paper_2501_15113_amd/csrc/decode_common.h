@@ -131,5 +131,66 @@ __device__ __forceinline__ void attend_page(const PageRegs<D> &r, const Frag (&q
   }
 }
 
+// The same page in two halves, so that the caller can request the next K tiles
+// as soon as the QK^T MFMAs have consumed the current ones.
+template <int D>
+__device__ __forceinline__ void page_scores(const PageRegs<D> &r, const Frag (&qv)[D / 32], floatx4 (&s)[2]) {
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    s[sb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk)
+      s[sb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.kr[sb][kk].b, qv[kk].b, s[sb], 0, 0, 0);
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void page_values(const PageRegs<D> &r, const floatx4 (&s)[2], int tok_base,
+                                            int n_tok, int g, float scale_log2, float &m_run,
+                                            float &l_run, floatx4 (&acc)[D / 16]) {
+  float sv[8];
+  float mloc = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int t = tok_base + 16 * (e >> 2) + 4 * g + (e & 3);
+    sv[e] = t < n_tok ? s[e >> 2][e & 3] * scale_log2 : -INFINITY;
+    mloc = fmaxf(mloc, sv[e]);
+  }
+  mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+  mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+  const float m_new = fmaxf(m_run, mloc);  // finite: the page holds >= 1 token
+  const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+  float lsum = 0.f;
+  Frag ph, plo;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float p = __builtin_amdgcn_exp2f(sv[e] - m_new);
+    lsum += p;
+    const __bf16 hi = (__bf16)p;
+    ph.b[e] = hi;
+    plo.b[e] = (__bf16)(p - (float)hi);
+  }
+  l_run = l_run * alpha + lsum;
+  m_run = m_new;
+#pragma unroll
+  for (int mb = 0; mb < D / 16; ++mb) {
+    acc[mb] *= alpha;
+    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, ph.b, acc[mb], 0, 0, 0);
+    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, plo.b, acc[mb], 0, 0, 0);
+  }
+}
+
+template <int D, bool NT>
+__device__ __forceinline__ void load_page_k(const uint4 *kp, int l, PageRegs<D> &r) {
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) r.kr[sb][kk].v = stream_load<NT>(kp + sb * 2 * D + kk * 64 + l);
+}
+template <int D, bool NT>
+__device__ __forceinline__ void load_page_v(const uint4 *vp, int l, PageRegs<D> &r) {
+#pragma unroll
+  for (int mb = 0; mb < D / 16; ++mb) r.vr[mb].v = stream_load<NT>(vp + mb * 64 + l);
+}
 
 }  // namespace taskkv

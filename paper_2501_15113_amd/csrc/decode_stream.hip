@@ -29,6 +29,11 @@ __device__ __forceinline__ int owner_of_page(int64_t p, int64_t T, int W) {
   return (int)(((p + 1) * W - 1) / T);
 }
 
+// Request the next K tiles between the QK^T MFMAs and the softmax of the current page.
+#ifndef TASKKV_STREAM_SPLIT
+#define TASKKV_STREAM_SPLIT 1
+#endif
+
 #ifndef TASKKV_STREAM_WAVES_PER_SIMD
 #define TASKKV_STREAM_WAVES_PER_SIMD 1
 #endif
@@ -135,14 +140,17 @@ void decode_stream_kernel(
   // stay in registers so that a request costs no memory access of its own
   int u_ld = u0, pref_ld = s_pref[u0], next_ld = s_pref[u0 + 1];
   int64_t off_ld = offsets[u0];
-  auto request = [&](int gp, PageRegs<D> &r) {
+  auto locate = [&](int gp) {   // token slot of global page gp (pages are requested in ascending order)
     while (gp >= next_ld) {
       ++u_ld;
       pref_ld = next_ld;
       next_ld = s_pref[u_ld + 1];
       off_ld = offsets[u_ld];
     }
-    const size_t tok = (size_t)off_ld + (size_t)(gp - pref_ld) * PAGE;
+    return (size_t)off_ld + (size_t)(gp - pref_ld) * PAGE;
+  };
+  auto request = [&](int gp, PageRegs<D> &r) {
+    const size_t tok = locate(gp);
     load_page<D, NT>(kc + tok * (D / 8), vc + tok * (D / 8), l, r);
   };
 #pragma unroll
@@ -200,8 +208,21 @@ void decode_stream_kernel(
           if (u_at >= 0) flush();
           enter_unit(gp);
         }
+#if TASKKV_STREAM_SPLIT
+        floatx4 sc[2];
+        page_scores<D>(ring[s], qv, sc);
+        size_t tok_next = 0;
+        const bool more = gp + NP < p1;
+        if (more) {
+          tok_next = locate(gp + NP);
+          load_page_k<D, NT>(kc + tok_next * (D / 8), l, ring[s]);
+        }
+        page_values<D>(ring[s], sc, (gp - pref_at) * PAGE, n_valid, g, scale_log2, m_run, l_run, acc);
+        if (more) load_page_v<D, NT>(vc + tok_next * (D / 8), l, ring[s]);
+#else
         attend_page<D>(ring[s], qv, (gp - pref_at) * PAGE, n_valid, g, scale_log2, m_run, l_run, acc);
         if (gp + NP < p1) request(gp + NP, ring[s]);
+#endif
       }
     }
   }
