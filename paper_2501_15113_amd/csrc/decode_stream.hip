@@ -51,18 +51,30 @@ void decode_stream_kernel(
   const int hg = blockIdx.y;
   const bool want_app = k_new != nullptr;
 
-  // ---- prologue: page prefix over units, shared by the block's four waves
+  // ---- prologue: one trip to memory for lens / offsets, then everything the
+  // waves need about the units (first page, token offset, length) lives in LDS
   __shared__ int s_pref[MAXU + 1];
+  __shared__ int s_len[MAXU];        // length used by this step, bit 31 = a token is appended
+  __shared__ int s_off[MAXU];        // offsets / CHUNK
   __shared__ int s_wtot[4];
   const int upt = (n_units + 255) / 256;
   const int first = tid * upt;
+  const bool publish = blockIdx.x == 0 && hg == 0;
   int sum = 0;
   for (int i = 0; i < upt; ++i) {
     const int u = first + i;
     if (u < n_units) {
       const int len_old = lens[u];
-      const int app = (want_app && len_old < (int)(offsets[u + 1] - offsets[u])) ? 1 : 0;
-      sum += (len_old + app + PAGE - 1) / PAGE;
+      const int64_t o0 = offsets[u], o1 = offsets[u + 1];
+      const bool can = want_app && len_old < (int)(o1 - o0);
+      const int len = len_old + (can ? 1 : 0);
+      s_len[u] = len | (can ? (int)0x80000000 : 0);
+      s_off[u] = (int)(o0 / CHUNK);
+      sum += (len + PAGE - 1) / PAGE;
+      if (publish) {
+        eff_len[u] = len;
+        if (want_app && !can) atomicOr(d_err, 1);
+      }
     }
   }
   int incl = sum;
@@ -75,20 +87,12 @@ void decode_stream_kernel(
   __syncthreads();
   int run = incl - sum;
   for (int ww = 0; ww < w; ++ww) run += s_wtot[ww];
-  const bool publish = blockIdx.x == 0 && hg == 0;
   for (int i = 0; i < upt; ++i) {
     const int u = first + i;
     if (u < n_units) {
-      const int len_old = lens[u];
-      const bool can = want_app && len_old < (int)(offsets[u + 1] - offsets[u]);
-      const int len = len_old + (can ? 1 : 0);
       s_pref[u] = run;
-      if (publish) {
-        eff_len[u] = len;
-        page_prefix[u] = run;
-        if (want_app && !can) atomicOr(d_err, 1);
-      }
-      run += (len + PAGE - 1) / PAGE;
+      if (publish) page_prefix[u] = run;
+      run += ((s_len[u] & 0x7fffffff) + PAGE - 1) / PAGE;
     }
   }
   if (tid == 255) {
@@ -118,12 +122,12 @@ void decode_stream_kernel(
   if (want_app) {
     uint16_t *kc16 = reinterpret_cast<uint16_t *>(kc), *vc16 = reinterpret_cast<uint16_t *>(vc);
     for (int u = u0; u < n_units && s_pref[u] < p1; ++u) {
-      const int len_old = lens[u];
-      const int64_t base = offsets[u];
-      if (len_old >= (int)(offsets[u + 1] - base)) continue;
+      const int sl = s_len[u];
+      if (sl >= 0) continue;                     // nothing appended to this unit
+      const int len_old = (sl & 0x7fffffff) - 1;
       const int ap = s_pref[u] + len_old / PAGE;
       if (ap < p0 || ap >= p1) continue;
-      const int64_t page = base + (len_old / PAGE) * PAGE;
+      const int64_t page = (int64_t)s_off[u] * CHUNK + (len_old / PAGE) * PAGE;
       const int t32 = len_old % PAGE, sb = t32 >> 4, r = t32 & 15;
       const int ga = (t32 & 15) >> 2, ea = 4 * (t32 >> 4) + (t32 & 3);
       for (int e = l; e < D; e += 64) {
@@ -139,13 +143,13 @@ void decode_stream_kernel(
   // unit of the next page to request; its first page, end page and token offset
   // stay in registers so that a request costs no memory access of its own
   int u_ld = u0, pref_ld = s_pref[u0], next_ld = s_pref[u0 + 1];
-  int64_t off_ld = offsets[u0];
+  int64_t off_ld = (int64_t)s_off[u0] * CHUNK;
   auto locate = [&](int gp) {   // token slot of global page gp (pages are requested in ascending order)
     while (gp >= next_ld) {
       ++u_ld;
       pref_ld = next_ld;
       next_ld = s_pref[u_ld + 1];
-      off_ld = offsets[u_ld];
+      off_ld = (int64_t)s_off[u_ld] * CHUNK;
     }
     return (size_t)off_ld + (size_t)(gp - pref_ld) * PAGE;
   };
@@ -182,9 +186,7 @@ void decode_stream_kernel(
     u_at = u;
     pref_at = s_pref[u];
     pref_next = s_pref[u + 1];
-    const int len_old = lens[u];
-    const bool can = want_app && len_old < (int)(offsets[u + 1] - offsets[u]);
-    n_valid = len_old + (can ? 1 : 0);
+    n_valid = s_len[u] & 0x7fffffff;
     const int b = u / Hkv, h = u % Hkv;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qv[kk].u = make_uint4(0, 0, 0, 0);
