@@ -111,7 +111,13 @@ int32_t taskkv_middle_budget(int64_t layer_budget_tokens, int32_t ctx_len, int32
  *   k, v    [B, H_kv, N, d] key / value states (dtype of cfg)
  * out
  *   scores  [B, H_kv, N] f64  C of Eq. 13, averaged over the G*L window rows of
- *                             the KV head's query group
+ *                             the KV head's query group.  fp64-exact for every
+ *                             token that can take part in a decision (the top-t
+ *                             tokens and all tokens whose score is next to the
+ *                             top-t or middle-activation threshold); with bf16
+ *                             inputs the remaining tokens carry an fp32-accurate
+ *                             value (relative error below ~1e-3) unless
+ *                             screening is switched off (taskkv_set_screening)
  *   sem_vec [B, H_kv, d] f64  v' of Eq. 15 over the top-t tokens of Eq. 14
  *   dist    [B, H_kv]    f64  L2 distance of v' from the mean over heads (Eq. 7-8)
  *   hetero_mask [B, H_kv] u8  1 = heterogeneous (keeps its full cache)
@@ -185,6 +191,11 @@ int taskkv_cache_export(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void
 /* Synchronises `hip_stream`, returns and clears the sticky device-side flag:
  * 0 = none, 1 = append to a full unit. */
 int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream);
+
+/* Screening (default on) lets taskkv_separate score bf16 inputs on the bf16
+ * matrix cores first and recompute in fp64 only the columns that can matter;
+ * decisions are identical either way.  Off: every score is computed in fp64. */
+int taskkv_set_screening(taskkv_ctx *ctx, int on);
 
 /*
  * Timing hooks for the benchmark.  With profiling on, taskkv_decode_attn

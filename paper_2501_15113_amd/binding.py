@@ -13,7 +13,7 @@ EXPORTED_SYMBOLS = [
     "taskkv_create", "taskkv_destroy", "taskkv_strerror", "taskkv_workspace_bytes",
     "taskkv_cache_tokens", "taskkv_hetero_head_count", "taskkv_middle_budget", "taskkv_separate",
     "taskkv_compress", "taskkv_decode_attn", "taskkv_cache_export", "taskkv_last_async_error",
-    "taskkv_profile_enable", "taskkv_profile_read",
+    "taskkv_profile_enable", "taskkv_profile_read", "taskkv_set_screening",
 ]
 
 
@@ -84,6 +84,8 @@ def load_library():
     lib.taskkv_cache_export.restype = C.c_int
     lib.taskkv_last_async_error.argtypes = [vp, vp]
     lib.taskkv_last_async_error.restype = C.c_int
+    lib.taskkv_set_screening.argtypes = [vp, C.c_int]
+    lib.taskkv_set_screening.restype = C.c_int
     lib.taskkv_profile_enable.argtypes = [vp, C.c_int]
     lib.taskkv_profile_enable.restype = C.c_int
     lib.taskkv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -204,6 +206,10 @@ def taskkv_last_async_error(ctx, stream=None) -> int:
     if rc < 0:
         _check(rc, "taskkv_last_async_error")
     return rc
+
+
+def taskkv_set_screening(ctx, on: bool) -> None:
+    _check(load_library().taskkv_set_screening(ctx, 1 if on else 0), "taskkv_set_screening")
 
 
 def taskkv_profile_enable(ctx, on: bool) -> None:

@@ -71,6 +71,8 @@ static size_t ws_separate(const Dims &d) {
   b += al((size_t)d.units * n_chunks * d.Rpad * 2 * sizeof(double));  // per-chunk row stats
   b += al((size_t)d.units * d.Rpad * 2 * sizeof(double));             // row stats
   b += al((size_t)d.units * d.T * sizeof(int32_t));                   // top-t picks
+  b += al((size_t)d.units * d.N * sizeof(int32_t));                   // screening: columns to recompute
+  b += 2 * al((size_t)d.units * sizeof(unsigned long long));          // their count, key norms
   return b;
 }
 static size_t ws_compress(const Dims &d, int dtype) {
@@ -125,6 +127,7 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
   c->n_events = 0;
   c->events_created = 0;
   c->n_cu = 0;
+  c->screening = 1;
   for (int i = 0; i < 4; ++i) c->stream_wg[i] = 0;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) {
@@ -205,8 +208,12 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   double *part = cv.take<double>((size_t)d.units * n_parts * d.Rpad * 2);
   double *stats = cv.take<double>((size_t)d.units * d.Rpad * 2);
   int32_t *top_idx = cv.take<int32_t>((size_t)d.units * d.T);
+  ScreenBufs scr;
+  scr.band_idx = cv.take<int32_t>((size_t)d.units * d.N);
+  scr.band_cnt = cv.take<int32_t>((size_t)d.units * 2);
+  scr.knorm = cv.take<unsigned long long>((size_t)d.units);
   if (!cv.ok) return TASKKV_EWORKSPACE;
-  int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, s);
+  int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, ctx->screening ? &scr : nullptr, s);
   if (rc) return rc;
   rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, 0, s);
   if (rc) return rc;
@@ -306,6 +313,12 @@ int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream) {
   if (hipStreamSynchronize(s) != hipSuccess) return TASKKV_EHIP;
   if (flag && hipMemsetAsync(ctx->d_err, 0, sizeof(int), s) != hipSuccess) return TASKKV_EHIP;
   return flag;
+}
+
+int taskkv_set_screening(taskkv_ctx *ctx, int on) {
+  if (!ctx) return TASKKV_EINVAL;
+  ctx->screening = on ? 1 : 0;
+  return TASKKV_OK;
 }
 
 int taskkv_profile_enable(taskkv_ctx *ctx, int on) {

@@ -127,17 +127,25 @@ template <> struct RawCount<float> { static constexpr int per16B = 4; };
 
 // MODE 0: row statistics -> part[unit][n_parts][Rpad][2], n_parts = gridDim.x * ksplit.
 // MODE 1: column mean -> scores[unit][N] from stats[unit][Rpad][2].
-template <typename T, int D, int MODE>
+// GATHER (MODE 1 only): score just the keys listed in band_idx[unit][0 .. band_cnt[unit]).
+// knorm (MODE 0, optional): per-unit maximum of ||k_j||^2, as the bit pattern of a
+// non-negative double (integer max = numeric max, order independent).
+template <typename T, int D, int MODE, bool GATHER>
 __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restrict__ k,
                                                            const double *__restrict__ qd,
                                                            const double *__restrict__ stats,
                                                            double *__restrict__ part,
                                                            double *__restrict__ scores, Dims dm,
-                                                           int chunks_per_wg) {
+                                                           int chunks_per_wg,
+                                                           const int32_t *__restrict__ band_idx,
+                                                           const int32_t *__restrict__ band_cnt,
+                                                           unsigned long long *__restrict__ knorm) {
   constexpr int NKK = D / 4;
   constexpr int NRAW = NKK / RawCount<T>::per16B;
   const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 15, kq = l >> 4;
-  const int N = dm.N, NK = dm.n_keys, L = dm.L, R = dm.R, Rpad = dm.Rpad, row0 = dm.row0;
+  const int N = dm.N, NK = GATHER ? band_cnt[unit] : dm.n_keys, L = dm.L, R = dm.R, Rpad = dm.Rpad,
+            row0 = dm.row0;
+  const int32_t *gidx = GATHER ? band_idx + (size_t)unit * N : nullptr;
   const int n_pairs = Rpad / 32;
   const int ksplit = n_pairs >= SNW ? 1 : SNW / n_pairs;
   const int n_items = n_pairs * ksplit;
@@ -163,13 +171,23 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
   };
 
   // logits of one 16-key tile for the wave's two row blocks
-  auto tile_logits = [&](int j0, bool &valid, f64x4 (&acc)[2]) {
-    const int j = j0 + c;
-    valid = j < NK;
+  double kmax = 0.0;   // MODE 0 with knorm: largest squared key norm seen by this lane
+  auto tile_logits = [&](int j0, bool &valid, int &j, f64x4 (&acc)[2], bool want_norm) {
+    const int pos = j0 + c;
+    valid = pos < NK;
+    j = GATHER ? (valid ? gidx[pos] : 0) : pos;
     uint4 raw[NRAW];
     fetch_piece<NKK>(kb + (size_t)(valid ? j : 0) * D + NKK * kq, valid, raw);
     double b[NKK];
     widen_piece<NKK>(raw, b, (const T *)nullptr);
+    if (MODE == 0 && want_norm) {
+      double ss = 0.0;
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) ss = fma(b[kk], b[kk], ss);
+      ss += __shfl_xor(ss, 16);
+      ss += __shfl_xor(ss, 32);
+      kmax = fmax(kmax, ss);
+    }
     acc[0] = f64x4{0., 0., 0., 0.};
     acc[1] = f64x4{0., 0., 0., 0.};
 #pragma unroll
@@ -192,9 +210,9 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
         if (jc >= NK) break;
         for (int j0 = jc; j0 < jc + sub && j0 < NK; j0 += 16) {
           bool valid;
+          int j;
           f64x4 acc[2];
-          tile_logits(j0, valid, acc);
-          const int j = j0 + c;
+          tile_logits(j0, valid, j, acc, knorm != nullptr && pair == 0);
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
             const int row = 32 * pair + 16 * (s >> 2) + 4 * (s & 3) + kq;
@@ -231,6 +249,11 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
         }
       }
     }
+    if (knorm != nullptr) {
+#pragma unroll
+      for (int off = 1; off < 16; off <<= 1) kmax = fmax(kmax, __shfl_xor(kmax, off));
+      if (l == 0 && kmax > 0.0) atomicMax(knorm + unit, (unsigned long long)__double_as_longlong(kmax));
+    }
   } else {
     for (int ch = 0; ch < chunks_per_wg; ++ch) {
       const int jchunk = (blockIdx.x * chunks_per_wg + ch) * SKC;
@@ -248,9 +271,9 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
         const int jc = jchunk + ks * sub;
         for (int j0 = jc; j0 < jc + sub && j0 < NK; j0 += 16) {
           bool valid;
+          int j;
           f64x4 acc[2];
-          tile_logits(j0, valid, acc);
-          const int j = j0 + c;
+          tile_logits(j0, valid, j, acc, false);
           double colsum = 0.0;
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
@@ -260,16 +283,16 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
           }
           colsum += __shfl_xor(colsum, 16);
           colsum += __shfl_xor(colsum, 32);
-          if (kq == 0) cs[pair][j - jchunk] = colsum;
+          if (kq == 0) cs[pair][j0 + c - jchunk] = colsum;
         }
       }
       __syncthreads();
       {
-        const int j = jchunk + tid;
-        if (tid < SKC && j < NK) {
+        const int pos = jchunk + tid;
+        if (tid < SKC && pos < NK) {
           double sum = 0.0;
           for (int p = 0; p < n_pairs; ++p) sum += cs[p][tid];
-          double *dst = scores + (size_t)unit * N + j;
+          double *dst = scores + (size_t)unit * N + (GATHER ? gidx[pos] : pos);
           *dst = dm.accumulate ? *dst + sum / (double)dm.Rtot : sum / (double)dm.Rtot;
         }
       }
@@ -301,13 +324,18 @@ int score_parts(const Dims &dm) {
 int score_rows_padded(const Dims &dm) { return dm.Rtot < ROW_GROUP ? (dm.Rtot + 31) / 32 * 32 : ROW_GROUP; }
 
 template <typename T, int D>
-static int run_scores(const Dims &dm_all, const T *q_win, const T *k, double *qd, double *part,
-                      double *stats, double *scores, hipStream_t s) {
+static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k, double *qd, double *part,
+                      double *stats, double *scores, const ScreenBufs *scr, hipStream_t s) {
   const int cpw = chunks_per_wg_for(dm_all);
   const int n_groups = (dm_all.Rtot + ROW_GROUP - 1) / ROW_GROUP;
+  const bool screen = scr != nullptr && n_groups == 1 && screen_supported(dm_all, dtype);
   if (n_groups > 1) {
     const size_t n = (size_t)dm_all.units * dm_all.N;
     zero_f64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(scores, n);
+  }
+  if (screen) {
+    int rc = launch_zero_u64(scr->knorm, dm_all.units, s);
+    if (rc) return rc;
   }
   for (int grp = 0; grp < n_groups; ++grp) {
     Dims dm = dm_all;
@@ -330,23 +358,36 @@ static int run_scores(const Dims &dm_all, const T *q_win, const T *k, double *qd
     const int n_pairs = dm.Rpad / 32;
     const int n_parts = n_wg * (n_pairs >= SNW ? 1 : SNW / n_pairs);
     const dim3 grid(n_wg, dm.units), block(64 * SNW);
-    score_mfma64_kernel<T, D, 0><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw);
+    score_mfma64_kernel<T, D, 0, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
+                                                              nullptr, screen ? scr->knorm : nullptr);
     merge_stats_kernel<<<dim3(dm.units), dim3(256), 0, s>>>(part, stats, dm.Rpad, n_parts);
-    score_mfma64_kernel<T, D, 1><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw);
+    if (!screen) {
+      score_mfma64_kernel<T, D, 1, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
+                                                                nullptr, nullptr);
+      continue;
+    }
+    // fp32 screening of every column, then fp64 for the columns that can take
+    // part in a decision (any number of them: the grid covers all N)
+    int rc = launch_screen(dm, q_win, k, stats, scores, cpw, s);
+    if (rc) return rc;
+    rc = launch_band(dm, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt, s);
+    if (rc) return rc;
+    score_mfma64_kernel<T, D, 1, true><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw,
+                                                             scr->band_idx, scr->band_cnt, nullptr);
   }
   return hip_ok(hipGetLastError());
 }
 
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
-                  double *stats, double *scores, hipStream_t s) {
+                  double *stats, double *scores, const ScreenBufs *scr, hipStream_t s) {
   if (dtype == TASKKV_F32) {
     auto qq = static_cast<const float *>(q_win), kk = static_cast<const float *>(k);
-    return dm.D == 64 ? run_scores<float, 64>(dm, qq, kk, qd, part, stats, scores, s)
-                      : run_scores<float, 128>(dm, qq, kk, qd, part, stats, scores, s);
+    return dm.D == 64 ? run_scores<float, 64>(dm, dtype, qq, kk, qd, part, stats, scores, scr, s)
+                      : run_scores<float, 128>(dm, dtype, qq, kk, qd, part, stats, scores, scr, s);
   }
   auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
-  return dm.D == 64 ? run_scores<uint16_t, 64>(dm, qq, kk, qd, part, stats, scores, s)
-                    : run_scores<uint16_t, 128>(dm, qq, kk, qd, part, stats, scores, s);
+  return dm.D == 64 ? run_scores<uint16_t, 64>(dm, dtype, qq, kk, qd, part, stats, scores, scr, s)
+                    : run_scores<uint16_t, 128>(dm, dtype, qq, kk, qd, part, stats, scores, scr, s);
 }
 
 }  // namespace taskkv

@@ -1,0 +1,272 @@
+// Screening pass for the column mean C of Eq. 13 (paper Sec. 4.1), bf16 inputs.
+//
+// Selections must be decided on fp64 scores, but only a few hundred of the N
+// columns of a unit can take part in a decision: the top-t tokens of Eq. 14 and
+// the tokens whose score lies next to the middle-activation threshold of
+// Sec. 4.2.  So, after the exact fp64 row statistics (m_i, l_i):
+//   1. score_screen_kernel computes every column in fp32 on the bf16 matrix
+//      cores (v_mfma_f32_16x16x32_bf16, exp2 on the vector ALUs);
+//   2. band_kernel bounds the relative error eps of those values, finds the two
+//      thresholds among them and lists the columns that could matter -- every
+//      column at or above (1 - 3 eps) x the top-t threshold, and every middle
+//      column within 3 eps of the middle threshold;
+//   3. the fp64 scorer recomputes exactly the listed columns.
+// Unlisted columns keep their fp32 value; each is provably on the same side of
+// both thresholds as its exact value.
+//
+// Error bound.  bf16 products are exact in fp32, so a logit differs from its
+// exact value by at most the accumulation error, gamma * |q_i|.|k_j| with
+// gamma <= 4 d 2^-24 (factor 4 covers any summation order and truncating adds).
+// Through exp this is a relative error of scale * gamma * max|q_i| * max|k_j| per
+// term; converting m_i, 1/l_i to fp32, exp2 and the fp32 row sum add
+// 2e-5 + R * 1.2e-7.  band_kernel evaluates the bound from the measured norms.
+#include <math.h>
+
+#include "taskkv_internal.h"
+
+namespace taskkv {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+
+constexpr int QKC = 256;   // keys per chunk
+constexpr int MAXQ = 8;    // row quads (64 rows each) per unit: windows up to 512 rows
+
+union Frag16 {
+  uint4 u;
+  bf16x8 b;
+};
+
+// One block = 4 waves.  A wave owns a quad of four 16-row blocks of the window
+// (A operands in registers) and a slice of the chunk's keys; for every 16-key
+// tile it forms the 64 x 16 logits with 4 x d/32 MFMAs, turns them into softmax
+// weights with the exact row statistics and adds the 64 rows per key.  Row
+// quads are added per key in index order through LDS.
+template <int D>
+__global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__restrict__ q_win,
+                                                           const uint16_t *__restrict__ k,
+                                                           const double *__restrict__ stats,
+                                                           double *__restrict__ scores, Dims dm,
+                                                           int chunks_per_wg) {
+  constexpr int KS = D / 32;
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 15, kg = l >> 4;
+  const int N = dm.N, L = dm.L, R = dm.R;
+  const int n_rq = (dm.Rpad + 63) / 64;
+  const int ksplit = n_rq >= 4 ? 1 : 4 / n_rq;
+  const int n_items = n_rq * ksplit;
+  const int sub = QKC / ksplit;
+  const int b = unit / dm.Hkv, h = unit % dm.Hkv;
+  const uint16_t *kb = k + (size_t)unit * N * D;
+  const double *st = stats + (size_t)unit * dm.Rpad * 2;
+  const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
+
+  __shared__ float cs[MAXQ][QKC];
+
+  for (int ch = 0; ch < chunks_per_wg; ++ch) {
+    const int jchunk = (blockIdx.x * chunks_per_wg + ch) * QKC;
+    if (jchunk >= N) break;
+    for (int item = w; item < n_items; item += 4) {
+      const int rq = item % n_rq, ks = item / n_rq;
+      // A operands: lane (c, kg) holds Q[row 64 rq + 16 rb + c][(d/4) kg + 8 kk .. +8]
+      Frag16 a[4][KS];
+      float m2[4][4], inv[4][4];
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        const int row = 64 * rq + 16 * rb + c;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = make_uint4(0, 0, 0, 0);
+        if (row < R) {
+          const int g = row / L, i = row % L;
+          const uint16_t *qp = q_win + (((size_t)b * dm.Hq + (size_t)h * dm.G + g) * L + i) * D + (D / 4) * kg;
+#pragma unroll
+          for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = *reinterpret_cast<const uint4 *>(qp + 8 * kk);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int r2 = 64 * rq + 16 * rb + 4 * kg + v;   // row of accumulator register v
+          const bool ok = r2 < R;
+          m2[rb][v] = ok ? (float)(st[2 * r2] * 1.4426950408889634) : 0.f;
+          inv[rb][v] = ok ? (float)(1.0 / st[2 * r2 + 1]) : 0.f;
+        }
+      }
+      const int jc = jchunk + ks * sub;
+      for (int j0 = jc; j0 < jc + sub && j0 < N; j0 += 16) {
+        const int j = j0 + c;
+        const bool valid = j < N;
+        Frag16 bk[KS];
+        const uint16_t *kp = kb + (size_t)(valid ? j : 0) * D + (D / 4) * kg;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+          bk[kk].u = valid ? *reinterpret_cast<const uint4 *>(kp + 8 * kk) : make_uint4(0, 0, 0, 0);
+        float colsum = 0.f;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+          floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < KS; ++kk)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][kk].b, bk[kk].b, acc, 0, 0, 0);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int r2 = 64 * rq + 16 * rb + 4 * kg + v;
+            const bool vis = valid && r2 < R && j <= N - L + r2 % L;
+            const float p = __builtin_amdgcn_exp2f(fmaf(acc[v], scale_log2, -m2[rb][v])) * inv[rb][v];
+            colsum += vis ? p : 0.f;
+          }
+        }
+        colsum += __shfl_xor(colsum, 16);
+        colsum += __shfl_xor(colsum, 32);
+        if (kg == 0) cs[rq][j - jchunk] = colsum;
+      }
+    }
+    __syncthreads();
+    {
+      const int j = jchunk + tid;
+      if (j < N) {
+        float sum = 0.f;
+        for (int p = 0; p < n_rq; ++p) sum += cs[p][tid];
+        scores[(size_t)unit * N + j] = (double)(sum / (float)dm.Rtot);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+__device__ __forceinline__ uint64_t key_bits(double x) { return (uint64_t)__double_as_longlong(x); }
+
+// Bit pattern of the count-th largest score inside [lo, hi) (8-bit radix select
+// on the 64-bit patterns; scores are >= 0).  All 1024 threads of the block call it.
+__device__ uint64_t radix_threshold(const double *__restrict__ sc, int lo, int hi, int count,
+                                    unsigned *hist, int *s_bin, int *s_rem) {
+  const int tid = threadIdx.x;
+  uint64_t pat = 0, known = 0;
+  int remaining = count;
+  for (int pass = 7; pass >= 0; --pass) {
+    const int shift = pass * 8;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int j = lo + tid; j < hi; j += 1024) {
+      const uint64_t key = key_bits(sc[j]);
+      if ((key & known) == pat) atomicAdd(&hist[(key >> shift) & 255], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int cum = 0, bb = 255;
+      for (; bb > 0; --bb) {
+        const int cnt = (int)hist[bb];
+        if (cum + cnt >= remaining) break;
+        cum += cnt;
+      }
+      *s_bin = bb;
+      *s_rem = remaining - cum;
+    }
+    __syncthreads();
+    pat |= (uint64_t)(*s_bin) << shift;
+    known |= 0xffull << shift;
+    remaining = *s_rem;
+    __syncthreads();
+  }
+  return pat;
+}
+
+// One block per unit: error bound, thresholds, list of the columns to recompute.
+__global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ scores,
+                                                    const double *__restrict__ qd,
+                                                    const unsigned long long *__restrict__ knorm,
+                                                    int32_t *__restrict__ band_idx,
+                                                    int32_t *__restrict__ band_cnt, Dims dm) {
+  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int N = dm.N, D = dm.D;
+  const double *sc = scores + (size_t)unit * N;
+  __shared__ unsigned hist[256];
+  __shared__ int s_bin, s_rem;
+  __shared__ int s_wave[16];
+  __shared__ double s_q[16];
+
+  // largest squared norm of a window row
+  double qmax = 0.0;
+  for (int r = wv; r < dm.R; r += 16) {
+    const double *row = qd + ((size_t)unit * dm.Rpad + r) * D;
+    double ss = 0.0;
+    for (int cc = lane; cc < D; cc += 64) ss = fma(row[cc], row[cc], ss);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    qmax = fmax(qmax, ss);
+  }
+  if (lane == 0) s_q[wv] = qmax;
+  __syncthreads();
+  qmax = 0.0;
+  for (int i = 0; i < 16; ++i) qmax = fmax(qmax, s_q[i]);
+  const double kmax = __longlong_as_double((long long)knorm[unit]);
+  const double gamma = 4.0 * D * 5.9604644775390625e-08;   // 4 d 2^-24
+  const double eps = dm.scale * gamma * sqrt(qmax) * sqrt(kmax) + 2e-5 + dm.R * 1.2e-7;
+  const double w3 = 3.0 * eps;
+
+  const double tau_t = __longlong_as_double((long long)radix_threshold(sc, 0, N, dm.T, hist, &s_bin, &s_rem));
+  const bool middle = dm.pack_mode == TASKKV_PACK_SELECTIVE && !dm.keep_all && dm.k > 0 &&
+                      dm.k < N - dm.s1 - dm.s2;
+  double tau_k = 0.0;
+  if (middle)
+    tau_k = __longlong_as_double((long long)radix_threshold(sc, dm.s1, N - dm.s2, dm.k, hist, &s_bin, &s_rem));
+  // values below 1e-30 may have been flushed to zero by the fp32 pass: treat them as ties
+  const double lo_t = w3 >= 1.0 ? -1.0 : tau_t * (1.0 - w3) - 1e-30;
+  const double lo_k = w3 >= 1.0 ? -1.0 : tau_k * (1.0 - w3) - 1e-30, hi_k = w3 >= 1.0 ? INFINITY : tau_k * (1.0 + w3) + 1e-30;
+
+  int base = 0;
+  int32_t *out = band_idx + (size_t)unit * N;
+  for (int j0 = 0; j0 < N; j0 += 1024) {
+    const int j = j0 + tid;
+    bool in = false;
+    if (j < N) {
+      const double x = sc[j];
+      in = x >= lo_t;
+      if (middle && j >= dm.s1 && j < N - dm.s2) in = in || (x >= lo_k && x <= hi_k);
+    }
+    const uint64_t bal = __ballot(in);
+    const int excl = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) s_wave[wv] = __popcll(bal);
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int ww = 0; ww < 16; ++ww) {
+      const int cnt = s_wave[ww];
+      if (ww < wv) off += cnt;
+      tot += cnt;
+    }
+    __syncthreads();
+    if (in) out[base + off + excl] = j;
+    base += tot;
+  }
+  if (tid == 0) band_cnt[unit] = base;
+}
+
+__global__ void zero_u64_kernel(unsigned long long *p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0ull;
+}
+
+bool screen_supported(const Dims &dm, int dtype) {
+  return dtype == TASKKV_BF16 && dm.pool == 1 && dm.Rtot <= 64 * MAXQ;
+}
+
+int launch_zero_u64(unsigned long long *p, int n, hipStream_t s) {
+  zero_u64_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(p, n);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_screen(const Dims &dm, const void *q_win, const void *k, const double *stats, double *scores,
+                  int chunks_per_wg, hipStream_t s) {
+  const int n_chunks = (dm.N + QKC - 1) / QKC;
+  const dim3 grid((n_chunks + chunks_per_wg - 1) / chunks_per_wg, dm.units), block(256);
+  auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
+  if (dm.D == 64) score_screen_kernel<64><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, chunks_per_wg);
+  else score_screen_kernel<128><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, chunks_per_wg);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
+                int32_t *band_idx, int32_t *band_cnt, hipStream_t s) {
+  band_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, band_idx, band_cnt, dm);
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace taskkv

@@ -42,6 +42,7 @@ struct taskkv_ctx {
   hipEvent_t ev_stop[taskkv::MAX_PROFILE_EVENTS];
   int events_created;
   int n_cu;           // compute units of the device
+  int screening;      // 1: fp32 screening + fp64 recompute of contested columns (bf16 inputs)
   int stream_wg[4];   // cached launch width of the streaming decode kernel per (D, NT) variant, 0 = unknown
 };
 
@@ -69,8 +70,20 @@ struct Carver {
 // ---- launchers (each validates nothing; api.hip has checked the arguments) ----
 int score_parts(const Dims &dm);
 int score_rows_padded(const Dims &dm);
+// Buffers of the fp32 screening pass (see score_screen.hip).
+struct ScreenBufs {
+  int32_t *band_idx;           // [units][N] columns to recompute in fp64
+  int32_t *band_cnt;           // [units]
+  unsigned long long *knorm;   // [units] max squared key norm (bit pattern of a double)
+};
+bool screen_supported(const Dims &dm, int dtype);
+int launch_zero_u64(unsigned long long *p, int n, hipStream_t s);
+int launch_screen(const Dims &dm, const void *q_win, const void *k, const double *stats, double *scores,
+                  int chunks_per_wg, hipStream_t s);
+int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
+                int32_t *band_idx, int32_t *band_cnt, hipStream_t s);
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
-                  double *stats, double *scores, hipStream_t s);
+                  double *stats, double *scores, const ScreenBufs *scr, hipStream_t s);
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
                   int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
                   hipStream_t s);

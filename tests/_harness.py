@@ -11,6 +11,7 @@ from taskkv_synth import to_numpy
 F32_REL_TOL = 1e-5      # max|o - ref| / max|ref| per (batch, query head) vector
 BF16_ABS_TOL = 1e-2     # max|o - ref| for bf16 inputs with fp32 accumulation
 SCORE_RTOL = 1e-9       # fp64 on both sides; differences are summation order and exp ulps
+SCREEN_RTOL = 5e-3      # columns left at their fp32 screening value (bound: see score_screen.hip)
 MIN_MARGIN = 1e-9       # a decision closer than this is not a well-posed test
 
 
@@ -50,7 +51,16 @@ def check_compression(ld, cfg, bufs, k_rows, v_rows, b, ref):
     """Scores, vectors, distances, mask, kept indices, lengths, packed rows."""
     Hkv, N = cfg.n_kv_heads, cfg.ctx_len
     scores = bufs.scores[b].cpu().numpy()
-    np.testing.assert_allclose(scores, ref["scores"], rtol=SCORE_RTOL, atol=1e-300)
+    screened = (cfg.dtype == 1 and cfg.pool_kernel == 1 and
+                (cfg.n_q_heads // cfg.n_kv_heads) * cfg.obs_window <= 512 and getattr(bufs, "screening", True))
+    if screened:
+        # fp32-accurate everywhere, fp64-exact on every column that can decide something
+        np.testing.assert_allclose(scores, ref["scores"], rtol=SCREEN_RTOL, atol=1e-30)
+        for h in range(Hkv):
+            idx = ref["picks"][h]
+            np.testing.assert_allclose(scores[h, idx], ref["scores"][h, idx], rtol=SCORE_RTOL, atol=1e-300)
+    else:
+        np.testing.assert_allclose(scores, ref["scores"], rtol=SCORE_RTOL, atol=1e-300)
     np.testing.assert_allclose(bufs.sem_vec[b].cpu().numpy(), ref["sem_vec"], rtol=1e-8, atol=1e-12)
     np.testing.assert_allclose(bufs.dist[b].cpu().numpy(), ref["dist"], rtol=1e-8, atol=1e-12)
     assert bufs.mask[b].cpu().numpy().tolist() == ref["mask"].tolist(), "hetero mask differs"

@@ -212,6 +212,34 @@ def test_empty_units_give_zero_output():
                 assert lens[h] == 0 and not out[0, h * G:(h + 1) * G].any()
 
 
+@pytest.mark.parametrize("kw", [dict(), dict(recipe="zipf", ctx_len=5000, n_middle=300, top_t=200),
+                                dict(ctx_len=9000, n_q_heads=32, n_kv_heads=4, obs_window=32, n_middle=500)])
+def test_screening_changes_no_decision(kw):
+    """With and without the fp32 screening pass: identical mask, kept indices and
+    top-t vectors; without it every score is fp64-exact."""
+    import paper_2501_15113_amd as tk
+    ses = _session()
+    wl = small_workload(name="screen", wid=159, **kw)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    res = []
+    for on in (True, False):
+        bufs = ses.LayerBuffers(cfg, 0)
+        with ses.Context([cfg], 0) as ctx:
+            tk.taskkv_set_screening(ctx.handle, on)
+            bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+            bufs.compress(ctx, ld.k, ld.v)
+            torch.cuda.synchronize()
+        res.append(bufs)
+    a, b = res
+    assert torch.equal(a.mask, b.mask) and torch.equal(a.kept_idx, b.kept_idx) and torch.equal(a.lens, b.lens)
+    assert torch.equal(a.sem_vec, b.sem_vec) and torch.equal(a.dist, b.dist)
+    ref = oracle_layer(ld, 0, cfg)
+    np.testing.assert_allclose(b.scores[0].cpu().numpy(), ref["scores"], rtol=1e-9, atol=1e-300)
+    rel = ((a.scores - b.scores).abs() / b.scores.clamp_min(1e-30)).max().item()
+    assert 0 < rel < 5e-3            # the screening pass really ran, within its bound
+
+
 def test_decode_is_deterministic():
     ses = _session()
     wl = small_workload(name="det", wid=155, ctx_len=5000, n_hetero=2)
