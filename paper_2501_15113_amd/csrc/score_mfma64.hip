@@ -128,8 +128,6 @@ template <> struct RawCount<float> { static constexpr int per16B = 4; };
 // MODE 0: row statistics -> part[unit][n_parts][Rpad][2], n_parts = gridDim.x * ksplit.
 // MODE 1: column mean -> scores[unit][N] from stats[unit][Rpad][2].
 // GATHER (MODE 1 only): score just the keys listed in band_idx[unit][0 .. band_cnt[unit]).
-// knorm (MODE 0, optional): per-unit maximum of ||k_j||^2, as the bit pattern of a
-// non-negative double (integer max = numeric max, order independent).
 template <typename T, int D, int MODE, bool GATHER>
 __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restrict__ k,
                                                            const double *__restrict__ qd,
@@ -138,8 +136,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
                                                            double *__restrict__ scores, Dims dm,
                                                            int chunks_per_wg,
                                                            const int32_t *__restrict__ band_idx,
-                                                           const int32_t *__restrict__ band_cnt,
-                                                           unsigned long long *__restrict__ knorm) {
+                                                           const int32_t *__restrict__ band_cnt) {
   constexpr int NKK = D / 4;
   constexpr int NRAW = NKK / RawCount<T>::per16B;
   const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 15, kq = l >> 4;
@@ -149,7 +146,11 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
   const int n_pairs = Rpad / 32;
   const int ksplit = n_pairs >= SNW ? 1 : SNW / n_pairs;
   const int n_items = n_pairs * ksplit;
-  const int sub = SKC / ksplit;  // keys per slice of a chunk
+  // keys per chunk and per key slice; the gathered pass uses the smallest chunk
+  // (one 16-key tile per wave) so that a few hundred listed keys spread over
+  // many blocks
+  const int ckeys = GATHER ? 16 * ksplit : SKC;
+  const int sub = ckeys / ksplit;
   const T *kb = k + (size_t)unit * N * D;
   const double *qb = qd + (size_t)unit * Rpad * D;
   const double *st = stats + (size_t)unit * Rpad * 2;
@@ -171,8 +172,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
   };
 
   // logits of one 16-key tile for the wave's two row blocks
-  double kmax = 0.0;   // MODE 0 with knorm: largest squared key norm seen by this lane
-  auto tile_logits = [&](int j0, bool &valid, int &j, f64x4 (&acc)[2], bool want_norm) {
+  auto tile_logits = [&](int j0, bool &valid, int &j, f64x4 (&acc)[2]) {
     const int pos = j0 + c;
     valid = pos < NK;
     j = GATHER ? (valid ? gidx[pos] : 0) : pos;
@@ -180,14 +180,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
     fetch_piece<NKK>(kb + (size_t)(valid ? j : 0) * D + NKK * kq, valid, raw);
     double b[NKK];
     widen_piece<NKK>(raw, b, (const T *)nullptr);
-    if (MODE == 0 && want_norm) {
-      double ss = 0.0;
-#pragma unroll
-      for (int kk = 0; kk < NKK; ++kk) ss = fma(b[kk], b[kk], ss);
-      ss += __shfl_xor(ss, 16);
-      ss += __shfl_xor(ss, 32);
-      kmax = fmax(kmax, ss);
-    }
+
     acc[0] = f64x4{0., 0., 0., 0.};
     acc[1] = f64x4{0., 0., 0., 0.};
 #pragma unroll
@@ -212,7 +205,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
           bool valid;
           int j;
           f64x4 acc[2];
-          tile_logits(j0, valid, j, acc, knorm != nullptr && pair == 0);
+          tile_logits(j0, valid, j, acc);
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
             const int row = 32 * pair + 16 * (s >> 2) + 4 * (s & 3) + kq;
@@ -249,14 +242,11 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
         }
       }
     }
-    if (knorm != nullptr) {
-#pragma unroll
-      for (int off = 1; off < 16; off <<= 1) kmax = fmax(kmax, __shfl_xor(kmax, off));
-      if (l == 0 && kmax > 0.0) atomicMax(knorm + unit, (unsigned long long)__double_as_longlong(kmax));
-    }
   } else {
-    for (int ch = 0; ch < chunks_per_wg; ++ch) {
-      const int jchunk = (blockIdx.x * chunks_per_wg + ch) * SKC;
+    for (int it = 0; GATHER || it < chunks_per_wg; ++it) {
+      // plain pass: chunks_per_wg consecutive chunks; gathered pass: grid-stride
+      const int chunk = GATHER ? blockIdx.x + it * gridDim.x : blockIdx.x * chunks_per_wg + it;
+      const int jchunk = chunk * ckeys;
       if (jchunk >= NK) break;
       for (int item = w; item < n_items; item += SNW) {
         const int pair = item % n_pairs, ks = item / n_pairs;
@@ -273,7 +263,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
           bool valid;
           int j;
           f64x4 acc[2];
-          tile_logits(j0, valid, j, acc, false);
+          tile_logits(j0, valid, j, acc);
           double colsum = 0.0;
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
@@ -289,7 +279,7 @@ __global__ __launch_bounds__(64 * SNW) void score_mfma64_kernel(const T *__restr
       __syncthreads();
       {
         const int pos = jchunk + tid;
-        if (tid < SKC && pos < NK) {
+        if (tid < ckeys && pos < NK) {
           double sum = 0.0;
           for (int p = 0; p < n_pairs; ++p) sum += cs[p][tid];
           double *dst = scores + (size_t)unit * N + (GATHER ? gidx[pos] : pos);
@@ -334,7 +324,7 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     zero_f64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(scores, n);
   }
   if (screen) {
-    int rc = launch_zero_u64(scr->knorm, dm_all.units, s);
+    int rc = launch_key_norms(dm_all, k, scr->knorm, s);
     if (rc) return rc;
   }
   for (int grp = 0; grp < n_groups; ++grp) {
@@ -359,11 +349,11 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     const int n_parts = n_wg * (n_pairs >= SNW ? 1 : SNW / n_pairs);
     const dim3 grid(n_wg, dm.units), block(64 * SNW);
     score_mfma64_kernel<T, D, 0, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
-                                                              nullptr, screen ? scr->knorm : nullptr);
+                                                              nullptr);
     merge_stats_kernel<<<dim3(dm.units), dim3(256), 0, s>>>(part, stats, dm.Rpad, n_parts);
     if (!screen) {
       score_mfma64_kernel<T, D, 1, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
-                                                                nullptr, nullptr);
+                                                                nullptr);
       continue;
     }
     // fp32 screening of every column, then fp64 for the columns that can take
@@ -372,8 +362,8 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     if (rc) return rc;
     rc = launch_band(dm, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt, s);
     if (rc) return rc;
-    score_mfma64_kernel<T, D, 1, true><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw,
-                                                             scr->band_idx, scr->band_cnt, nullptr);
+    score_mfma64_kernel<T, D, 1, true><<<dim3(64, dm.units), block, 0, s>>>(k, qd, stats, part, scores, dm,
+                                                                           cpw, scr->band_idx, scr->band_cnt);
   }
   return hip_ok(hipGetLastError());
 }

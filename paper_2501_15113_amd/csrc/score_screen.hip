@@ -22,7 +22,7 @@
 // 2e-5 + R * 1.2e-7.  band_kernel evaluates the bound from the measured norms.
 #include <math.h>
 
-#include "taskkv_internal.h"
+#include "select_common.h"
 
 namespace taskkv {
 
@@ -131,43 +131,6 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
   }
 }
 
-__device__ __forceinline__ uint64_t key_bits(double x) { return (uint64_t)__double_as_longlong(x); }
-
-// Bit pattern of the count-th largest score inside [lo, hi) (8-bit radix select
-// on the 64-bit patterns; scores are >= 0).  All 1024 threads of the block call it.
-__device__ uint64_t radix_threshold(const double *__restrict__ sc, int lo, int hi, int count,
-                                    unsigned *hist, int *s_bin, int *s_rem) {
-  const int tid = threadIdx.x;
-  uint64_t pat = 0, known = 0;
-  int remaining = count;
-  for (int pass = 7; pass >= 0; --pass) {
-    const int shift = pass * 8;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    for (int j = lo + tid; j < hi; j += 1024) {
-      const uint64_t key = key_bits(sc[j]);
-      if ((key & known) == pat) atomicAdd(&hist[(key >> shift) & 255], 1u);
-    }
-    __syncthreads();
-    if (tid == 0) {
-      int cum = 0, bb = 255;
-      for (; bb > 0; --bb) {
-        const int cnt = (int)hist[bb];
-        if (cum + cnt >= remaining) break;
-        cum += cnt;
-      }
-      *s_bin = bb;
-      *s_rem = remaining - cum;
-    }
-    __syncthreads();
-    pat |= (uint64_t)(*s_bin) << shift;
-    known |= 0xffull << shift;
-    remaining = *s_rem;
-    __syncthreads();
-  }
-  return pat;
-}
-
 // One block per unit: error bound, thresholds, list of the columns to recompute.
 __global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ scores,
                                                     const double *__restrict__ qd,
@@ -201,12 +164,13 @@ __global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ s
   const double eps = dm.scale * gamma * sqrt(qmax) * sqrt(kmax) + 2e-5 + dm.R * 1.2e-7;
   const double w3 = 3.0 * eps;
 
-  const double tau_t = __longlong_as_double((long long)radix_threshold(sc, 0, N, dm.T, hist, &s_bin, &s_rem));
+  int unused;
+  const double tau_t = __longlong_as_double((long long)radix_threshold(sc, 0, N, dm.T, hist, &s_bin, &s_rem, unused));
   const bool middle = dm.pack_mode == TASKKV_PACK_SELECTIVE && !dm.keep_all && dm.k > 0 &&
                       dm.k < N - dm.s1 - dm.s2;
   double tau_k = 0.0;
   if (middle)
-    tau_k = __longlong_as_double((long long)radix_threshold(sc, dm.s1, N - dm.s2, dm.k, hist, &s_bin, &s_rem));
+    tau_k = __longlong_as_double((long long)radix_threshold(sc, dm.s1, N - dm.s2, dm.k, hist, &s_bin, &s_rem, unused));
   // values below 1e-30 may have been flushed to zero by the fp32 pass: treat them as ties
   const double lo_t = w3 >= 1.0 ? -1.0 : tau_t * (1.0 - w3) - 1e-30;
   const double lo_k = w3 >= 1.0 ? -1.0 : tau_k * (1.0 - w3) - 1e-30, hi_k = w3 >= 1.0 ? INFINITY : tau_k * (1.0 + w3) + 1e-30;
@@ -244,12 +208,49 @@ __global__ void zero_u64_kernel(unsigned long long *p, int n) {
   if (i < n) p[i] = 0ull;
 }
 
+// Per-unit maximum of ||k_j||^2 (bf16 rows), slightly over-estimated: fp32 sums
+// scaled by 1.001.  Stored as the bit pattern of a non-negative double, so the
+// integer atomic max is the numeric max and the result is order independent.
+template <int D>
+__global__ __launch_bounds__(256) void key_norm_kernel(const uint16_t *__restrict__ k,
+                                                       unsigned long long *__restrict__ knorm, int N) {
+  const int unit = blockIdx.y;
+  const uint16_t *kb = k + (size_t)unit * N * D;
+  float best = 0.f;
+  for (int j = blockIdx.x * 256 + threadIdx.x; j < N; j += gridDim.x * 256) {
+    const uint4 *row = reinterpret_cast<const uint4 *>(kb + (size_t)j * D);
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 8; ++i) {
+      const uint4 x = row[i];
+      const uint32_t wd[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float lo = __uint_as_float(wd[e] << 16), hi = __uint_as_float(wd[e] & 0xffff0000u);
+        ss = fmaf(lo, lo, ss);
+        ss = fmaf(hi, hi, ss);
+      }
+    }
+    best = fmaxf(best, ss);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
+  if ((threadIdx.x & 63) == 0 && best > 0.f)
+    atomicMax(knorm + unit, (unsigned long long)__double_as_longlong((double)best * 1.001));
+}
+
 bool screen_supported(const Dims &dm, int dtype) {
   return dtype == TASKKV_BF16 && dm.pool == 1 && dm.Rtot <= 64 * MAXQ;
 }
 
-int launch_zero_u64(unsigned long long *p, int n, hipStream_t s) {
-  zero_u64_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(p, n);
+int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s) {
+  zero_u64_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(knorm, dm.units);
+  int gx = (dm.N + 255) / 256;
+  if (gx > 64) gx = 64;
+  const dim3 grid(gx, dm.units), block(256);
+  auto kk = static_cast<const uint16_t *>(k);
+  if (dm.D == 64) key_norm_kernel<64><<<grid, block, 0, s>>>(kk, knorm, dm.N);
+  else key_norm_kernel<128><<<grid, block, 0, s>>>(kk, knorm, dm.N);
   return hip_ok(hipGetLastError());
 }
 

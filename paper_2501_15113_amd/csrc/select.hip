@@ -5,11 +5,11 @@
 // ties go to the lower index.
 #include <math.h>
 
-#include "taskkv_internal.h"
+#include "select_common.h"
 
 namespace taskkv {
 
-__device__ __forceinline__ uint64_t key_of(double x) { return (uint64_t)__double_as_longlong(x); }
+__device__ __forceinline__ uint64_t key_of(double x) { return score_key(x); }
 
 // Exclusive scan of one flag per thread over a 1024-thread block.
 __device__ __forceinline__ int block_scan_flag(bool f, int &total, int *s_wave) {
@@ -67,34 +67,9 @@ __global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__
   __shared__ int s_bin, s_rem;
   __shared__ int s_wave[16];
 
-  uint64_t pat = 0, known = 0;
-  int remaining = count;
   if (count > 0) {
-    for (int pass = 7; pass >= 0; --pass) {
-      const int shift = pass * 8;
-      if (tid < 256) hist[tid] = 0;
-      __syncthreads();
-      for (int j = lo + tid; j < hi; j += 1024) {
-        const uint64_t key = key_of(sc[j]);
-        if ((key & known) == pat) atomicAdd(&hist[(key >> shift) & 255], 1u);
-      }
-      __syncthreads();
-      if (tid == 0) {
-        int cum = 0, b = 255;
-        for (; b > 0; --b) {
-          const int c = (int)hist[b];
-          if (cum + c >= remaining) break;
-          cum += c;
-        }
-        s_bin = b;
-        s_rem = remaining - cum;
-      }
-      __syncthreads();
-      pat |= (uint64_t)s_bin << shift;
-      known |= 0xffull << shift;
-      remaining = s_rem;
-      __syncthreads();
-    }
+    int remaining;
+    const uint64_t pat = radix_threshold(sc, lo, hi, count, hist, &s_bin, &s_rem, remaining);
     // pat = the count-th largest score; `remaining` of the entries equal to it
     // are taken, lowest index first.
     int eq_base = 0, out_base = 0;

@@ -77,7 +77,7 @@ struct ScreenBufs {
   unsigned long long *knorm;   // [units] max squared key norm (bit pattern of a double)
 };
 bool screen_supported(const Dims &dm, int dtype);
-int launch_zero_u64(unsigned long long *p, int n, hipStream_t s);
+int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);
 int launch_screen(const Dims &dm, const void *q_win, const void *k, const double *stats, double *scores,
                   int chunks_per_wg, hipStream_t s);
 int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
