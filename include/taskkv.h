@@ -192,10 +192,12 @@ int taskkv_cache_export(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void
  * 0 = none, 1 = append to a full unit. */
 int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream);
 
-/* Screening (default on) lets taskkv_separate score bf16 inputs on the bf16
- * matrix cores first and recompute in fp64 only the columns that can matter;
- * decisions are identical either way.  Off: every score is computed in fp64. */
-int taskkv_set_screening(taskkv_ctx *ctx, int on);
+/* Screening lets taskkv_separate score bf16 inputs on the bf16 matrix cores
+ * first and recompute in fp64 only the columns that can matter; decisions are
+ * identical either way.  mode 0: never (every score in fp64); 1 (default): when
+ * the layer is large enough for it to pay; 2: whenever the inputs allow
+ * (bf16, no pooling, at most 512 window rows per KV head). */
+int taskkv_set_screening(taskkv_ctx *ctx, int mode);
 
 /*
  * Timing hooks for the benchmark.  With profiling on, taskkv_decode_attn

@@ -208,8 +208,9 @@ def taskkv_last_async_error(ctx, stream=None) -> int:
     return rc
 
 
-def taskkv_set_screening(ctx, on: bool) -> None:
-    _check(load_library().taskkv_set_screening(ctx, 1 if on else 0), "taskkv_set_screening")
+def taskkv_set_screening(ctx, mode: int) -> None:
+    """0 = never, 1 = automatic (default), 2 = whenever the inputs allow."""
+    _check(load_library().taskkv_set_screening(ctx, int(mode)), "taskkv_set_screening")
 
 
 def taskkv_profile_enable(ctx, on: bool) -> None:

@@ -212,6 +212,7 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   scr.band_idx = cv.take<int32_t>((size_t)d.units * d.N);
   scr.band_cnt = cv.take<int32_t>((size_t)d.units * 2);
   scr.knorm = cv.take<unsigned long long>((size_t)d.units);
+  scr.mode = ctx->screening;
   if (!cv.ok) return TASKKV_EWORKSPACE;
   int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, ctx->screening ? &scr : nullptr, s);
   if (rc) return rc;
@@ -315,9 +316,9 @@ int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream) {
   return flag;
 }
 
-int taskkv_set_screening(taskkv_ctx *ctx, int on) {
-  if (!ctx) return TASKKV_EINVAL;
-  ctx->screening = on ? 1 : 0;
+int taskkv_set_screening(taskkv_ctx *ctx, int mode) {
+  if (!ctx || mode < 0 || mode > 2) return TASKKV_EINVAL;
+  ctx->screening = mode;
   return TASKKV_OK;
 }
 

@@ -318,7 +318,11 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
                       double *stats, double *scores, const ScreenBufs *scr, hipStream_t s) {
   const int cpw = chunks_per_wg_for(dm_all);
   const int n_groups = (dm_all.Rtot + ROW_GROUP - 1) / ROW_GROUP;
-  const bool screen = scr != nullptr && n_groups == 1 && screen_supported(dm_all, dtype);
+  // screening pays once the fp64 column pass is large compared with the extra
+  // launches (mode 1 = decide here, 2 = whenever possible)
+  const bool big = (double)dm_all.units * dm_all.Rtot * dm_all.N >= 1e8;
+  const bool screen = scr != nullptr && n_groups == 1 && screen_supported(dm_all, dtype) &&
+                      (scr->mode == 2 || big);
   if (n_groups > 1) {
     const size_t n = (size_t)dm_all.units * dm_all.N;
     zero_f64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(scores, n);

@@ -42,7 +42,7 @@ struct taskkv_ctx {
   hipEvent_t ev_stop[taskkv::MAX_PROFILE_EVENTS];
   int events_created;
   int n_cu;           // compute units of the device
-  int screening;      // 1: fp32 screening + fp64 recompute of contested columns (bf16 inputs)
+  int screening;      // fp32 screening + fp64 recompute of contested columns: 0 off, 1 auto, 2 always
   int stream_wg[4];   // cached launch width of the streaming decode kernel per (D, NT) variant, 0 = unknown
 };
 
@@ -75,6 +75,7 @@ struct ScreenBufs {
   int32_t *band_idx;           // [units][N] columns to recompute in fp64
   int32_t *band_cnt;           // [units]
   unsigned long long *knorm;   // [units] max squared key norm (bit pattern of a double)
+  int mode;                    // 1 = when it pays, 2 = whenever the inputs allow
 };
 bool screen_supported(const Dims &dm, int dtype);
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);

@@ -22,9 +22,11 @@ def cfg_from_workload(wl, n_hetero=None, n_middle=None, **override) -> tk.LayerC
 class Context:
     """Owns a taskkv_ctx sized for the given cfgs."""
 
-    def __init__(self, cfgs, reserve: int, device: int = 0):
+    def __init__(self, cfgs, reserve: int, device: int = 0, screening: int = 1):
         self.bytes = max(tk.taskkv_workspace_bytes(c, reserve) for c in cfgs)
         self.handle = tk.taskkv_create(device, self.bytes)
+        self.screening = screening
+        tk.taskkv_set_screening(self.handle, screening)
 
     def close(self):
         if self.handle is not None:

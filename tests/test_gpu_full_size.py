@@ -14,7 +14,8 @@ def test_cfg4_mistral_shaped_zipf():
 
 
 def test_cfg5_load_imbalance_stress():
-    run_layer(WORKLOADS["cfg5"], check_batches=(3,), check_steps={0, 63})
+    # automatic screening, as the benchmark runs it (it is on at this size)
+    run_layer(WORKLOADS["cfg5"], check_batches=(3,), check_steps={0, 63}, screening=1)
 
 
 @pytest.mark.parametrize("layer", [0, 5])

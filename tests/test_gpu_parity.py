@@ -16,7 +16,7 @@ def _session():
 
 
 def run_layer(wl, layer=0, check_batches=(0,), steps=None, check_steps=None, reserve=None,
-              append=True, cfg_override=None, mutate=None):
+              append=True, cfg_override=None, mutate=None, screening=2):
     """separate -> compress -> export -> decode on the GPU; every output of the
     chosen batch elements is compared with the oracle."""
     ses = _session()
@@ -36,7 +36,8 @@ def run_layer(wl, layer=0, check_batches=(0,), steps=None, check_steps=None, res
     steps = wl.decode_steps if steps is None else steps
     reserve = steps if reserve is None else reserve
     bufs = ses.LayerBuffers(cfg, reserve)
-    with ses.Context([cfg], reserve) as ctx:
+    bufs.screening = screening > 0
+    with ses.Context([cfg], reserve, screening=screening) as ctx:
         bufs.separate(ctx, ld.q_win, ld.k, ld.v)
         bufs.compress(ctx, ld.k, ld.v)
         k_rows, v_rows = bufs.export(ctx)
@@ -74,6 +75,10 @@ def test_cfg1_fp32_mha():
 
 def test_cfg2_llama_shaped_layer():
     run_layer(WORKLOADS["cfg2"], check_steps=set(range(0, 128, 9)) | {127})
+
+
+def test_cfg2_without_screening():
+    run_layer(WORKLOADS["cfg2"], steps=2, screening=0)
 
 
 # ------------------------------------------------------------------ small sweeps
@@ -223,10 +228,9 @@ def test_screening_changes_no_decision(kw):
     ld = make_layer(wl, 0, "cuda:0")
     cfg = ses.cfg_from_workload(wl)
     res = []
-    for on in (True, False):
+    for mode in (2, 0):
         bufs = ses.LayerBuffers(cfg, 0)
-        with ses.Context([cfg], 0) as ctx:
-            tk.taskkv_set_screening(ctx.handle, on)
+        with ses.Context([cfg], 0, screening=mode) as ctx:
             bufs.separate(ctx, ld.q_win, ld.k, ld.v)
             bufs.compress(ctx, ld.k, ld.v)
             torch.cuda.synchronize()
