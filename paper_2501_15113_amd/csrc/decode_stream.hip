@@ -29,11 +29,6 @@ __device__ __forceinline__ int owner_of_page(int64_t p, int64_t T, int W) {
   return (int)(((p + 1) * W - 1) / T);
 }
 
-// Request the next K tiles between the QK^T MFMAs and the softmax of the current page.
-#ifndef TASKKV_STREAM_SPLIT
-#define TASKKV_STREAM_SPLIT 1
-#endif
-
 #ifndef TASKKV_STREAM_WAVES_PER_SIMD
 #define TASKKV_STREAM_WAVES_PER_SIMD 1
 #endif
@@ -157,10 +152,6 @@ void decode_stream_kernel(
     const size_t tok = locate(gp);
     load_page<D, NT>(kc + tok * (D / 8), vc + tok * (D / 8), l, r);
   };
-#pragma unroll
-  for (int s = 0; s < NP; ++s)
-    if (p0 + s < p1) request(p0 + s, ring[s]);
-
   int u_at = -1;           // unit being accumulated
   int n_valid = 0;         // its token count
   int pref_at = 0, pref_next = 0;
@@ -180,6 +171,12 @@ void decode_stream_kernel(
         *reinterpret_cast<floatx4 *>(po + pi * D + 16 * mb + 4 * g) = acc[mb];
     }
   };
+  // Vector memory operations complete in order, and the compiler places one
+  // static wait per use: a load that only some paths issue (the query rows of
+  // a new unit) would make every later wait assume the worst case and drain
+  // the ring on every page.  The rare path therefore ends with all of its own
+  // memory traffic complete, so that joining it changes nothing for the
+  // common path.
   auto enter_unit = [&](int gp) {
     int u = u_at < 0 ? u0 : u_at;
     while (gp >= s_pref[u + 1]) ++u;
@@ -199,33 +196,49 @@ void decode_stream_kernel(
     l_run = 0.f;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[mb] = floatx4{0.f, 0.f, 0.f, 0.f};
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): stores of flush() and the query loads are done
+  };
+  // One page: scores, request of the K tiles NP pages ahead, softmax and
+  // values, request of the V tiles.
+  auto page_step = [&](PageRegs<D> &r, int gp, bool more) {
+    if (u_at < 0 || gp >= pref_next) {
+      if (u_at >= 0) flush();
+      enter_unit(gp);
+    }
+    floatx4 sc[2];
+    page_scores<D>(r, qv, sc);
+    size_t tok_next = 0;
+    if (more) {
+      tok_next = locate(gp + NP);
+      load_page_k<D, NT>(kc + tok_next * (D / 8), l, r);
+    }
+    page_values<D>(r, sc, (gp - pref_at) * PAGE, n_valid, g, scale_log2, m_run, l_run, acc);
+    if (more) load_page_v<D, NT>(vc + tok_next * (D / 8), l, r);
   };
 
-  for (int gp0 = p0; gp0 < p1; gp0 += NP) {
+  int gp0 = p0;
+  if (p1 - p0 >= 2 * NP) {
+    // steady state: every page of the loop refills its ring slot, so the number
+    // of loads in flight at each wait is the same on every path and the waits
+    // leave the other NP - 1 pages in flight
+#pragma unroll
+    for (int s = 0; s < NP; ++s) request(p0 + s, ring[s]);
+    enter_unit(p0);
+    for (; gp0 + 2 * NP <= p1; gp0 += NP) {
+#pragma unroll
+      for (int s = 0; s < NP; ++s) page_step(ring[s], gp0 + s, true);
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < NP; ++s)
+      if (p0 + s < p1) request(p0 + s, ring[s]);
+  }
+  // the last pages of the range (fewer than 2 NP), refilling only while pages remain
+  for (; gp0 < p1; gp0 += NP) {
 #pragma unroll
     for (int s = 0; s < NP; ++s) {
       const int gp = gp0 + s;
-      if (gp < p1) {
-        if (u_at < 0 || gp >= pref_next) {
-          if (u_at >= 0) flush();
-          enter_unit(gp);
-        }
-#if TASKKV_STREAM_SPLIT
-        floatx4 sc[2];
-        page_scores<D>(ring[s], qv, sc);
-        size_t tok_next = 0;
-        const bool more = gp + NP < p1;
-        if (more) {
-          tok_next = locate(gp + NP);
-          load_page_k<D, NT>(kc + tok_next * (D / 8), l, ring[s]);
-        }
-        page_values<D>(ring[s], sc, (gp - pref_at) * PAGE, n_valid, g, scale_log2, m_run, l_run, acc);
-        if (more) load_page_v<D, NT>(vc + tok_next * (D / 8), l, ring[s]);
-#else
-        attend_page<D>(ring[s], qv, (gp - pref_at) * PAGE, n_valid, g, scale_log2, m_run, l_run, acc);
-        if (gp + NP < p1) request(gp + NP, ring[s]);
-#endif
-      }
+      if (gp < p1) page_step(ring[s], gp, gp + NP < p1);
     }
   }
   flush();
