@@ -199,6 +199,16 @@ int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream);
  * (bf16, no pooling, at most 512 window rows per KV head). */
 int taskkv_set_screening(taskkv_ctx *ctx, int mode);
 
+/* Decode attention (Eq. 1 on the kept keys) deals the pages of a step to the
+ * resident waves.  On MI355X the odd XCDs sustain less read bandwidth than the
+ * even ones under a saturating stream, so waves of even workgroups take
+ * (1024 + skew) / 1024 of an equal share and waves of odd workgroups
+ * (1024 - skew) / 1024.  skew in [0, 128]; 0 deals equal shares; the default
+ * (56) is the measured ratio.  Outputs stay within the stated tolerance for
+ * any value; bit patterns depend on it (it moves the split points of the
+ * partial sums).  Returns TASKKV_EINVAL for a value out of range. */
+int taskkv_set_stream_skew(taskkv_ctx *ctx, int skew);
+
 /*
  * Timing hooks for the benchmark.  With profiling on, taskkv_decode_attn
  * brackets its attention kernel with HIP events on the launch stream (up to

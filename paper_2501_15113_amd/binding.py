@@ -13,7 +13,7 @@ EXPORTED_SYMBOLS = [
     "taskkv_create", "taskkv_destroy", "taskkv_strerror", "taskkv_workspace_bytes",
     "taskkv_cache_tokens", "taskkv_hetero_head_count", "taskkv_middle_budget", "taskkv_separate",
     "taskkv_compress", "taskkv_decode_attn", "taskkv_cache_export", "taskkv_last_async_error",
-    "taskkv_profile_enable", "taskkv_profile_read", "taskkv_set_screening",
+    "taskkv_profile_enable", "taskkv_profile_read", "taskkv_set_screening", "taskkv_set_stream_skew",
 ]
 
 
@@ -86,6 +86,8 @@ def load_library():
     lib.taskkv_last_async_error.restype = C.c_int
     lib.taskkv_set_screening.argtypes = [vp, C.c_int]
     lib.taskkv_set_screening.restype = C.c_int
+    lib.taskkv_set_stream_skew.argtypes = [vp, C.c_int]
+    lib.taskkv_set_stream_skew.restype = C.c_int
     lib.taskkv_profile_enable.argtypes = [vp, C.c_int]
     lib.taskkv_profile_enable.restype = C.c_int
     lib.taskkv_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -211,6 +213,11 @@ def taskkv_last_async_error(ctx, stream=None) -> int:
 def taskkv_set_screening(ctx, mode: int) -> None:
     """0 = never, 1 = automatic (default), 2 = whenever the inputs allow."""
     _check(load_library().taskkv_set_screening(ctx, int(mode)), "taskkv_set_screening")
+
+
+def taskkv_set_stream_skew(ctx, skew: int) -> None:
+    """Share (in 1/1024ths) that decode attention moves from waves on odd XCDs to even ones; 0 = equal."""
+    _check(load_library().taskkv_set_stream_skew(ctx, int(skew)), "taskkv_set_stream_skew")
 
 
 def taskkv_profile_enable(ctx, on: bool) -> None:

@@ -91,7 +91,8 @@ static size_t decode_slots(const Dims &d, int64_t capacity) {
 static size_t ws_decode(const Dims &d, int64_t capacity) {
   const size_t n = decode_slots(d, capacity);
   return 2 * al(n * d.G * sizeof(float)) + al(n * d.G * d.D * sizeof(float)) +
-         2 * al(((size_t)d.units + 1) * sizeof(int32_t));
+         al(((size_t)d.units + 1) * sizeof(int32_t)) +
+         al(((size_t)d.units + 1 + STREAM_MAX_WG * 4 + 1) * sizeof(int32_t));   // page prefix + wave range starts
 }
 
 }  // namespace taskkv
@@ -128,6 +129,7 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
   c->events_created = 0;
   c->n_cu = 0;
   c->screening = 1;
+  c->stream_skew = STREAM_SKEW_DEFAULT;
   for (int i = 0; i < 4; ++i) c->stream_wg[i] = 0;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) {
@@ -286,7 +288,7 @@ int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void 
   float *pl = cv.take<float>(n_slots * d.G);
   float *po = cv.take<float>(n_slots * d.G * d.D);
   int32_t *eff_len = cv.take<int32_t>((size_t)d.units + 1);
-  int32_t *page_prefix = cv.take<int32_t>((size_t)d.units + 1);
+  int32_t *page_prefix = cv.take<int32_t>((size_t)d.units + 1 + STREAM_MAX_WG * 4 + 1);
   if (!cv.ok) return TASKKV_EWORKSPACE;
   if (cfg->dtype == TASKKV_BF16 && d.units <= STREAM_MAX_UNITS)
     return launch_decode_stream(ctx, d, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens,
@@ -319,6 +321,12 @@ int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream) {
 int taskkv_set_screening(taskkv_ctx *ctx, int mode) {
   if (!ctx || mode < 0 || mode > 2) return TASKKV_EINVAL;
   ctx->screening = mode;
+  return TASKKV_OK;
+}
+
+int taskkv_set_stream_skew(taskkv_ctx *ctx, int skew) {
+  if (!ctx || skew < 0 || skew > 128) return TASKKV_EINVAL;
+  ctx->stream_skew = skew;
   return TASKKV_OK;
 }
 

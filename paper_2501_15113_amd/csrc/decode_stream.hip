@@ -24,9 +24,28 @@ namespace taskkv {
 
 constexpr int MAXU = STREAM_MAX_UNITS;
 
-// Wave that owns page p when T pages are dealt to W waves.
-__device__ __forceinline__ int owner_of_page(int64_t p, int64_t T, int W) {
-  return (int)(((p + 1) * W - 1) / T);
+// First page of wave i when T pages are dealt to W waves.  Workgroups go to
+// the eight XCDs round robin, and under a saturating read stream the odd XCDs
+// of this part deliver about a tenth less bandwidth than their even
+// neighbours (measured on every launch and every allocation), so with equal
+// ranges the even half of the chip idles while the odd half finishes.  The
+// waves of even workgroups therefore take (1024 + skew) / 1024 of an equal
+// share and those of odd workgroups (1024 - skew) / 1024; a pair of workgroups
+// (eight waves) always covers eight equal shares.  W is a multiple of 8
+// whenever skew != 0.
+__device__ __forceinline__ int64_t range_start(int i, int64_t T, int W, int skew) {
+  const int r = i & 7;
+  const int64_t c = (int64_t)(i - r) * 1024 +
+                    (r <= 4 ? r * (1024 + skew) : 4 * (1024 + skew) + (r - 4) * (1024 - skew));
+  return c * T / ((int64_t)W * 1024);
+}
+// Wave that owns page p, given the table of range starts the decode kernel
+// left behind (range_tab[W] = T).
+__device__ __forceinline__ int owner_of_page(int p, int64_t T, int W, const int32_t *__restrict__ range_tab) {
+  int i = (int)(((int64_t)(p + 1) * W - 1) / T);   // exact for equal ranges, a neighbour otherwise
+  while (i + 1 < W && range_tab[i + 1] <= p) ++i;
+  while (i > 0 && range_tab[i] > p) --i;
+  return i;
 }
 
 #ifndef TASKKV_STREAM_WAVES_PER_SIMD
@@ -40,7 +59,7 @@ void decode_stream_kernel(
     const uint16_t *__restrict__ v_new, uint4 *kc, uint4 *vc, const int64_t *__restrict__ offsets,
     const int32_t *__restrict__ lens, int32_t *__restrict__ eff_len, int32_t *__restrict__ page_prefix,
     int *__restrict__ d_err, float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ po,
-    int n_units, int Hq, int Hkv, int G, float scale_log2) {
+    int n_units, int Hq, int Hkv, int G, float scale_log2, int skew) {
   constexpr int KK = D / 32, MB = D / 16, PSTRIDE = PAGE * (D / 8);  // uint4 per page
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, g = l >> 4, c = l & 15;
   const int hg = blockIdx.y;
@@ -98,7 +117,12 @@ void decode_stream_kernel(
   const int64_t T = s_pref[n_units];
   const int W = gridDim.x * 4;
   const int wid = blockIdx.x * 4 + w;
-  const int p0 = (int)((int64_t)wid * T / W), p1 = (int)((int64_t)(wid + 1) * T / W);
+  const int p0 = (int)range_start(wid, T, W, skew), p1 = (int)range_start(wid + 1, T, W, skew);
+  if (hg == 0 && l == 0) {   // the combine kernel looks the ranges up instead of recomputing them
+    int32_t *range_tab = page_prefix + n_units + 1;
+    range_tab[wid] = p0;
+    if (wid == W - 1) range_tab[W] = p1;
+  }
   if (p0 >= p1) return;
 
   // first unit of my range: largest u with s_pref[u] <= p0
@@ -270,19 +294,19 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
     if (tid < D) out[(size_t)bq * D + tid] = 0.f;
     return;
   }
-  const int wa = owner_of_page(pa, T, W), wb = owner_of_page(pb - 1, T, W);
+  const int32_t *range_tab = page_prefix + n_units + 1;
+  const int wa = owner_of_page(pa, T, W, range_tab), wb = owner_of_page(pb - 1, T, W, range_tab);
   const int nparts = wb - wa + 1;
   const size_t slot0 = (size_t)wa + u;
   const int dl = tid % DL, cl = tid / DL;
   __shared__ float4 red_o[NCL][DL];
   __shared__ float red_m[NCL], red_l[NCL];
   // a wave between the first and last owner wrote a partial unless its page range is empty
-  const bool dense = T >= W;   // then every wave owns at least one page (skips the 64-bit divisions)
+  const bool dense = T >= 2 * (int64_t)W;   // then every wave owns at least one page (skips the 64-bit divisions)
   auto has_pages = [&](int i) {
     if (i >= nparts) return false;
     if (dense) return true;
-    const int64_t wv = wa + i;
-    return wv * T / W < (wv + 1) * T / W;
+    return range_tab[wa + i] < range_tab[wa + i + 1];
   };
   float m_run = -INFINITY, l_run = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -353,13 +377,14 @@ static void run_stream(taskkv_ctx *ctx, const Dims &dm, const uint16_t *q, const
                        const uint16_t *vn, uint4 *kc, uint4 *vc, const int64_t *offsets, int32_t *lens,
                        int32_t *eff_len, int32_t *page_prefix, float *pm, float *pl, float *po,
                        float *out, int n_wg, bool fused, hipStream_t s) {
+  const int skew = (n_wg & 1) ? 0 : ctx->stream_skew;
   const dim3 grid(n_wg, (dm.G + 15) / 16), block(256);
   const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
   const bool prof = ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS;
   if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
   decode_stream_kernel<D, TASKKV_STREAM_NP, NT><<<grid, block, 0, s>>>(
       q, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, ctx->d_err, pm, pl, po, dm.units, dm.Hq,
-      dm.Hkv, dm.G, scale_log2);
+      dm.Hkv, dm.G, scale_log2, skew);
   if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
   combine_stream_kernel<D><<<dim3(dm.B * dm.Hq), dim3(1024), 0, s>>>(
       pm, pl, po, page_prefix, eff_len, fused ? lens : nullptr, out, dm.units, dm.Hq, dm.Hkv, dm.G, n_wg * 4);

@@ -13,6 +13,7 @@ constexpr int PAGE = 32;                    // tokens per matrix-core page of th
 constexpr int MAX_PROFILE_EVENTS = 4096;
 constexpr int STREAM_MAX_UNITS = 4096;  // units the streaming decode kernel can index in LDS
 constexpr int STREAM_MAX_WG = 1024;     // workgroups (4 waves each) it is ever launched with
+constexpr int STREAM_SKEW_DEFAULT = 56; // share moved from odd to even workgroups, in 1/1024ths (measured)
 
 // Resolved problem sizes handed to kernels by value.
 struct Dims {
@@ -42,6 +43,7 @@ struct taskkv_ctx {
   hipEvent_t ev_stop[taskkv::MAX_PROFILE_EVENTS];
   int events_created;
   int n_cu;           // compute units of the device
+  int stream_skew;    // 1/1024ths of an equal share moved from the waves of odd workgroups to even ones
   int screening;      // fp32 screening + fp64 recompute of contested columns: 0 off, 1 auto, 2 always
   int stream_wg[4];   // cached launch width of the streaming decode kernel per (D, NT) variant, 0 = unknown
 };

@@ -114,6 +114,13 @@ def test_small_sweep(i):
     run_layer(wl, check_batches=tuple(range(min(2, wl.batch))))
 
 
+def test_more_units_than_the_streaming_kernel_indexes():
+    """4400 (batch, KV head) units: decode runs on the chunk-grid kernels."""
+    wl = small_workload(name="many_units", wid=190, batch=1100, n_q_heads=8, n_kv_heads=4, head_dim=64,
+                        ctx_len=70, n_sink=2, n_recent=5, n_middle=6, obs_window=4, top_t=9, decode_steps=3)
+    run_layer(wl, check_batches=(0, 547, 1099))
+
+
 def test_full_window_reproduces_exact_semantic_vector():
     """L = N, t = N, one query head per KV head: the separator's vector is the
     un-approximated definition (Eq. 1-2), computed by the oracle's direct
