@@ -88,11 +88,14 @@ static size_t decode_slots(const Dims &d, int64_t capacity) {
   const size_t stream_slots = (size_t)STREAM_MAX_WG * 4 + d.units;
   return chunk_slots > stream_slots ? chunk_slots : stream_slots;
 }
+static size_t stream_table_ints(const Dims &d) {
+  return (size_t)d.units + 1 + STREAM_MAX_WG * 4 + 1 + 2 * (size_t)d.units;
+}
 static size_t ws_decode(const Dims &d, int64_t capacity) {
   const size_t n = decode_slots(d, capacity);
   return 2 * al(n * d.G * sizeof(float)) + al(n * d.G * d.D * sizeof(float)) +
          al(((size_t)d.units + 1) * sizeof(int32_t)) +
-         al(((size_t)d.units + 1 + STREAM_MAX_WG * 4 + 1) * sizeof(int32_t));   // page prefix + wave range starts
+         al(stream_table_ints(d) * sizeof(int32_t));   // page prefix, wave range starts, first/last wave of each unit
 }
 
 }  // namespace taskkv
@@ -288,7 +291,7 @@ int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void 
   float *pl = cv.take<float>(n_slots * d.G);
   float *po = cv.take<float>(n_slots * d.G * d.D);
   int32_t *eff_len = cv.take<int32_t>((size_t)d.units + 1);
-  int32_t *page_prefix = cv.take<int32_t>((size_t)d.units + 1 + STREAM_MAX_WG * 4 + 1);
+  int32_t *page_prefix = cv.take<int32_t>(stream_table_ints(d));
   if (!cv.ok) return TASKKV_EWORKSPACE;
   if (cfg->dtype == TASKKV_BF16 && d.units <= STREAM_MAX_UNITS)
     return launch_decode_stream(ctx, d, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens,

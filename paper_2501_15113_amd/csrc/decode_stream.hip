@@ -39,14 +39,18 @@ __device__ __forceinline__ int64_t range_start(int i, int64_t T, int W, int skew
                     (r <= 4 ? r * (1024 + skew) : 4 * (1024 + skew) + (r - 4) * (1024 - skew));
   return c * T / ((int64_t)W * 1024);
 }
-// Wave that owns page p, given the table of range starts the decode kernel
-// left behind (range_tab[W] = T).
-__device__ __forceinline__ int owner_of_page(int p, int64_t T, int W, const int32_t *__restrict__ range_tab) {
-  int i = (int)(((int64_t)(p + 1) * W - 1) / T);   // exact for equal ranges, a neighbour otherwise
-  while (i + 1 < W && range_tab[i + 1] <= p) ++i;
-  while (i > 0 && range_tab[i] > p) --i;
-  return i;
-}
+// What the decode kernel leaves behind for the combine kernel, after the
+// units + 1 page prefixes: the first page of every wave's range (W + 1
+// entries, the last one is T), then for every unit the first and the last
+// wave that hold pages of it.
+struct StreamTables {
+  int32_t *range_tab, *unit_first, *unit_last;
+  __host__ __device__ StreamTables(int32_t *page_prefix, int n_units) {
+    range_tab = page_prefix + n_units + 1;
+    unit_first = range_tab + STREAM_MAX_WG * 4 + 1;
+    unit_last = unit_first + n_units;
+  }
+};
 
 #ifndef TASKKV_STREAM_WAVES_PER_SIMD
 #define TASKKV_STREAM_WAVES_PER_SIMD 1
@@ -118,10 +122,11 @@ void decode_stream_kernel(
   const int W = gridDim.x * 4;
   const int wid = blockIdx.x * 4 + w;
   const int p0 = (int)range_start(wid, T, W, skew), p1 = (int)range_start(wid + 1, T, W, skew);
-  if (hg == 0 && l == 0) {   // the combine kernel looks the ranges up instead of recomputing them
-    int32_t *range_tab = page_prefix + n_units + 1;
-    range_tab[wid] = p0;
-    if (wid == W - 1) range_tab[W] = p1;
+  const StreamTables tabs(page_prefix, n_units);
+  const bool scribe = hg == 0 && l == 0;   // one lane per wave keeps the tables
+  if (scribe) {
+    tabs.range_tab[wid] = p0;
+    if (wid == W - 1) tabs.range_tab[W] = p1;
   }
   if (p0 >= p1) return;
 
@@ -194,6 +199,7 @@ void decode_stream_kernel(
       for (int mb = 0; mb < MB; ++mb)
         *reinterpret_cast<floatx4 *>(po + pi * D + 16 * mb + 4 * g) = acc[mb];
     }
+    if (scribe && pref_next <= p1) tabs.unit_last[u_at] = wid;   // the unit ends inside my range
   };
   // Vector memory operations complete in order, and the compiler places one
   // static wait per use: a load that only some paths issue (the query rows of
@@ -208,6 +214,7 @@ void decode_stream_kernel(
     pref_at = s_pref[u];
     pref_next = s_pref[u + 1];
     n_valid = s_len[u] & 0x7fffffff;
+    if (scribe && gp == pref_at) tabs.unit_first[u] = wid;        // the unit starts inside my range
     const int b = u / Hkv, h = u % Hkv;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qv[kk].u = make_uint4(0, 0, 0, 0);
@@ -290,23 +297,24 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
   if (lens_out != nullptr && slot == 0 && tid == 0) lens_out[u] = eff_len[u];
   const int64_t T = page_prefix[n_units];
   const int pa = page_prefix[u], pb = page_prefix[u + 1];
+  // requested together with the prefixes (one trip to memory); meaningless for a unit without pages
+  const StreamTables tabs(const_cast<int32_t *>(page_prefix), n_units);
+  const int wa = tabs.unit_first[u], wb = tabs.unit_last[u];
   if (pa >= pb) {
     if (tid < D) out[(size_t)bq * D + tid] = 0.f;
     return;
   }
-  const int32_t *range_tab = page_prefix + n_units + 1;
-  const int wa = owner_of_page(pa, T, W, range_tab), wb = owner_of_page(pb - 1, T, W, range_tab);
   const int nparts = wb - wa + 1;
   const size_t slot0 = (size_t)wa + u;
   const int dl = tid % DL, cl = tid / DL;
   __shared__ float4 red_o[NCL][DL];
   __shared__ float red_m[NCL], red_l[NCL];
   // a wave between the first and last owner wrote a partial unless its page range is empty
-  const bool dense = T >= 2 * (int64_t)W;   // then every wave owns at least one page (skips the 64-bit divisions)
+  const bool dense = T >= 2 * (int64_t)W;   // then every wave owns at least one page (skips the table look-ups)
   auto has_pages = [&](int i) {
     if (i >= nparts) return false;
     if (dense) return true;
-    return range_tab[wa + i] < range_tab[wa + i + 1];
+    return tabs.range_tab[wa + i] < tabs.range_tab[wa + i + 1];
   };
   float m_run = -INFINITY, l_run = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
