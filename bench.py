@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5 (default cfg5: largest context, "
                     "the load-imbalance stress case)")
+    ap.add_argument("--layer-batched", action="store_true",
+                    help="workloads with several layers: keep all layers' caches in one allocation and "
+                         "serve a decode step of the whole stack with one taskkv_decode_attn call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device copies (a kernel of known traffic against which "
@@ -112,8 +115,17 @@ def main():
 
     layers = [make_layer(wl, r, dev) for r in range(wl.n_layers)]
     cfgs = [session.cfg_from_workload(wl, ld.n_hetero, ld.n_middle) for ld in layers]
-    bufs = [session.LayerBuffers(c, steps_dec, dev) for c in cfgs]
-    dec_in = [[ld.decode_inputs(s) for s in range(steps_dec)] for ld in layers]
+    batched = args.layer_batched and wl.n_layers > 1
+    if batched:
+        stack = session.LayerStack(cfgs, steps_dec, dev)
+        bufs = stack.layers
+        dec_in = []
+        for s in range(steps_dec):
+            parts = [ld.decode_inputs(s) for ld in layers]
+            dec_in.append(tuple(torch.cat([p[i] for p in parts]) for i in range(3)))
+    else:
+        bufs = [session.LayerBuffers(c, steps_dec, dev) for c in cfgs]
+        dec_in = [[ld.decode_inputs(s) for s in range(steps_dec)] for ld in layers]
     torch.cuda.synchronize()
 
     tokens0 = sum(kept_tokens_total(wl, ld.n_hetero, ld.n_middle) for ld in layers)
@@ -122,7 +134,7 @@ def main():
     step_bytes = [(tokens0 + (s + 1) * units) * wl.head_dim * 2 * esize for s in range(steps_dec)]
     pass_bytes = float(sum(step_bytes))
 
-    ctx = session.Context(cfgs, steps_dec)
+    ctx = session.Context(cfgs + ([stack.cfg] if batched else []), steps_dec)
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def one_pass(record):
@@ -131,11 +143,16 @@ def main():
         for ld, b in zip(layers, bufs):
             b.separate(ctx, ld.q_win, ld.k, ld.v)
             b.compress(ctx, ld.k, ld.v)
+        if batched:
+            stack.rebase()
         e1.record()
         for s in range(steps_dec):
-            for li, b in enumerate(bufs):
-                q, kn, vn = dec_in[li][s]
-                b.decode(ctx, q, kn, vn)
+            if batched:
+                stack.decode(ctx, *dec_in[s])
+            else:
+                for li, b in enumerate(bufs):
+                    q, kn, vn = dec_in[li][s]
+                    b.decode(ctx, q, kn, vn)
         e2.record()
         if record is not None:
             record.append((e0, e1, e2))
@@ -164,7 +181,7 @@ def main():
     wall_p, _, dec_ms_p = timed(args.steps)
     kern_ms, launches = tk.taskkv_profile_read(ctx.handle)
     tk.taskkv_profile_enable(ctx.handle, False)
-    total_launches = args.steps * steps_dec * wl.n_layers
+    total_launches = args.steps * steps_dec * (1 if batched else wl.n_layers)
     bytes_per_launch = pass_bytes * args.steps / total_launches
     avg_kernel_ms = kern_ms / max(launches, 1)
     achieved = bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
@@ -177,7 +194,8 @@ def main():
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.batch} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
                                f"N={wl.ctx_len} layers={wl.n_layers} sinks/recent={wl.n_sink}/{wl.n_recent} "
-                               f"decode_steps={steps_dec}",
+                               f"decode_steps={steps_dec}" + (" (one decode call per step for all layers)"
+                                                              if batched else ""),
                    "kept_tokens_after_compress": tokens0, "kv_bytes_per_decode_step": step_bytes[0]},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "decode_us_per_step": round(dec_ms * 1e3 / (args.steps * steps_dec), 3),

@@ -251,6 +251,33 @@ def test_screening_changes_no_decision(kw):
     assert 0 < rel < 5e-3            # the screening pass really ran, within its bound
 
 
+def test_layer_stack_decode_matches_per_layer_calls():
+    """Three layers with different head counts and budgets: one decode call over
+    the stacked caches gives what the per-layer calls give (same kernels, other
+    split points of the partial sums) and leaves the same lengths."""
+    ses = _session()
+    wl = small_workload(name="stack", wid=195, ctx_len=1500, n_middle=200, n_recent=100, decode_steps=5)
+    shapes = [(1, 200), (2, 90), (0, 333)]
+    lds = [make_layer(wl, r, "cuda:0") for r in range(3)]
+    cfgs = [ses.cfg_from_workload(wl, nh, nm) for nh, nm in shapes]
+    solo = [ses.LayerBuffers(c, wl.decode_steps) for c in cfgs]
+    stack = ses.LayerStack(cfgs, wl.decode_steps)
+    with ses.Context(cfgs + [stack.cfg], wl.decode_steps) as ctx:
+        for ld, a, b in zip(lds, solo, stack.layers):
+            for bufs in (a, b):
+                bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+                bufs.compress(ctx, ld.k, ld.v)
+        stack.rebase()
+        for step in range(wl.decode_steps):
+            ins = [ld.decode_inputs(step) for ld in lds]
+            ref = torch.cat([a.decode(ctx, *i).clone() for a, i in zip(solo, ins)])
+            out = stack.decode(ctx, *(torch.cat([i[j] for i in ins]) for j in range(3)))
+            torch.testing.assert_close(out, ref, rtol=0, atol=2e-5)
+        assert torch.equal(stack.lens, torch.cat([a.lens for a in solo]))
+        from paper_2501_15113_amd import taskkv_last_async_error
+        assert taskkv_last_async_error(ctx.handle) == 0
+
+
 def test_decode_is_deterministic():
     ses = _session()
     wl = small_workload(name="det", wid=155, ctx_len=5000, n_hetero=2)
