@@ -145,6 +145,7 @@ void decode_stream_kernel(
   // stores it before requesting any page (it is the only reader of that page).
   if (want_app) {
     uint16_t *kc16 = reinterpret_cast<uint16_t *>(kc), *vc16 = reinterpret_cast<uint16_t *>(vc);
+    bool stored = false;
     for (int u = u0; u < n_units && s_pref[u] < p1; ++u) {
       const int sl = s_len[u];
       if (sl >= 0) continue;                     // nothing appended to this unit
@@ -158,8 +159,9 @@ void decode_stream_kernel(
         kc16[((size_t)page + sb * 16) * D + (size_t)((e >> 3) * 16 + r) * 8 + (e & 7)] = k_new[(size_t)u * D + e];
         vc16[(size_t)page * D + (size_t)((e >> 4) * 64 + ga * 16 + (e & 15)) * 8 + ea] = v_new[(size_t)u * D + e];
       }
+      stored = true;
     }
-    __threadfence_block();
+    if (stored) __threadfence_block();   // the token is in place before its page is requested
   }
 
   // ---- ring of NP pages in flight
