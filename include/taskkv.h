@@ -199,6 +199,13 @@ int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream);
  * (bf16, no pooling, at most 512 window rows per KV head). */
 int taskkv_set_screening(taskkv_ctx *ctx, int mode);
 
+/* Row maxima and softmax denominators of the window scores (Eq. 12) are needed
+ * to fp64 accuracy.  For bf16 inputs they come from exact integer dot products
+ * on the int8 matrix cores (engine 1, default); engine 0 uses the fp64 matrix
+ * instruction, as fp32 inputs always do.  Both give the same decisions and
+ * scores that agree to fp64 rounding. */
+int taskkv_set_stats_engine(taskkv_ctx *ctx, int engine);
+
 /* Decode attention (Eq. 1 on the kept keys) deals the pages of a step to the
  * resident waves.  On MI355X the odd XCDs sustain less read bandwidth than the
  * even ones under a saturating stream, so waves of even workgroups take

@@ -14,6 +14,7 @@ EXPORTED_SYMBOLS = [
     "taskkv_cache_tokens", "taskkv_hetero_head_count", "taskkv_middle_budget", "taskkv_separate",
     "taskkv_compress", "taskkv_decode_attn", "taskkv_cache_export", "taskkv_last_async_error",
     "taskkv_profile_enable", "taskkv_profile_read", "taskkv_set_screening", "taskkv_set_stream_skew",
+    "taskkv_set_stats_engine",
 ]
 
 
@@ -86,6 +87,8 @@ def load_library():
     lib.taskkv_last_async_error.restype = C.c_int
     lib.taskkv_set_screening.argtypes = [vp, C.c_int]
     lib.taskkv_set_screening.restype = C.c_int
+    lib.taskkv_set_stats_engine.argtypes = [vp, C.c_int]
+    lib.taskkv_set_stats_engine.restype = C.c_int
     lib.taskkv_set_stream_skew.argtypes = [vp, C.c_int]
     lib.taskkv_set_stream_skew.restype = C.c_int
     lib.taskkv_profile_enable.argtypes = [vp, C.c_int]
@@ -213,6 +216,11 @@ def taskkv_last_async_error(ctx, stream=None) -> int:
 def taskkv_set_screening(ctx, mode: int) -> None:
     """0 = never, 1 = automatic (default), 2 = whenever the inputs allow."""
     _check(load_library().taskkv_set_screening(ctx, int(mode)), "taskkv_set_screening")
+
+
+def taskkv_set_stats_engine(ctx, engine: int) -> None:
+    """Row statistics of bf16 inputs: 1 = int8 digits (default), 0 = fp64 matrix instruction."""
+    _check(load_library().taskkv_set_stats_engine(ctx, int(engine)), "taskkv_set_stats_engine")
 
 
 def taskkv_set_stream_skew(ctx, skew: int) -> None:

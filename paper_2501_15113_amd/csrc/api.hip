@@ -73,6 +73,10 @@ static size_t ws_separate(const Dims &d) {
   b += al((size_t)d.units * d.T * sizeof(int32_t));                   // top-t picks
   b += al((size_t)d.units * d.N * sizeof(int32_t));                   // screening: columns to recompute
   b += 2 * al((size_t)d.units * sizeof(unsigned long long));          // their count, key norms
+  b += al((size_t)d.units * d.Rpad * d.D * 4);                        // int8 pass: digits of the window rows
+  b += al((size_t)d.units * d.Rpad * sizeof(double));                 //   row factors
+  b += al((size_t)d.units * I8_QCAP * sizeof(QTiny));                 //   remainders that do not fit
+  b += al((size_t)d.units * sizeof(int32_t));                         //   their count
   return b;
 }
 static size_t ws_compress(const Dims &d, int dtype) {
@@ -132,6 +136,7 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
   c->events_created = 0;
   c->n_cu = 0;
   c->screening = 1;
+  c->stats_engine = 1;
   c->stream_skew = STREAM_SKEW_DEFAULT;
   for (int i = 0; i < 4; ++i) c->stream_wg[i] = 0;
   hipDeviceProp_t prop;
@@ -218,8 +223,14 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   scr.band_cnt = cv.take<int32_t>((size_t)d.units * 2);
   scr.knorm = cv.take<unsigned long long>((size_t)d.units);
   scr.mode = ctx->screening;
+  I8Bufs i8;
+  i8.qdig = cv.take<char>((size_t)d.units * d.Rpad * d.D * 4);
+  i8.gq = cv.take<double>((size_t)d.units * d.Rpad);
+  i8.qtiny = cv.take<QTiny>((size_t)d.units * I8_QCAP);
+  i8.qcnt = cv.take<int32_t>((size_t)d.units);
   if (!cv.ok) return TASKKV_EWORKSPACE;
-  int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, ctx->screening ? &scr : nullptr, s);
+  int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, ctx->screening ? &scr : nullptr,
+                         ctx->stats_engine ? &i8 : nullptr, s);
   if (rc) return rc;
   rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, 0, s);
   if (rc) return rc;
@@ -324,6 +335,12 @@ int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream) {
 int taskkv_set_screening(taskkv_ctx *ctx, int mode) {
   if (!ctx || mode < 0 || mode > 2) return TASKKV_EINVAL;
   ctx->screening = mode;
+  return TASKKV_OK;
+}
+
+int taskkv_set_stats_engine(taskkv_ctx *ctx, int engine) {
+  if (!ctx || engine < 0 || engine > 1) return TASKKV_EINVAL;
+  ctx->stats_engine = engine;
   return TASKKV_OK;
 }
 

@@ -1,0 +1,442 @@
+// Row statistics of the window scores (paper Sec. 4.1, Eq. 12: the maximum and
+// the softmax denominator of every window row) for bf16 inputs, on the int8
+// matrix cores, with fp64 accuracy.
+//
+// The decisions downstream (Eq. 14 top-t, the middle-activation pick of
+// Sec. 4.2) need the denominators to about 1e-10, which fp32 logits cannot
+// give, and the fp64 matrix instruction of this part sustains only 45 TFLOP/s.
+// bf16 operands, however, make the dot products exactly computable in
+// integers: an element is +-M * 2^(e - 134) with an 8-bit M.  Every row (of
+// the window and of K) gets its own exponent E = the largest e of the row, and
+// an element is placed on the row's grid as H = M << (e - E + 20), a number
+// below 2^28 (the largest element of the row has its top bit at bit 27).  H is
+// cut into four 7-bit digits, signed by the element's sign, and
+//
+//   sum_c Hq[c] Hk[c] = sum_{a,b} 128^(a+b) sum_c dq_a[c] dk_b[c],
+//
+// where each inner sum is a v_mfma_i32_32x32x32_i8 contraction with exact
+// int32 accumulation (|sum| <= 4 * 128 * 127^2 per class a+b; the 32x32x32
+// shape issues at twice the rate of 16x16x64 on this part: 4.8 against 2.7
+// POP/s measured).  The seven class sums are combined in fp64 by Horner's rule
+// from the top class down (rounding 1e-16) and scaled by the two row factors
+// 2^(E - 154): the logit is then the exact dot product, rounded a few times in
+// fp64, like the plain fp64 definition.
+//
+// Elements more than 20 binary orders below their row's largest do not fit the
+// window.  They are rare (Gaussian bf16 data has them at a rate of a few 1e-6
+// per element) and handled without approximation.  With x = xh + r (the part
+// inside the window and the remainder),
+//
+//   q . k = qh . kh  +  sum_c rq[c] k[c]  +  sum_c qh[c] rk[c]:
+//
+// the first term is the integer contraction, the second runs over a short
+// per-unit list of window-row remainders, the third over a short per-step list
+// of key remainders, both in fp64.  Should a list overflow (data with a huge
+// dynamic range inside most rows), the logits concerned come from plain fp64
+// dot products instead.
+//
+// Lane layout of the instruction (checked on the device): A[i][k] in lane
+// i + 32 (k / 16), bytes k % 16; B[j][k] likewise; D[8 (v / 4) + 4 (l / 32) +
+// v % 4][l % 32] in register v.  Keys are the A rows, window rows the B rows.
+#include <math.h>
+
+#include "taskkv_internal.h"
+
+namespace taskkv {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int I8_WAVES = 8;                 // waves per block, one 32-row block each
+constexpr int I8_THREADS = 64 * I8_WAVES;
+constexpr int I8_KEYS = 64;                 // keys converted per step (2 tiles of 32)
+constexpr int I8_ROWS = 32 * I8_WAVES;      // window rows one block covers
+constexpr int I8_KCAP = 8;                  // listed key remainders per converting wave and step
+
+__device__ __forceinline__ void bf16_fields(uint32_t b, int &e, int &M, bool &neg) {
+  const int ef = (b >> 7) & 0xff, fr = b & 0x7f;
+  M = ef ? (0x80 | fr) : fr;   // subnormals: no hidden bit, exponent field 1
+  e = ef ? ef : 1;
+  neg = (b & 0x8000u) != 0;
+}
+// Part of an element inside the 28-bit window of a row with exponent E.
+__device__ __forceinline__ uint32_t window_part(int M, int e, int E) {
+  const int sh = e - E + 20;   // <= 20
+  const uint32_t up = (uint32_t)M << (sh & 31), down = (uint32_t)M >> min(-sh, 31);
+  return sh >= 0 ? up : down;   // both computed: no branch per element
+}
+__device__ __forceinline__ bool fits_window(int M, int e, int E) {
+  const int sh = e - E + 20;
+  const int back = min(-sh, 31);
+  return sh >= 0 || (((uint32_t)M >> back) << back) == (uint32_t)M;
+}
+__device__ __forceinline__ double bf16_to_double(uint32_t b) { return (double)__uint_as_float(b << 16); }
+
+// 16 elements (8 dwords of bf16 pairs) -> four 16-byte digit vectors; returns
+// whether every element fits the window.
+__device__ __forceinline__ bool digits_of(const uint32_t (&w)[8], int E, v4i (&dig)[4]) {
+  bool all_fit = true;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) dig[t] = v4i{0, 0, 0, 0};
+#pragma unroll
+  for (int x = 0; x < 16; ++x) {
+    const uint32_t b = (x & 1) ? (w[x >> 1] >> 16) : (w[x >> 1] & 0xffffu);
+    int e, M;
+    bool neg;
+    bf16_fields(b, e, M, neg);
+    const uint32_t H = window_part(M, e, E);
+    all_fit = all_fit && fits_window(M, e, E);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int d = (int)((H >> (7 * t)) & 127u);
+      const uint32_t byte = (uint32_t)(neg ? -d : d) & 0xffu;
+      dig[t][x >> 2] |= (int)(byte << (8 * (x & 3)));
+    }
+  }
+  return all_fit;
+}
+__device__ __forceinline__ int row_exponent_of(const uint32_t (&w)[8]) {
+  int E = 1;
+#pragma unroll
+  for (int x = 0; x < 16; ++x) {
+    const uint32_t b = (x & 1) ? (w[x >> 1] >> 16) : (w[x >> 1] & 0xffffu);
+    int e, M;
+    bool neg;
+    bf16_fields(b, e, M, neg);
+    if (M != 0 && e > E) E = e;
+  }
+  return E;
+}
+
+// Window rows [row0, row0 + R) of every unit -> digit vectors in operand
+// layout qdig[unit][rb][ks][t][lane] (rb: 32-row block, ks: 32 channels), the
+// row factors gq = scale * 2^(E - 126) (that is scale * 2^56 * 2^(E - 182)),
+// and the list of remainders.  One wave per (unit, 32-row block).
+template <int D>
+__global__ __launch_bounds__(64) void q_digits_kernel(const uint16_t *__restrict__ q, v4i *__restrict__ qdig,
+                                                      double *__restrict__ gq, QTiny *__restrict__ qtiny,
+                                                      int32_t *__restrict__ qcnt, Dims dm) {
+  constexpr int KS = D / 32;
+  const int n_rb = dm.Rpad / 32;
+  const int unit = blockIdx.x / n_rb, rb = blockIdx.x % n_rb, l = threadIdx.x;
+  const int r = rb * 32 + (l & 31), half = l >> 5;
+  uint32_t w[KS][8];
+  const bool live = r < dm.R;
+  if (live) {
+    const int rg = dm.row0 + r;
+    const int b = unit / dm.Hkv, h = unit % dm.Hkv, g = rg / dm.L, i = rg % dm.L;
+    const uint16_t *src = q + (((size_t)b * dm.Hq + h * dm.G + g) * dm.L + i) * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint4 lo = *reinterpret_cast<const uint4 *>(src + ks * 32 + half * 16);
+      const uint4 hi = *reinterpret_cast<const uint4 *>(src + ks * 32 + half * 16 + 8);
+      w[ks][0] = lo.x; w[ks][1] = lo.y; w[ks][2] = lo.z; w[ks][3] = lo.w;
+      w[ks][4] = hi.x; w[ks][5] = hi.y; w[ks][6] = hi.z; w[ks][7] = hi.w;
+    }
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int x = 0; x < 8; ++x) w[ks][x] = 0u;
+  }
+  int E = 1;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const int e = row_exponent_of(w[ks]);
+    E = e > E ? e : E;
+  }
+  E = max(E, __shfl_xor(E, 32));
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    v4i dig[4];
+    const bool ok = digits_of(w[ks], E, dig);
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      qdig[((((size_t)unit * n_rb + rb) * KS + ks) * 4 + t) * 64 + l] = dig[t];
+    if (!ok) {
+      // the remainders of the elements that do not fit go on the unit's list
+      for (int x = 0; x < 16; ++x) {
+        const uint32_t b = (x & 1) ? (w[ks][x >> 1] >> 16) : (w[ks][x >> 1] & 0xffffu);
+        int e, M;
+        bool neg;
+        bf16_fields(b, e, M, neg);
+        if (fits_window(M, e, E)) continue;
+        const double kept = ldexp((double)window_part(M, e, E), E - 154);
+        const double rem = bf16_to_double(b) - (neg ? -kept : kept);
+        const int at = atomicAdd(qcnt + unit, 1);
+        if (at < I8_QCAP) {
+          QTiny ent;
+          ent.row = r;
+          ent.c = ks * 32 + half * 16 + x;
+          ent.r = rem;
+          qtiny[(size_t)unit * I8_QCAP + at] = ent;
+        }
+      }
+    }
+  }
+  if (half == 0) gq[(size_t)unit * dm.Rpad + r] = ldexp(dm.scale, E - 126);
+}
+
+__global__ void zero_i32_kernel(int32_t *p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// part[unit][n_parts][Rpad][2] <- (row maximum, denominator) over the keys of
+// this block; grid = (key ranges, units, groups of I8_ROWS window rows).
+template <int D>
+__global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
+    const uint16_t *__restrict__ k, const v4i *__restrict__ qdig, const double *__restrict__ gq,
+    const double *__restrict__ qd, const QTiny *__restrict__ qtiny, const int32_t *__restrict__ qcnt,
+    double *__restrict__ part, Dims dm, int keys_per_wg) {
+  constexpr int KS = D / 32, SEGS = D / 16;
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, half = l >> 5;
+  const int N = dm.N, NK = dm.n_keys, L = dm.L, R = dm.R, Rpad = dm.Rpad, row0 = dm.row0;
+  const int n_rb = Rpad / 32;
+  const uint16_t *kb = k + (size_t)unit * N * D;
+  const double *qdu = qd + (size_t)unit * Rpad * D;
+  const int n_tiny_all = qcnt[unit];
+  const bool q_overflow = n_tiny_all > I8_QCAP;   // then every logit takes the plain fp64 route
+  const int n_tiny = q_overflow ? 0 : n_tiny_all;
+  const QTiny *tiny = qtiny + (size_t)unit * I8_QCAP;
+
+  __shared__ v4i s_dig[2][I8_KEYS / 32][KS][4][64];
+  __shared__ double s_fk[2][I8_KEYS];
+  __shared__ QTiny s_ktiny[2][I8_WAVES][I8_KCAP];   // .row = key of the step
+  __shared__ int s_kcnt[2][I8_WAVES];
+
+  // my 32-row block: operands, factor, statistics (lane: row c32)
+  const int rb = blockIdx.z * I8_WAVES + w;
+  const bool have = rb < n_rb;
+  const int row = (have ? rb : 0) * 32 + c32;
+  v4i qv[KS][4];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      qv[ks][t] = qdig[((((size_t)unit * n_rb + (have ? rb : 0)) * KS + ks) * 4 + t) * 64 + l];
+  const double gqr = gq[(size_t)unit * Rpad + row];
+  double m = -INFINITY, ls = 0.0;
+
+  const int kbase = blockIdx.x * keys_per_wg;
+  const int kend = min(kbase + keys_per_wg, NK);
+  const int n_steps = kend > kbase ? (kend - kbase + I8_KEYS - 1) / I8_KEYS : 0;
+
+  // converter role: thread -> (key of the step, 16-channel segment); the SEGS
+  // threads of a key sit in adjacent lanes
+  const bool converter = tid < I8_KEYS * SEGS;
+  const int ck = tid / SEGS, cseg = tid % SEGS;
+  uint32_t raw[8];
+  auto fetch = [&](int step) {
+    const int j = kbase + step * I8_KEYS + ck;
+    if (converter && step < n_steps && j < NK) {
+      const uint4 lo = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + cseg * 16);
+      const uint4 hi = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + cseg * 16 + 8);
+      raw[0] = lo.x; raw[1] = lo.y; raw[2] = lo.z; raw[3] = lo.w;
+      raw[4] = hi.x; raw[5] = hi.y; raw[6] = hi.z; raw[7] = hi.w;
+    } else {
+#pragma unroll
+      for (int x = 0; x < 8; ++x) raw[x] = 0u;
+    }
+  };
+  auto convert = [&](int buf) {
+    int E = row_exponent_of(raw);
+#pragma unroll
+    for (int off = 1; off < SEGS; off <<= 1) E = max(E, __shfl_xor(E, off));
+    v4i dig[4];
+    const bool ok = digits_of(raw, E, dig);
+    if (converter) {
+      const int tile = ck >> 5, ks = cseg >> 1, lane = (ck & 31) + 32 * (cseg & 1);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) s_dig[buf][tile][ks][t][lane] = dig[t];
+      if (cseg == 0) s_fk[buf][ck] = ldexp(1.0, E - 182);
+    }
+    // remainders of the elements that do not fit: the wave's own short list,
+    // filled lane by lane (no atomics, nothing to reset); a count above the
+    // capacity tells the readers to take the plain route for this step
+    unsigned long long bad = __ballot(converter && !ok);
+    int cnt = 0;
+    while (bad) {
+      const int src = __ffsll((long long)bad) - 1;
+      bad &= bad - 1;
+      if (l == src) {
+        for (int x = 0; x < 16; ++x) {
+          const uint32_t b = (x & 1) ? (raw[x >> 1] >> 16) : (raw[x >> 1] & 0xffffu);
+          int e, M;
+          bool neg;
+          bf16_fields(b, e, M, neg);
+          if (fits_window(M, e, E)) continue;
+          if (cnt < I8_KCAP) {
+            const double kept = ldexp((double)window_part(M, e, E), E - 154);
+            QTiny ent;
+            ent.row = ck;
+            ent.c = cseg * 16 + x;
+            ent.r = bf16_to_double(b) - (neg ? -kept : kept);
+            s_ktiny[buf][w][cnt] = ent;
+          }
+          ++cnt;
+        }
+      }
+      cnt = __shfl(cnt, src);
+    }
+    if (l == 0) s_kcnt[buf][w] = cnt;
+  };
+
+  fetch(0);
+  if (n_steps > 0) convert(0);
+  fetch(1);
+  __syncthreads();
+
+  for (int step = 0; step < n_steps; ++step) {
+    const int buf = step & 1;
+    if (step + 1 < n_steps) convert(buf ^ 1);
+    fetch(step + 2);
+    const int jstep = kbase + step * I8_KEYS;
+    int k_listed = 0;
+    bool plain = q_overflow;
+#pragma unroll
+    for (int ww = 0; ww < I8_WAVES; ++ww) {
+      const int cw = s_kcnt[buf][ww];
+      k_listed += cw;
+      plain = plain || cw > I8_KCAP;
+    }
+    if (have) {
+#pragma unroll 1
+      for (int tile = 0; tile < I8_KEYS / 32; ++tile) {
+        const int j0 = jstep + tile * 32;
+        if (j0 >= kend) break;
+        double t16[16];
+        if (!plain) {
+          v4i ka[KS][4];
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ka[ks][t] = s_dig[buf][tile][ks][t][l];
+          // classes a + b = 6 ... 0, Horner in fp64
+#pragma unroll
+          for (int cls = 6; cls >= 0; --cls) {
+            v16i acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+              const int b = cls - a;
+              if (b < 0 || b > 3) continue;
+#pragma unroll
+              for (int ks = 0; ks < KS; ++ks)
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[ks][a], qv[ks][b], acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) t16[v] = cls == 6 ? (double)acc[v] : t16[v] * 128.0 + (double)acc[v];
+          }
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            t16[v] = t16[v] * s_fk[buf][tile * 32 + 8 * (v >> 2) + 4 * half + (v & 3)] * gqr;
+          // remainders of this row's elements that did not fit: r * k[c]
+          for (int e = 0; e < n_tiny; ++e) {
+            const QTiny ent = tiny[e];
+            if (ent.row != row) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int j = j0 + 8 * (v >> 2) + 4 * half + (v & 3);
+              if (j < NK) t16[v] += ent.r * dm.scale * bf16_to_double(kb[(size_t)j * D + ent.c]);
+            }
+          }
+          // remainders of key elements that did not fit: qh[c] * r
+          if (k_listed) {
+            for (int ww = 0; ww < I8_WAVES; ++ww) {
+              const int cw = s_kcnt[buf][ww];
+              for (int e = 0; e < cw; ++e) {
+                const QTiny ent = s_ktiny[buf][ww][e];
+                const int kk = ent.row - tile * 32;          // key within the tile
+                if (kk < 0 || kk >= 32 || ((kk >> 2) & 1) != half) continue;
+                double qh = qdu[(size_t)row * D + ent.c];
+                for (int e2 = 0; e2 < n_tiny; ++e2) {
+                  const QTiny q2 = tiny[e2];
+                  if (q2.row == row && q2.c == ent.c) qh -= q2.r;
+                }
+                const int vv = 4 * (kk >> 3) + (kk & 3);
+                const double add = qh * ent.r * dm.scale;
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                  if (v == vv) t16[v] += add;
+              }
+            }
+          }
+        } else {
+          // plain fp64 dot products for the lane's sixteen keys
+#pragma unroll
+          for (int v = 0; v < 16; ++v) t16[v] = 0.0;
+          for (int cc = 0; cc < D; ++cc) {
+            const double qe = qdu[(size_t)row * D + cc];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int j = j0 + 8 * (v >> 2) + 4 * half + (v & 3);
+              t16[v] += qe * bf16_to_double(kb[(size_t)(j < NK ? j : 0) * D + cc]);
+            }
+          }
+#pragma unroll
+          for (int v = 0; v < 16; ++v) t16[v] *= dm.scale;
+        }
+        // the tile's visible logits join the running statistics at once:
+        // seventeen exponentials for sixteen logits, no per-logit selects
+        double mx = m;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int j = j0 + 8 * (v >> 2) + 4 * half + (v & 3);
+          const bool vis = j < NK && row < R && j <= N - L + (row0 + row) % L;
+          t16[v] = vis ? t16[v] : -INFINITY;
+          mx = fmax(mx, t16[v]);
+        }
+        if (mx > -INFINITY) {
+          double sum = ls * exp(m - mx);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sum += exp(t16[v] - mx);
+          ls = sum;
+          m = mx;
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // merge the two key halves of every row and write the block's partial
+  if (have) {
+    const double mo = __shfl_xor(m, 32), lo = __shfl_xor(ls, 32);
+    const double mn = fmax(m, mo);
+    if (mn > -INFINITY) ls = ls * exp(m - mn) + lo * exp(mo - mn);
+    m = mn;
+    if (half == 0) {
+      double *pp = part + ((size_t)unit * gridDim.x + blockIdx.x) * Rpad * 2;
+      pp[2 * row] = m;
+      pp[2 * row + 1] = ls;
+    }
+  }
+}
+
+bool i8_stats_supported(const Dims &dm, int dtype) {
+  return dtype == TASKKV_BF16 && (dm.D == 64 || dm.D == 128);
+}
+
+// Row statistics of one row group: digits of the window rows, then the
+// statistics partials; n_wg key ranges of keys_per_wg keys each.
+int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
+                    double *part, int n_wg, int keys_per_wg, hipStream_t s) {
+  const int n_rb = dm.Rpad / 32;
+  auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
+  auto qdig = static_cast<v4i *>(bufs.qdig);
+  zero_i32_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(bufs.qcnt, dm.units);
+  const dim3 grid(n_wg, dm.units, (dm.Rpad + I8_ROWS - 1) / I8_ROWS);
+  if (dm.D == 64) {
+    q_digits_kernel<64><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
+    score_i8_stats_kernel<64><<<grid, dim3(I8_THREADS), 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt,
+                                                               part, dm, keys_per_wg);
+  } else {
+    q_digits_kernel<128><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
+    score_i8_stats_kernel<128><<<grid, dim3(I8_THREADS), 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt,
+                                                                part, dm, keys_per_wg);
+  }
+  return hip_ok(hipGetLastError());
+}
+
+}  // namespace taskkv

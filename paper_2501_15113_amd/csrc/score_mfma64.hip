@@ -315,7 +315,7 @@ int score_rows_padded(const Dims &dm) { return dm.Rtot < ROW_GROUP ? (dm.Rtot + 
 
 template <typename T, int D>
 static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k, double *qd, double *part,
-                      double *stats, double *scores, const ScreenBufs *scr, hipStream_t s) {
+                      double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8, hipStream_t s) {
   const int cpw = chunks_per_wg_for(dm_all);
   const int n_groups = (dm_all.Rtot + ROW_GROUP - 1) / ROW_GROUP;
   // screening pays once the fp64 column pass is large compared with the extra
@@ -352,9 +352,16 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     const int n_pairs = dm.Rpad / 32;
     const int n_parts = n_wg * (n_pairs >= SNW ? 1 : SNW / n_pairs);
     const dim3 grid(n_wg, dm.units), block(64 * SNW);
-    score_mfma64_kernel<T, D, 0, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
-                                                              nullptr);
-    merge_stats_kernel<<<dim3(dm.units), dim3(256), 0, s>>>(part, stats, dm.Rpad, n_parts);
+    if (i8 != nullptr && i8_stats_supported(dm, dtype)) {
+      // bf16 inputs: exact integer dot products on the int8 matrix cores
+      int rc = launch_i8_stats(dm, q_win, k, qd, *i8, part, n_wg, cpw * SKC, s);
+      if (rc) return rc;
+      merge_stats_kernel<<<dim3(dm.units), dim3(256), 0, s>>>(part, stats, dm.Rpad, n_wg);
+    } else {
+      score_mfma64_kernel<T, D, 0, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
+                                                                nullptr);
+      merge_stats_kernel<<<dim3(dm.units), dim3(256), 0, s>>>(part, stats, dm.Rpad, n_parts);
+    }
     if (!screen) {
       score_mfma64_kernel<T, D, 1, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
                                                                 nullptr);
@@ -373,15 +380,15 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
 }
 
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
-                  double *stats, double *scores, const ScreenBufs *scr, hipStream_t s) {
+                  double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8, hipStream_t s) {
   if (dtype == TASKKV_F32) {
     auto qq = static_cast<const float *>(q_win), kk = static_cast<const float *>(k);
-    return dm.D == 64 ? run_scores<float, 64>(dm, dtype, qq, kk, qd, part, stats, scores, scr, s)
-                      : run_scores<float, 128>(dm, dtype, qq, kk, qd, part, stats, scores, scr, s);
+    return dm.D == 64 ? run_scores<float, 64>(dm, dtype, qq, kk, qd, part, stats, scores, scr, i8, s)
+                      : run_scores<float, 128>(dm, dtype, qq, kk, qd, part, stats, scores, scr, i8, s);
   }
   auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
-  return dm.D == 64 ? run_scores<uint16_t, 64>(dm, dtype, qq, kk, qd, part, stats, scores, scr, s)
-                    : run_scores<uint16_t, 128>(dm, dtype, qq, kk, qd, part, stats, scores, scr, s);
+  return dm.D == 64 ? run_scores<uint16_t, 64>(dm, dtype, qq, kk, qd, part, stats, scores, scr, i8, s)
+                    : run_scores<uint16_t, 128>(dm, dtype, qq, kk, qd, part, stats, scores, scr, i8, s);
 }
 
 }  // namespace taskkv

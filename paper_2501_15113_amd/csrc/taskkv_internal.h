@@ -44,6 +44,7 @@ struct taskkv_ctx {
   int events_created;
   int n_cu;           // compute units of the device
   int stream_skew;    // 1/1024ths of an equal share moved from the waves of odd workgroups to even ones
+  int stats_engine;   // row statistics of bf16 inputs: 0 = fp64 matrix instruction, 1 = int8 digits
   int screening;      // fp32 screening + fp64 recompute of contested columns: 0 off, 1 auto, 2 always
   int stream_wg[4];   // cached launch width of the streaming decode kernel per (D, NT) variant, 0 = unknown
 };
@@ -79,6 +80,21 @@ struct ScreenBufs {
   unsigned long long *knorm;   // [units] max squared key norm (bit pattern of a double)
   int mode;                    // 1 = when it pays, 2 = whenever the inputs allow
 };
+// Buffers of the int8 row-statistics pass (see score_i8.hip).
+constexpr int I8_QCAP = 4096;   // listed window-row remainders per unit
+struct QTiny {
+  int32_t row, c;   // window row and channel of an element that does not fit its row's window
+  double r;         // its remainder
+};
+struct I8Bufs {
+  void *qdig;       // [units][Rpad/16][D/64][4][64] 16-byte digit vectors of the window rows
+  double *gq;       // [units][Rpad] row factors
+  QTiny *qtiny;     // [units][I8_QCAP]
+  int32_t *qcnt;    // [units]
+};
+bool i8_stats_supported(const Dims &dm, int dtype);
+int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
+                    double *part, int n_wg, int keys_per_wg, hipStream_t s);
 bool screen_supported(const Dims &dm, int dtype);
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);
 int launch_screen(const Dims &dm, const void *q_win, const void *k, const double *stats, double *scores,
@@ -86,7 +102,7 @@ int launch_screen(const Dims &dm, const void *q_win, const void *k, const double
 int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
                 int32_t *band_idx, int32_t *band_cnt, hipStream_t s);
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
-                  double *stats, double *scores, const ScreenBufs *scr, hipStream_t s);
+                  double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8, hipStream_t s);
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
                   int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
                   hipStream_t s);
