@@ -162,6 +162,71 @@ def test_decode_without_append():
     run_layer(small_workload(name="noappend", wid=151), append=False, reserve=0)
 
 
+# ------------------------------------------------------------------ int8 row statistics
+def _shrink(t, rate, seed):
+    """Scales a seeded fraction of the elements by 2^-21 ... 2^-60: elements far
+    below their row's largest do not fit the 28-bit window of the int8 engine."""
+    g = torch.Generator(device=t.device).manual_seed(seed)
+    pick = torch.rand(t.shape, generator=g, device=t.device) < rate
+    expo = torch.randint(21, 61, t.shape, generator=g, device=t.device)
+    t.copy_(torch.where(pick, torch.ldexp(t.float(), -expo).to(t.dtype), t))
+
+
+@pytest.mark.parametrize("rate_q,rate_k,what", [
+    (0.002, 0.0005, "a few remainders on both lists"),
+    (0.0, 0.02, "key lists overflow: plain fp64 dot products for those steps"),
+    (0.7, 0.001, "window-row list overflows: plain fp64 dot products everywhere"),
+    (0.01, 0.004, "many remainders, same channels on both sides"),
+])
+def test_int8_statistics_with_elements_outside_the_window(rate_q, rate_k, what):
+    def tiny(ld):
+        _shrink(ld.q_win, rate_q, 11)
+        _shrink(ld.k, rate_k, 12)
+    wl = small_workload(name="i8tiny", wid=196, ctx_len=1400, n_q_heads=16, n_kv_heads=4, decode_steps=1)
+    run_layer(wl, mutate=tiny, check_batches=(0, 1))
+
+
+@pytest.mark.parametrize("side", ["window rows", "keys", "both"])
+def test_int8_statistics_when_the_remainders_carry_the_logits(side):
+    """One channel 2^30 times larger than the rest pushes every other element
+    of the row out of the 28-bit window; the other side is zero in that channel,
+    so the logits consist of the listed remainders alone.  Compression only (the
+    fp32 decode path is not meant for such keys)."""
+    def shape(ld):
+        if side in ("window rows", "both"):
+            ld.q_win[:, :, ::8, 0] = 2.0 ** 30
+            ld.k[..., 0] = 0
+        if side in ("keys", "both"):
+            special = ld.k[:, :, 3::16, :]
+            keep = torch.zeros(ld.k.shape[-1], dtype=torch.bool, device=ld.k.device)
+            keep[[1, 5, 9, 17]] = True
+            special[..., ~keep] = 0
+            special[..., 1] = -(2.0 ** 30)
+            ld.q_win[..., 1] = 0
+    wl = small_workload(name="i8rem", wid=198, ctx_len=1200, n_q_heads=16, n_kv_heads=4)
+    run_layer(wl, mutate=shape, check_batches=(0, 1), steps=0)
+
+
+def test_statistics_engines_agree():
+    """int8 digits against the fp64 matrix instruction: same masks, scores equal
+    to fp64 rounding."""
+    ses = _session()
+    from paper_2501_15113_amd import taskkv_set_stats_engine
+    wl = small_workload(name="engines", wid=197, ctx_len=3000, n_q_heads=16, n_kv_heads=4)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl, ld.n_hetero, ld.n_middle)
+    got = []
+    for engine in (0, 1):
+        bufs = ses.LayerBuffers(cfg, 0)
+        with ses.Context([cfg], 0, screening=0) as ctx:
+            taskkv_set_stats_engine(ctx.handle, engine)
+            bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+            got.append((bufs.scores.cpu().numpy(), bufs.mask.cpu().numpy(), bufs.sem_vec.cpu().numpy()))
+    np.testing.assert_allclose(got[1][0], got[0][0], rtol=1e-12, atol=1e-300)
+    assert (got[1][1] == got[0][1]).all()
+    np.testing.assert_allclose(got[1][2], got[0][2], rtol=1e-11, atol=1e-15)
+
+
 # ------------------------------------------------------------------ ties
 def test_all_equal_scores_take_lowest_positions():
     """K == 0 makes every score before the window equal: the tie rule alone
