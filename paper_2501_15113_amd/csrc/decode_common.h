@@ -84,13 +84,6 @@ __device__ __forceinline__ void attend_page(const PageRegs<D> &r, const Frag (&q
                                             int n_tok, int g, float scale_log2, float &m_run,
                                             float &l_run, floatx4 (&acc)[D / 16]) {
   constexpr int KK = D / 32, MB = D / 16;
-#ifdef TASKKV_EXP_NOCOMPUTE  // experiment only: touch the data, skip the math
-  unsigned x = 0;
-  for (int sb = 0; sb < 2; ++sb) for (int kk = 0; kk < KK; ++kk) x ^= r.kr[sb][kk].u.x ^ r.kr[sb][kk].u.y ^ r.kr[sb][kk].u.z ^ r.kr[sb][kk].u.w;
-  for (int mb = 0; mb < MB; ++mb) x ^= r.vr[mb].u.x ^ r.vr[mb].u.y ^ r.vr[mb].u.z ^ r.vr[mb].u.w;
-  acc[0][0] += __uint_as_float(x & 0x3fffffffu); m_run = 0.f; l_run = 1.f;
-  return;
-#endif
   floatx4 s[2];
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb) {

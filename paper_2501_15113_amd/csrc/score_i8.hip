@@ -72,6 +72,26 @@ __device__ __forceinline__ bool fits_window(int M, int e, int E) {
 }
 __device__ __forceinline__ double bf16_to_double(uint32_t b) { return (double)__uint_as_float(b << 16); }
 
+// exp(x) for x <= 0 (-inf included) to about 3e-16: x = (64 n + j) ln2 / 64 + r
+// with |r| <= ln2 / 128, exp(x) = 2^n * 2^(j/64) * e^r; 2^(j/64) from a table
+// of 64 doubles, e^r - 1 from five terms (r^6 / 720 < 4e-17).  Thirteen fp64
+// operations where the library routine takes about twice as many; the row
+// statistics need one exponential per logit, which is what bounds the kernel.
+__device__ __forceinline__ double exp_nonpos(double x, const double *tab) {
+  x = fmax(x, -800.0);                                   // e^-800 underflows to 0
+  const double kf = rint(x * 92.332482616893656877);     // 64 / ln 2
+  double r = fma(kf, -1.08304246932675596327e-02, x);    // ln2_hi / 64, 32 significant bits
+  r = fma(kf, -2.98158582698529328128e-12, r);           // ln2_lo / 64
+  const int ki = (int)kf;
+  const double r2 = r * r;
+  double q = fma(r, 8.33333333333333321769e-03, 4.16666666666666643537e-02);
+  q = fma(q, r, 1.66666666666666657415e-01);
+  q = fma(q, r, 0.5);
+  const double pm1 = fma(q, r2, r);                      // e^r - 1
+  const double y = tab[ki & 63];
+  return ldexp(fma(y, pm1, y), ki >> 6);
+}
+
 // 16 elements (8 dwords of bf16 pairs) -> four 16-byte digit vectors; returns
 // whether every element fits the window.
 __device__ __forceinline__ bool digits_of(const uint32_t (&w)[8], int E, v4i (&dig)[4]) {
@@ -204,6 +224,8 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
   __shared__ double s_fk[2][I8_KEYS];
   __shared__ QTiny s_ktiny[2][I8_WAVES][I8_KCAP];   // .row = key of the step
   __shared__ int s_kcnt[2][I8_WAVES];
+  __shared__ double s_pow[64];                       // 2^(j/64)
+  if (tid < 64) s_pow[tid] = exp2((double)tid * 0.015625);
 
   // my 32-row block: operands, factor, statistics (lane: row c32)
   const int rb = blockIdx.z * I8_WAVES + w;
@@ -312,9 +334,12 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
           for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int t = 0; t < 4; ++t) ka[ks][t] = s_dig[buf][tile][ks][t][l];
-          // classes a + b = 6 ... 0, Horner in fp64
-#pragma unroll
-          for (int cls = 6; cls >= 0; --cls) {
+          // classes a + b = 6 ... 0: Horner from the top class down, two classes
+          // joined in int32 (|class sum| < 2^23) before every fp64 step.
+          // (Interleaving the instructions of two classes, so that no two
+          // consecutive ones accumulate into the same registers, was measured
+          // 4 % slower: the second register block costs more than it hides.)
+          auto class_sum = [&](int cls) {
             v16i acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0;
@@ -326,8 +351,18 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
               for (int ks = 0; ks < KS; ++ks)
                 acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[ks][a], qv[ks][b], acc, 0, 0, 0);
             }
+            return acc;
+          };
+          {
+            const v16i top = class_sum(6);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) t16[v] = cls == 6 ? (double)acc[v] : t16[v] * 128.0 + (double)acc[v];
+            for (int v = 0; v < 16; ++v) t16[v] = (double)top[v];
+          }
+#pragma unroll
+          for (int cls = 5; cls >= 1; cls -= 2) {
+            const v16i hi = class_sum(cls), lo = class_sum(cls - 1);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)(hi[v] * 128 + lo[v]));
           }
 #pragma unroll
           for (int v = 0; v < 16; ++v)
@@ -389,9 +424,9 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
           mx = fmax(mx, t16[v]);
         }
         if (mx > -INFINITY) {
-          double sum = ls * exp(m - mx);
+          double sum = ls * exp_nonpos(m - mx, s_pow);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) sum += exp(t16[v] - mx);
+          for (int v = 0; v < 16; ++v) sum += exp_nonpos(t16[v] - mx, s_pow);
           ls = sum;
           m = mx;
         }
