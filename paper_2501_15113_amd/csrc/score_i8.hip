@@ -208,7 +208,7 @@ template <int D>
 __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
     const uint16_t *__restrict__ k, const v4i *__restrict__ qdig, const double *__restrict__ gq,
     const double *__restrict__ qd, const QTiny *__restrict__ qtiny, const int32_t *__restrict__ qcnt,
-    double *__restrict__ part, Dims dm, int keys_per_wg) {
+    double *__restrict__ part, unsigned long long *__restrict__ knorm, Dims dm, int keys_per_wg) {
   constexpr int KS = D / 32, SEGS = D / 16;
   const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, half = l >> 5;
   const int N = dm.N, NK = dm.n_keys, L = dm.L, R = dm.R, Rpad = dm.Rpad, row0 = dm.row0;
@@ -261,7 +261,23 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
       for (int x = 0; x < 8; ++x) raw[x] = 0u;
     }
   };
+  // the screening pass wants the largest squared key norm of the unit (slightly
+  // over-estimated): the converters see every key once
+  const bool want_norm = knorm != nullptr && blockIdx.z == 0;
+  float norm_best = 0.f;
   auto convert = [&](int buf) {
+    if (want_norm) {
+      float ss = 0.f;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const float lo = __uint_as_float(raw[x] << 16), hi = __uint_as_float(raw[x] & 0xffff0000u);
+        ss = fmaf(lo, lo, ss);
+        ss = fmaf(hi, hi, ss);
+      }
+#pragma unroll
+      for (int off = 1; off < SEGS; off <<= 1) ss += __shfl_xor(ss, off);
+      norm_best = fmaxf(norm_best, ss);
+    }
     int E = row_exponent_of(raw);
 #pragma unroll
     for (int off = 1; off < SEGS; off <<= 1) E = max(E, __shfl_xor(E, off));
@@ -311,8 +327,15 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
 
   for (int step = 0; step < n_steps; ++step) {
     const int buf = step & 1;
-    if (step + 1 < n_steps) convert(buf ^ 1);
-    fetch(step + 2);
+    // The two waves that share a SIMD (w and w + 4) would otherwise run the same
+    // phases at the same time, matrix pipe idle during both conversions and both
+    // exponential phases: the upper four waves convert after their tiles, which
+    // shifts them by one phase against their partners.
+    const bool convert_first = (w & 1) == 0;
+    if (convert_first) {
+      if (step + 1 < n_steps) convert(buf ^ 1);
+      fetch(step + 2);
+    }
     const int jstep = kbase + step * I8_KEYS;
     int k_listed = 0;
     bool plain = q_overflow;
@@ -432,9 +455,19 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
         }
       }
     }
+    if (!convert_first) {
+      if (step + 1 < n_steps) convert(buf ^ 1);
+      fetch(step + 2);
+    }
     __syncthreads();
   }
 
+  if (want_norm) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) norm_best = fmaxf(norm_best, __shfl_xor(norm_best, off));
+    if (l == 0 && norm_best > 0.f)
+      atomicMax(knorm + unit, (unsigned long long)__double_as_longlong((double)norm_best * 1.001));
+  }
   // merge the two key halves of every row and write the block's partial
   if (have) {
     const double mo = __shfl_xor(m, 32), lo = __shfl_xor(ls, 32);
@@ -456,7 +489,7 @@ bool i8_stats_supported(const Dims &dm, int dtype) {
 // Row statistics of one row group: digits of the window rows, then the
 // statistics partials; n_wg key ranges of keys_per_wg keys each.
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
-                    double *part, int n_wg, int keys_per_wg, hipStream_t s) {
+                    double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, hipStream_t s) {
   const int n_rb = dm.Rpad / 32;
   auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
   auto qdig = static_cast<v4i *>(bufs.qdig);
@@ -465,11 +498,11 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
   if (dm.D == 64) {
     q_digits_kernel<64><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
     score_i8_stats_kernel<64><<<grid, dim3(I8_THREADS), 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt,
-                                                               part, dm, keys_per_wg);
+                                                               part, knorm, dm, keys_per_wg);
   } else {
     q_digits_kernel<128><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
     score_i8_stats_kernel<128><<<grid, dim3(I8_THREADS), 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt,
-                                                                part, dm, keys_per_wg);
+                                                                part, knorm, dm, keys_per_wg);
   }
   return hip_ok(hipGetLastError());
 }

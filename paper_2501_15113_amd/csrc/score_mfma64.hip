@@ -315,7 +315,7 @@ int score_rows_padded(const Dims &dm) { return dm.Rtot < ROW_GROUP ? (dm.Rtot + 
 
 template <typename T, int D>
 static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k, double *qd, double *part,
-                      double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8, hipStream_t s) {
+                      double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8b, hipStream_t s) {
   const int cpw = chunks_per_wg_for(dm_all);
   const int n_groups = (dm_all.Rtot + ROW_GROUP - 1) / ROW_GROUP;
   // screening pays once the fp64 column pass is large compared with the extra
@@ -327,8 +327,11 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     const size_t n = (size_t)dm_all.units * dm_all.N;
     zero_f64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(scores, n);
   }
+  // the int8 statistics pass reads every key anyway and leaves the key norms
+  // the screening pass needs; otherwise they get a pass of their own
+  const bool i8 = i8b != nullptr && i8_stats_supported(dm_all, dtype);
   if (screen) {
-    int rc = launch_key_norms(dm_all, k, scr->knorm, s);
+    int rc = i8 ? launch_zero_u64(scr->knorm, dm_all.units, s) : launch_key_norms(dm_all, k, scr->knorm, s);
     if (rc) return rc;
   }
   for (int grp = 0; grp < n_groups; ++grp) {
@@ -352,9 +355,9 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     const int n_pairs = dm.Rpad / 32;
     const int n_parts = n_wg * (n_pairs >= SNW ? 1 : SNW / n_pairs);
     const dim3 grid(n_wg, dm.units), block(64 * SNW);
-    if (i8 != nullptr && i8_stats_supported(dm, dtype)) {
+    if (i8) {
       // bf16 inputs: exact integer dot products on the int8 matrix cores
-      int rc = launch_i8_stats(dm, q_win, k, qd, *i8, part, n_wg, cpw * SKC, s);
+      int rc = launch_i8_stats(dm, q_win, k, qd, *i8b, part, screen ? scr->knorm : nullptr, n_wg, cpw * SKC, s);
       if (rc) return rc;
       merge_stats_kernel<<<dim3(dm.units), dim3(256), 0, s>>>(part, stats, dm.Rpad, n_wg);
     } else {

@@ -243,6 +243,11 @@ bool screen_supported(const Dims &dm, int dtype) {
   return dtype == TASKKV_BF16 && dm.pool == 1 && dm.Rtot <= 64 * MAXQ;
 }
 
+int launch_zero_u64(unsigned long long *p, int n, hipStream_t s) {
+  zero_u64_kernel<<<dim3((n + 255) / 256), dim3(256), 0, s>>>(p, n);
+  return hip_ok(hipGetLastError());
+}
+
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s) {
   zero_u64_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(knorm, dm.units);
   int gx = (dm.N + 255) / 256;

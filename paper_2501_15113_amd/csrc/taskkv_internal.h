@@ -94,7 +94,8 @@ struct I8Bufs {
 };
 bool i8_stats_supported(const Dims &dm, int dtype);
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
-                    double *part, int n_wg, int keys_per_wg, hipStream_t s);
+                    double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, hipStream_t s);
+int launch_zero_u64(unsigned long long *p, int n, hipStream_t s);
 bool screen_supported(const Dims &dm, int dtype);
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);
 int launch_screen(const Dims &dm, const void *q_win, const void *k, const double *stats, double *scores,
