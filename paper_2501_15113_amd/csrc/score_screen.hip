@@ -140,8 +140,7 @@ __global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ s
   const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int N = dm.N, D = dm.D;
   const double *sc = scores + (size_t)unit * N;
-  __shared__ unsigned hist[256];
-  __shared__ int s_bin, s_rem;
+  __shared__ RadixScratch rs;
   __shared__ int s_wave[16];
   __shared__ double s_q[16];
 
@@ -165,12 +164,12 @@ __global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ s
   const double w3 = 3.0 * eps;
 
   int unused;
-  const double tau_t = __longlong_as_double((long long)radix_threshold(sc, 0, N, dm.T, hist, &s_bin, &s_rem, unused));
+  const double tau_t = __longlong_as_double((long long)radix_threshold(sc, 0, N, dm.T, rs, unused));
   const bool middle = dm.pack_mode == TASKKV_PACK_SELECTIVE && !dm.keep_all && dm.k > 0 &&
                       dm.k < N - dm.s1 - dm.s2;
   double tau_k = 0.0;
   if (middle)
-    tau_k = __longlong_as_double((long long)radix_threshold(sc, dm.s1, N - dm.s2, dm.k, hist, &s_bin, &s_rem, unused));
+    tau_k = __longlong_as_double((long long)radix_threshold(sc, dm.s1, N - dm.s2, dm.k, rs, unused));
   // values below 1e-30 may have been flushed to zero by the fp32 pass: treat them as ties
   const double lo_t = w3 >= 1.0 ? -1.0 : tau_t * (1.0 - w3) - 1e-30;
   const double lo_k = w3 >= 1.0 ? -1.0 : tau_k * (1.0 - w3) - 1e-30, hi_k = w3 >= 1.0 ? INFINITY : tau_k * (1.0 + w3) + 1e-30;

@@ -63,13 +63,12 @@ __global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__
     return;
   }
   const double *sc = scores + (size_t)unit * N;
-  __shared__ unsigned hist[256];
-  __shared__ int s_bin, s_rem;
+  __shared__ RadixScratch rs;
   __shared__ int s_wave[16];
 
   if (count > 0) {
     int remaining;
-    const uint64_t pat = radix_threshold(sc, lo, hi, count, hist, &s_bin, &s_rem, remaining);
+    const uint64_t pat = radix_threshold(sc, lo, hi, count, rs, remaining);
     // pat = the count-th largest score; `remaining` of the entries equal to it
     // are taken, lowest index first.
     int eq_base = 0, out_base = 0;

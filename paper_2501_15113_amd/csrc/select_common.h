@@ -23,52 +23,102 @@ __device__ __forceinline__ void hist_add_merged(unsigned *hist, bool active, uns
   }
 }
 
+// Candidates the radix select keeps in LDS once few enough remain.
+constexpr int RADIX_CAND = 4096;
+struct RadixScratch {
+  unsigned hist[256];
+  int bin, rem, n;
+  uint64_t cand[RADIX_CAND];
+};
+
 // Bit pattern of the count-th largest score inside [lo, hi), and how many of
 // the entries equal to it belong to the top `count` (lowest index first).
-// 8-bit digits, most significant first.  Called by all 1024 threads of a block;
-// hist[256], s_bin, s_rem are block-shared scratch.
+// 8-bit digits, most significant first.  Every digit costs a sweep over the
+// scores (L2 latency bound: one block per unit), so as soon as the entries
+// that still share the threshold's known digits fit RADIX_CAND, one more sweep
+// copies their bit patterns to LDS and the remaining digits are settled there:
+// typically three sweeps plus the copy instead of eight.  Called by all 1024
+// threads of a block.
 __device__ __forceinline__ uint64_t radix_threshold(const double *__restrict__ sc, int lo, int hi, int count,
-                                                    unsigned *hist, int *s_bin, int *s_rem, int &take_equal) {
-  const int tid = threadIdx.x;
+                                                    RadixScratch &rs, int &take_equal) {
+  const int tid = threadIdx.x, lane = tid & 63;
   uint64_t pat = 0, known = 0;
   int remaining = count;
+  bool in_lds = false;
+  int n_cand = 0;
   for (int pass = 7; pass >= 0; --pass) {
     const int shift = pass * 8;
-    if (tid < 256) hist[tid] = 0;
+    if (tid < 256) rs.hist[tid] = 0;
     __syncthreads();
-    for (int j0 = lo; j0 < hi; j0 += 4096) {
-      uint64_t key[4];
-      bool ok[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int j = j0 + r * 1024 + tid;
-        ok[r] = j < hi;
-        key[r] = ok[r] ? score_key(sc[j]) : 0;
+    if (in_lds) {
+      for (int i = tid; i < n_cand; i += 1024) {
+        const uint64_t key = rs.cand[i];
+        if ((key & known) == pat) atomicAdd(&rs.hist[(unsigned)(key >> shift) & 255u], 1u);
       }
+    } else {
+      for (int j0 = lo; j0 < hi; j0 += 4096) {
+        uint64_t key[4];
+        bool ok[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const bool hit = ok[r] && (key[r] & known) == pat;
-        const unsigned digit = (unsigned)(key[r] >> shift) & 255u;
-        if (pass == 7) hist_add_merged(hist, hit, digit);
-        else if (hit) atomicAdd(&hist[digit], 1u);
+        for (int r = 0; r < 4; ++r) {
+          const int j = j0 + r * 1024 + tid;
+          ok[r] = j < hi;
+          key[r] = ok[r] ? score_key(sc[j]) : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const bool hit = ok[r] && (key[r] & known) == pat;
+          const unsigned digit = (unsigned)(key[r] >> shift) & 255u;
+          if (pass == 7) hist_add_merged(rs.hist, hit, digit);
+          else if (hit) atomicAdd(&rs.hist[digit], 1u);
+        }
       }
     }
     __syncthreads();
     if (tid == 0) {
       int cum = 0, b = 255;
       for (; b > 0; --b) {
-        const int c = (int)hist[b];
+        const int c = (int)rs.hist[b];
         if (cum + c >= remaining) break;
         cum += c;
       }
-      *s_bin = b;
-      *s_rem = remaining - cum;
+      rs.bin = b;
+      rs.rem = remaining - cum;
+      rs.n = 0;
     }
     __syncthreads();
-    pat |= (uint64_t)(*s_bin) << shift;
+    const int n_match = (int)rs.hist[rs.bin];   // entries that share all digits known after this pass
+    pat |= (uint64_t)rs.bin << shift;
     known |= 0xffull << shift;
-    remaining = *s_rem;
+    remaining = rs.rem;
     __syncthreads();
+    if (!in_lds && pass >= 2 && n_match <= RADIX_CAND) {
+      for (int j0 = lo; j0 < hi; j0 += 4096) {
+        uint64_t key[4];
+        bool ok[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int j = j0 + r * 1024 + tid;
+          ok[r] = j < hi;
+          key[r] = ok[r] ? score_key(sc[j]) : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const bool hit = ok[r] && (key[r] & known) == pat;
+          const uint64_t bal = __ballot(hit);
+          if (bal) {
+            const int leader = __ffsll((unsigned long long)bal) - 1;
+            int base = 0;
+            if (lane == leader) base = atomicAdd(&rs.n, __popcll(bal));
+            base = __shfl(base, leader);
+            if (hit) rs.cand[base + __popcll(bal & ((1ull << lane) - 1ull))] = key[r];
+          }
+        }
+      }
+      __syncthreads();
+      n_cand = rs.n;
+      in_lds = true;
+    }
   }
   take_equal = remaining;
   return pat;
