@@ -90,27 +90,44 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
         }
       }
       const int jc = jchunk + ks * sub;
+      // the next tile's keys are requested before the current tile is worked on
+      auto load_keys = [&](int j0, Frag16 (&dst)[KS]) {
+        const int j = j0 + c;
+        const bool ok = j0 < jc + sub && j < N;
+        const uint16_t *kp = kb + (size_t)(ok ? j : 0) * D + (D / 4) * kg;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+          dst[kk].u = ok ? *reinterpret_cast<const uint4 *>(kp + 8 * kk) : make_uint4(0, 0, 0, 0);
+      };
+      Frag16 bk[KS], bk_next[KS];
+      load_keys(jc, bk_next);
       for (int j0 = jc; j0 < jc + sub && j0 < N; j0 += 16) {
         const int j = j0 + c;
         const bool valid = j < N;
-        Frag16 bk[KS];
-        const uint16_t *kp = kb + (size_t)(valid ? j : 0) * D + (D / 4) * kg;
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-          bk[kk].u = valid ? *reinterpret_cast<const uint4 *>(kp + 8 * kk) : make_uint4(0, 0, 0, 0);
+        for (int kk = 0; kk < KS; ++kk) bk[kk] = bk_next[kk];
+        load_keys(j0 + 16, bk_next);
         float colsum = 0.f;
+        const bool all_visible = j0 + 15 <= N - L;   // before the window: no causal mask inside the tile
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
           floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int kk = 0; kk < KS; ++kk)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][kk].b, bk[kk].b, acc, 0, 0, 0);
+          if (all_visible) {
+            // rows past R have inv = 0; keys past N are dropped when the sums are stored
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const int r2 = 64 * rq + 16 * rb + 4 * kg + v;
-            const bool vis = valid && r2 < R && j <= N - L + r2 % L;
-            const float p = __builtin_amdgcn_exp2f(fmaf(acc[v], scale_log2, -m2[rb][v])) * inv[rb][v];
-            colsum += vis ? p : 0.f;
+            for (int v = 0; v < 4; ++v)
+              colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[v], scale_log2, -m2[rb][v])), inv[rb][v], colsum);
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const int r2 = 64 * rq + 16 * rb + 4 * kg + v;
+              const bool vis = valid && r2 < R && j <= N - L + r2 % L;
+              const float p = __builtin_amdgcn_exp2f(fmaf(acc[v], scale_log2, -m2[rb][v])) * inv[rb][v];
+              colsum += vis ? p : 0.f;
+            }
           }
         }
         colsum += __shfl_xor(colsum, 16);
