@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the decode attention kernel from rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel); None until measured for the
 # default workload -- see profiles/.
-MEASURED_TRAFFIC = {"cfg5": 572.9e6}  # profiles/decode_stream_kernel_cfg5_hbm_traffic.txt
+MEASURED_TRAFFIC = {"cfg5": 573.2e6}  # profiles/decode_stream_kernel_cfg5_hbm_traffic.txt
 
 
 def n_long_units(wl, n_het):
