@@ -56,18 +56,30 @@ __global__ void q_to_f64_kernel(const T *__restrict__ q, double *__restrict__ qd
   qd[idx] = val;
 }
 
-// Fixed-order merge of the per-part row statistics.
+// Fixed-order merge of the per-part row statistics: one thread per row, the
+// records requested four at a time (the loop is bound by memory latency).
 __global__ void merge_stats_kernel(const double *__restrict__ part, double *__restrict__ stats,
                                    int Rpad, int n_parts) {
   const int unit = blockIdx.x;
   for (int r = threadIdx.x; r < Rpad; r += blockDim.x) {
     double m = -INFINITY, l = 0.0;
-    for (int c = 0; c < n_parts; ++c) {
-      const double *pp = part + (((size_t)unit * n_parts + c) * Rpad + r) * 2;
-      const double mc = pp[0], lc = pp[1];
-      if (mc > -INFINITY) {
-        const double mn = fmax(m, mc);
-        l = l * exp(m - mn) + lc * exp(mc - mn);
+    for (int c0 = 0; c0 < n_parts; c0 += 4) {
+      double mc[4], lc[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool ok = c0 + u < n_parts;
+        const double *pp = part + (((size_t)unit * n_parts + (ok ? c0 + u : 0)) * Rpad + r) * 2;
+        mc[u] = ok ? pp[0] : -INFINITY;
+        lc[u] = ok ? pp[1] : 0.0;
+      }
+      double mn = m;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) mn = fmax(mn, mc[u]);
+      if (mn > -INFINITY) {
+        double sum = l * exp(m - mn);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sum += lc[u] * exp(mc[u] - mn);
+        l = sum;
         m = mn;
       }
     }

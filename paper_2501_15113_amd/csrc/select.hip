@@ -97,22 +97,32 @@ __device__ __forceinline__ double elem_to_double(uint16_t x) {
   return (double)__uint_as_float(uint32_t(x) << 16);
 }
 
-// Eq. 15: v'[unit] = sum over the picked tokens of C[j] * V[j, :], fp64,
-// ascending token order.
+// Eq. 15: v'[unit] = sum over the picked tokens of C[j] * V[j, :] in fp64.  One
+// block per unit: 1024 / D groups of D channel threads; group g adds the picks
+// g, g + groups, ... (independent loads instead of one chain of t dependent
+// ones), and the group sums are added in group order.
 template <typename T>
-__global__ void semvec_kernel(const double *__restrict__ scores, const T *__restrict__ v,
-                              const int32_t *__restrict__ top_idx, double *__restrict__ sem, Dims dm) {
-  const int unit = blockIdx.x, c = threadIdx.x;
-  if (c >= dm.D) return;
+__global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__ scores, const T *__restrict__ v,
+                                                      const int32_t *__restrict__ top_idx,
+                                                      double *__restrict__ sem, Dims dm) {
+  const int unit = blockIdx.x, D = dm.D;
+  const int c = threadIdx.x % D, grp = threadIdx.x / D, n_grp = 1024 / D;
   const double *sc = scores + (size_t)unit * dm.N;
-  const T *vb = v + (size_t)unit * dm.N * dm.D;
+  const T *vb = v + (size_t)unit * dm.N * D;
   const int32_t *idx = top_idx + (size_t)unit * dm.T;
+  __shared__ double red[16][128];
   double acc = 0.0;
-  for (int n = 0; n < dm.T; ++n) {
+  for (int n = grp; n < dm.T; n += n_grp) {
     const int j = idx[n];
-    acc += sc[j] * elem_to_double(vb[(size_t)j * dm.D + c]);
+    acc += sc[j] * elem_to_double(vb[(size_t)j * D + c]);
   }
-  sem[(size_t)unit * dm.D + c] = acc;
+  red[grp][c] = acc;
+  __syncthreads();
+  if (grp == 0) {
+    double sum = 0.0;
+    for (int g = 0; g < n_grp; ++g) sum += red[g][c];
+    sem[(size_t)unit * D + c] = sum;
+  }
 }
 
 // Eq. 7-8 and the ranking rule: one block per batch element.
@@ -182,10 +192,10 @@ int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const vo
                        const int32_t *top_idx, double *sem_vec, double *dist, uint8_t *mask,
                        hipStream_t s) {
   if (dtype == TASKKV_F32)
-    semvec_kernel<float><<<dim3(dm.units), dim3(128), 0, s>>>(scores, static_cast<const float *>(v),
+    semvec_kernel<float><<<dim3(dm.units), dim3(1024), 0, s>>>(scores, static_cast<const float *>(v),
                                                              top_idx, sem_vec, dm);
   else
-    semvec_kernel<uint16_t><<<dim3(dm.units), dim3(128), 0, s>>>(
+    semvec_kernel<uint16_t><<<dim3(dm.units), dim3(1024), 0, s>>>(
         scores, static_cast<const uint16_t *>(v), top_idx, sem_vec, dm);
   dist_mask_kernel<<<dim3(dm.B), dim3(256), 0, s>>>(sem_vec, dist, mask, dm);
   return hip_ok(hipGetLastError());
