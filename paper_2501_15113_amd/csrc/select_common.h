@@ -75,16 +75,34 @@ __device__ __forceinline__ uint64_t radix_threshold(const double *__restrict__ s
       }
     }
     __syncthreads();
-    if (tid == 0) {
-      int cum = 0, b = 255;
-      for (; b > 0; --b) {
-        const int c = (int)rs.hist[b];
-        if (cum + c >= remaining) break;
-        cum += c;
+    if (tid < 64) {
+      // the bin that holds the remaining-th largest entry: lane i owns bins
+      // 255 - 4 i ... 252 - 4 i, a wave scan gives the count above each lane's bins
+      int c[4], own = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        c[q] = (int)rs.hist[255 - 4 * tid - q];
+        own += c[q];
       }
-      rs.bin = b;
-      rs.rem = remaining - cum;
-      rs.n = 0;
+      int incl = own;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (tid >= off) incl += t;
+      }
+      int cum = incl - own;   // entries in bins above mine
+      const uint64_t reach = __ballot(incl >= remaining);
+      const int owner = reach ? __ffsll((unsigned long long)reach) - 1 : 63;   // else bin 0 takes what is left
+      if (tid == owner) {
+        int q = 0;   // the lane's fourth bin is taken when the first three do not reach
+        for (; q < 3; ++q) {
+          if (cum + c[q] >= remaining) break;
+          cum += c[q];
+        }
+        rs.bin = 255 - 4 * tid - q;
+        rs.rem = remaining - cum;
+        rs.n = 0;
+      }
     }
     __syncthreads();
     const int n_match = (int)rs.hist[rs.bin];   // entries that share all digits known after this pass
