@@ -114,6 +114,31 @@ def test_small_sweep(i):
     run_layer(wl, check_batches=tuple(range(min(2, wl.batch))))
 
 
+def _random_case(i):
+    """Seeded draw of a small layer: shapes, window, budgets, dtype, recipe."""
+    rng = np.random.default_rng(9000 + i)
+    n_kv = int(rng.choice([1, 2, 3, 4, 8]))
+    g = int(rng.choice([1, 2, 4, 5, 8]))
+    n = int(rng.integers(40, 5000))
+    kw = dict(batch=int(rng.integers(1, 4)), n_kv_heads=n_kv, n_q_heads=n_kv * g,
+              head_dim=int(rng.choice([64, 128])), ctx_len=n,
+              obs_window=int(rng.integers(1, min(48, n) + 1)), top_t=int(rng.integers(1, 400)),
+              n_sink=int(rng.integers(0, 9)), n_recent=int(rng.integers(0, min(300, n // 2))),
+              n_middle=int(rng.integers(0, min(600, n))), n_hetero=int(rng.integers(0, n_kv + 1)),
+              add_centre_head=int(rng.integers(0, 2)), dtype=str(rng.choice(["bf16", "bf16", "f32"])),
+              recipe=str(rng.choice(["gauss", "scaled", "zipf"])), decode_steps=int(rng.integers(1, 5)))
+    if rng.random() < 0.25:
+        kw["pool_kernel"] = int(rng.choice([3, 7]))
+    return kw
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_random_small_layers(i):
+    kw = _random_case(i)
+    wl = small_workload(name=f"rand{i}", wid=300 + i, **kw)
+    run_layer(wl, check_batches=tuple(range(min(2, wl.batch))), screening=1 + i % 2)
+
+
 def test_more_units_than_the_streaming_kernel_indexes():
     """4400 (batch, KV head) units: decode runs on the chunk-grid kernels."""
     wl = small_workload(name="many_units", wid=190, batch=1100, n_q_heads=8, n_kv_heads=4, head_dim=64,
