@@ -439,12 +439,19 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
         // the tile's visible logits join the running statistics at once:
         // seventeen exponentials for sixteen logits, no per-logit selects
         double mx = m;
+        if (j0 + 31 < NK && j0 + 31 <= N - L) {
+          // a tile before the window: every key is visible to every row (rows
+          // past R carry zero digits; their statistics are never read)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int j = j0 + 8 * (v >> 2) + 4 * half + (v & 3);
-          const bool vis = j < NK && row < R && j <= N - L + (row0 + row) % L;
-          t16[v] = vis ? t16[v] : -INFINITY;
-          mx = fmax(mx, t16[v]);
+          for (int v = 0; v < 16; ++v) mx = fmax(mx, t16[v]);
+        } else {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int j = j0 + 8 * (v >> 2) + 4 * half + (v & 3);
+            const bool vis = j < NK && row < R && j <= N - L + (row0 + row) % L;
+            t16[v] = vis ? t16[v] : -INFINITY;
+            mx = fmax(mx, t16[v]);
+          }
         }
         if (mx > -INFINITY) {
           double sum = ls * exp_nonpos(m - mx, s_pow);
