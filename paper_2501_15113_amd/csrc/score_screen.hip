@@ -61,10 +61,31 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
   const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
 
   __shared__ float cs[MAXQ][QKC];
+  // the chunk's keys, read from memory once per block and shared by the four
+  // waves (each would otherwise fetch every key itself); rows padded by 16 bytes
+  // so that the sixteen keys of a tile fall into different banks
+  constexpr int KROW = D * 2 + 16;
+  __shared__ __attribute__((aligned(16))) unsigned char s_keys[QKC * KROW];
 
   for (int ch = 0; ch < chunks_per_wg; ++ch) {
     const int jchunk = (blockIdx.x * chunks_per_wg + ch) * QKC;
     if (jchunk >= N) break;
+    {
+      constexpr int PARTS = D / 8;   // 16-byte pieces per key
+      uint4 piece[QKC * PARTS / 256];
+#pragma unroll
+      for (int i = 0; i < QKC * PARTS / 256; ++i) {
+        const int idx = i * 256 + tid, key = idx / PARTS, part = idx % PARTS;
+        const int j = jchunk + key;
+        piece[i] = j < N ? *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + part * 8) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < QKC * PARTS / 256; ++i) {
+        const int idx = i * 256 + tid, key = idx / PARTS, part = idx % PARTS;
+        *reinterpret_cast<uint4 *>(s_keys + key * KROW + part * 16) = piece[i];
+      }
+    }
+    __syncthreads();
     for (int item = w; item < n_items; item += 4) {
       const int rq = item % n_rq, ks = item / n_rq;
       // A operands: lane (c, kg) holds Q[row 64 rq + 16 rb + c][(d/4) kg + 8 kk .. +8]
@@ -90,23 +111,13 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
         }
       }
       const int jc = jchunk + ks * sub;
-      // the next tile's keys are requested before the current tile is worked on
-      auto load_keys = [&](int j0, Frag16 (&dst)[KS]) {
-        const int j = j0 + c;
-        const bool ok = j0 < jc + sub && j < N;
-        const uint16_t *kp = kb + (size_t)(ok ? j : 0) * D + (D / 4) * kg;
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-          dst[kk].u = ok ? *reinterpret_cast<const uint4 *>(kp + 8 * kk) : make_uint4(0, 0, 0, 0);
-      };
-      Frag16 bk[KS], bk_next[KS];
-      load_keys(jc, bk_next);
       for (int j0 = jc; j0 < jc + sub && j0 < N; j0 += 16) {
         const int j = j0 + c;
         const bool valid = j < N;
+        Frag16 bk[KS];
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) bk[kk] = bk_next[kk];
-        load_keys(j0 + 16, bk_next);
+        for (int kk = 0; kk < KS; ++kk)
+          bk[kk].u = *reinterpret_cast<const uint4 *>(s_keys + (j - jchunk) * KROW + ((D / 4) * kg + 8 * kk) * 2);
         float colsum = 0.f;
         const bool all_visible = j0 + 15 <= N - L;   // before the window: no causal mask inside the tile
 #pragma unroll
