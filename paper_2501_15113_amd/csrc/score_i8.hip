@@ -93,39 +93,40 @@ __device__ __forceinline__ double exp_nonpos(double x, const double *tab) {
 }
 
 // 16 elements (8 dwords of bf16 pairs) -> four 16-byte digit vectors; returns
-// whether every element fits the window.
+// whether every element fits the window.  An element times 2^(154 - E) is below
+// 2^28 in magnitude, so the scaling and the conversion to an integer S (towards
+// zero: the magnitude keeps window_part's bits) are exact float operations, and
+// the element fits when converting back returns the scaled value.  Digits are
+// those of S in two's complement: three of 0 ... 127 and the signed top one,
+// S >> 21 in -128 ... 127, so that S = sum of digit_t 128^t whatever the sign.
 __device__ __forceinline__ bool digits_of(const uint32_t (&w)[8], int E, v4i (&dig)[4]) {
   bool all_fit = true;
 #pragma unroll
   for (int t = 0; t < 4; ++t) dig[t] = v4i{0, 0, 0, 0};
 #pragma unroll
   for (int x = 0; x < 16; ++x) {
-    const uint32_t b = (x & 1) ? (w[x >> 1] >> 16) : (w[x >> 1] & 0xffffu);
-    int e, M;
-    bool neg;
-    bf16_fields(b, e, M, neg);
-    const uint32_t H = window_part(M, e, E);
-    all_fit = all_fit && fits_window(M, e, E);
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int d = (int)((H >> (7 * t)) & 127u);
-      const uint32_t byte = (uint32_t)(neg ? -d : d) & 0xffu;
-      dig[t][x >> 2] |= (int)(byte << (8 * (x & 3)));
-    }
+    const float val = __uint_as_float((x & 1) ? (w[x >> 1] & 0xffff0000u) : (w[x >> 1] << 16));
+    const float scaled = ldexpf(val, 154 - E);
+    const int S = (int)scaled;
+    all_fit = all_fit && (float)S == scaled;
+    const int sh = 8 * (x & 3);
+    dig[0][x >> 2] |= (S & 127) << sh;
+    dig[1][x >> 2] |= ((S >> 7) & 127) << sh;
+    dig[2][x >> 2] |= ((S >> 14) & 127) << sh;
+    dig[3][x >> 2] |= (int)(((uint32_t)(S >> 21) & 0xffu) << sh);
   }
   return all_fit;
 }
+// Largest exponent field (at least 1) among the non-zero elements: the field
+// sits above the fraction, so it is that of the largest magnitude pattern.
 __device__ __forceinline__ int row_exponent_of(const uint32_t (&w)[8]) {
-  int E = 1;
+  uint32_t best = 0;
 #pragma unroll
-  for (int x = 0; x < 16; ++x) {
-    const uint32_t b = (x & 1) ? (w[x >> 1] >> 16) : (w[x >> 1] & 0xffffu);
-    int e, M;
-    bool neg;
-    bf16_fields(b, e, M, neg);
-    if (M != 0 && e > E) E = e;
+  for (int x = 0; x < 8; ++x) {
+    const uint32_t mag = w[x] & 0x7fff7fffu;
+    best = max(best, max(mag & 0xffffu, mag >> 16));
   }
-  return E;
+  return max((int)(best >> 7), 1);
 }
 
 // Window rows [row0, row0 + R) of every unit -> digit vectors in operand
