@@ -72,24 +72,61 @@ __device__ __forceinline__ bool fits_window(int M, int e, int E) {
 }
 __device__ __forceinline__ double bf16_to_double(uint32_t b) { return (double)__uint_as_float(b << 16); }
 
-// exp(x) for x <= 0 (-inf included) to about 3e-16: x = (64 n + j) ln2 / 64 + r
-// with |r| <= ln2 / 128, exp(x) = 2^n * 2^(j/64) * e^r; 2^(j/64) from a table
-// of 64 doubles, e^r - 1 from five terms (r^6 / 720 < 4e-17).  Thirteen fp64
+// exp(x) for x <= 0 to a relative 2e-13: x = (256 n + j) ln2 / 256 + r with
+// |r| <= ln2 / 512, exp(x) = 2^n * 2^(j/256) * e^r; 2^(j/256) from a table of
+// 256 doubles, e^r - 1 from three terms (r^4 / 24 < 1.5e-13).  Eleven fp64
 // operations where the library routine takes about twice as many; the row
 // statistics need one exponential per logit, which is what bounds the kernel.
+// CLAMP = false for arguments known to be finite (any size: a huge negative
+// one ends as 2^(-large) = 0); -inf needs the clamp, e^-800 underflows to 0.
+constexpr int EXP_TAB = 256;
+template <bool CLAMP>
 __device__ __forceinline__ double exp_nonpos(double x, const double *tab) {
-  x = fmax(x, -800.0);                                   // e^-800 underflows to 0
-  const double kf = rint(x * 92.332482616893656877);     // 64 / ln 2
-  double r = fma(kf, -1.08304246932675596327e-02, x);    // ln2_hi / 64, 32 significant bits
-  r = fma(kf, -2.98158582698529328128e-12, r);           // ln2_lo / 64
+  if (CLAMP) x = fmax(x, -800.0);
+  const double kf = rint(x * 369.3299304675746322841407);   // 256 / ln 2
+  double r = fma(kf, -0.00270760617331688990816474, x);      // ln2_hi / 256, 32 significant bits
+  r = fma(kf, -7.453964567463233203210912e-13, r);           // ln2_lo / 256
   const int ki = (int)kf;
-  const double r2 = r * r;
-  double q = fma(r, 8.33333333333333321769e-03, 4.16666666666666643537e-02);
-  q = fma(q, r, 1.66666666666666657415e-01);
-  q = fma(q, r, 0.5);
-  const double pm1 = fma(q, r2, r);                      // e^r - 1
-  const double y = tab[ki & 63];
-  return ldexp(fma(y, pm1, y), ki >> 6);
+  double q = fma(r, 1.66666666666666657415e-01, 0.5);
+  q = q * r;
+  const double pm1 = fma(q, r, r);                           // e^r - 1
+  const double y = tab[ki & (EXP_TAB - 1)];
+  return ldexp(fma(y, pm1, y), ki >> 8);
+}
+
+// carry * exp(x0) + sum of exp(x[v]) over sixteen arguments, all <= 0, in three
+// sweeps -- range reduction, table reads, polynomial -- so that the seventeen
+// table reads are in flight together instead of each being waited for where
+// it is used.  x0 may be -inf (clamped); CLAMP says whether x[] may be.
+template <bool CLAMP>
+__device__ __forceinline__ double exp_sum17(double carry, double x0, const double (&x)[16], const double *tab) {
+  double r[17];
+  int ki[17];
+#pragma unroll
+  for (int v = 0; v < 17; ++v) {
+    double xv = v == 16 ? x0 : x[v];
+    if (CLAMP || v == 16) xv = fmax(xv, -800.0);
+    const double kf = rint(xv * 369.3299304675746322841407);
+    r[v] = fma(kf, -7.453964567463233203210912e-13, fma(kf, -0.00270760617331688990816474, xv));
+    ki[v] = (int)kf;
+  }
+  double y[17];
+#pragma unroll
+  for (int v = 0; v < 17; ++v) y[v] = tab[ki[v] & (EXP_TAB - 1)];
+  __builtin_amdgcn_sched_barrier(0);   // the compiler would otherwise move every read down to its use
+#pragma unroll
+  for (int v = 0; v < 17; ++v) {
+    const double q = fma(r[v], 1.66666666666666657415e-01, 0.5) * r[v];
+    r[v] = fma(q, r[v], r[v]);         // e^r - 1
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  double sum = 0.0;
+#pragma unroll
+  for (int v = 0; v < 17; ++v) {
+    const double e = ldexp(fma(y[v], r[v], y[v]), ki[v] >> 8);
+    sum = v == 16 ? fma(carry, e, sum) : sum + e;
+  }
+  return sum;
 }
 
 // 16 elements (8 dwords of bf16 pairs) -> four 16-byte digit vectors; returns
@@ -225,8 +262,8 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
   __shared__ double s_fk[2][I8_KEYS];
   __shared__ QTiny s_ktiny[2][I8_WAVES][I8_KCAP];   // .row = key of the step
   __shared__ int s_kcnt[2][I8_WAVES];
-  __shared__ double s_pow[64];                       // 2^(j/64)
-  if (tid < 64) s_pow[tid] = exp2((double)tid * 0.015625);
+  __shared__ double s_pow[EXP_TAB];                  // 2^(j/256)
+  if (tid < EXP_TAB) s_pow[tid] = exp2((double)tid * (1.0 / EXP_TAB));
 
   // my 32-row block: operands, factor, statistics (lane: row c32)
   const int rb = blockIdx.z * I8_WAVES + w;
@@ -395,9 +432,13 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
           for (int e = 0; e < n_tiny; ++e) {
             const QTiny ent = tiny[e];
             if (ent.row != row) continue;
+            // the key indices are formed inside the loop on purpose: hoisted, their
+            // sixteen addresses and compares would be paid by every tile
+            int jl = j0 + 4 * half;
+            asm volatile("" : "+v"(jl));
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-              const int j = j0 + 8 * (v >> 2) + 4 * half + (v & 3);
+              const int j = jl + 8 * (v >> 2) + (v & 3);
               if (j < NK) t16[v] += ent.r * dm.scale * bf16_to_double(kb[(size_t)j * D + ent.c]);
             }
           }
@@ -442,9 +483,14 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
         double mx = m;
         if (j0 + 31 < NK && j0 + 31 <= N - L) {
           // a tile before the window: every key is visible to every row (rows
-          // past R carry zero digits; their statistics are never read)
+          // past R carry zero digits; their statistics are never read), so the
+          // maximum and all sixteen arguments are finite
 #pragma unroll
           for (int v = 0; v < 16; ++v) mx = fmax(mx, t16[v]);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) t16[v] -= mx;
+          ls = exp_sum17<false>(ls, m - mx, t16, s_pow);
+          m = mx;
         } else {
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
@@ -453,13 +499,12 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
             t16[v] = vis ? t16[v] : -INFINITY;
             mx = fmax(mx, t16[v]);
           }
-        }
-        if (mx > -INFINITY) {
-          double sum = ls * exp_nonpos(m - mx, s_pow);
+          if (mx > -INFINITY) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) sum += exp_nonpos(t16[v] - mx, s_pow);
-          ls = sum;
-          m = mx;
+            for (int v = 0; v < 16; ++v) t16[v] -= mx;
+            ls = exp_sum17<true>(ls, m - mx, t16, s_pow);
+            m = mx;
+          }
         }
       }
     }

@@ -38,11 +38,28 @@ def oracle_layer(ld, b, cfg):
             ms = np.sort(P[h, lo:hi])[::-1]
             if ms[cfg.n_middle - 1] != ms[cfg.n_middle]:
                 margins.append((ms[cfg.n_middle - 1] - ms[cfg.n_middle]) / ms[cfg.n_middle - 1])
-    ds = np.sort(sep["dist"])[::-1]
-    gaps = np.abs(np.diff(ds)) / max(ds[0], 1e-300)
-    gaps = gaps[gaps > 0]          # exact ties are decided by the index rule on both sides
-    if gaps.size:
-        margins.append(gaps.min())
+    # head ranking: only the two comparisons that can change the mask, the cut
+    # after the n_hetero farthest heads and the choice of the closest remaining
+    # head.  Equal distances are a tie for both sides (index rule) only when the
+    # two heads' vectors are identical bit for bit, so that both sides compute
+    # the same value twice; an equality that holds in exact arithmetic only (two
+    # KV heads are always equally far from their mean) is decided by rounding
+    # and counts as margin 0.
+    d, vec = sep["dist"], sep["sem_vec"]
+    H = len(d)
+    order = sorted(range(H), key=lambda h: (-d[h], h))
+    nh = min(cfg.n_hetero, H)
+    pairs = []
+    if cfg.add_centre_head and H - nh <= 1:
+        pass                                   # every head ends up marked, whatever the order
+    else:
+        if 0 < nh < H:
+            pairs.append((order[nh - 1], order[nh]))
+        if cfg.add_centre_head:
+            pairs.append((order[-2], order[-1]))
+    for a, c in pairs:
+        if not np.array_equal(vec[a], vec[c]):
+            margins.append(abs(d[a] - d[c]) / max(d.max(), 1e-300))
     sep.update(kept=kept, k_cache=kc, v_cache=vc, margin=min(margins) if margins else 1.0)
     return sep
 

@@ -87,8 +87,8 @@ SWEEP = [
     dict(dtype="f32", head_dim=64, n_q_heads=4, n_kv_heads=4, ctx_len=700, recipe="gauss", offset=3.0),
     dict(dtype="f32", head_dim=128, n_q_heads=12, n_kv_heads=4, ctx_len=1030, n_hetero=2),
     dict(head_dim=64, n_q_heads=16, n_kv_heads=4, ctx_len=2100, n_middle=300, n_recent=100),
-    dict(n_q_heads=32, n_kv_heads=2, ctx_len=1111, n_hetero=1),        # G = 16
-    dict(n_q_heads=40, n_kv_heads=2, ctx_len=900, n_hetero=1, obs_window=8),   # G = 20: two head slices
+    dict(n_q_heads=48, n_kv_heads=3, ctx_len=1111, n_hetero=1),        # G = 16
+    dict(n_q_heads=60, n_kv_heads=3, ctx_len=900, n_hetero=1, obs_window=8),   # G = 20: two head slices
     dict(n_hetero=0, ctx_len=640),                                     # nobody keeps everything
     dict(n_hetero=4, ctx_len=640),                                     # everybody keeps everything
     dict(add_centre_head=1, n_hetero=1, ctx_len=800),
@@ -101,7 +101,7 @@ SWEEP = [
     dict(obs_window=1, ctx_len=520),
     dict(obs_window=50, ctx_len=50, n_sink=2, n_recent=3, n_middle=4, top_t=10),   # L = N
     dict(batch=3, ctx_len=33, n_sink=1, n_recent=2, n_middle=3, obs_window=5, top_t=7),
-    dict(n_q_heads=40, n_kv_heads=2, ctx_len=600, obs_window=32, batch=1),   # 640 window rows: two row groups
+    dict(n_q_heads=60, n_kv_heads=3, ctx_len=600, obs_window=32, batch=1),   # 640 window rows: two row groups
     dict(ctx_len=700, obs_window=700, top_t=700, batch=1),             # L = N with G = 2: 1400 rows, 3 groups
     dict(n_sink=0, n_recent=0, n_middle=0, ctx_len=700, n_hetero=1),   # the other heads keep nothing
     dict(ctx_len=1536, n_sink=0, n_recent=480, n_middle=32, decode_steps=4),   # append crosses a chunk edge
@@ -129,6 +129,10 @@ def _random_case(i):
               recipe=str(rng.choice(["gauss", "scaled", "zipf"])), decode_steps=int(rng.integers(1, 5)))
     if rng.random() < 0.25:
         kw["pool_kernel"] = int(rng.choice([3, 7]))
+    if n_kv == 2 and kw["n_hetero"] + kw["add_centre_head"] == 1:
+        # two heads are equally far from their mean in exact arithmetic: which of
+        # them ranks first is rounding noise, not a property of the method
+        kw["n_hetero"], kw["add_centre_head"] = 2, 0
     return kw
 
 
