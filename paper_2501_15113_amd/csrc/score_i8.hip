@@ -259,7 +259,7 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
   const QTiny *tiny = qtiny + (size_t)unit * I8_QCAP;
 
   __shared__ v4i s_dig[2][I8_KEYS / 32][KS][4][64];
-  __shared__ double s_fk[2][I8_KEYS];
+  __shared__ int s_ek[2][I8_KEYS];                   // key factor f_k = 2^s_ek
   __shared__ QTiny s_ktiny[2][I8_WAVES][I8_KCAP];   // .row = key of the step
   __shared__ int s_kcnt[2][I8_WAVES];
   __shared__ double s_pow[EXP_TAB];                  // 2^(j/256)
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
       const int tile = ck >> 5, ks = cseg >> 1, lane = (ck & 31) + 32 * (cseg & 1);
 #pragma unroll
       for (int t = 0; t < 4; ++t) s_dig[buf][tile][ks][t][lane] = dig[t];
-      if (cseg == 0) s_fk[buf][ck] = ldexp(1.0, E - 182);
+      if (cseg == 0) s_ek[buf][ck] = E - 182;
     }
     // remainders of the elements that do not fit: the wave's own short list,
     // filled lane by lane (no atomics, nothing to reset); a count above the
@@ -395,6 +395,15 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
           for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int t = 0; t < 4; ++t) ka[ks][t] = s_dig[buf][tile][ks][t][l];
+          // exponents of the lane's sixteen keys, read here so that they have
+          // arrived long before the last Horner step needs them
+          int ek[16];
+#pragma unroll
+          for (int v4 = 0; v4 < 4; ++v4) {
+            const v4i e4 = *reinterpret_cast<const v4i *>(&s_ek[buf][tile * 32 + 8 * v4 + 4 * half]);
+#pragma unroll
+            for (int x = 0; x < 4; ++x) ek[4 * v4 + x] = e4[x];
+          }
           // classes a + b = 6 ... 0: Horner from the top class down, two classes
           // joined in int32 (|class sum| < 2^23) before every fp64 step.
           // (Interleaving the instructions of two classes, so that no two
@@ -427,7 +436,7 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
           }
 #pragma unroll
           for (int v = 0; v < 16; ++v)
-            t16[v] = t16[v] * s_fk[buf][tile * 32 + 8 * (v >> 2) + 4 * half + (v & 3)] * gqr;
+            t16[v] = ldexp(t16[v] * gqr, ek[v]);
           // remainders of this row's elements that did not fit: r * k[c]
           for (int e = 0; e < n_tiny; ++e) {
             const QTiny ent = tiny[e];
