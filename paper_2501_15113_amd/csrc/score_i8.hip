@@ -9,13 +9,14 @@
 // integers: an element is +-M * 2^(e - 134) with an 8-bit M.  Every row (of
 // the window and of K) gets its own exponent E = the largest e of the row, and
 // an element is placed on the row's grid as H = M << (e - E + 20), a number
-// below 2^28 (the largest element of the row has its top bit at bit 27).  H is
-// cut into four 7-bit digits, signed by the element's sign, and
+// below 2^28 (the largest element of the row has its top bit at bit 27).  The
+// signed value S = +-H is cut into the four digits of its two's complement
+// form, three of 0 ... 127 and the signed top one (S >> 21, -128 ... 127), and
 //
-//   sum_c Hq[c] Hk[c] = sum_{a,b} 128^(a+b) sum_c dq_a[c] dk_b[c],
+//   sum_c Sq[c] Sk[c] = sum_{a,b} 128^(a+b) sum_c dq_a[c] dk_b[c],
 //
 // where each inner sum is a v_mfma_i32_32x32x32_i8 contraction with exact
-// int32 accumulation (|sum| <= 4 * 128 * 127^2 per class a+b; the 32x32x32
+// int32 accumulation (|sum| <= 4 * 128 * 128 * 127 < 2^23 per class a+b; the 32x32x32
 // shape issues at twice the rate of 16x16x64 on this part: 4.8 against 2.7
 // POP/s measured).  The seven class sums are combined in fp64 by Horner's rule
 // from the top class down (rounding 1e-16) and scaled by the two row factors

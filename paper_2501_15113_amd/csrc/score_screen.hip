@@ -169,18 +169,28 @@ __global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ s
   const int N = dm.N, D = dm.D;
   const double *sc = scores + (size_t)unit * N;
   __shared__ RadixScratch rs;
-  __shared__ int s_wave[16];
+  __shared__ int s_cnt[32];
   __shared__ double s_q[16];
 
   // largest squared norm of a window row
   double qmax = 0.0;
-  for (int r = wv; r < dm.R; r += 16) {
-    const double *row = qd + ((size_t)unit * dm.Rpad + r) * D;
-    double ss = 0.0;
-    for (int cc = lane; cc < D; cc += 64) ss = fma(row[cc], row[cc], ss);
+  for (int r0 = wv; r0 < dm.R; r0 += 16 * 8) {
+    // eight rows of the wave at a time: sixteen loads in flight, not two
+    double e[8][2];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-    qmax = fmax(qmax, ss);
+    for (int i = 0; i < 8; ++i) {
+      const int r = r0 + 16 * i;
+      const double *row = qd + ((size_t)unit * dm.Rpad + (r < dm.R ? r : r0)) * D;
+      e[i][0] = row[lane];
+      e[i][1] = D > 64 ? row[64 + lane] : 0.0;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      double ss = fma(e[i][0], e[i][0], e[i][1] * e[i][1]);
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+      qmax = fmax(qmax, ss);   // a row past R repeats row r0
+    }
   }
   if (lane == 0) s_q[wv] = qmax;
   __syncthreads();
@@ -202,32 +212,12 @@ __global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ s
   const double lo_t = w3 >= 1.0 ? -1.0 : tau_t * (1.0 - w3) - 1e-30;
   const double lo_k = w3 >= 1.0 ? -1.0 : tau_k * (1.0 - w3) - 1e-30, hi_k = w3 >= 1.0 ? INFINITY : tau_k * (1.0 + w3) + 1e-30;
 
-  int base = 0;
-  int32_t *out = band_idx + (size_t)unit * N;
-  for (int j0 = 0; j0 < N; j0 += 1024) {
-    const int j = j0 + tid;
-    bool in = false;
-    if (j < N) {
-      const double x = sc[j];
-      in = x >= lo_t;
-      if (middle && j >= dm.s1 && j < N - dm.s2) in = in || (x >= lo_k && x <= hi_k);
-    }
-    const uint64_t bal = __ballot(in);
-    const int excl = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) s_wave[wv] = __popcll(bal);
-    __syncthreads();
-    int off = 0, tot = 0;
-#pragma unroll
-    for (int ww = 0; ww < 16; ++ww) {
-      const int cnt = s_wave[ww];
-      if (ww < wv) off += cnt;
-      tot += cnt;
-    }
-    __syncthreads();
-    if (in) out[base + off + excl] = j;
-    base += tot;
-  }
-  if (tid == 0) band_cnt[unit] = base;
+  const int listed = list_ascending(sc, 0, N, 0, band_idx + (size_t)unit * N, s_cnt, [&](int j, double x) {
+    bool in = x >= lo_t;
+    if (middle && j >= dm.s1 && j < N - dm.s2) in = in || (x >= lo_k && x <= hi_k);
+    return in ? 1 : 0;
+  });
+  if (tid == 0) band_cnt[unit] = listed;
 }
 
 __global__ void zero_u64_kernel(unsigned long long *p, int n) {

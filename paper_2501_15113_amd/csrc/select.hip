@@ -11,25 +11,6 @@ namespace taskkv {
 
 __device__ __forceinline__ uint64_t key_of(double x) { return score_key(x); }
 
-// Exclusive scan of one flag per thread over a 1024-thread block.
-__device__ __forceinline__ int block_scan_flag(bool f, int &total, int *s_wave) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const uint64_t bal = __ballot(f);
-  const int excl = __popcll(bal & ((1ull << lane) - 1ull));
-  if (lane == 0) s_wave[wv] = __popcll(bal);
-  __syncthreads();
-  int off = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < 16; ++w) {
-    const int c = s_wave[w];
-    if (w < wv) off += c;
-    tot += c;
-  }
-  __syncthreads();
-  total = tot;
-  return off + excl;
-}
-
 // Average pooling of the selection scores: stride 1, zero padding, fixed
 // divisor (Sec. 5.4 names only the kernel size).
 __global__ void pool_kernel(const double *__restrict__ c, double *__restrict__ p, int N, int width) {
@@ -64,28 +45,17 @@ __global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__
   }
   const double *sc = scores + (size_t)unit * N;
   __shared__ RadixScratch rs;
-  __shared__ int s_wave[16];
+  __shared__ int s_cnt[32];
 
   if (count > 0) {
     int remaining;
     const uint64_t pat = radix_threshold(sc, lo, hi, count, rs, remaining);
     // pat = the count-th largest score; `remaining` of the entries equal to it
     // are taken, lowest index first.
-    int eq_base = 0, out_base = 0;
-    for (int base = lo; base < hi; base += 1024) {
-      const int j = base + tid;
-      const bool in = j < hi;
-      const uint64_t key = in ? key_of(sc[j]) : 0;
-      const bool gt = in && key > pat;
-      const bool eq = in && key == pat;
-      int tot_eq, tot_sel;
-      const int eq_rank = eq_base + block_scan_flag(eq, tot_eq, s_wave);
-      const bool sel = gt || (eq && eq_rank < remaining);
-      const int pos = out_base + block_scan_flag(sel, tot_sel, s_wave);
-      if (sel) orow[prefix + pos] = j;
-      eq_base += tot_eq;
-      out_base += tot_sel;
-    }
+    list_ascending(sc, lo, hi, remaining, orow + prefix, s_cnt, [&](int, double x) {
+      const uint64_t key = key_of(x);
+      return key > pat ? 1 : (key == pat ? 2 : 0);
+    });
   }
   for (int i = tid; i < prefix; i += 1024) orow[i] = i;
   for (int i = tid; i < suffix; i += 1024) orow[prefix + count + gap + i] = N - suffix + i;

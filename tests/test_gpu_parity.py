@@ -275,6 +275,47 @@ def test_duplicated_keys_tie_to_lower_index():
     run_layer(small_workload(name="dups", wid=153, ctx_len=1000, n_middle=120), mutate=dup)
 
 
+@pytest.mark.parametrize("n_middle", [40, 700])
+def test_compress_on_scores_of_any_magnitude(n_middle):
+    """taskkv_compress ranks whatever non-negative scores the caller hands over:
+    zeros, denormals, values whose leading bits differ (the selection's first
+    sweep assumes a common leading nibble and must notice when there is none),
+    and long runs of equal values."""
+    from oracle import taskkv_oracle as orc
+    ses = _session()
+    wl = small_workload(name="magnitudes", wid=159, batch=2, ctx_len=3000, n_middle=n_middle, n_hetero=1)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 0)
+    rng = np.random.default_rng(77 + n_middle)
+    B, H, N = wl.batch, wl.n_kv_heads, wl.ctx_len
+    sc = rng.random((B, H, N)) * 1e-4
+    sc[0, 0, rng.integers(0, N, 900)] = 0.0
+    sc[0, 1, rng.integers(0, N, 300)] = 5e-324
+    sc[0, 1, rng.integers(0, N, 300)] = 3.0 + rng.random(300)            # leading nibble 4 next to 3
+    sc[0, 2, :] = np.ldexp(rng.random(N), rng.integers(-1000, 2, N))      # every exponent there is
+    sc[0, 3, :] = 0.25
+    sc[0, 3, rng.integers(0, N, 20)] = 0.5
+    sc[1, 0, :] = 0.0
+    sc[1, 1, :] = np.floor(rng.random(N) * 8) / 8                         # eight distinct values
+    mask = np.zeros((B, H), dtype=np.uint8)
+    mask[:, H - 1 if n_middle == 40 else 0] = 1
+    with ses.Context([cfg], 0) as ctx:
+        bufs.scores.copy_(torch.from_numpy(sc))
+        bufs.mask.copy_(torch.from_numpy(mask))
+        bufs.compress(ctx, ld.k, ld.v)
+        torch.cuda.synchronize()
+        kept_gpu = bufs.kept_idx.cpu().numpy().reshape(B, H, -1)
+        lens = bufs.lens.cpu().numpy().reshape(B, H)
+        for b in range(B):
+            kept, _, _ = orc.compress(to_numpy(ld.k[b]), to_numpy(ld.v[b]), sc[b], mask[b], cfg.n_sink,
+                                      cfg.n_recent, cfg.n_middle, cfg.pool_kernel, cfg.pack_mode, "bf16")
+            for h in range(H):
+                assert lens[b, h] == len(kept[h])
+                if not mask[b, h]:
+                    assert kept_gpu[b, h, :len(kept[h])].tolist() == list(kept[h]), (b, h)
+
+
 # ------------------------------------------------------------------ device-side conditions
 def test_append_to_full_unit_sets_flag_and_drops_token():
     ses = _session()
