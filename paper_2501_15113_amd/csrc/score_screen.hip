@@ -37,6 +37,21 @@ union Frag16 {
   bf16x8 b;
 };
 
+// x summed over the four lanes l, l ^ 16, l ^ 32, l ^ 48 with the two lane
+// swaps of this part (vector ALU instructions; a shuffle would go through the
+// LDS and be waited for).  permlane32_swap(a, b) exchanges the upper half of a
+// with the lower half of b, permlane16_swap the odd 16-lane rows of a with the
+// even rows of b: fed the same value twice, the two results add up to
+// x + x[l ^ 32] and x + x[l ^ 16] in every lane.
+__device__ __forceinline__ float sum_lanes_16_32(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto h = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const float y = __uint_as_float(h[0]) + __uint_as_float(h[1]);
+  const unsigned v = __float_as_uint(y);
+  const auto q = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return __uint_as_float(q[0]) + __uint_as_float(q[1]);
+}
+
 // One block = 4 waves.  A wave owns a quad of four 16-row blocks of the window
 // (A operands in registers) and a slice of the chunk's keys; for every 16-key
 // tile it forms the 64 x 16 logits with 4 x d/32 MFMAs, turns them into softmax
@@ -111,39 +126,54 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
         }
       }
       const int jc = jchunk + ks * sub;
-      for (int j0 = jc; j0 < jc + sub && j0 < N; j0 += 16) {
-        const int j = j0 + c;
-        const bool valid = j < N;
-        Frag16 bk[KS];
+      // K tiles of the next step are read from LDS before this step's work, and
+      // the sixteen matrix instructions of a tile (four accumulators, one per row
+      // block) are issued together, ahead of the exponentials
+      auto read_tile = [&](int j0, Frag16 (&bk)[KS]) {
+        const int key = min(j0 + c - jchunk, QKC - 1);
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk)
-          bk[kk].u = *reinterpret_cast<const uint4 *>(s_keys + (j - jchunk) * KROW + ((D / 4) * kg + 8 * kk) * 2);
+          bk[kk].u = *reinterpret_cast<const uint4 *>(s_keys + key * KROW + ((D / 4) * kg + 8 * kk) * 2);
+      };
+      const int jend = min(jc + sub, N);
+      Frag16 bk[KS], bk_next[KS];
+      if (jc < jend) read_tile(jc, bk);
+      for (int j0 = jc; j0 < jend; j0 += 16) {
+        const int j = j0 + c;
+        const bool valid = j < N;
+        if (j0 + 16 < jend) read_tile(j0 + 16, bk_next);
+        floatx4 acc[4];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) acc[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb)
+            acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][kk].b, bk[kk].b, acc[rb], 0, 0, 0);
         float colsum = 0.f;
-        const bool all_visible = j0 + 15 <= N - L;   // before the window: no causal mask inside the tile
+        if (j0 + 15 <= N - L) {
+          // before the window: no causal mask inside the tile.  Rows past R have
+          // inv = 0; keys past N are dropped when the sums are stored
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-          floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int kk = 0; kk < KS; ++kk)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][kk].b, bk[kk].b, acc, 0, 0, 0);
-          if (all_visible) {
-            // rows past R have inv = 0; keys past N are dropped when the sums are stored
+          for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-              colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[v], scale_log2, -m2[rb][v])), inv[rb][v], colsum);
-          } else {
+              colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[rb][v], scale_log2, -m2[rb][v])), inv[rb][v], colsum);
+        } else {
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
               const int r2 = 64 * rq + 16 * rb + 4 * kg + v;
               const bool vis = valid && r2 < R && j <= N - L + r2 % L;
-              const float p = __builtin_amdgcn_exp2f(fmaf(acc[v], scale_log2, -m2[rb][v])) * inv[rb][v];
+              const float p = __builtin_amdgcn_exp2f(fmaf(acc[rb][v], scale_log2, -m2[rb][v])) * inv[rb][v];
               colsum += vis ? p : 0.f;
             }
-          }
         }
-        colsum += __shfl_xor(colsum, 16);
-        colsum += __shfl_xor(colsum, 32);
+        colsum = sum_lanes_16_32(colsum);
         if (kg == 0) cs[rq][j - jchunk] = colsum;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) bk[kk] = bk_next[kk];
       }
     }
     __syncthreads();
