@@ -118,8 +118,7 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
   // merge the four waves (fixed order) and write the chunk's partial
   __shared__ float sm[4][16], sl[4][16];
   __shared__ float so[4][16][D + 1];
-  float l_tot = l_run + __shfl_xor(l_run, 16);
-  l_tot += __shfl_xor(l_tot, 32);
+  const float l_tot = sum_lanes_16_32(l_run);
   if (g == 0) { sm[w][c] = m_run; sl[w][c] = l_tot; }
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)

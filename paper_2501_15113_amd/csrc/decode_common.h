@@ -3,6 +3,7 @@
 
 #include <math.h>
 
+#include "lane_ops.h"
 #include "taskkv_internal.h"
 
 namespace taskkv {
@@ -100,8 +101,7 @@ __device__ __forceinline__ void attend_page(const PageRegs<D> &r, const Frag (&q
     sv[e] = t < n_tok ? s[e >> 2][e & 3] * scale_log2 : -INFINITY;
     mloc = fmaxf(mloc, sv[e]);
   }
-  mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-  mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+  mloc = max_lanes_16_32(mloc);
   const float m_new = fmaxf(m_run, mloc);  // finite: the page holds >= 1 token
   const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
   float lsum = 0.f;
@@ -149,8 +149,7 @@ __device__ __forceinline__ void page_values(const PageRegs<D> &r, const floatx4 
     sv[e] = t < n_tok ? s[e >> 2][e & 3] * scale_log2 : -INFINITY;
     mloc = fmaxf(mloc, sv[e]);
   }
-  mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-  mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+  mloc = max_lanes_16_32(mloc);
   const float m_new = fmaxf(m_run, mloc);  // finite: the page holds >= 1 token
   const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
   float lsum = 0.f;

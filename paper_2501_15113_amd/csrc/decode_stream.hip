@@ -192,8 +192,7 @@ void decode_stream_kernel(
   const int slot_h = hg * 16 + c;
 
   auto flush = [&]() {
-    float l_tot = l_run + __shfl_xor(l_run, 16);
-    l_tot += __shfl_xor(l_tot, 32);
+    const float l_tot = sum_lanes_16_32(l_run);
     if (slot_h < G) {
       const size_t pi = ((size_t)wid + u_at) * G + slot_h;
       if (g == 0) { pm[pi] = m_run; pl[pi] = l_tot; }

@@ -22,6 +22,7 @@
 // 2e-5 + R * 1.2e-7.  band_kernel evaluates the bound from the measured norms.
 #include <math.h>
 
+#include "lane_ops.h"
 #include "select_common.h"
 
 namespace taskkv {
@@ -36,21 +37,6 @@ union Frag16 {
   uint4 u;
   bf16x8 b;
 };
-
-// x summed over the four lanes l, l ^ 16, l ^ 32, l ^ 48 with the two lane
-// swaps of this part (vector ALU instructions; a shuffle would go through the
-// LDS and be waited for).  permlane32_swap(a, b) exchanges the upper half of a
-// with the lower half of b, permlane16_swap the odd 16-lane rows of a with the
-// even rows of b: fed the same value twice, the two results add up to
-// x + x[l ^ 32] and x + x[l ^ 16] in every lane.
-__device__ __forceinline__ float sum_lanes_16_32(float x) {
-  const unsigned u = __float_as_uint(x);
-  const auto h = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  const float y = __uint_as_float(h[0]) + __uint_as_float(h[1]);
-  const unsigned v = __float_as_uint(y);
-  const auto q = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-  return __uint_as_float(q[0]) + __uint_as_float(q[1]);
-}
 
 // One block = 4 waves.  A wave owns a quad of four 16-row blocks of the window
 // (A operands in registers) and a slice of the chunk's keys; for every 16-key
