@@ -332,7 +332,7 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
   const int n_groups = (dm_all.Rtot + ROW_GROUP - 1) / ROW_GROUP;
   // screening pays once the fp64 column pass is large compared with the extra
   // launches (mode 1 = decide here, 2 = whenever possible)
-  const bool big = (double)dm_all.units * dm_all.Rtot * dm_all.N >= 1e8;
+  const bool big = (double)dm_all.units * dm_all.Rtot * dm_all.N >= 3e7;   // measured: loses at 8e6, wins at 7e7
   const bool screen = scr != nullptr && n_groups == 1 && screen_supported(dm_all, dtype) &&
                       (scr->mode == 2 || big);
   if (n_groups > 1) {
