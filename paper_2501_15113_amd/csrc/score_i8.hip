@@ -48,10 +48,8 @@ namespace taskkv {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int I8_WAVES = 8;                 // waves per block, one 32-row block each
-constexpr int I8_THREADS = 64 * I8_WAVES;
+constexpr int I8_WAVES = 8;                 // waves per block at most, one 32-row block each
 constexpr int I8_KEYS = 64;                 // keys converted per step (2 tiles of 32)
-constexpr int I8_ROWS = 32 * I8_WAVES;      // window rows one block covers
 constexpr int I8_KCAP = 8;                  // listed key remainders per converting wave and step
 
 __device__ __forceinline__ void bf16_fields(uint32_t b, int &e, int &M, bool &neg) {
@@ -242,13 +240,16 @@ __global__ void zero_i32_kernel(int32_t *p, int n) {
 }
 
 // part[unit][n_parts][Rpad][2] <- (row maximum, denominator) over the keys of
-// this block; grid = (key ranges, units, groups of I8_ROWS window rows).
-template <int D>
-__global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
+// this block; grid = (key ranges, units, groups of 32 NW window rows).  NW
+// waves per block, one 32-row block each: 8, or 4 when the window has at most
+// 128 rows (two such blocks share a compute unit, so that every SIMD still
+// holds two waves with rows to work on).
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void score_i8_stats_kernel(
     const uint16_t *__restrict__ k, const v4i *__restrict__ qdig, const double *__restrict__ gq,
     const double *__restrict__ qd, const QTiny *__restrict__ qtiny, const int32_t *__restrict__ qcnt,
     double *__restrict__ part, unsigned long long *__restrict__ knorm, Dims dm, int keys_per_wg) {
-  constexpr int KS = D / 32, SEGS = D / 16;
+  constexpr int KS = D / 32, SEGS = D / 16, THREADS = 64 * NW;
   const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, half = l >> 5;
   const int N = dm.N, NK = dm.n_keys, L = dm.L, R = dm.R, Rpad = dm.Rpad, row0 = dm.row0;
   const int n_rb = Rpad / 32;
@@ -261,13 +262,13 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
 
   __shared__ v4i s_dig[2][I8_KEYS / 32][KS][4][64];
   __shared__ int s_ek[2][I8_KEYS];                   // key factor f_k = 2^s_ek
-  __shared__ QTiny s_ktiny[2][I8_WAVES][I8_KCAP];   // .row = key of the step
-  __shared__ int s_kcnt[2][I8_WAVES];
+  __shared__ QTiny s_ktiny[2][NW][I8_KCAP];   // .row = key of the step
+  __shared__ int s_kcnt[2][NW];
   __shared__ double s_pow[EXP_TAB];                  // 2^(j/256)
-  if (tid < EXP_TAB) s_pow[tid] = exp2((double)tid * (1.0 / EXP_TAB));
+  for (int i = tid; i < EXP_TAB; i += THREADS) s_pow[i] = exp2((double)i * (1.0 / EXP_TAB));
 
   // my 32-row block: operands, factor, statistics (lane: row c32)
-  const int rb = blockIdx.z * I8_WAVES + w;
+  const int rb = blockIdx.z * NW + w;
   const bool have = rb < n_rb;
   const int row = (have ? rb : 0) * 32 + c32;
   v4i qv[KS][4];
@@ -283,21 +284,25 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
   const int kend = min(kbase + keys_per_wg, NK);
   const int n_steps = kend > kbase ? (kend - kbase + I8_KEYS - 1) / I8_KEYS : 0;
 
-  // converter role: thread -> (key of the step, 16-channel segment); the SEGS
-  // threads of a key sit in adjacent lanes
-  const bool converter = tid < I8_KEYS * SEGS;
-  const int ck = tid / SEGS, cseg = tid % SEGS;
-  uint32_t raw[8];
+  // converter role: thread -> ITEMS (key of the step, 16-channel segment)
+  // pairs; the SEGS threads of a key sit in adjacent lanes, and the keys of a
+  // wave's item all lie in one tile
+  constexpr int ITEMS = (I8_KEYS * SEGS + THREADS - 1) / THREADS;
+  uint32_t raw[ITEMS][8];
   auto fetch = [&](int step) {
-    const int j = kbase + step * I8_KEYS + ck;
-    if (converter && step < n_steps && j < NK) {
-      const uint4 lo = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + cseg * 16);
-      const uint4 hi = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + cseg * 16 + 8);
-      raw[0] = lo.x; raw[1] = lo.y; raw[2] = lo.z; raw[3] = lo.w;
-      raw[4] = hi.x; raw[5] = hi.y; raw[6] = hi.z; raw[7] = hi.w;
-    } else {
 #pragma unroll
-      for (int x = 0; x < 8; ++x) raw[x] = 0u;
+    for (int it = 0; it < ITEMS; ++it) {
+      const int item = tid + it * THREADS, ck = item / SEGS, cseg = item % SEGS;
+      const int j = kbase + step * I8_KEYS + ck;
+      if (item < I8_KEYS * SEGS && step < n_steps && j < NK) {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + cseg * 16);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + cseg * 16 + 8);
+        raw[it][0] = lo.x; raw[it][1] = lo.y; raw[it][2] = lo.z; raw[it][3] = lo.w;
+        raw[it][4] = hi.x; raw[it][5] = hi.y; raw[it][6] = hi.z; raw[it][7] = hi.w;
+      } else {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) raw[it][x] = 0u;
+      }
     }
   };
   // the screening pass wants the largest squared key norm of the unit (slightly
@@ -305,56 +310,61 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
   const bool want_norm = knorm != nullptr && blockIdx.z == 0;
   float norm_best = 0.f;
   auto convert = [&](int buf) {
-    if (want_norm) {
-      float ss = 0.f;
+    int cnt = 0;   // entries on this wave's list of key remainders
 #pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        const float lo = __uint_as_float(raw[x] << 16), hi = __uint_as_float(raw[x] & 0xffff0000u);
-        ss = fmaf(lo, lo, ss);
-        ss = fmaf(hi, hi, ss);
-      }
+    for (int it = 0; it < ITEMS; ++it) {
+      const int item = tid + it * THREADS, ck = item / SEGS, cseg = item % SEGS;
+      const bool converter = item < I8_KEYS * SEGS;
+      if (want_norm) {
+        float ss = 0.f;
 #pragma unroll
-      for (int off = 1; off < SEGS; off <<= 1) ss += __shfl_xor(ss, off);
-      norm_best = fmaxf(norm_best, ss);
-    }
-    int E = row_exponent_of(raw);
-#pragma unroll
-    for (int off = 1; off < SEGS; off <<= 1) E = max(E, __shfl_xor(E, off));
-    v4i dig[4];
-    const bool ok = digits_of(raw, E, dig);
-    if (converter) {
-      const int tile = ck >> 5, ks = cseg >> 1, lane = (ck & 31) + 32 * (cseg & 1);
-#pragma unroll
-      for (int t = 0; t < 4; ++t) s_dig[buf][tile][ks][t][lane] = dig[t];
-      if (cseg == 0) s_ek[buf][ck] = E - 182;
-    }
-    // remainders of the elements that do not fit: the wave's own short list,
-    // filled lane by lane (no atomics, nothing to reset); a count above the
-    // capacity tells the readers to take the plain route for this step
-    unsigned long long bad = __ballot(converter && !ok);
-    int cnt = 0;
-    while (bad) {
-      const int src = __ffsll((long long)bad) - 1;
-      bad &= bad - 1;
-      if (l == src) {
-        for (int x = 0; x < 16; ++x) {
-          const uint32_t b = (x & 1) ? (raw[x >> 1] >> 16) : (raw[x >> 1] & 0xffffu);
-          int e, M;
-          bool neg;
-          bf16_fields(b, e, M, neg);
-          if (fits_window(M, e, E)) continue;
-          if (cnt < I8_KCAP) {
-            const double kept = ldexp((double)window_part(M, e, E), E - 154);
-            QTiny ent;
-            ent.row = ck;
-            ent.c = cseg * 16 + x;
-            ent.r = bf16_to_double(b) - (neg ? -kept : kept);
-            s_ktiny[buf][w][cnt] = ent;
-          }
-          ++cnt;
+        for (int x = 0; x < 8; ++x) {
+          const float lo = __uint_as_float(raw[it][x] << 16), hi = __uint_as_float(raw[it][x] & 0xffff0000u);
+          ss = fmaf(lo, lo, ss);
+          ss = fmaf(hi, hi, ss);
         }
+#pragma unroll
+        for (int off = 1; off < SEGS; off <<= 1) ss += __shfl_xor(ss, off);
+        norm_best = fmaxf(norm_best, ss);
       }
-      cnt = __shfl(cnt, src);
+      int E = row_exponent_of(raw[it]);
+#pragma unroll
+      for (int off = 1; off < SEGS; off <<= 1) E = max(E, __shfl_xor(E, off));
+      v4i dig[4];
+      const bool ok = digits_of(raw[it], E, dig);
+      if (converter) {
+        const int tile = ck >> 5, ks = cseg >> 1, lane = (ck & 31) + 32 * (cseg & 1);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) s_dig[buf][tile][ks][t][lane] = dig[t];
+        if (cseg == 0) s_ek[buf][ck] = E - 182;
+      }
+      // remainders of the elements that do not fit: the wave's own short list,
+      // filled lane by lane (no atomics, nothing to reset); a count above the
+      // capacity tells the readers to take the plain route for this step
+      unsigned long long bad = __ballot(converter && !ok);
+      while (bad) {
+        const int src = __ffsll((long long)bad) - 1;
+        bad &= bad - 1;
+        if (l == src) {
+          for (int x = 0; x < 16; ++x) {
+            const uint32_t b = (x & 1) ? (raw[it][x >> 1] >> 16) : (raw[it][x >> 1] & 0xffffu);
+            int e, M;
+            bool neg;
+            bf16_fields(b, e, M, neg);
+            if (fits_window(M, e, E)) continue;
+            if (cnt < I8_KCAP) {
+              const double kept = ldexp((double)window_part(M, e, E), E - 154);
+              QTiny ent;
+              ent.row = ck;
+              ent.c = cseg * 16 + x;
+              ent.r = bf16_to_double(b) - (neg ? -kept : kept);
+              s_ktiny[buf][w][cnt] = ent;
+            }
+            ++cnt;
+          }
+        }
+        cnt = __shfl(cnt, src);
+      }
     }
     if (l == 0) s_kcnt[buf][w] = cnt;
   };
@@ -379,7 +389,7 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
     int k_listed = 0;
     bool plain = q_overflow;
 #pragma unroll
-    for (int ww = 0; ww < I8_WAVES; ++ww) {
+    for (int ww = 0; ww < NW; ++ww) {
       const int cw = s_kcnt[buf][ww];
       k_listed += cw;
       plain = plain || cw > I8_KCAP;
@@ -454,7 +464,7 @@ __global__ __launch_bounds__(I8_THREADS) void score_i8_stats_kernel(
           }
           // remainders of key elements that did not fit: qh[c] * r
           if (k_listed) {
-            for (int ww = 0; ww < I8_WAVES; ++ww) {
+            for (int ww = 0; ww < NW; ++ww) {
               const int cw = s_kcnt[buf][ww];
               for (int e = 0; e < cw; ++e) {
                 const QTiny ent = s_ktiny[buf][ww][e];
@@ -557,15 +567,20 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
   auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
   auto qdig = static_cast<v4i *>(bufs.qdig);
   zero_i32_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(bufs.qcnt, dm.units);
-  const dim3 grid(n_wg, dm.units, (dm.Rpad + I8_ROWS - 1) / I8_ROWS);
+  const bool small = n_rb <= 4;   // at most 128 window rows: blocks of four waves
+  const int rows_per_block = small ? 128 : 256;
+  const dim3 grid(n_wg, dm.units, (dm.Rpad + rows_per_block - 1) / rows_per_block);
+  auto launch = [&](auto kernel, int threads) {
+    kernel<<<grid, dim3(threads), 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, part, knorm, dm, keys_per_wg);
+  };
   if (dm.D == 64) {
     q_digits_kernel<64><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
-    score_i8_stats_kernel<64><<<grid, dim3(I8_THREADS), 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt,
-                                                               part, knorm, dm, keys_per_wg);
+    if (small) launch(score_i8_stats_kernel<64, 4>, 256);
+    else launch(score_i8_stats_kernel<64, 8>, 512);
   } else {
     q_digits_kernel<128><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
-    score_i8_stats_kernel<128><<<grid, dim3(I8_THREADS), 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt,
-                                                                part, knorm, dm, keys_per_wg);
+    if (small) launch(score_i8_stats_kernel<128, 4>, 256);
+    else launch(score_i8_stats_kernel<128, 8>, 512);
   }
   return hip_ok(hipGetLastError());
 }
