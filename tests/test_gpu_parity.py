@@ -283,7 +283,7 @@ def test_compress_on_scores_of_any_magnitude(n_middle):
     and long runs of equal values."""
     from oracle import taskkv_oracle as orc
     ses = _session()
-    wl = small_workload(name="magnitudes", wid=159, batch=2, ctx_len=3000, n_middle=n_middle, n_hetero=1)
+    wl = small_workload(name="magnitudes", wid=159, batch=2, ctx_len=9000, n_middle=n_middle, n_hetero=1)   # more than the selection keeps in LDS
     ld = make_layer(wl, 0, "cuda:0")
     cfg = ses.cfg_from_workload(wl)
     bufs = ses.LayerBuffers(cfg, 0)
