@@ -105,6 +105,14 @@ SWEEP = [
     dict(ctx_len=700, obs_window=700, top_t=700, batch=1),             # L = N with G = 2: 1400 rows, 3 groups
     dict(n_sink=0, n_recent=0, n_middle=0, ctx_len=700, n_hetero=1),   # the other heads keep nothing
     dict(ctx_len=1536, n_sink=0, n_recent=480, n_middle=32, decode_steps=4),   # append crosses a chunk edge
+    # the largest shapes the library accepts
+    dict(n_q_heads=64, n_kv_heads=1, n_hetero=0, obs_window=8, ctx_len=700, batch=1),   # G = 64: four head slices
+    dict(n_q_heads=64, n_kv_heads=1, n_hetero=0, obs_window=8, ctx_len=700, batch=1, head_dim=64, dtype="f32"),
+    dict(n_q_heads=256, n_kv_heads=256, n_hetero=30, ctx_len=300, batch=1, obs_window=4, top_t=20,
+         n_middle=10, n_recent=8),                                     # 256 KV heads
+    dict(n_q_heads=192, n_kv_heads=3, n_hetero=1, obs_window=8, ctx_len=520, batch=1, head_dim=64),   # 512 window rows
+    dict(n_q_heads=12, n_kv_heads=3, n_hetero=1, obs_window=32, ctx_len=40000, n_middle=2000, n_recent=1000,
+         batch=1, decode_steps=2),                                     # a long context, budgets in the thousands
 ]
 
 
