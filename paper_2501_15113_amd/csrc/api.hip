@@ -223,6 +223,7 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   scr.band_cnt = cv.take<int32_t>((size_t)d.units * 2);
   scr.knorm = cv.take<unsigned long long>((size_t)d.units);
   scr.mode = ctx->screening;
+  scr.n_cu = ctx->n_cu;
   I8Bufs i8;
   i8.qdig = cv.take<char>((size_t)d.units * d.Rpad * d.D * 4);
   i8.gq = cv.take<double>((size_t)d.units * d.Rpad);

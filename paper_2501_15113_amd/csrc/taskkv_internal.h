@@ -79,6 +79,7 @@ struct ScreenBufs {
   int32_t *band_cnt;           // [units]
   unsigned long long *knorm;   // [units] max squared key norm (bit pattern of a double)
   int mode;                    // 1 = when it pays, 2 = whenever the inputs allow
+  int n_cu;                    // compute units of the device
 };
 // Buffers of the int8 row-statistics pass (see score_i8.hip).
 constexpr int I8_QCAP = 4096;   // listed window-row remainders per unit
