@@ -41,6 +41,8 @@
 // v % 4][l % 32] in register v.  Keys are the A rows, window rows the B rows.
 #include <math.h>
 
+#include <type_traits>
+
 #include "taskkv_internal.h"
 
 namespace taskkv {
@@ -264,6 +266,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   __shared__ int s_ek[2][I8_KEYS];                   // key factor f_k = 2^s_ek
   __shared__ QTiny s_ktiny[2][NW][I8_KCAP];   // .row = key of the step
   __shared__ int s_kcnt[2][NW];
+  __shared__ int s_knz[2][NW];                       // bit t: tile t of the step has a non-zero lowest key digit
   __shared__ double s_pow[EXP_TAB];                  // 2^(j/256)
   for (int i = tid; i < EXP_TAB; i += THREADS) s_pow[i] = exp2((double)i * (1.0 / EXP_TAB));
 
@@ -279,6 +282,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
       qv[ks][t] = qdig[((((size_t)unit * n_rb + (have ? rb : 0)) * KS + ks) * 4 + t) * 64 + l];
   const double gqr = gq[(size_t)unit * Rpad + row];
   double m = -INFINITY, ls = 0.0;
+  // The lowest digit of an element is non-zero only if the element is 2^14 times
+  // smaller than the largest of its row, so the lowest digits of a whole 32-row
+  // block (all channels) are often all zero: the products with them are left out.
+  bool q_low = false;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) q_low = q_low || (qv[ks][0][0] | qv[ks][0][1] | qv[ks][0][2] | qv[ks][0][3]) != 0;
+  const bool q_low_zero = __ballot(q_low) == 0ull;
 
   const int kbase = blockIdx.x * keys_per_wg;
   const int kend = min(kbase + keys_per_wg, NK);
@@ -311,6 +321,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   float norm_best = 0.f;
   auto convert = [&](int buf) {
     int cnt = 0;   // entries on this wave's list of key remainders
+    int low_tiles = 0;   // tiles in which one of this wave's keys has a non-zero lowest digit
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
       const int item = tid + it * THREADS, ck = item / SEGS, cseg = item % SEGS;
@@ -332,6 +343,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
       for (int off = 1; off < SEGS; off <<= 1) E = max(E, __shfl_xor(E, off));
       v4i dig[4];
       const bool ok = digits_of(raw[it], E, dig);
+      if (__ballot(converter && (dig[0][0] | dig[0][1] | dig[0][2] | dig[0][3]) != 0) != 0ull)
+        low_tiles |= 1 << ((((w + it * NW) * 64) / SEGS) >> 5);   // the keys of a wave's item lie in one tile
       if (converter) {
         const int tile = ck >> 5, ks = cseg >> 1, lane = (ck & 31) + 32 * (cseg & 1);
 #pragma unroll
@@ -366,7 +379,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
         cnt = __shfl(cnt, src);
       }
     }
-    if (l == 0) s_kcnt[buf][w] = cnt;
+    if (l == 0) {
+      s_kcnt[buf][w] = cnt;
+      s_knz[buf][w] = low_tiles;
+    }
   };
 
   fetch(0);
@@ -386,14 +402,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
       fetch(step + 2);
     }
     const int jstep = kbase + step * I8_KEYS;
-    int k_listed = 0;
+    int k_listed = 0, knz = 0;
     bool plain = q_overflow;
 #pragma unroll
     for (int ww = 0; ww < NW; ++ww) {
       const int cw = s_kcnt[buf][ww];
       k_listed += cw;
       plain = plain || cw > I8_KCAP;
+      knz |= s_knz[buf][ww];
     }
+    knz = __builtin_amdgcn_readfirstlane(knz);
     if (have) {
 #pragma unroll 1
       for (int tile = 0; tile < I8_KEYS / 32; ++tile) {
@@ -420,30 +438,54 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
           // (Interleaving the instructions of two classes, so that no two
           // consecutive ones accumulate into the same registers, was measured
           // 4 % slower: the second register block costs more than it hides.)
-          auto class_sum = [&](int cls) {
-            v16i acc;
+          // KZ / QZ: the tile's lowest key digits / the row block's lowest
+          // digits are all zero, so the products with digit 0 on that side drop
+          // out; four straight-line variants, chosen once per tile.
+          auto contract = [&](auto kz, auto qz) {
+            constexpr bool KZ = decltype(kz)::value, QZ = decltype(qz)::value;
+            auto class_sum = [&](int cls) {
+              v16i acc;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0;
+              for (int v = 0; v < 16; ++v) acc[v] = 0;
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-              const int b = cls - a;
-              if (b < 0 || b > 3) continue;
+              for (int a = KZ ? 1 : 0; a < 4; ++a) {
+                const int b = cls - a;
+                if (b < (QZ ? 1 : 0) || b > 3) continue;
 #pragma unroll
-              for (int ks = 0; ks < KS; ++ks)
-                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[ks][a], qv[ks][b], acc, 0, 0, 0);
+                for (int ks = 0; ks < KS; ++ks)
+                  acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka[ks][a], qv[ks][b], acc, 0, 0, 0);
+              }
+              return acc;
+            };
+            {
+              const v16i top = class_sum(6);
+#pragma unroll
+              for (int v = 0; v < 16; ++v) t16[v] = (double)top[v];
             }
-            return acc;
+#pragma unroll
+            for (int cls = 5; cls >= 1; cls -= 2) {
+              if (KZ && QZ && cls == 1) {
+                // classes 1 and 0 are empty
+#pragma unroll
+                for (int v = 0; v < 16; ++v) t16[v] *= 16384.0;
+              } else if ((KZ || QZ) && cls == 1) {
+                const v16i hi = class_sum(1);   // class 0 is empty
+#pragma unroll
+                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)(hi[v] * 128));
+              } else {
+                const v16i hi = class_sum(cls), lo = class_sum(cls - 1);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)(hi[v] * 128 + lo[v]));
+              }
+            }
           };
-          {
-            const v16i top = class_sum(6);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) t16[v] = (double)top[v];
-          }
-#pragma unroll
-          for (int cls = 5; cls >= 1; cls -= 2) {
-            const v16i hi = class_sum(cls), lo = class_sum(cls - 1);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)(hi[v] * 128 + lo[v]));
+          const bool k_low_zero = !((knz >> tile) & 1);
+          if (k_low_zero) {
+            if (q_low_zero) contract(std::true_type{}, std::true_type{});
+            else contract(std::true_type{}, std::false_type{});
+          } else {
+            if (q_low_zero) contract(std::false_type{}, std::true_type{});
+            else contract(std::false_type{}, std::false_type{});
           }
 #pragma unroll
           for (int v = 0; v < 16; ++v)
