@@ -68,49 +68,64 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
   constexpr int KROW = D * 2 + 16;
   __shared__ __attribute__((aligned(16))) unsigned char s_keys[QKC * KROW];
 
+  // A operands: lane (c, kg) holds Q[row 64 rq + 16 rb + c][(d/4) kg + 8 kk .. +8].
+  // They and the rows' statistics are loaded when the wave's row quad changes:
+  // once per block when there are at most four quad-slice items.
+  Frag16 a[4][KS];
+  float m2[4][4], inv[4][4];
+  int cur_rq = -1;
+  auto load_rows = [&](int rq) {
+    if (rq == cur_rq) return;
+    cur_rq = rq;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) {
+      const int row = 64 * rq + 16 * rb + c;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = make_uint4(0, 0, 0, 0);
+      if (row < R) {
+        const int g = row / L, i = row % L;
+        const uint16_t *qp = q_win + (((size_t)b * dm.Hq + (size_t)h * dm.G + g) * L + i) * D + (D / 4) * kg;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = *reinterpret_cast<const uint4 *>(qp + 8 * kk);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r2 = 64 * rq + 16 * rb + 4 * kg + v;   // row of accumulator register v
+        const bool ok = r2 < R;
+        m2[rb][v] = ok ? (float)(st[2 * r2] * 1.4426950408889634) : 0.f;
+        inv[rb][v] = ok ? (float)(1.0 / st[2 * r2 + 1]) : 0.f;
+      }
+    }
+  };
+
   for (int ch = 0; ch < chunks_per_wg; ++ch) {
     const int jchunk = (blockIdx.x * chunks_per_wg + ch) * QKC;
     if (jchunk >= N) break;
     {
+      // in rounds of eight 16-byte pieces per thread: few registers, so that the
+      // window rows can stay in registers across chunks
       constexpr int PARTS = D / 8;   // 16-byte pieces per key
-      uint4 piece[QKC * PARTS / 256];
+      constexpr int ROUND = 8, N_ROUNDS = QKC * PARTS / 256 / ROUND;
+#pragma unroll 1
+      for (int rd = 0; rd < N_ROUNDS; ++rd) {
+        uint4 piece[ROUND];
 #pragma unroll
-      for (int i = 0; i < QKC * PARTS / 256; ++i) {
-        const int idx = i * 256 + tid, key = idx / PARTS, part = idx % PARTS;
-        const int j = jchunk + key;
-        piece[i] = j < N ? *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + part * 8) : make_uint4(0, 0, 0, 0);
-      }
+        for (int i = 0; i < ROUND; ++i) {
+          const int idx = (rd * ROUND + i) * 256 + tid, key = idx / PARTS, part = idx % PARTS;
+          const int j = jchunk + key;
+          piece[i] = j < N ? *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + part * 8) : make_uint4(0, 0, 0, 0);
+        }
 #pragma unroll
-      for (int i = 0; i < QKC * PARTS / 256; ++i) {
-        const int idx = i * 256 + tid, key = idx / PARTS, part = idx % PARTS;
-        *reinterpret_cast<uint4 *>(s_keys + key * KROW + part * 16) = piece[i];
+        for (int i = 0; i < ROUND; ++i) {
+          const int idx = (rd * ROUND + i) * 256 + tid, key = idx / PARTS, part = idx % PARTS;
+          *reinterpret_cast<uint4 *>(s_keys + key * KROW + part * 16) = piece[i];
+        }
       }
     }
     __syncthreads();
     for (int item = w; item < n_items; item += 4) {
       const int rq = item % n_rq, ks = item / n_rq;
-      // A operands: lane (c, kg) holds Q[row 64 rq + 16 rb + c][(d/4) kg + 8 kk .. +8]
-      Frag16 a[4][KS];
-      float m2[4][4], inv[4][4];
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        const int row = 64 * rq + 16 * rb + c;
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = make_uint4(0, 0, 0, 0);
-        if (row < R) {
-          const int g = row / L, i = row % L;
-          const uint16_t *qp = q_win + (((size_t)b * dm.Hq + (size_t)h * dm.G + g) * L + i) * D + (D / 4) * kg;
-#pragma unroll
-          for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = *reinterpret_cast<const uint4 *>(qp + 8 * kk);
-        }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int r2 = 64 * rq + 16 * rb + 4 * kg + v;   // row of accumulator register v
-          const bool ok = r2 < R;
-          m2[rb][v] = ok ? (float)(st[2 * r2] * 1.4426950408889634) : 0.f;
-          inv[rb][v] = ok ? (float)(1.0 / st[2 * r2 + 1]) : 0.f;
-        }
-      }
+      load_rows(rq);
       const int jc = jchunk + ks * sub;
       // K tiles of the next step are read from LDS before this step's work, and
       // the sixteen matrix instructions of a tile (four accumulators, one per row
