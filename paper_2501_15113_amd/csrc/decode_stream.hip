@@ -371,7 +371,11 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
 // Ring depth.  A wave can have at most 63 vector memory instructions in flight
 // (the hardware counter is 6 bits) and a page is 16 of them, so rings deeper
 // than 3 pages cannot be kept full; 2 pages at two waves per SIMD measured
-// fastest (deeper rings drop to one wave per SIMD).
+// fastest (deeper rings drop to one wave per SIMD).  Pages of 64-wide heads are
+// half the size (8 instructions): 3 of them measured 3 % faster than 2 or 4.
+#ifndef TASKKV_STREAM_NP64
+#define TASKKV_STREAM_NP64 3
+#endif
 #ifndef TASKKV_STREAM_NP
 #define TASKKV_STREAM_NP 2
 #endif
@@ -391,7 +395,7 @@ static void run_stream(taskkv_ctx *ctx, const Dims &dm, const uint16_t *q, const
   const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
   const bool prof = ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS;
   if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
-  decode_stream_kernel<D, TASKKV_STREAM_NP, NT><<<grid, block, 0, s>>>(
+  decode_stream_kernel<D, (D == 64 ? TASKKV_STREAM_NP64 : TASKKV_STREAM_NP), NT><<<grid, block, 0, s>>>(
       q, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, ctx->d_err, pm, pl, po, dm.units, dm.Hq,
       dm.Hkv, dm.G, scale_log2, skew);
   if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
@@ -410,8 +414,8 @@ int launch_decode_stream(taskkv_ctx *ctx, const Dims &dm, const void *q, const v
     int per_cu = 0;
     hipError_t e;
     if (dm.D == 64)
-      e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, TASKKV_STREAM_NP, true>, 256, 0)
-             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, TASKKV_STREAM_NP, false>, 256, 0);
+      e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, TASKKV_STREAM_NP64, true>, 256, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, TASKKV_STREAM_NP64, false>, 256, 0);
     else
       e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<128, TASKKV_STREAM_NP, true>, 256, 0)
              : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<128, TASKKV_STREAM_NP, false>, 256, 0);
