@@ -153,6 +153,10 @@ __device__ __forceinline__ uint64_t radix_threshold(const double *__restrict__ s
       in_lds = true;
     }
     const int shift = pass * 8;
+    // The leading byte takes a handful of values, and so does every digit while
+    // more than half of the entries still share all digits known so far (many
+    // equal scores): lanes with equal digits are then merged into one atomic.
+    const bool concentrated = pass == 7 || 2 * (int64_t)n_match0 > hi - lo;
     if (tid < 256) rs.hist[tid] = 0;
     __syncthreads();
     if (in_lds) {
@@ -174,7 +178,7 @@ __device__ __forceinline__ uint64_t radix_threshold(const double *__restrict__ s
         for (int r = 0; r < SWEEP_U; ++r) {
           const bool hit = ok[r] && (key[r] & known) == pat;
           const unsigned digit = (unsigned)(key[r] >> shift) & 255u;
-          if (pass == 7) hist_add_merged(rs.hist, hit, digit);   // the leading byte takes a handful of values
+          if (concentrated) hist_add_merged(rs.hist, hit, digit);
           else if (hit) atomicAdd(&rs.hist[digit], 1u);
         }
       }
