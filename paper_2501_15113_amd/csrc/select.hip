@@ -82,9 +82,20 @@ __global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__
   const int32_t *idx = top_idx + (size_t)unit * dm.T;
   __shared__ double red[16][128];
   double acc = 0.0;
-  for (int n = grp; n < dm.T; n += n_grp) {
-    const int j = idx[n];
-    acc += sc[j] * elem_to_double(vb[(size_t)j * D + c]);
+  for (int n0 = grp; n0 < dm.T; n0 += 4 * n_grp) {
+    // four picks of the group at a time: their index, score and value loads
+    // overlap instead of forming one chain per pick
+    int j[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) j[u] = n0 + u * n_grp < dm.T ? idx[n0 + u * n_grp] : -1;
+    double w[4], x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      w[u] = j[u] >= 0 ? sc[j[u]] : 0.0;
+      x[u] = j[u] >= 0 ? elem_to_double(vb[(size_t)j[u] * D + c]) : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc += w[u] * x[u];   // same order as one pick at a time
   }
   red[grp][c] = acc;
   __syncthreads();
