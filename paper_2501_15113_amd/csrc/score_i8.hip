@@ -424,15 +424,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
           for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int t = 0; t < 4; ++t) ka[ks][t] = s_dig[buf][tile][ks][t][l];
-          // exponents of the lane's sixteen keys, read here so that they have
-          // arrived long before the last Horner step needs them
-          int ek[16];
-#pragma unroll
-          for (int v4 = 0; v4 < 4; ++v4) {
-            const v4i e4 = *reinterpret_cast<const v4i *>(&s_ek[buf][tile * 32 + 8 * v4 + 4 * half]);
-#pragma unroll
-            for (int x = 0; x < 4; ++x) ek[4 * v4 + x] = e4[x];
-          }
           // classes a + b = 6 ... 0: Horner from the top class down, two classes
           // joined in int32 (|class sum| < 2^23) before every fp64 step.
           // (Interleaving the instructions of two classes, so that no two
@@ -487,9 +478,19 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
             if (q_low_zero) contract(std::false_type{}, std::true_type{});
             else contract(std::false_type{}, std::false_type{});
           }
+          {
+            // exponents of the lane's sixteen keys (read late: sixteen registers
+            // fewer across the matrix phase keep most temporaries out of scratch memory)
+            int ek[16];
 #pragma unroll
-          for (int v = 0; v < 16; ++v)
-            t16[v] = ldexp(t16[v] * gqr, ek[v]);
+            for (int v4 = 0; v4 < 4; ++v4) {
+              const v4i e4 = *reinterpret_cast<const v4i *>(&s_ek[buf][tile * 32 + 8 * v4 + 4 * half]);
+#pragma unroll
+              for (int x = 0; x < 4; ++x) ek[4 * v4 + x] = e4[x];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) t16[v] = ldexp(t16[v] * gqr, ek[v]);
+          }
           // remainders of this row's elements that did not fit: r * k[c]
           for (int e = 0; e < n_tiny; ++e) {
             const QTiny ent = tiny[e];
