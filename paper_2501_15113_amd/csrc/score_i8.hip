@@ -434,10 +434,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
           // out; four straight-line variants, chosen once per tile.
           auto contract = [&](auto kz, auto qz) {
             constexpr bool KZ = decltype(kz)::value, QZ = decltype(qz)::value;
-            auto class_sum = [&](int cls) {
-              v16i acc;
-#pragma unroll
-              for (int v = 0; v < 16; ++v) acc[v] = 0;
+            // acc += the digit products of class cls
+            auto class_sum = [&](int cls, v16i acc) {
 #pragma unroll
               for (int a = KZ ? 1 : 0; a < 4; ++a) {
                 const int b = cls - a;
@@ -448,8 +446,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
               }
               return acc;
             };
+            v16i zero;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) zero[v] = 0;
             {
-              const v16i top = class_sum(6);
+              const v16i top = class_sum(6, zero);
 #pragma unroll
               for (int v = 0; v < 16; ++v) t16[v] = (double)top[v];
             }
@@ -460,13 +461,18 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
                 for (int v = 0; v < 16; ++v) t16[v] *= 16384.0;
               } else if ((KZ || QZ) && cls == 1) {
-                const v16i hi = class_sum(1);   // class 0 is empty
+                const v16i hi = class_sum(1, zero);   // class 0 is empty
 #pragma unroll
                 for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)(hi[v] * 128));
               } else {
-                const v16i hi = class_sum(cls), lo = class_sum(cls - 1);
+                // the lower class is accumulated on top of 128 x the upper one: one
+                // accumulator block instead of two
+                v16i acc = class_sum(cls, zero);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)(hi[v] * 128 + lo[v]));
+                for (int v = 0; v < 16; ++v) acc[v] *= 128;
+                acc = class_sum(cls - 1, acc);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)acc[v]);
               }
             }
           };
