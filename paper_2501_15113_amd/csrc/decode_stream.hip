@@ -370,8 +370,9 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
 
 // Ring depth.  A wave can have at most 63 vector memory instructions in flight
 // (the hardware counter is 6 bits) and a page is 16 of them, so rings deeper
-// than 3 pages cannot be kept full; 2 pages at two waves per SIMD measured
-// fastest (deeper rings drop to one wave per SIMD).  Pages of 64-wide heads are
+// than 3 pages cannot be kept full; 2 pages measured fastest for 128-wide
+// heads, at one wave per SIMD (fitting two waves into the register file costs
+// spills and measured 5 % slower; 3 pages: 1 % slower).  Pages of 64-wide heads are
 // half the size (8 instructions): 3 of them measured 3 % faster than 2 or 4.
 #ifndef TASKKV_STREAM_NP64
 #define TASKKV_STREAM_NP64 3
