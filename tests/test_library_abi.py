@@ -38,6 +38,9 @@ def test_budget_helpers_match_oracle():
         assert tk.taskkv_hetero_head_count(32, 0.25, 4, layer, 32) == orc.hetero_head_count(32, 0.25, 4, layer, 32)
         assert tk.taskkv_hetero_head_count(8, 0.3, 1, layer, 32) == orc.hetero_head_count(8, 0.3, 1, layer, 32)
     assert tk.taskkv_hetero_head_count(8, 0.3, 1, 0, 1) == orc.hetero_head_count(8, 0.3, 1, 0, 1)
+    for n, beta, m, R in [(32, 0.5, 0, 17), (8, 0.25, 1, 5), (8, 0.25, 1, 3), (40, 0.9, 50, 7), (8, 0.0, 0, 4)]:
+        for layer in range(R):
+            assert tk.taskkv_hetero_head_count(n, beta, m, layer, R) == orc.hetero_head_count(n, beta, m, layer, R)
     for args in [(104857, 32768, 8, 1, 4, 128), (104857, 32768, 8, 3, 4, 128), (100, 50, 4, 4, 1, 1),
                  (10, 50, 4, 1, 1, 1), (1000, 64, 8, 2, 4, 4)]:
         assert tk.taskkv_middle_budget(*args) == orc.middle_budget(*args)

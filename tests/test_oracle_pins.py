@@ -158,6 +158,10 @@ def test_centre_and_distances_hand_case():
     assert orc.hetero_mask(dist, 1, add_centre_head=True).tolist() == [1, 0, 0, 1]
     assert orc.hetero_mask(dist, 0).tolist() == [0, 0, 0, 0]
     assert orc.hetero_mask(dist, 9).tolist() == [1, 1, 1, 1]
+    # a 3-4-5 triangle: two heads at (0,0) and (6,8) are both 5 from their mean (the L1 distance would be 7)
+    centre, dist = orc.centre_and_distances(np.array([[0.0, 0.0], [6.0, 8.0]]))
+    np.testing.assert_allclose(centre, [3, 4])
+    np.testing.assert_allclose(dist, [5, 5], rtol=1e-15)
 
 
 def test_add_centre_head_picks_closest_remaining():
@@ -296,6 +300,22 @@ def test_split_and_merge_equals_unsplit():
     np.testing.assert_allclose(orc.merge_partials(parts), ref, rtol=1e-13)
 
 
+def test_compress_ranks_the_middle_by_pooled_scores():
+    """One spike against a plateau: alone the spike is the best middle token,
+    averaged over three neighbours the centre of the plateau is."""
+    N, d = 11, 2
+    scores = np.zeros((1, N))
+    scores[0, 3] = 10.0
+    scores[0, 6:9] = 6.0
+    k, v = rand(1, N, d), rand(1, N, d)
+    mask = np.zeros(1, dtype=np.uint8)
+    kept, kc, vc = orc.compress(k, v, scores, mask, 1, 1, 1, pool_kernel=1)
+    assert kept[0].tolist() == [0, 3, 10]
+    kept, kc, vc = orc.compress(k, v, scores, mask, 1, 1, 1, pool_kernel=3)
+    assert kept[0].tolist() == [0, 7, 10]
+    assert kc[0].tobytes() == k[0, [0, 7, 10]].tobytes() and vc[0].tobytes() == v[0, [0, 7, 10]].tobytes()
+
+
 # ----------------------------------------------------------------- Eq. 16-17
 def test_layer_schedule_golden():
     path = os.path.join(os.path.dirname(__file__), "golden", "layer_schedule.txt")
@@ -306,6 +326,11 @@ def test_layer_schedule_golden():
     fs = [orc.hetero_head_count(32, 0.25, 4, r, 32) for r in range(32)]
     assert fs[0] == 8 and fs[-1] == 4 and all(a >= b for a, b in zip(fs, fs[1:]))
     assert orc.hetero_head_count(8, 0.3, 1, 0, 1) == 2      # single layer: no interpolation term
+    # Eq. 16 is the straight line from n*beta at r = 0 to m at r = R-1: from 16 to 0 over 17 layers it
+    # passes through every integer, no rounding involved
+    assert [orc.hetero_head_count(32, 0.5, 0, r, 17) for r in range(17)] == list(range(16, -1, -1))
+    # fractional values go to the nearest integer, halves upwards: 2 -> 1 over 5 layers is 2, 1.75, 1.5, 1.25, 1
+    assert [orc.hetero_head_count(8, 0.25, 1, r, 5) for r in range(5)] == [2, 2, 2, 1, 1]
 
 
 def test_middle_budget_identity():
@@ -357,6 +382,9 @@ def test_compressed_cache_groups_and_means():
         ref = torch.tensor(k[bounds[g]:bounds[g + 1]].astype(np.float64).mean(axis=0)).to(torch.bfloat16)
         np.testing.assert_allclose(kc[s1 + g], ref.float().numpy(), rtol=2 ** -7)
         assert torch.tensor(kc[s1 + g]).to(torch.bfloat16).float().numpy().tobytes() == kc[s1 + g].tobytes()
+        ref_v = torch.tensor(v[bounds[g]:bounds[g + 1]].astype(np.float64).mean(axis=0)).to(torch.bfloat16)
+        np.testing.assert_allclose(vc[s1 + g], ref_v.float().numpy(), rtol=2 ** -7)
+    assert vc[:s1].tobytes() == v[:s1].tobytes() and vc[-s2:].tobytes() == v[-s2:].tobytes()
     # constant rows compress to themselves; one group per token is the identity
     const = np.tile(k[5], (N, 1))
     cc, _, _ = orc.compressed_cache(const, const, False, s1, s2, 4, "bf16")
