@@ -32,7 +32,7 @@ def run_layer(wl, layer=0, check_batches=(0,), steps=None, check_steps=None, res
             break
         print(f"[{wl.name}] decision margin {worst:.2e} < {MIN_MARGIN}: next draw", flush=True)
         bump += 1
-    assert worst >= MIN_MARGIN
+    assert worst >= MIN_MARGIN, "decision margin below MIN_MARGIN: not a well-posed instance"
     steps = wl.decode_steps if steps is None else steps
     reserve = steps if reserve is None else reserve
     bufs = ses.LayerBuffers(cfg, reserve)
@@ -322,6 +322,39 @@ def test_compress_on_scores_of_any_magnitude(n_middle):
                 assert lens[b, h] == len(kept[h])
                 if not mask[b, h]:
                     assert kept_gpu[b, h, :len(kept[h])].tolist() == list(kept[h]), (b, h)
+
+
+def test_pooled_scores_keep_the_full_divisor_at_the_edges():
+    """Average pooling with zero padding and the fixed divisor w: a run of four
+    ones at either end of the context pools to 4/7 and loses against an interior
+    plateau of 0.6 (dividing by the number of valid neighbours would make it
+    1.0 and win); two equal plateaus tie to the lower position."""
+    import tests._harness as harness
+    ses = _session()
+    wl = small_workload(name="pool-edges", wid=232, batch=1, ctx_len=600, n_sink=0, n_recent=0, n_middle=1,
+                        n_hetero=0, pool_kernel=7)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 0)
+    H, N = wl.n_kv_heads, wl.ctx_len
+    sc = np.zeros((1, H, N))
+    sc[0, 0, 0:4] = 1.0
+    sc[0, 0, 100:107] = 0.6
+    sc[0, 1, N - 4:N] = 1.0
+    sc[0, 1, 300:307] = 0.6
+    sc[0, 2, 200:207] = 0.5
+    sc[0, 2, 400:407] = 0.5
+    sc[0, 3] = np.random.default_rng(5).random(N)
+    mask = np.zeros((1, H), dtype=np.uint8)
+    with ses.Context([cfg], 0) as ctx:
+        bufs.scores.copy_(torch.from_numpy(sc))
+        bufs.mask.copy_(torch.from_numpy(mask))
+        bufs.compress(ctx, ld.k, ld.v)
+        torch.cuda.synchronize()
+        kept_gpu = bufs.kept_idx.cpu().numpy().reshape(H, -1)
+    assert kept_gpu[:3, 0].tolist() == [103, 303, 203]
+    kept, _, _ = harness.orc.compress(to_numpy(ld.k[0]), to_numpy(ld.v[0]), sc[0], mask[0], 0, 0, 1, 7, 0, "bf16")
+    assert [int(x[0]) for x in kept] == kept_gpu[:, 0].tolist()
 
 
 # ------------------------------------------------------------------ device-side conditions
