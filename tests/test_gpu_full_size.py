@@ -67,3 +67,87 @@ def test_cfg3_whole_stack_in_one_call():
         # every layer holds the budget of Eq. 17: about 40 % of its full cache
         per_layer = lens.reshape(wl.n_layers, -1).sum(axis=1) - steps * B * wl.n_kv_heads
         assert np.all(np.abs(per_layer / (B * wl.n_kv_heads * wl.ctx_len) - 0.4) < 0.002)
+
+
+@pytest.mark.parametrize("name", ["cfg5", "cfg4"])
+def test_outputs_are_consistent_for_every_unit(name):
+    """Properties that hold at any size, checked for every unit of the full
+    workload with library routines (the oracle above checks sampled batch
+    elements value by value): the mask marks exactly the farthest heads of the
+    distances recomputed from the semantic vectors, which are the weighted sums
+    of the t best-scored value rows; every compressed unit keeps the sinks, the
+    recent window and a middle set no unkept token of which scores higher
+    (equal scores: lower positions kept); packed rows are bit copies of the
+    source rows; and the decode output is dense softmax attention over the
+    unit's own cache."""
+    import torch
+
+    from paper_2501_15113_amd import session as ses, taskkv_last_async_error
+    from taskkv_synth import make_layer
+
+    wl = WORKLOADS[name]
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl, ld.n_hetero, ld.n_middle)
+    B, H, G, N, d = wl.batch, wl.n_kv_heads, wl.group, wl.ctx_len, wl.head_dim
+    s1, s2, k_mid, t = wl.n_sink, wl.n_recent, ld.n_middle, min(wl.top_t, N)
+    bufs = ses.LayerBuffers(cfg, 1)
+    with ses.Context([cfg], 1, screening=1) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        bufs.compress(ctx, ld.k, ld.v)
+        k_rows, v_rows = bufs.export(ctx)
+        q, kn, vn = ld.decode_inputs(0)
+        out = bufs.decode(ctx, q, kn, vn).clone()
+        torch.cuda.synchronize()
+        assert taskkv_last_async_error(ctx.handle) == 0
+    sc, mask = bufs.scores, bufs.mask.bool()
+    assert (sc >= 0).all() and torch.allclose(sc.sum(dim=2), torch.ones(B, H, dtype=sc.dtype, device=sc.device),
+                                              rtol=1e-4)
+    # separator: v' from the t best columns, distances from v', mask from the distances
+    top = torch.topk(sc, t, dim=2)
+    picked_v = torch.gather(ld.v, 2, top.indices[..., None].expand(B, H, t, d)).double()
+    sem = (top.values[..., None] * picked_v).sum(dim=2)
+    torch.testing.assert_close(bufs.sem_vec, sem, rtol=1e-9, atol=1e-12)
+    dist = (sem - sem.mean(dim=1, keepdim=True)).norm(dim=2)
+    torch.testing.assert_close(bufs.dist, dist, rtol=1e-9, atol=1e-12)
+    far = torch.topk(bufs.dist, ld.n_hetero, dim=1).indices
+    want = torch.zeros_like(mask)
+    want.scatter_(1, far, True)
+    assert torch.equal(mask, want)
+    assert mask.sum(dim=1).tolist() == [ld.n_hetero] * B
+    # cache allocation
+    lens = bufs.lens.cpu().view(B, H)
+    offs = bufs.offsets.cpu()
+    kept = bufs.kept_idx.view(B, H, -1)
+    sinks = torch.arange(s1, device=kept.device, dtype=kept.dtype)
+    recent = torch.arange(N - s2, N, device=kept.device, dtype=kept.dtype)
+    for b in range(B):
+        for h in range(H):
+            u = b * H + h
+            rows = slice(int(offs[u]), int(offs[u]) + int(lens[b, h]) - 1)       # before the appended token
+            if mask[b, h]:
+                assert lens[b, h] == N + 1 and (kept[b, h] == -1).all()
+                idx = None
+                assert torch.equal(k_rows[rows].view(torch.int16), ld.k[b, h].view(torch.int16))
+                assert torch.equal(v_rows[rows].view(torch.int16), ld.v[b, h].view(torch.int16))
+            else:
+                assert lens[b, h] == s1 + k_mid + s2 + 1
+                idx = kept[b, h].long()
+                assert (idx[1:] > idx[:-1]).all()
+                assert torch.equal(kept[b, h, :s1], sinks) and torch.equal(kept[b, h, s1 + k_mid:], recent)
+                mid = sc[b, h, s1:N - s2]
+                chosen = torch.zeros(N - s1 - s2, dtype=torch.bool, device=mid.device)
+                chosen[idx[s1:s1 + k_mid] - s1] = True
+                lo, hi = mid[chosen].min(), mid[~chosen].max()
+                assert lo >= hi
+                if lo == hi:
+                    where = torch.arange(N - s1 - s2, device=mid.device)
+                    assert where[chosen & (mid == lo)].max() < where[~chosen & (mid == lo)].min()
+                assert torch.equal(k_rows[rows].view(torch.int16), ld.k[b, h][idx].view(torch.int16))
+                assert torch.equal(v_rows[rows].view(torch.int16), ld.v[b, h][idx].view(torch.int16))
+            # decode over the unit's own rows plus the appended token
+            kk = torch.cat([ld.k[b, h] if idx is None else ld.k[b, h][idx], kn[b, h][None]]).double()
+            vv = torch.cat([ld.v[b, h] if idx is None else ld.v[b, h][idx], vn[b, h][None]]).double()
+            qq = q[b, h * G:(h + 1) * G].double()
+            ref = torch.softmax(qq @ kk.T / d ** 0.5, dim=1) @ vv
+            err = (out[b, h * G:(h + 1) * G].double() - ref).abs().max().item()
+            assert err <= 1e-2, f"unit ({b},{h}): max-abs error {err:.3e}"
