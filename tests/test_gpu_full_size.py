@@ -151,3 +151,15 @@ def test_outputs_are_consistent_for_every_unit(name):
             ref = torch.softmax(qq @ kk.T / d ** 0.5, dim=1) @ vv
             err = (out[b, h * G:(h + 1) * G].double() - ref).abs().max().item()
             assert err <= 1e-2, f"unit ({b},{h}): max-abs error {err:.3e}"
+
+
+def test_context_of_a_million_tokens():
+    """Far beyond the named workloads: one batch element, three KV heads of
+    2^20 + 77 tokens, a middle budget of 30000 and 2000 top-t tokens on
+    Zipf-weighted keys; every index and length fits the library's 32-bit page
+    arithmetic with room to spare."""
+    from taskkv_synth import small_workload
+    wl = small_workload(name="million", wid=801, batch=1, n_kv_heads=3, n_q_heads=6, n_hetero=1,
+                        ctx_len=(1 << 20) + 77, obs_window=32, top_t=2000, n_middle=30000, n_recent=5000,
+                        decode_steps=2, recipe="zipf")
+    run_layer(wl, screening=1)
