@@ -218,9 +218,10 @@ int taskkv_set_stream_skew(taskkv_ctx *ctx, int skew);
 
 /*
  * Timing hooks for the benchmark.  With profiling on, taskkv_decode_attn
- * brackets its attention kernel with HIP events on the launch stream (up to
- * 4096 launches are kept).  taskkv_profile_read synchronises, sums the
- * recorded durations into *total_ms / *launches and clears the record.
+ * attaches two HIP events to the launch of its attention kernel, on the launch
+ * stream; they record when the kernel began and ended (up to 4096 launches
+ * are kept).  taskkv_profile_read synchronises, sums the recorded durations
+ * into *total_ms / *launches and clears the record.
  */
 int taskkv_profile_enable(taskkv_ctx *ctx, int on);
 int taskkv_profile_read(taskkv_ctx *ctx, double *total_ms, int64_t *launches);

@@ -326,21 +326,20 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
                   float *po, float *out, hipStream_t s) {
   const dim3 grid((unsigned)(capacity / CHUNK), (dm.G + 15) / 16), block(256);
   const dim3 cgrid(dm.B * dm.Hq), cblock(1024);
-  const bool prof = ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS;
   if (dtype == TASKKV_F32) {
     if (k_new) {
       int rc = launch_append(dm, dtype, k_new, v_new, k_cache, v_cache, offsets, lens, ctx->d_err, s);
       if (rc) return rc;
     }
-    if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
     auto qq = static_cast<const float *>(q);
     auto kc = static_cast<const float *>(k_cache), vc = static_cast<const float *>(v_cache);
     const float scale = (float)dm.scale;
     if (dm.D == 64)
-      decode_f32_kernel<64><<<grid, block, 0, s>>>(qq, kc, vc, offsets, lens, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale);
+      launch_attention(ctx, decode_f32_kernel<64>, grid, block, s, qq, kc, vc, offsets, lens, pm, pl, po, dm.units,
+                       dm.Hq, dm.Hkv, dm.G, scale);
     else
-      decode_f32_kernel<128><<<grid, block, 0, s>>>(qq, kc, vc, offsets, lens, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale);
-    if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
+      launch_attention(ctx, decode_f32_kernel<128>, grid, block, s, qq, kc, vc, offsets, lens, pm, pl, po, dm.units,
+                       dm.Hq, dm.Hkv, dm.G, scale);
     if (dm.D == 64)
       combine_kernel<64, false><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
     else
@@ -359,19 +358,16 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
   auto vn = fused ? static_cast<const uint16_t *>(v_new) : nullptr;
   auto kc = static_cast<uint4 *>(k_cache), vc = static_cast<uint4 *>(v_cache);
   const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
-  if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
   const bool nt = (size_t)capacity * dm.D * 4 > NT_THRESHOLD_BYTES;
-#define TASKKV_LAUNCH_CHUNK(DD, NTV)                                                                   \
-  decode_bf16_kernel<DD, NTV><<<grid, block, 0, s>>>(qq, kn, vn, kc, vc, offsets, lens, eff_len,      \
-                                                     ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, \
-                                                     dm.G, scale_log2)
+#define TASKKV_LAUNCH_CHUNK(DD, NTV)                                                                      \
+  launch_attention(ctx, decode_bf16_kernel<DD, NTV>, grid, block, s, qq, kn, vn, kc, vc, offsets, lens, \
+                   eff_len, ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale_log2)
   if (dm.D == 64) {
     if (nt) TASKKV_LAUNCH_CHUNK(64, true); else TASKKV_LAUNCH_CHUNK(64, false);
   } else {
     if (nt) TASKKV_LAUNCH_CHUNK(128, true); else TASKKV_LAUNCH_CHUNK(128, false);
   }
 #undef TASKKV_LAUNCH_CHUNK
-  if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
   if (dm.D == 64)
     combine_kernel<64, true><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, eff_len, fused ? lens : nullptr, out, dm.Hq, dm.Hkv, dm.G);
   else

@@ -1,12 +1,31 @@
 // Device helpers shared by the decode attention kernels (bf16 matrix-core path).
 #pragma once
 
+#include <hip/hip_ext.h>
 #include <math.h>
 
 #include "lane_ops.h"
 #include "taskkv_internal.h"
 
 namespace taskkv {
+
+// Launch of a decode attention kernel.  With profiling on, two events are
+// attached to the launch itself: they take the kernel's own begin and end
+// times from its completion signal, so the recorded duration holds no dispatch
+// latency and the stream gets no extra packets (events recorded before and
+// after the launch read 2-3 us more than the kernel runs).  Arguments are
+// converted to the kernel's parameter types before they are packed.
+template <typename... P, typename... A>
+inline void launch_attention(taskkv_ctx *ctx, void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t s,
+                             A... args) {
+  if (ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS) {
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ctx->ev_start[ctx->n_events], ctx->ev_stop[ctx->n_events], 0,
+                          static_cast<P>(args)...);
+    ++ctx->n_events;
+  } else {
+    kernel<<<grid, block, 0, s>>>(static_cast<P>(args)...);
+  }
+}
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;

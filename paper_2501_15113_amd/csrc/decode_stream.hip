@@ -394,12 +394,9 @@ static void run_stream(taskkv_ctx *ctx, const Dims &dm, const uint16_t *q, const
   const int skew = (n_wg & 1) ? 0 : ctx->stream_skew;
   const dim3 grid(n_wg, (dm.G + 15) / 16), block(256);
   const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
-  const bool prof = ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS;
-  if (prof) (void)hipEventRecord(ctx->ev_start[ctx->n_events], s);
-  decode_stream_kernel<D, (D == 64 ? TASKKV_STREAM_NP64 : TASKKV_STREAM_NP), NT><<<grid, block, 0, s>>>(
-      q, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, ctx->d_err, pm, pl, po, dm.units, dm.Hq,
-      dm.Hkv, dm.G, scale_log2, skew);
-  if (prof) (void)hipEventRecord(ctx->ev_stop[ctx->n_events++], s);
+  launch_attention(ctx, decode_stream_kernel<D, (D == 64 ? TASKKV_STREAM_NP64 : TASKKV_STREAM_NP), NT>, grid, block,
+                   s, q, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, ctx->d_err, pm, pl, po, dm.units,
+                   dm.Hq, dm.Hkv, dm.G, scale_log2, skew);
   combine_stream_kernel<D><<<dim3(dm.B * dm.Hq), dim3(1024), 0, s>>>(
       pm, pl, po, page_prefix, eff_len, fused ? lens : nullptr, out, dm.units, dm.Hq, dm.Hkv, dm.G, n_wg * 4);
 }

@@ -492,3 +492,33 @@ def test_argument_errors_are_reported():
                                bufs.mask)
     finally:
         tk.taskkv_destroy(small)
+
+
+@pytest.mark.parametrize("dtype,ctx_len", [("bf16", 6000), ("f32", 900)])
+def test_profiling_changes_no_output_and_times_the_kernel(dtype, ctx_len):
+    """The benchmark's timing hook attaches events to the attention kernel's
+    launch: outputs stay bit for bit the same, every launch is counted, and the
+    recorded time is positive and below the wall time of the calls."""
+    import time
+    import paper_2501_15113_amd as tk
+    ses = _session()
+    wl = small_workload(name="prof", wid=233, dtype=dtype, ctx_len=ctx_len, n_hetero=2)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 8)
+    with ses.Context([cfg], 8) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        bufs.compress(ctx, ld.k, ld.v)
+        q, _, _ = ld.decode_inputs(0)
+        plain = bufs.decode(ctx, q).clone()
+        torch.cuda.synchronize()
+        tk.taskkv_profile_enable(ctx.handle, True)
+        t0 = time.perf_counter()
+        for _ in range(5):
+            assert torch.equal(bufs.decode(ctx, q), plain)
+        ms, launches = tk.taskkv_profile_read(ctx.handle)
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        tk.taskkv_profile_enable(ctx.handle, False)
+        assert launches == 5 and 0.0 < ms < wall_ms
+        assert torch.equal(bufs.decode(ctx, q), plain)
+        assert tk.taskkv_profile_read(ctx.handle) == (0.0, 0)
