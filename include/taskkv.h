@@ -221,7 +221,8 @@ int taskkv_set_stream_skew(taskkv_ctx *ctx, int skew);
  * attaches two HIP events to the launch of its attention kernel, on the launch
  * stream; they record when the kernel began and ended (up to 4096 launches
  * are kept).  taskkv_profile_read synchronises, sums the recorded durations
- * into *total_ms / *launches and clears the record.
+ * into *total_ms / *launches and clears the record.  Keep profiling off while
+ * the stream is being captured into a HIP graph.
  */
 int taskkv_profile_enable(taskkv_ctx *ctx, int on);
 int taskkv_profile_read(taskkv_ctx *ctx, double *total_ms, int64_t *launches);
