@@ -392,10 +392,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 
   for (int step = 0; step < n_steps; ++step) {
     const int buf = step & 1;
-    // The two waves that share a SIMD (w and w + 4) would otherwise run the same
-    // phases at the same time, matrix pipe idle during both conversions and both
-    // exponential phases: the upper four waves convert after their tiles, which
-    // shifts them by one phase against their partners.
+    // All waves leave the barrier together and would run the same phases at the
+    // same time, the matrix pipe idle during every conversion and every
+    // exponential phase: half of the waves convert after their tiles instead of
+    // before them.  (Which half hardly matters: odd waves, the upper four, or
+    // pairs measured within 1 % of each other; all waves on one side: 2-3 % slower.)
     const bool convert_first = (w & 1) == 0;
     if (convert_first) {
       if (step + 1 < n_steps) convert(buf ^ 1);
