@@ -195,6 +195,18 @@ def test_softmax_scale_override():
     run_layer(small_workload(name="scale", wid=150), cfg_override=dict(softmax_scale=0.05))
 
 
+@pytest.mark.parametrize("dtype,ctx_len", [("bf16", 6000), ("f32", 1500)])
+@pytest.mark.parametrize("scale", [3.0, 1.0, 1e-3, 1e-6])
+def test_peaky_and_flat_softmax(dtype, ctx_len, scale):
+    """Logits of the order of +-100 (a softmax that is nearly one-hot) down to
+    1e-4 (nearly uniform weights, decision margins near the 1e-9 limit): the
+    statistics, the selections and the attention outputs hold their bars.  (In
+    fp32 arithmetic the error of a logit grows with its size; at scale 3 the
+    attention error reaches 6.5e-6 of the 1e-5 allowed.)"""
+    run_layer(small_workload(name=f"peaky-{dtype}-{scale}", wid=240, dtype=dtype, ctx_len=ctx_len, n_hetero=2),
+              cfg_override=dict(softmax_scale=scale))
+
+
 def test_decode_without_append():
     run_layer(small_workload(name="noappend", wid=151), append=False, reserve=0)
 
