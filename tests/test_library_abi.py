@@ -72,3 +72,35 @@ def test_invalid_cfg_is_rejected_on_the_host(bad):
         tk.taskkv_cache_tokens(_cfg(**bad), 0)
     with pytest.raises(tk.TaskKVError):
         tk.taskkv_workspace_bytes(_cfg(**bad), 0)
+
+
+def _imports_of(path):
+    import ast
+    names = set()
+    for node in ast.walk(ast.parse(open(path).read())):
+        if isinstance(node, ast.Import):
+            names.update(a.name.split(".")[0] for a in node.names)
+        elif isinstance(node, ast.ImportFrom) and node.level == 0 and node.module:
+            names.add(node.module.split(".")[0])
+    return names
+
+
+def test_product_and_oracle_do_not_import_each_other():
+    """The oracle is test infrastructure: nothing in the package or in the input
+    generators imports it, and it imports neither of them."""
+    import glob
+    for path in glob.glob(os.path.join(ROOT, "paper_2501_15113_amd", "*.py")) + \
+            glob.glob(os.path.join(ROOT, "taskkv_synth", "*.py")):
+        assert "oracle" not in _imports_of(path), path
+    for path in glob.glob(os.path.join(ROOT, "oracle", "*.py")):
+        assert not {"paper_2501_15113_amd", "taskkv_synth", "torch", "ctypes"} & _imports_of(path), path
+    for src in glob.glob(os.path.join(ROOT, "paper_2501_15113_amd", "csrc", "*")):
+        assert "oracle" not in open(src).read(), src
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    from paper_2501_15113_amd import binding
+    monkeypatch.setenv("TASKKV_LIBRARY", str(tmp_path / "nothing_here.so"))
+    monkeypatch.setattr(binding, "_LIB", None, raising=False)
+    with pytest.raises(tk.TaskKVError):
+        binding.load_library()
