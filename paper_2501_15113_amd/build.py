@@ -47,5 +47,25 @@ def build_library(verbose: bool = True) -> str:
     return LIB
 
 
+def build_c_caller(verbose: bool = True) -> str:
+    """Compile tests/c_caller/taskkv_c_caller.c with gcc, as C, against the
+    header and the library: the test program that calls the C ABI with no
+    Python or C++ in between."""
+    src = os.path.join(ROOT, "tests", "c_caller", "taskkv_c_caller.c")
+    exe = os.path.join(ROOT, "tests", "c_caller", "taskkv_c_caller")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-O1", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"), src,
+           "-L", PKG, "-ltaskkv", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2501_15113_amd", f"-Wl,-rpath,{os.path.join(rocm, 'lib')}", "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"gcc failed on the C caller:\n{r.stdout}\n{r.stderr}")
+    if verbose:
+        print(f"built {exe}", file=sys.stderr)
+    return exe
+
+
 if __name__ == "__main__":
     build_library()
+    build_c_caller()

@@ -104,3 +104,13 @@ def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB", None, raising=False)
     with pytest.raises(tk.TaskKVError):
         binding.load_library()
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/taskkv.h compiles as C99 on its own: no C++, no HIP or torch types in the signatures."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "taskkv.h"\nint main(void) { taskkv_layer_cfg c; (void)c; return TASKKV_OK; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I",
+                        os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
