@@ -78,22 +78,9 @@ __device__ __forceinline__ double bf16_to_double(uint32_t b) { return (double)__
 // 256 doubles, e^r - 1 from three terms (r^4 / 24 < 1.5e-13).  Eleven fp64
 // operations where the library routine takes about twice as many; the row
 // statistics need one exponential per logit, which is what bounds the kernel.
-// CLAMP = false for arguments known to be finite (any size: a huge negative
-// one ends as 2^(-large) = 0); -inf needs the clamp, e^-800 underflows to 0.
+// Arguments known to be finite need no clamp (any size: a huge negative one
+// ends as 2^(-large) = 0); -inf does, e^-800 underflows to 0.
 constexpr int EXP_TAB = 256;
-template <bool CLAMP>
-__device__ __forceinline__ double exp_nonpos(double x, const double *tab) {
-  if (CLAMP) x = fmax(x, -800.0);
-  const double kf = rint(x * 369.3299304675746322841407);   // 256 / ln 2
-  double r = fma(kf, -0.00270760617331688990816474, x);      // ln2_hi / 256, 32 significant bits
-  r = fma(kf, -7.453964567463233203210912e-13, r);           // ln2_lo / 256
-  const int ki = (int)kf;
-  double q = fma(r, 1.66666666666666657415e-01, 0.5);
-  q = q * r;
-  const double pm1 = fma(q, r, r);                           // e^r - 1
-  const double y = tab[ki & (EXP_TAB - 1)];
-  return ldexp(fma(y, pm1, y), ki >> 8);
-}
 
 // carry * exp(x0) + sum of exp(x[v]) over sixteen arguments, all <= 0, in three
 // sweeps -- range reduction, table reads, polynomial -- so that the seventeen
@@ -107,7 +94,8 @@ __device__ __forceinline__ double exp_sum17(double carry, double x0, const doubl
   for (int v = 0; v < 17; ++v) {
     double xv = v == 16 ? x0 : x[v];
     if (CLAMP || v == 16) xv = fmax(xv, -800.0);
-    const double kf = rint(xv * 369.3299304675746322841407);
+    const double kf = rint(xv * 369.3299304675746322841407);   // 256 / ln 2
+    // minus kf * ln2 / 256 in two parts: the high one has 32 significant bits
     r[v] = fma(kf, -7.453964567463233203210912e-13, fma(kf, -0.00270760617331688990816474, xv));
     ki[v] = (int)kf;
   }
