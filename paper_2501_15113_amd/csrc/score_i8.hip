@@ -474,6 +474,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
             }
           };
           const bool k_low_zero = !((knz >> tile) & 1);
+          // The matrix phase runs at raised priority: when both waves of a SIMD
+          // are ready, the one with matrix instructions to issue goes first and
+          // the other one's vector work fills the gaps behind them (-2.5 %).
+          __builtin_amdgcn_s_setprio(1);
           if (k_low_zero) {
             if (q_low_zero) contract(std::true_type{}, std::true_type{});
             else contract(std::true_type{}, std::false_type{});
@@ -481,6 +485,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
             if (q_low_zero) contract(std::false_type{}, std::true_type{});
             else contract(std::false_type{}, std::false_type{});
           }
+          __builtin_amdgcn_s_setprio(0);
           {
             // exponents of the lane's sixteen keys (read late: sixteen registers
             // fewer across the matrix phase keep most temporaries out of scratch memory)
