@@ -9,6 +9,11 @@ region.  The reported value is the decode part's effective KV bandwidth:
 bytes of kept K and V rows that each decode step must read (sum over units of
 len * d * 2 * sizeof) divided by the GPU time of the decode calls.
 
+The default run reports the load-imbalance stress workload (cfg5) as `value`
+and adds short measurements of the other bf16 workloads as `also_cfg2`,
+`also_cfg4` and `also_cfg3` (the 32-layer stack, with one decode call per
+layer and with one call for the whole stack); `--only` leaves them out.
+
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -24,10 +29,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+INT8_PEAK_TOPS = 5000.0
 # HBM bytes per launch of the decode attention kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE scaled by a copy kernel); None until measured for the
-# default workload -- see profiles/.
-MEASURED_TRAFFIC = {"cfg5": 573.2e6}  # profiles/decode_stream_kernel_cfg5_hbm_traffic.txt
+# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size).  These are
+# figures from the committed profile files, not counters read in this run.
+PROFILED_TRAFFIC = {
+    "cfg5": (573.2e6, "profiles/decode_stream_kernel_cfg5_hbm_traffic.txt"),
+}
+# Matrix-core utilisation of the row-statistics kernel by counter, same caveat.
+PROFILED_MFMA_UTIL = {
+    "cfg5": (0.301, "profiles/score_kernels_cfg5_mfma_utilisation.txt"),
+}
+ALSO_FIELDS = ("config", "value", "unit", "pct_hbm_peak", "decode_us_per_step", "compress_ms_per_layer",
+               "roofline")
 
 
 def n_long_units(wl, n_het):
@@ -47,18 +61,12 @@ def kept_tokens_total(wl, n_het, n_mid):
     return wl.batch * (n_long * wl.ctx_len + (wl.n_kv_heads - n_long) * short)
 
 
-def cpu_baseline(wl, layers, budget_s=12.0):
-    """The CPU oracle, as it stands, on a bounded sample: batch element 0 of
-    layer 0 -- one compression, then decode steps until the time budget."""
+def _oracle_leg(wl, ld, budget_s):
+    """One batch element of one layer through the oracle: compression once, then
+    decode steps (no append) until the time budget is used."""
     import numpy as np
     from oracle import taskkv_oracle as orc
     from taskkv_synth import to_numpy
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = 1
-    ld = layers[0]
     q, k, v = to_numpy(ld.q_win[0]), to_numpy(ld.k[0]), to_numpy(ld.v[0])
     t0 = time.perf_counter()
     sep = orc.separate(q, k, v, wl.top_t, ld.n_hetero, bool(wl.add_centre_head))
@@ -77,11 +85,32 @@ def cpu_baseline(wl, layers, budget_s=12.0):
         t_dec += time.perf_counter() - t0
         nbytes += sum(len(a) for a in kc) * wl.head_dim * 2 * esize
         steps += 1
-    return {"value": nbytes / t_dec / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"batch element 0 of layer 0: {steps} decode steps over its {len(kc)} units "
-                      f"(no append), fp64 numpy; compression of that batch element took "
-                      f"{t_comp * 1e3:.0f} ms",
-            "compress_ms_per_layer_scaled": t_comp * 1e3 * wl.batch}
+    return {"decode_gbs": nbytes / t_dec / 1e9, "decode_steps": steps, "units": len(kc),
+            "compress_ms_one_batch_element": t_comp * 1e3}
+
+
+def cpu_baseline(wl, layers, budget_s=5.0):
+    """The CPU oracle, as it stands, on a bounded sample (batch element 0 of
+    layer 0), in two legs: the numerical library held to one thread, and with
+    the threads it takes by default on this host."""
+    from threadpoolctl import threadpool_info, threadpool_limits
+    ld = layers[0]
+    with threadpool_limits(limits=1):
+        single = _oracle_leg(wl, ld, budget_s)
+    pools = threadpool_info()
+    threads = max([p.get("num_threads", 1) for p in pools] or [1])
+    multi = _oracle_leg(wl, ld, budget_s)
+    return {"value": multi["decode_gbs"], "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "nproc": os.cpu_count(),
+            "sample": f"batch element 0 of layer 0, fp64 numpy: one compression, then {multi['decode_steps']} decode "
+                      f"steps over its {multi['units']} units (no append); `value` is the leg with the numerical "
+                      f"library's default thread pool ({threads} threads), `single_thread` the same with the pool "
+                      f"held to one thread ({single['decode_steps']} decode steps)",
+            "compress_ms_per_layer_scaled": multi["compress_ms_one_batch_element"] * wl.batch,
+            "single_thread": {"value": single["decode_gbs"], "unit": "GB/s", "cores": 1,
+                              "compress_ms_per_layer_scaled": single["compress_ms_one_batch_element"] * wl.batch},
+            "note": "the oracle is plain numpy (no OpenMP C++ build exists); its own Python loops run on one "
+                    "core in both legs, only the library routines inside use the pool"}
 
 
 def main():
@@ -99,22 +128,26 @@ def main():
                     help="also run three 1 GiB device copies (a kernel of known traffic against which "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled)")
     ap.add_argument("--only", action="store_true",
-                    help="with the default workload: leave out the short extra measurement of cfg2 "
-                         "(the 8192-token single layer) that is reported beside it")
+                    help="with the default workload: leave out the short extra measurements of the other "
+                         "workloads that are reported beside it")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)")
-    out = measure(args, args.workload, not args.no_cpu_baseline)
+    out = measure(args, args.workload, not args.no_cpu_baseline, args.layer_batched, args.steps, args.warmup)
     if args.workload == "cfg5" and not args.only:
-        # the 8192-token layer moves 9.6 MB per decode step (1.2 us at peak): it measures latency, not
-        # bandwidth, so it is reported beside the headline workload rather than as `value`
-        small = measure(args, "cfg2", False)
-        out["also_cfg2"] = {k: small[k] for k in ("config", "value", "unit", "pct_hbm_peak", "decode_us_per_step",
-                                                  "compress_ms_per_layer", "roofline")}
+        # The other workloads, a few passes each.  The 8192-token layer moves 9.6 MB per decode step
+        # (1.2 us at peak) and the 65536-token one 71 MB: they measure latency more than bandwidth.  The
+        # 32-layer stack moves more per step than the headline workload, but as 32 calls.
+        k_extra, w_extra = min(args.steps, 5), min(args.warmup, 1)
+        pick = lambda m: {k: m[k] for k in ALSO_FIELDS}
+        out["also_cfg2"] = pick(measure(args, "cfg2", False, False, k_extra, w_extra))
+        out["also_cfg4"] = pick(measure(args, "cfg4", False, False, k_extra, w_extra))
+        out["also_cfg3"] = {"per_layer": pick(measure(args, "cfg3", False, False, min(k_extra, 3), w_extra)),
+                            "stacked": pick(measure(args, "cfg3", False, True, min(k_extra, 3), w_extra))}
     print(json.dumps(out))
 
 
-def measure(args, workload, with_cpu_baseline):
+def measure(args, workload, with_cpu_baseline, layer_batched, steps, warmup):
     """One workload: warm-up passes, the timed passes, the same passes again with the kernel's own
     events, and (optionally) the oracle on the host.  Returns the fields of the JSON line."""
     import torch
@@ -127,10 +160,15 @@ def measure(args, workload, with_cpu_baseline):
     torch.cuda.set_device(0)
     esize = 4 if wl.dtype == "f32" else 2
     steps_dec = wl.decode_steps
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free0, _ = torch.cuda.mem_get_info()
 
     layers = [make_layer(wl, r, dev) for r in range(wl.n_layers)]
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()          # the generators' fp32 temporaries are not part of the path
     cfgs = [session.cfg_from_workload(wl, ld.n_hetero, ld.n_middle) for ld in layers]
-    batched = args.layer_batched and wl.n_layers > 1
+    batched = layer_batched and wl.n_layers > 1
     if batched:
         stack = session.LayerStack(cfgs, steps_dec, dev)
         bufs = stack.layers
@@ -141,7 +179,9 @@ def measure(args, workload, with_cpu_baseline):
     else:
         bufs = [session.LayerBuffers(c, steps_dec, dev) for c in cfgs]
         dec_in = [[ld.decode_inputs(s) for s in range(steps_dec)] for ld in layers]
+    ctx = session.Context(cfgs + ([stack.cfg] if batched else []), steps_dec)
     torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
 
     tokens0 = sum(kept_tokens_total(wl, ld.n_hetero, ld.n_middle) for ld in layers)
     units = wl.batch * wl.n_kv_heads * wl.n_layers
@@ -149,17 +189,19 @@ def measure(args, workload, with_cpu_baseline):
     step_bytes = [(tokens0 + (s + 1) * units) * wl.head_dim * 2 * esize for s in range(steps_dec)]
     pass_bytes = float(sum(step_bytes))
 
-    ctx = session.Context(cfgs + ([stack.cfg] if batched else []), steps_dec)
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def one_pass(record):
-        e0, e1, e2 = ev(), ev(), ev()
-        e0.record()
+    def compress_all():
         for ld, b in zip(layers, bufs):
             b.separate(ctx, ld.q_win, ld.k, ld.v)
             b.compress(ctx, ld.k, ld.v)
         if batched:
-            stack.rebase()
+            stack.rebase(ctx)
+
+    def one_pass(record):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        compress_all()
         e1.record()
         for s in range(steps_dec):
             if batched:
@@ -172,7 +214,7 @@ def measure(args, workload, with_cpu_baseline):
         if record is not None:
             record.append((e0, e1, e2))
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_pass(None)
     torch.cuda.synchronize()
 
@@ -188,24 +230,25 @@ def measure(args, workload, with_cpu_baseline):
         dec_ms = sum(b.elapsed_time(c) for _, b, c in rec)
         return wall, comp_ms, dec_ms
 
-    wall, comp_ms, dec_ms = timed(args.steps)
-    value = pass_bytes * args.steps / (dec_ms * 1e-3) / 1e9
+    wall, comp_ms, dec_ms = timed(steps)
+    value = pass_bytes * steps / (dec_ms * 1e-3) / 1e9
 
     # same region again with the library's own HIP events around the dominant kernel
-    tk.taskkv_profile_enable(ctx.handle, True)
-    wall_p, _, dec_ms_p = timed(args.steps)
+    tk.taskkv_profile_enable(ctx.handle, 1)
+    wall_p, _, dec_ms_p = timed(steps)
     kern_ms, launches = tk.taskkv_profile_read(ctx.handle)
-    tk.taskkv_profile_enable(ctx.handle, False)
-    total_launches = args.steps * steps_dec * (1 if batched else wl.n_layers)
-    bytes_per_launch = pass_bytes * args.steps / total_launches
+    tk.taskkv_profile_enable(ctx.handle, 0)
+    total_launches = steps * steps_dec * (1 if batched else wl.n_layers)
+    bytes_per_launch = pass_bytes * steps / total_launches
     avg_kernel_ms = kern_ms / max(launches, 1)
     achieved = bytes_per_launch / (avg_kernel_ms * 1e-3) / 1e9
     assert tk.taskkv_last_async_error(ctx.handle) == 0
+    traffic, traffic_src = PROFILED_TRAFFIC.get(wl.name, (None, None))
 
     out = {
         "metric": "ragged-cache decode attn: effective KV GB/s (% HBM peak) + compress ms/layer",
-        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(wall * 1e3 / steps, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.batch} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} d={wl.head_dim} "
                                f"N={wl.ctx_len} layers={wl.n_layers} sinks/recent={wl.n_sink}/{wl.n_recent} "
@@ -213,14 +256,54 @@ def measure(args, workload, with_cpu_baseline):
                                                               if batched else ""),
                    "kept_tokens_after_compress": tokens0, "kv_bytes_per_decode_step": step_bytes[0]},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
-        "decode_us_per_step": round(dec_ms * 1e3 / (args.steps * steps_dec), 3),
-        "compress_ms_per_layer": round(comp_ms / (args.steps * wl.n_layers), 4),
+        "decode_us_per_step": round(dec_ms * 1e3 / (steps * steps_dec), 3),
+        "compress_ms_per_layer": round(comp_ms / (steps * wl.n_layers), 4),
         "roofline": {"bound": "hbm", "kernel": "decode_stream_kernel" if wl.dtype == "bf16" else "decode_f32_kernel",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(wl.name),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_source": (traffic_src + " (a committed rocprofv3 --pmc reading, not a counter of this run)")
+                     if traffic_src else None,
                      "avg_kernel_us": round(avg_kernel_ms * 1e3, 3), "launches_timed": int(launches),
-                     "value_with_kernel_events": round(pass_bytes * args.steps / (dec_ms_p * 1e-3) / 1e9, 1)},
+                     "launches_run": int(total_launches),
+                     "value_with_kernel_events": round(pass_bytes * steps / (dec_ms_p * 1e-3) / 1e9, 1)},
     }
+    if workload == args.workload:
+        # the separator's dominant kernel (row statistics, Eq. 12) with its own events, compress passes only
+        if wl.dtype == "bf16":
+            tk.taskkv_profile_enable(ctx.handle, 2)
+            for _ in range(steps):
+                compress_all()
+            st_ms, st_n = tk.taskkv_profile_read(ctx.handle)
+            tk.taskkv_profile_enable(ctx.handle, 0)
+            if st_n:
+                t_s = st_ms / st_n * 1e-3
+                macs = wl.batch * wl.n_q_heads * wl.obs_window * wl.ctx_len * wl.head_dim
+                k_bytes = wl.batch * wl.n_kv_heads * wl.ctx_len * wl.head_dim * esize
+                util, util_src = PROFILED_MFMA_UTIL.get(wl.name, (None, None))
+                out["roofline_scoring"] = {
+                    "bound": "mfma", "kernel": "score_i8_stats_kernel", "dtype": "int8",
+                    "achieved": round(16 * 2 * macs / t_s / 1e12, 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                    "frac": round(16 * 2 * macs / t_s / 1e12 / INT8_PEAK_TOPS, 4),
+                    "ops_counted": "16 int8 digit products per bf16 product of Eq. 12 (all-zero digit blocks that "
+                                   "the kernel skips are counted as done)",
+                    "method_tflops": round(2 * macs / t_s / 1e12, 1),
+                    "hbm_gbs": round(k_bytes / t_s / 1e9, 1), "avg_kernel_us": round(t_s * 1e6, 1),
+                    "launches_timed": int(st_n),
+                    "mfma_util_counter": util,
+                    "mfma_util_source": (util_src + " (a committed rocprofv3 --pmc reading, not a counter of this run)")
+                    if util_src else None}
+        # device memory held while full K/V and the ragged cache coexist (the peak of compress + decode)
+        kv_full = sum(ld.k.numel() + ld.v.numel() for ld in layers) * esize
+        cache = (stack.k_cache.numel() + stack.v_cache.numel()) * esize if batched else \
+            sum(b.k_cache.numel() + b.v_cache.numel() for b in bufs) * esize
+        out["peak_device_bytes"] = {
+            "value": int(free0 - free1),
+            "what": "device memory taken between the start of the workload and the timed region (hipMemGetInfo): "
+                    "prefill Q window / K / V of every layer, separator outputs, ragged caches, decode inputs of "
+                    "every step and the library workspace, all resident at once; nothing is allocated after that",
+            "full_kv_bytes": int(kv_full), "ragged_cache_bytes": int(cache),
+            "ragged_over_full": round(cache / kv_full, 4), "library_workspace_bytes": int(ctx.bytes),
+            "held_after_prefill_release": int(cache + ctx.bytes)}
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -231,6 +314,10 @@ def measure(args, workload, with_cpu_baseline):
     if with_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, layers)
     ctx.close()
+    del layers, bufs, dec_in
+    if batched:
+        del stack
+    torch.cuda.empty_cache()
     return out
 
 

@@ -13,8 +13,10 @@
  *     row-major in the stated shape, 16-byte aligned.  Inputs are never
  *     written unless stated.  Scalars and the cfg struct are host values.
  *   - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream);
- *     no entry point synchronises the device or allocates memory, except
- *     taskkv_create / taskkv_destroy / taskkv_last_async_error.
+ *     no entry point synchronises the device or allocates device memory,
+ *     except taskkv_create / taskkv_destroy (both), taskkv_last_async_error and
+ *     taskkv_profile_read (they wait for the stream / the recorded launches);
+ *     taskkv_profile_enable creates HIP event objects on its first call.
  *   - Return value: TASKKV_OK or a negative taskkv_status.  Host-visible
  *     argument errors are reported before anything is enqueued.  Conditions
  *     only the device can see (appending to a full cache) set a sticky flag
@@ -80,7 +82,8 @@ typedef struct taskkv_layer_cfg {
   float softmax_scale;     /* 0 => 1/sqrt(d) */
 } taskkv_layer_cfg;
 
-/* Create a context on `device_id` with `workspace_bytes` of scratch (see
+/*
+ * Create a context on `device_id` with `workspace_bytes` of scratch (see
  * taskkv_workspace_bytes).  Allocates; the only call besides destroy that does. */
 int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes);
 void taskkv_destroy(taskkv_ctx *ctx);
@@ -147,7 +150,13 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
  *                              TASKKV_PACK_COMPRESSED mode a compensation token is
  *                              listed by the first position of its group
  * capacity_tokens must be >= taskkv_cache_tokens(cfg, reserve_decode_tokens)
- * (else TASKKV_ECAPACITY).  Middle tokens are the n_middle best of the pooled
+ * (else TASKKV_ECAPACITY).  cfg must name the same ctx_len, n_sink, n_recent,
+ * n_middle, pack_mode and pool_kernel as the taskkv_separate call that produced
+ * `scores` whenever that call screened them (see taskkv_set_screening): the
+ * fp32 values off the decision columns are good for that selection only.  The
+ * library checks this for the scores buffer of the ctx's last screening
+ * taskkv_separate and returns TASKKV_EINVAL on a mismatch; switch screening off
+ * to compress one set of scores under several budgets.  Middle tokens are the n_middle best of the pooled
  * scores inside [s1, N - s2), ties to the lower index; rows are copied
  * bit-for-bit; slots past a unit's length are zero-filled.  In
  * TASKKV_PACK_COMPRESSED mode group g of n covers middle offsets
@@ -180,6 +189,37 @@ int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void 
                        const int64_t *offsets, int32_t *lens, float *out, void *hip_stream);
 
 /*
+ * A decode step of a whole stack of layers in one call (the step of Sec. 5.5.3
+ * for every layer at once; it serves callers that have all layers' queries at
+ * hand, e.g. a benchmark or speculative pipelines -- in an ordinary decoder
+ * layer r+1's query depends on layer r's output).  The layers' ragged caches
+ * lie one after the other in k_cache / v_cache: layer r was compressed into
+ * the slice that starts at token sum(layer_capacity_tokens[0..r)), with its
+ * own offsets / lens arrays.  All layers share B, H_q, H_kv, d, dtype and the
+ * softmax scale (cfg: any layer's cfg; only these fields are read).
+ *
+ * taskkv_stack_rebase writes the offsets array of the stack:
+ *   layer_offsets  [n_layers, units_per_layer + 1] i64 (device)  row r = the
+ *                  offsets taskkv_compress wrote for layer r
+ *   layer_capacity_tokens [n_layers] i64 (HOST)  capacity of each layer's slice
+ *   stacked_offsets [n_layers * units_per_layer + 1] i64 (device, out)
+ * n_layers * units_per_layer <= 65535.
+ *
+ * taskkv_decode_attn_layers is taskkv_decode_attn with (layer, batch element)
+ * in place of the batch element:
+ *   q [n_layers, B, H_q, d], k_new / v_new [n_layers, B, H_kv, d] or both NULL,
+ *   lens [n_layers * B * H_kv] (the layers' lens arrays, contiguous, layer-major),
+ *   offsets = stacked_offsets, capacity_tokens = the sum of the layers' capacities,
+ *   out [n_layers, B, H_q, d] f32.
+ */
+int taskkv_stack_rebase(taskkv_ctx *ctx, int32_t n_layers, int32_t units_per_layer, const int64_t *layer_offsets,
+                        const int64_t *layer_capacity_tokens, int64_t *stacked_offsets, void *hip_stream);
+int taskkv_decode_attn_layers(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, int32_t n_layers, const void *q,
+                              const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                              int64_t capacity_tokens, const int64_t *offsets, int32_t *lens, float *out,
+                              void *hip_stream);
+
+/*
  * Inspection: copy the cache back to plain rows.  k_rows / v_rows are
  * [capacity_tokens, d] row-major (dtype of cfg); token p of unit u lands in row
  * offsets[u] + p.  Rows past a unit's length are written as stored (zeros).
@@ -188,8 +228,12 @@ int taskkv_cache_export(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void
                         const void *v_cache, int64_t capacity_tokens, const int64_t *offsets,
                         void *k_rows, void *v_rows, void *hip_stream);
 
-/* Synchronises `hip_stream`, returns and clears the sticky device-side flag:
- * 0 = none, 1 = append to a full unit. */
+/* Synchronises `hip_stream`, returns and clears the sticky device-side flag (the
+ * clearing store is enqueued on `hip_stream`).  Bits: 1 = a token was appended
+ * to a full unit and dropped; 2 = taskkv_compress was given a hetero_mask that
+ * marks more keep-everything heads than cfg's counts (n_hetero, plus one with
+ * add_centre_head) leave room for in capacity_tokens: the units that did not
+ * fit were left empty (length 0, no region), nothing was written out of bounds. */
 int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream);
 
 /* Screening lets taskkv_separate score bf16 inputs on the bf16 matrix cores
@@ -217,12 +261,17 @@ int taskkv_set_stats_engine(taskkv_ctx *ctx, int engine);
 int taskkv_set_stream_skew(taskkv_ctx *ctx, int skew);
 
 /*
- * Timing hooks for the benchmark.  With profiling on, taskkv_decode_attn
- * attaches two HIP events to the launch of its attention kernel, on the launch
- * stream; they record when the kernel began and ended (up to 4096 launches
- * are kept).  taskkv_profile_read synchronises, sums the recorded durations
- * into *total_ms / *launches and clears the record.  Keep profiling off while
- * the stream is being captured into a HIP graph.
+ * Timing hooks for the benchmark.  on = 1: taskkv_decode_attn attaches two HIP
+ * events to the launch of its attention kernel, on the launch stream; they
+ * record when the kernel began and ended.  on = 2: taskkv_separate does the
+ * same for its row-statistics kernel (Eq. 12, bf16 inputs).  on = 0: off.  2048 event pairs are
+ * created by the first taskkv_profile_enable(ctx, 1); when all are in use the
+ * next launch first waits for the recorded ones and adds their durations to a
+ * running total, so every launch is counted however many there are (and the
+ * host no longer runs ahead of the device: use it for measurement passes).
+ * taskkv_profile_read waits for the recorded launches, returns the total in
+ * *total_ms / *launches and clears it.  Keep profiling off while the stream is
+ * being captured into a HIP graph.
  */
 int taskkv_profile_enable(taskkv_ctx *ctx, int on);
 int taskkv_profile_read(taskkv_ctx *ctx, double *total_ms, int64_t *launches);

@@ -14,7 +14,7 @@ EXPORTED_SYMBOLS = [
     "taskkv_cache_tokens", "taskkv_hetero_head_count", "taskkv_middle_budget", "taskkv_separate",
     "taskkv_compress", "taskkv_decode_attn", "taskkv_cache_export", "taskkv_last_async_error",
     "taskkv_profile_enable", "taskkv_profile_read", "taskkv_set_screening", "taskkv_set_stream_skew",
-    "taskkv_set_stats_engine",
+    "taskkv_set_stats_engine", "taskkv_stack_rebase", "taskkv_decode_attn_layers",
 ]
 
 
@@ -81,6 +81,10 @@ def load_library():
     lib.taskkv_compress.restype = C.c_int
     lib.taskkv_decode_attn.argtypes = [vp, cfgp, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     lib.taskkv_decode_attn.restype = C.c_int
+    lib.taskkv_stack_rebase.argtypes = [vp, i32, i32, vp, C.POINTER(i64), vp, vp]
+    lib.taskkv_stack_rebase.restype = C.c_int
+    lib.taskkv_decode_attn_layers.argtypes = [vp, cfgp, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.taskkv_decode_attn_layers.restype = C.c_int
     lib.taskkv_cache_export.argtypes = [vp, cfgp, vp, vp, i64, vp, vp, vp, vp]
     lib.taskkv_cache_export.restype = C.c_int
     lib.taskkv_last_async_error.argtypes = [vp, vp]
@@ -196,6 +200,26 @@ def taskkv_decode_attn(ctx, cfg, q, k_new, v_new, k_cache, v_cache, capacity_tok
         _ptr(lens, torch.int32), _ptr(out, torch.float32), _stream(stream)), "taskkv_decode_attn")
 
 
+def taskkv_stack_rebase(ctx, n_layers, units_per_layer, layer_offsets, layer_capacity_tokens, stacked_offsets,
+                        stream=None) -> None:
+    import torch
+    caps = (C.c_int64 * n_layers)(*[int(c) for c in layer_capacity_tokens])
+    _check(load_library().taskkv_stack_rebase(
+        ctx, n_layers, units_per_layer, _ptr(layer_offsets, torch.int64), caps,
+        _ptr(stacked_offsets, torch.int64), _stream(stream)), "taskkv_stack_rebase")
+
+
+def taskkv_decode_attn_layers(ctx, cfg, n_layers, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets,
+                              lens, out, stream=None) -> None:
+    import torch
+    e = _elem(cfg)
+    _check(load_library().taskkv_decode_attn_layers(
+        ctx, C.byref(cfg), n_layers, _ptr(q, e), _ptr(k_new, e, allow_none=True),
+        _ptr(v_new, e, allow_none=True), _ptr(k_cache, e), _ptr(v_cache, e), capacity_tokens,
+        _ptr(offsets, torch.int64), _ptr(lens, torch.int32), _ptr(out, torch.float32), _stream(stream)),
+        "taskkv_decode_attn_layers")
+
+
 def taskkv_cache_export(ctx, cfg, k_cache, v_cache, capacity_tokens, offsets, k_rows, v_rows,
                         stream=None) -> None:
     import torch
@@ -228,12 +252,13 @@ def taskkv_set_stream_skew(ctx, skew: int) -> None:
     _check(load_library().taskkv_set_stream_skew(ctx, int(skew)), "taskkv_set_stream_skew")
 
 
-def taskkv_profile_enable(ctx, on: bool) -> None:
-    _check(load_library().taskkv_profile_enable(ctx, 1 if on else 0), "taskkv_profile_enable")
+def taskkv_profile_enable(ctx, on) -> None:
+    """0 / False = off, 1 / True = time the decode attention kernel, 2 = the separator's row-statistics kernel."""
+    _check(load_library().taskkv_profile_enable(ctx, int(on)), "taskkv_profile_enable")
 
 
 def taskkv_profile_read(ctx):
-    """(total milliseconds, launches) of the decode attention kernel since the last read."""
+    """(total milliseconds, launches) of the profiled kernel since the last read."""
     ms, n = C.c_double(), C.c_int64()
     _check(load_library().taskkv_profile_read(ctx, C.byref(ms), C.byref(n)), "taskkv_profile_read")
     return ms.value, n.value

@@ -8,6 +8,20 @@
 
 namespace taskkv {
 
+// Makes `device` current for the lifetime of the object and puts the caller's
+// device back afterwards.
+struct DeviceGuard {
+  int prev;
+  bool ok;
+  explicit DeviceGuard(int device) : prev(-1), ok(false) {
+    if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+    ok = hipSetDevice(device) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
 static bool resolve(const taskkv_layer_cfg *c, Dims &d) {
   if (!c) return false;
   if (c->batch < 1 || c->n_kv_heads < 1 || c->n_kv_heads > 256 || c->n_q_heads < 1) return false;
@@ -102,6 +116,18 @@ static size_t ws_decode(const Dims &d, int64_t capacity) {
          al(stream_table_ints(d) * sizeof(int32_t));   // page prefix, wave range starts, first/last wave of each unit
 }
 
+int profile_harvest(taskkv_ctx *ctx) {
+  for (int i = 0; i < ctx->n_events; ++i) {
+    if (hipEventSynchronize(ctx->ev_stop[i]) != hipSuccess) return TASKKV_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]) != hipSuccess) return TASKKV_EHIP;
+    ctx->prof_ms += ms;
+  }
+  ctx->prof_launches += ctx->n_events;
+  ctx->n_events = 0;
+  return TASKKV_OK;
+}
+
 }  // namespace taskkv
 
 using namespace taskkv;
@@ -124,7 +150,8 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
   *out = nullptr;
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || device_id < 0 || device_id >= n_dev) return TASKKV_EHIP;
-  if (hipSetDevice(device_id) != hipSuccess) return TASKKV_EHIP;
+  DeviceGuard guard(device_id);   // the caller's current device is put back on return
+  if (!guard.ok) return TASKKV_EHIP;
   taskkv_ctx *c = new (std::nothrow) taskkv_ctx();
   if (!c) return TASKKV_EHIP;
   c->device = device_id;
@@ -134,11 +161,14 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
   c->profiling = 0;
   c->n_events = 0;
   c->events_created = 0;
+  c->prof_ms = 0.0;
+  c->prof_launches = 0;
   c->n_cu = 0;
   c->screening = 1;
   c->stats_engine = 1;
   c->stream_skew = STREAM_SKEW_DEFAULT;
   for (int i = 0; i < 4; ++i) c->stream_wg[i] = 0;
+  c->screened_scores = nullptr;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) {
     delete c;
@@ -160,7 +190,7 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
 
 void taskkv_destroy(taskkv_ctx *ctx) {
   if (!ctx) return;
-  (void)hipSetDevice(ctx->device);
+  DeviceGuard guard(ctx->device);
   (void)hipDeviceSynchronize();
   for (int i = 0; i < ctx->events_created; ++i) {
     (void)hipEventDestroy(ctx->ev_start[i]);
@@ -229,7 +259,15 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   i8.gq = cv.take<double>((size_t)d.units * d.Rpad);
   i8.qtiny = cv.take<QTiny>((size_t)d.units * I8_QCAP);
   i8.qcnt = cv.take<int32_t>((size_t)d.units);
+  i8.prof = ctx;
   if (!cv.ok) return TASKKV_EWORKSPACE;
+  if (scores_screened(d, cfg->dtype, &scr)) {
+    ctx->screened_scores = scores;
+    const int sel[6] = {cfg->ctx_len, cfg->n_sink, cfg->n_recent, cfg->n_middle, cfg->pack_mode, cfg->pool_kernel};
+    for (int i = 0; i < 6; ++i) ctx->screened_sel[i] = sel[i];
+  } else if (ctx->screened_scores == scores) {
+    ctx->screened_scores = nullptr;
+  }
   int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, ctx->screening ? &scr : nullptr,
                          ctx->stats_engine ? &i8 : nullptr, s);
   if (rc) return rc;
@@ -249,6 +287,12 @@ int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k,
   if (capacity_tokens % CHUNK) return TASKKV_EINVAL;
   if (capacity_tokens < cache_tokens(d, reserve_decode_tokens)) return TASKKV_ECAPACITY;
   if (capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
+  if (scores == ctx->screened_scores) {
+    // screened scores are exact only where the separator's own budget can decide
+    const int sel[6] = {cfg->ctx_len, cfg->n_sink, cfg->n_recent, cfg->n_middle, cfg->pack_mode, cfg->pool_kernel};
+    for (int i = 0; i < 6; ++i)
+      if (sel[i] != ctx->screened_sel[i]) return TASKKV_EINVAL;
+  }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   Carver cv(ctx->ws, ctx->ws_bytes);
   const double *sel_scores = scores;
@@ -312,6 +356,28 @@ int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void 
                        lens, eff_len, pm, pl, po, out, s);
 }
 
+int taskkv_stack_rebase(taskkv_ctx *ctx, int32_t n_layers, int32_t units_per_layer, const int64_t *layer_offsets,
+                        const int64_t *layer_capacity_tokens, int64_t *stacked_offsets, void *hip_stream) {
+  if (!ctx || n_layers < 1 || units_per_layer < 1 || !layer_offsets || !layer_capacity_tokens || !stacked_offsets)
+    return TASKKV_EINVAL;
+  if ((int64_t)n_layers * units_per_layer > 65535) return TASKKV_EINVAL;
+  for (int r = 0; r < n_layers; ++r)
+    if (layer_capacity_tokens[r] < 0 || layer_capacity_tokens[r] % CHUNK) return TASKKV_EINVAL;
+  return launch_stack_rebase(layer_offsets, layer_capacity_tokens, n_layers, units_per_layer, stacked_offsets,
+                             static_cast<hipStream_t>(hip_stream));
+}
+
+int taskkv_decode_attn_layers(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, int32_t n_layers, const void *q,
+                              const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                              int64_t capacity_tokens, const int64_t *offsets, int32_t *lens, float *out,
+                              void *hip_stream) {
+  if (!cfg || n_layers < 1 || (int64_t)cfg->batch * n_layers > 0x7fffffff) return TASKKV_EINVAL;
+  taskkv_layer_cfg all = *cfg;
+  all.batch = cfg->batch * n_layers;   // the step sees (layer, batch element) pairs as batch elements
+  return taskkv_decode_attn(ctx, &all, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens, out,
+                            hip_stream);
+}
+
 int taskkv_cache_export(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k_cache,
                         const void *v_cache, int64_t capacity_tokens, const int64_t *offsets,
                         void *k_rows, void *v_rows, void *hip_stream) {
@@ -325,6 +391,7 @@ int taskkv_cache_export(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void
 
 int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream) {
   if (!ctx) return TASKKV_EINVAL;
+  DeviceGuard guard(ctx->device);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   int flag = 0;
   if (hipMemcpyAsync(&flag, ctx->d_err, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return TASKKV_EHIP;
@@ -352,30 +419,33 @@ int taskkv_set_stream_skew(taskkv_ctx *ctx, int skew) {
 }
 
 int taskkv_profile_enable(taskkv_ctx *ctx, int on) {
-  if (!ctx) return TASKKV_EINVAL;
-  if (on && !ctx->events_created) {
-    for (int i = 0; i < MAX_PROFILE_EVENTS; ++i) {
-      if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess) return TASKKV_EHIP;
-      if (hipEventCreate(&ctx->ev_stop[i]) != hipSuccess) return TASKKV_EHIP;
+  if (!ctx || on < 0 || on > 2) return TASKKV_EINVAL;
+  if (on) {
+    // the event pairs are made on first use; a failure leaves the pairs made so
+    // far usable and no half-made pair behind
+    while (ctx->events_created < MAX_PROFILE_EVENTS) {
+      const int i = ctx->events_created;
+      if (hipEventCreate(&ctx->ev_start[i]) != hipSuccess) break;
+      if (hipEventCreate(&ctx->ev_stop[i]) != hipSuccess) {
+        (void)hipEventDestroy(ctx->ev_start[i]);
+        break;
+      }
       ctx->events_created = i + 1;
     }
+    if (ctx->events_created == 0) return TASKKV_EHIP;
   }
-  ctx->profiling = on ? 1 : 0;
+  ctx->profiling = on;
   return TASKKV_OK;
 }
 
 int taskkv_profile_read(taskkv_ctx *ctx, double *total_ms, int64_t *launches) {
   if (!ctx || !total_ms || !launches) return TASKKV_EINVAL;
-  double tot = 0.0;
-  for (int i = 0; i < ctx->n_events; ++i) {
-    if (hipEventSynchronize(ctx->ev_stop[i]) != hipSuccess) return TASKKV_EHIP;
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, ctx->ev_start[i], ctx->ev_stop[i]) != hipSuccess) return TASKKV_EHIP;
-    tot += ms;
-  }
-  *total_ms = tot;
-  *launches = ctx->n_events;
-  ctx->n_events = 0;
+  const int rc = profile_harvest(ctx);
+  if (rc) return rc;
+  *total_ms = ctx->prof_ms;
+  *launches = ctx->prof_launches;
+  ctx->prof_ms = 0.0;
+  ctx->prof_launches = 0;
   return TASKKV_OK;
 }
 

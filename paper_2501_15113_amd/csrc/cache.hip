@@ -24,18 +24,11 @@ __device__ __forceinline__ double elem_as_double(uint16_t x) {
   return (double)__uint_as_float(uint32_t(x) << 16);
 }
 
-// Largest u with offsets[u] <= tok, or -1 if tok is past the last region.
-__device__ __forceinline__ int find_unit(const int64_t *__restrict__ offsets, int n_units, int64_t tok) {
-  if (tok >= offsets[n_units]) return -1;
-  int lo = 0, hi = n_units - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (offsets[mid] <= tok) lo = mid; else hi = mid - 1;
-  }
-  return lo;
-}
-
-// lens / offsets from the mask (single block; units are few).
+// lens / offsets from the mask (single block; units are few).  A mask that
+// marks more keep-everything heads than the cfg's counts provide room for
+// cannot be laid out in `capacity` tokens: the units that do not fit are left
+// empty (no region, length 0), so that nothing downstream reads or writes past
+// the buffer, and bit 2 of the sticky flag reports it.
 __global__ void layout_kernel(const uint8_t *__restrict__ mask, int64_t *__restrict__ offsets,
                               int32_t *__restrict__ lens, int *__restrict__ d_err, Dims dm,
                               int reserve, int64_t capacity) {
@@ -45,14 +38,20 @@ __global__ void layout_kernel(const uint8_t *__restrict__ mask, int64_t *__restr
   __syncthreads();
   if (threadIdx.x == 0) {
     int64_t off = 0;
+    bool overflow = false;
     for (int u = 0; u < dm.units; ++u) {
       offsets[u] = off;
       int64_t cap = ((int64_t)lens[u] + reserve + CHUNK - 1) / CHUNK * CHUNK;
       if (cap < CHUNK) cap = CHUNK;  // every unit owns at least one chunk
+      if (off + cap > capacity) {
+        lens[u] = 0;
+        cap = 0;
+        overflow = true;
+      }
       off += cap;
     }
     offsets[dm.units] = off;
-    if (off > capacity) atomicOr(d_err, 2);
+    if (overflow) atomicOr(d_err, 2);
   }
 }
 
@@ -251,6 +250,37 @@ __global__ void append_kernel(const T *__restrict__ k_new, const T *__restrict__
     vc[((size_t)base + p) * D + c] = vval;
   }
   if (c == 0) lens[u] = p + 1;
+}
+
+// Offsets of a stack of layers whose caches lie one after the other in one
+// allocation: entry r * units + u = layer r's offsets[u] + the tokens of the
+// layers before it; the last entry = all tokens.
+struct StackBases {
+  int64_t base[STACK_REBASE_LAYERS + 1];
+};
+__global__ void stack_rebase_kernel(const int64_t *__restrict__ layer_offsets, int64_t *__restrict__ stacked,
+                                    StackBases bases, int layer0, int n_here, int units, int is_last) {
+  const int r = blockIdx.y, u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_here || u >= units) return;
+  stacked[(size_t)(layer0 + r) * units + u] = layer_offsets[(size_t)(layer0 + r) * (units + 1) + u] + bases.base[r];
+  if (is_last && r == n_here - 1 && u == 0) stacked[(size_t)(layer0 + n_here) * units] = bases.base[n_here];
+}
+
+int launch_stack_rebase(const int64_t *layer_offsets, const int64_t *layer_capacity, int n_layers, int units,
+                        int64_t *stacked, hipStream_t s) {
+  int64_t run = 0;
+  for (int l0 = 0; l0 < n_layers; l0 += STACK_REBASE_LAYERS) {
+    const int n_here = n_layers - l0 < STACK_REBASE_LAYERS ? n_layers - l0 : STACK_REBASE_LAYERS;
+    StackBases b;
+    for (int r = 0; r < n_here; ++r) {
+      b.base[r] = run;
+      run += layer_capacity[l0 + r];
+    }
+    b.base[n_here] = run;
+    stack_rebase_kernel<<<dim3((units + 255) / 256, n_here), dim3(256), 0, s>>>(layer_offsets, stacked, b, l0, n_here,
+                                                                              units, l0 + n_here == n_layers);
+  }
+  return hip_ok(hipGetLastError());
 }
 
 int launch_layout(const Dims &dm, const uint8_t *mask, int reserve, int64_t capacity, int64_t *offsets,

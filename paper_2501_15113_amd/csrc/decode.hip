@@ -19,10 +19,6 @@
 
 namespace taskkv {
 
-#ifndef TASKKV_DEC_PIPE
-#define TASKKV_DEC_PIPE 1
-#endif
-
 // bf16 cache, matrix-core path.  Block = 4 waves; wave w takes pages w, w+4, ...
 // of its chunk.  Per 32-token page and wave: 2*D/32 MFMAs for S^T = K q^T
 // (rows = tokens, columns = the <=16 query heads of the group), online softmax
@@ -97,7 +93,6 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) acc[mb] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-#if TASKKV_DEC_PIPE
   for (int pg = w; pg < n_pages; pg += 8) {
     if (pg + 4 < n_pages)
       load_page<D, NT>(kbase + (size_t)(pg + 4) * PSTRIDE, vbase + (size_t)(pg + 4) * PSTRIDE, l, rb);
@@ -108,12 +103,6 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
       attend_page<D>(rb, qv, (pg + 4) * PAGE, n_tok, g, scale_log2, m_run, l_run, acc);
     }
   }
-#else
-  for (int pg = w; pg < n_pages; pg += 4) {
-    if (pg != w) load_page<D, NT>(kbase + (size_t)pg * PSTRIDE, vbase + (size_t)pg * PSTRIDE, l, ra);
-    attend_page<D>(ra, qv, pg * PAGE, n_tok, g, scale_log2, m_run, l_run, acc);
-  }
-#endif
 
   // merge the four waves (fixed order) and write the chunk's partial
   __shared__ float sm[4][16], sl[4][16];
@@ -153,7 +142,7 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(
     float *__restrict__ pl, float *__restrict__ po, int n_units, int Hq, int Hkv, int G, float scale) {
   const int chunk = blockIdx.x, hg = blockIdx.y;
   const int64_t tok0 = (int64_t)chunk * CHUNK;
-  const int u = find_unit_d(offsets, n_units, tok0);
+  const int u = find_unit(offsets, n_units, tok0);
   if (u < 0) return;
   const int local0 = (int)(tok0 - offsets[u]);
   const int len = lens[u];
@@ -261,7 +250,9 @@ __global__ __launch_bounds__(1024) void combine_kernel(const float *__restrict__
   const int b = bq / Hq, hq = bq % Hq, h = hq / G, slot = hq % G;
   const int u = b * Hkv + h;
   const int64_t chunk0 = offsets[u] / CHUNK;
-  const int len = len_src[u];
+  // a unit without a region (left empty by an overflowing layout) has no
+  // chunk and therefore no block that recorded its length
+  const int len = offsets[u + 1] > offsets[u] ? len_src[u] : 0;
   if (lens_out != nullptr && slot == 0 && tid == 0) lens_out[u] = len;
   const int nch = (len + CHUNK - 1) / CHUNK;
   const int dl = tid % DL, cl = tid / DL;

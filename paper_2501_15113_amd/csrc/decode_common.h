@@ -1,7 +1,6 @@
 // Device helpers shared by the decode attention kernels (bf16 matrix-core path).
 #pragma once
 
-#include <hip/hip_ext.h>
 #include <math.h>
 
 #include "lane_ops.h"
@@ -9,36 +8,15 @@
 
 namespace taskkv {
 
-// Launch of a decode attention kernel.  With profiling on, two events are
-// attached to the launch itself: they take the kernel's own begin and end
-// times from its completion signal, so the recorded duration holds no dispatch
-// latency and the stream gets no extra packets (events recorded before and
-// after the launch read 2-3 us more than the kernel runs).  Arguments are
-// converted to the kernel's parameter types before they are packed.
+// Launch of a decode attention kernel (timed when profiling mode 1 is on).
 template <typename... P, typename... A>
 inline void launch_attention(taskkv_ctx *ctx, void (*kernel)(P...), dim3 grid, dim3 block, hipStream_t s,
                              A... args) {
-  if (ctx->profiling && ctx->n_events < MAX_PROFILE_EVENTS) {
-    hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ctx->ev_start[ctx->n_events], ctx->ev_stop[ctx->n_events], 0,
-                          static_cast<P>(args)...);
-    ++ctx->n_events;
-  } else {
-    kernel<<<grid, block, 0, s>>>(static_cast<P>(args)...);
-  }
+  launch_profiled(ctx, 1, kernel, grid, block, s, args...);
 }
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
-
-__device__ __forceinline__ int find_unit_d(const int64_t *__restrict__ offsets, int n_units, int64_t tok) {
-  if (tok >= offsets[n_units]) return -1;
-  int lo = 0, hi = n_units - 1;
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (offsets[mid] <= tok) lo = mid; else hi = mid - 1;
-  }
-  return lo;
-}
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -70,7 +48,7 @@ constexpr size_t NT_THRESHOLD_BYTES = size_t(32) << 20;
 // instead of a dependent binary-search chain.
 __device__ __forceinline__ int find_unit_fast(const int64_t *__restrict__ offsets, int n_units,
                                               int64_t tok, int lane) {
-  if (n_units > 256) return find_unit_d(offsets, n_units, tok);
+  if (n_units > 256) return find_unit(offsets, n_units, tok);
   int64_t v[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -100,53 +78,9 @@ __device__ __forceinline__ void load_page(const uint4 *kp, const uint4 *vp, int 
   for (int mb = 0; mb < D / 16; ++mb) r.vr[mb].v = stream_load<NT>(vp + mb * 64 + l);
 }
 
-// One 32-token page: S^T = K q^T, online softmax (exp2 domain), O^T += V^T P^T.
-template <int D>
-__device__ __forceinline__ void attend_page(const PageRegs<D> &r, const Frag (&qv)[D / 32], int tok_base,
-                                            int n_tok, int g, float scale_log2, float &m_run,
-                                            float &l_run, floatx4 (&acc)[D / 16]) {
-  constexpr int KK = D / 32, MB = D / 16;
-  floatx4 s[2];
-#pragma unroll
-  for (int sb = 0; sb < 2; ++sb) {
-    s[sb] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      s[sb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.kr[sb][kk].b, qv[kk].b, s[sb], 0, 0, 0);
-  }
-  float sv[8];
-  float mloc = -INFINITY;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int t = tok_base + 16 * (e >> 2) + 4 * g + (e & 3);
-    sv[e] = t < n_tok ? s[e >> 2][e & 3] * scale_log2 : -INFINITY;
-    mloc = fmaxf(mloc, sv[e]);
-  }
-  mloc = max_lanes_16_32(mloc);
-  const float m_new = fmaxf(m_run, mloc);  // finite: the page holds >= 1 token
-  const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-  float lsum = 0.f;
-  Frag ph, plo;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float p = __builtin_amdgcn_exp2f(sv[e] - m_new);
-    lsum += p;
-    const __bf16 hi = (__bf16)p;
-    ph.b[e] = hi;
-    plo.b[e] = (__bf16)(p - (float)hi);
-  }
-  l_run = l_run * alpha + lsum;
-  m_run = m_new;
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    acc[mb] *= alpha;
-    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, ph.b, acc[mb], 0, 0, 0);
-    acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, plo.b, acc[mb], 0, 0, 0);
-  }
-}
-
-// The same page in two halves, so that the caller can request the next K tiles
-// as soon as the QK^T MFMAs have consumed the current ones.
+// One 32-token page: S^T = K q^T, online softmax (exp2 domain), O^T += V^T P^T,
+// in two halves, so that a caller can request the next K tiles as soon as the
+// QK^T MFMAs have consumed the current ones.
 template <int D>
 __device__ __forceinline__ void page_scores(const PageRegs<D> &r, const Frag (&qv)[D / 32], floatx4 (&s)[2]) {
 #pragma unroll
@@ -191,6 +125,15 @@ __device__ __forceinline__ void page_values(const PageRegs<D> &r, const floatx4 
     acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, ph.b, acc[mb], 0, 0, 0);
     acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.vr[mb].b, plo.b, acc[mb], 0, 0, 0);
   }
+}
+
+template <int D>
+__device__ __forceinline__ void attend_page(const PageRegs<D> &r, const Frag (&qv)[D / 32], int tok_base,
+                                            int n_tok, int g, float scale_log2, float &m_run,
+                                            float &l_run, floatx4 (&acc)[D / 16]) {
+  floatx4 s[2];
+  page_scores<D>(r, qv, s);
+  page_values<D>(r, s, tok_base, n_tok, g, scale_log2, m_run, l_run, acc);
 }
 
 template <int D, bool NT>

@@ -622,7 +622,8 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
   const int rows_per_block = small ? 128 : 256;
   const dim3 grid(n_wg, dm.units, (dm.Rpad + rows_per_block - 1) / rows_per_block);
   auto launch = [&](auto kernel, int threads) {
-    kernel<<<grid, dim3(threads), 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, part, knorm, dm, keys_per_wg);
+    launch_profiled(bufs.prof, 2, kernel, grid, dim3(threads), s, kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, part,
+                    knorm, dm, keys_per_wg);
   };
   if (dm.D == 64) {
     q_digits_kernel<64><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);

@@ -346,11 +346,7 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
                       double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8b, hipStream_t s) {
   const int cpw = chunks_per_wg_for(dm_all);
   const int n_groups = (dm_all.Rtot + ROW_GROUP - 1) / ROW_GROUP;
-  // screening pays once the fp64 column pass is large compared with the extra
-  // launches (mode 1 = decide here, 2 = whenever possible)
-  const bool big = (double)dm_all.units * dm_all.Rtot * dm_all.N >= 3e7;   // measured: loses at 8e6, wins at 7e7
-  const bool screen = scr != nullptr && n_groups == 1 && screen_supported(dm_all, dtype) &&
-                      (scr->mode == 2 || big);
+  const bool screen = scores_screened(dm_all, dtype, scr);
   if (n_groups > 1) {
     const size_t n = (size_t)dm_all.units * dm_all.N;
     zero_f64_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(scores, n);
@@ -415,6 +411,15 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
                                                                            cpw, scr->band_idx, scr->band_cnt);
   }
   return hip_ok(hipGetLastError());
+}
+
+// Whether the column means of this layer go through the fp32 screening pass:
+// it pays once the fp64 column pass is large compared with the extra launches
+// (mode 1 = decide here, 2 = whenever possible).
+bool scores_screened(const Dims &dm, int dtype, const ScreenBufs *scr) {
+  const int n_groups = (dm.Rtot + ROW_GROUP - 1) / ROW_GROUP;
+  const bool big = (double)dm.units * dm.Rtot * dm.N >= 3e7;   // measured: loses at 8e6, wins at 7e7
+  return scr != nullptr && scr->mode != 0 && n_groups == 1 && screen_supported(dm, dtype) && (scr->mode == 2 || big);
 }
 
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,

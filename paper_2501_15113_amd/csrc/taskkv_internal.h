@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "taskkv.h"
@@ -10,9 +11,10 @@ namespace taskkv {
 
 constexpr int CHUNK = TASKKV_CHUNK_TOKENS;  // tokens per split-K work item / region alignment
 constexpr int PAGE = 32;                    // tokens per matrix-core page of the bf16 cache
-constexpr int MAX_PROFILE_EVENTS = 4096;
+constexpr int MAX_PROFILE_EVENTS = 2048;  // event pairs in flight; a full record is summed up and reused
 constexpr int STREAM_MAX_UNITS = 4096;  // units the streaming decode kernel can index in LDS
 constexpr int STREAM_MAX_WG = 1024;     // workgroups (4 waves each) it is ever launched with
+constexpr int STACK_REBASE_LAYERS = 64;  // layers one launch of the offset rebasing kernel covers
 constexpr int STREAM_SKEW_DEFAULT = 56; // share moved from odd to even workgroups, in 1/1024ths (measured)
 
 // Resolved problem sizes handed to kernels by value.
@@ -38,15 +40,21 @@ struct taskkv_ctx {
   size_t ws_bytes;
   int *d_err;  // sticky device flag
   int profiling;
-  int n_events;
+  int n_events;          // event pairs attached to launches and not yet summed up
   hipEvent_t ev_start[taskkv::MAX_PROFILE_EVENTS];
   hipEvent_t ev_stop[taskkv::MAX_PROFILE_EVENTS];
-  int events_created;
+  int events_created;    // pairs that exist (all of them once profiling has been switched on)
+  double prof_ms;        // durations summed up so far
+  int64_t prof_launches; // launches they belong to
   int n_cu;           // compute units of the device
   int stream_skew;    // 1/1024ths of an equal share moved from the waves of odd workgroups to even ones
   int stats_engine;   // row statistics of bf16 inputs: 0 = fp64 matrix instruction, 1 = int8 digits
   int screening;      // fp32 screening + fp64 recompute of contested columns: 0 off, 1 auto, 2 always
   int stream_wg[4];   // cached launch width of the streaming decode kernel per (D, NT) variant, 0 = unknown
+  // what the last taskkv_separate screened its scores for: off the listed
+  // columns they are fp32 values, good only for this selection
+  const double *screened_scores;
+  int screened_sel[6];   // ctx_len, n_sink, n_recent, n_middle, pack_mode, pool_kernel
 };
 
 namespace taskkv {
@@ -70,6 +78,18 @@ struct Carver {
   }
 };
 
+// Unit that owns token slot `tok` of the ragged cache: the largest u with
+// offsets[u] <= tok, or -1 if tok is past the last region.
+__device__ __forceinline__ int find_unit(const int64_t *__restrict__ offsets, int n_units, int64_t tok) {
+  if (tok >= offsets[n_units]) return -1;
+  int lo = 0, hi = n_units - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (offsets[mid] <= tok) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
 // ---- launchers (each validates nothing; api.hip has checked the arguments) ----
 int score_parts(const Dims &dm);
 int score_rows_padded(const Dims &dm);
@@ -92,6 +112,7 @@ struct I8Bufs {
   double *gq;       // [units][Rpad] row factors
   QTiny *qtiny;     // [units][I8_QCAP]
   int32_t *qcnt;    // [units]
+  taskkv_ctx *prof; // ctx whose profiling hook may time the statistics kernel (or null)
 };
 bool i8_stats_supported(const Dims &dm, int dtype);
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
@@ -103,6 +124,7 @@ int launch_screen(const Dims &dm, const void *q_win, const void *k, const double
                   int chunks_per_wg, hipStream_t s);
 int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
                 int32_t *band_idx, int32_t *band_cnt, hipStream_t s);
+bool scores_screened(const Dims &dm, int dtype, const ScreenBufs *scr);
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
                   double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8, hipStream_t s);
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
@@ -114,6 +136,8 @@ int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const vo
                        hipStream_t s);
 int launch_layout(const Dims &dm, const uint8_t *mask, int reserve, int64_t capacity, int64_t *offsets,
                   int32_t *lens, int *d_err, hipStream_t s);
+int launch_stack_rebase(const int64_t *layer_offsets, const int64_t *layer_capacity, int n_layers, int units,
+                        int64_t *stacked, hipStream_t s);
 int launch_pack(const Dims &dm, int dtype, const void *k, const void *v, const int32_t *kept_idx,
                 const uint8_t *mask, const int64_t *offsets, const int32_t *lens, const void *comp_k,
                 const void *comp_v, void *k_cache, void *v_cache, int64_t capacity, hipStream_t s);
@@ -134,5 +158,33 @@ int launch_decode_stream(taskkv_ctx *ctx, const Dims &dm, const void *q, const v
                          float *pm, float *pl, float *po, float *out, hipStream_t s);
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? TASKKV_OK : TASKKV_EHIP; }
+
+// Adds the durations of the recorded event pairs to the running totals and frees
+// the pairs for reuse (waits for the launches they are attached to).
+int profile_harvest(taskkv_ctx *ctx);
+
+// Launch of a kernel that the profiling hook can time (mode: 1 = the decode
+// attention kernel, 2 = the row-statistics kernel of the separator).  When the
+// ctx profiles this mode, two events are attached to the launch itself: they
+// take the kernel's own begin and end times from its completion signal, so the
+// recorded duration holds no dispatch latency and the stream gets no extra
+// packets (events recorded before and after the launch read 2-3 us more than
+// the kernel runs).  When every pair is in use the recorded ones are summed up
+// first (this waits for their launches: profiling is for measurement passes,
+// not for the timed ones).  Arguments are converted to the kernel's parameter
+// types before they are packed.
+template <typename... P, typename... A>
+inline void launch_profiled(taskkv_ctx *ctx, int mode, void (*kernel)(P...), dim3 grid, dim3 block,
+                            hipStream_t s, A... args) {
+  const bool timed = ctx != nullptr && ctx->profiling == mode;
+  if (timed && ctx->n_events >= ctx->events_created) (void)profile_harvest(ctx);
+  if (timed && ctx->n_events < ctx->events_created) {
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, s, ctx->ev_start[ctx->n_events], ctx->ev_stop[ctx->n_events], 0,
+                          static_cast<P>(args)...);
+    ++ctx->n_events;
+  } else {
+    kernel<<<grid, block, 0, s>>>(static_cast<P>(args)...);
+  }
+}
 
 }  // namespace taskkv

@@ -43,8 +43,9 @@ class Context:
 class LayerBuffers:
     """All device buffers one layer needs for separate -> compress -> decode."""
 
-    def __init__(self, cfg: tk.LayerCfg, reserve: int, device="cuda:0", cache=None):
-        """cache = (k_cache, v_cache, lens) views to use instead of fresh allocations."""
+    def __init__(self, cfg: tk.LayerCfg, reserve: int, device="cuda:0", cache=None, offsets=None):
+        """cache = (k_cache, v_cache, lens) views, offsets = a [B*Hkv+1] int64 view, to use
+        instead of fresh allocations."""
         self.cfg, self.reserve = cfg, reserve
         B, Hkv, Hq, d, N = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.ctx_len
         dev = torch.device(device)
@@ -60,7 +61,7 @@ class LayerBuffers:
             self.lens = torch.empty(B * Hkv, dtype=torch.int32, device=dev)
         else:
             self.k_cache, self.v_cache, self.lens = cache
-        self.offsets = torch.empty(B * Hkv + 1, dtype=torch.int64, device=dev)
+        self.offsets = torch.empty(B * Hkv + 1, dtype=torch.int64, device=dev) if offsets is None else offsets
         self.row = cfg.n_sink + cfg.n_middle + cfg.n_recent
         self.kept_idx = torch.empty(B * Hkv, max(self.row, 1), dtype=torch.int32, device=dev)
         self.out = torch.empty(B, Hq, d, dtype=torch.float32, device=dev)
@@ -90,11 +91,10 @@ class LayerBuffers:
 
 class LayerStack:
     """The ragged caches of several layers in one allocation, so that a single
-    taskkv_decode_attn call serves one decode step of all of them: the call sees
-    layers x batch "batch elements".  Each layer is compressed into its own
-    slice through its LayerBuffers; rebase() then writes the layers' region
-    offsets, shifted by the slice starts, into one offsets array.  Only buffer
-    views and index shifts happen here."""
+    taskkv_decode_attn_layers call serves one decode step of all of them.  Each
+    layer is compressed into its own slice through its LayerBuffers;
+    rebase() then has the library write the stack's offsets array
+    (taskkv_stack_rebase).  Only buffer views are made here."""
 
     def __init__(self, cfgs, reserve: int, device="cuda:0"):
         c0 = cfgs[0]
@@ -102,39 +102,37 @@ class LayerStack:
             assert (c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.dtype, c.softmax_scale) == \
                    (c0.batch, c0.n_q_heads, c0.n_kv_heads, c0.head_dim, c0.dtype, c0.softmax_scale)
         dev = torch.device(device)
-        d, U = c0.head_dim, c0.batch * c0.n_kv_heads
+        d, U, R = c0.head_dim, c0.batch * c0.n_kv_heads, len(cfgs)
         self.elem = torch.float32 if c0.dtype == tk.F32 else torch.bfloat16
-        caps = [tk.taskkv_cache_tokens(c, reserve) for c in cfgs]
-        self.bases = [sum(caps[:r]) for r in range(len(cfgs))]
-        self.capacity = sum(caps)
+        self.caps = [tk.taskkv_cache_tokens(c, reserve) for c in cfgs]
+        bases = [sum(self.caps[:r]) for r in range(R)]
+        self.capacity = sum(self.caps)
         self.k_cache = torch.empty(self.capacity * d, dtype=self.elem, device=dev)
         self.v_cache = torch.empty(self.capacity * d, dtype=self.elem, device=dev)
-        self.lens = torch.empty(len(cfgs) * U, dtype=torch.int32, device=dev)
-        self.offsets = torch.empty(len(cfgs) * U + 1, dtype=torch.int64, device=dev)
+        self.lens = torch.empty(R * U, dtype=torch.int32, device=dev)
+        self.layer_offsets = torch.empty(R, U + 1, dtype=torch.int64, device=dev)
+        self.offsets = torch.empty(R * U + 1, dtype=torch.int64, device=dev)
         self.layers = [
             LayerBuffers(c, reserve, device,
                          cache=(self.k_cache[b * d:(b + cap) * d], self.v_cache[b * d:(b + cap) * d],
-                                self.lens[r * U:(r + 1) * U]))
-            for r, (c, b, cap) in enumerate(zip(cfgs, self.bases, caps))]
-        # what the decode call is told: every field it reads is common to the layers
-        self.cfg = tk.LayerCfg(batch=c0.batch * len(cfgs), n_q_heads=c0.n_q_heads, n_kv_heads=c0.n_kv_heads,
+                                self.lens[r * U:(r + 1) * U]), offsets=self.layer_offsets[r])
+            for r, (c, b, cap) in enumerate(zip(cfgs, bases, self.caps))]
+        self.cfg0, self.n_layers, self._U = c0, R, U
+        # for sizing the ctx workspace: what the decode call resolves its cfg to
+        self.cfg = tk.LayerCfg(batch=c0.batch * R, n_q_heads=c0.n_q_heads, n_kv_heads=c0.n_kv_heads,
                                head_dim=d, ctx_len=c0.ctx_len, obs_window=c0.obs_window, top_t=c0.top_t,
                                n_sink=c0.n_sink, n_recent=c0.n_recent,
                                n_middle=max(c.n_middle for c in cfgs), n_hetero=max(c.n_hetero for c in cfgs),
                                add_centre_head=c0.add_centre_head, pool_kernel=c0.pool_kernel,
                                pack_mode=c0.pack_mode, dtype=c0.dtype, softmax_scale=c0.softmax_scale)
         self.out = torch.empty(self.cfg.batch, c0.n_q_heads, d, dtype=torch.float32, device=dev)
-        self._U = U
 
-    def rebase(self):
+    def rebase(self, ctx: Context):
         """Call after every layer has been compressed."""
-        U = self._U
-        for r, (lb, base) in enumerate(zip(self.layers, self.bases)):
-            self.offsets[r * U:(r + 1) * U] = lb.offsets[:U] + base
-        self.offsets[-1] = self.capacity
+        tk.taskkv_stack_rebase(ctx.handle, self.n_layers, self._U, self.layer_offsets, self.caps, self.offsets)
 
     def decode(self, ctx: Context, q, k_new=None, v_new=None):
         """q [layers*B,Hq,d], k_new / v_new [layers*B,Hkv,d], layer-major."""
-        tk.taskkv_decode_attn(ctx.handle, self.cfg, q, k_new, v_new, self.k_cache, self.v_cache,
-                              self.capacity, self.offsets, self.lens, self.out)
+        tk.taskkv_decode_attn_layers(ctx.handle, self.cfg0, self.n_layers, q, k_new, v_new, self.k_cache,
+                                     self.v_cache, self.capacity, self.offsets, self.lens, self.out)
         return self.out

@@ -6,13 +6,19 @@
  * the inputs with the seeded generators and checks the outputs against the
  * oracle.
  *
- * usage: taskkv_c_caller DIR
+ * usage: taskkv_c_caller DIR [stack]
  *   DIR/cfg.txt    the sixteen fields of taskkv_layer_cfg in order, then the
  *                  number of tokens to reserve per unit for decoding
  *   DIR/q_win.bin  [B, Hq, L, d]   DIR/k.bin, DIR/v.bin  [B, Hkv, N, d]
  *   DIR/q.bin      [B, Hq, d]      DIR/k_new.bin, DIR/v_new.bin  [B, Hkv, d]
  * writes mask.bin (u8), dist.bin (f64), lens.bin (i32), offsets.bin (i64),
  * kept_idx.bin (i32), out.bin (f32).
+ *
+ * With `stack` it then treats the same tensors as a stack of two layers that
+ * differ in their middle budget (layer 1 keeps half of layer 0's), compresses
+ * both into one cache allocation, has taskkv_stack_rebase write the stack's
+ * offsets and runs one taskkv_decode_attn_layers step for both layers; it
+ * writes out_stack.bin (f32 [2, B, Hq, d]) and lens_stack.bin (i32 [2, B*Hkv]).
  */
 #include <stdio.h>
 #include <stdlib.h>
@@ -76,10 +82,11 @@ static int store(const char *dir, const char *name, const void *dev, size_t byte
 }
 
 int main(int argc, char **argv) {
-  if (argc != 2) {
-    fprintf(stderr, "usage: %s DIR\n", argv[0]);
+  if (argc != 2 && !(argc == 3 && strcmp(argv[2], "stack") == 0)) {
+    fprintf(stderr, "usage: %s DIR [stack]\n", argv[0]);
     return 1;
   }
+  const int with_stack = argc == 3;
   const char *dir = argv[1];
   taskkv_layer_cfg cfg;
   int reserve = 0;
@@ -97,7 +104,20 @@ int main(int argc, char **argv) {
   const size_t row = (size_t)cfg.n_sink + cfg.n_middle + cfg.n_recent;
 
   const int64_t capacity = taskkv_cache_tokens(&cfg, reserve);
-  const size_t ws = taskkv_workspace_bytes(&cfg, reserve);
+  size_t ws = taskkv_workspace_bytes(&cfg, reserve);
+  /* the stacked decode step needs the workspace of a cfg with (layers x B) batch elements */
+  taskkv_layer_cfg cfg_l1 = cfg, cfg_both = cfg;
+  cfg_l1.n_middle = cfg.n_middle / 2;
+  cfg_both.batch = 2 * cfg.batch;
+  const int64_t cap_l1 = taskkv_cache_tokens(&cfg_l1, reserve);
+  if (with_stack) {
+    const size_t ws_both = taskkv_workspace_bytes(&cfg_both, reserve);
+    if (cap_l1 <= 0 || ws_both == 0) {
+      fprintf(stderr, "the library rejects the stacked cfg\n");
+      return 1;
+    }
+    ws = ws_both > ws ? ws_both : ws;
+  }
   if (capacity <= 0 || ws == 0) {
     fprintf(stderr, "the library rejects this cfg\n");
     return 1;
@@ -144,6 +164,46 @@ int main(int argc, char **argv) {
       (row && store(dir, "kept_idx.bin", kept_idx, units * row * sizeof(int32_t))) ||
       store(dir, "out.bin", out, B * Hq * d * sizeof(float)))
     return 1;
+  if (with_stack) {
+    /* two layers in one allocation: layer 0 = cfg, layer 1 = cfg_l1, same input tensors */
+    const int64_t caps[2] = {capacity, cap_l1};
+    const int64_t cap_all = capacity + cap_l1;
+    void *k_all, *v_all, *q2, *kn2, *vn2;
+    int64_t *layer_off, *stack_off;
+    int32_t *lens2, *kept2 = NULL;
+    float *out2;
+    CHECK_HIP(hipMalloc(&k_all, (size_t)cap_all * d * esz));
+    CHECK_HIP(hipMalloc(&v_all, (size_t)cap_all * d * esz));
+    CHECK_HIP(hipMalloc((void **)&layer_off, 2 * (units + 1) * sizeof(int64_t)));
+    CHECK_HIP(hipMalloc((void **)&stack_off, (2 * units + 1) * sizeof(int64_t)));
+    CHECK_HIP(hipMalloc((void **)&lens2, 2 * units * sizeof(int32_t)));
+    if (row) CHECK_HIP(hipMalloc((void **)&kept2, units * row * sizeof(int32_t)));
+    CHECK_HIP(hipMalloc((void **)&out2, 2 * B * Hq * d * sizeof(float)));
+    CHECK_HIP(hipMalloc(&q2, 2 * B * Hq * d * esz));
+    CHECK_HIP(hipMalloc(&kn2, 2 * units * d * esz));
+    CHECK_HIP(hipMalloc(&vn2, 2 * units * d * esz));
+    for (int r = 0; r < 2; ++r) {
+      CHECK_HIP(hipMemcpy((char *)q2 + r * B * Hq * d * esz, q, B * Hq * d * esz, hipMemcpyDeviceToDevice));
+      CHECK_HIP(hipMemcpy((char *)kn2 + r * units * d * esz, k_new, units * d * esz, hipMemcpyDeviceToDevice));
+      CHECK_HIP(hipMemcpy((char *)vn2 + r * units * d * esz, v_new, units * d * esz, hipMemcpyDeviceToDevice));
+    }
+    CHECK_TK(taskkv_compress(ctx, &cfg, k, v, scores, mask, k_all, v_all, capacity, reserve, layer_off, lens2,
+                             kept_idx, stream));
+    CHECK_TK(taskkv_compress(ctx, &cfg_l1, k, v, scores, mask, (char *)k_all + (size_t)capacity * d * esz,
+                             (char *)v_all + (size_t)capacity * d * esz, cap_l1, reserve, layer_off + units + 1,
+                             lens2 + units, kept2, stream));
+    CHECK_TK(taskkv_stack_rebase(ctx, 2, (int32_t)units, layer_off, caps, stack_off, stream));
+    CHECK_TK(taskkv_decode_attn_layers(ctx, &cfg, 2, q2, kn2, vn2, k_all, v_all, cap_all, stack_off, lens2, out2,
+                                       stream));
+    CHECK_HIP(hipStreamSynchronize(stream));
+    if (taskkv_last_async_error(ctx, stream) != 0) {
+      fprintf(stderr, "the device reported an error in the stacked step\n");
+      return 4;
+    }
+    if (store(dir, "out_stack.bin", out2, 2 * B * Hq * d * sizeof(float)) ||
+        store(dir, "lens_stack.bin", lens2, 2 * units * sizeof(int32_t)))
+      return 1;
+  }
   taskkv_destroy(ctx);
   CHECK_HIP(hipStreamDestroy(stream));
   printf("ok: %zu units, cache of %lld tokens, workspace %zu bytes\n", units, (long long)capacity, ws);

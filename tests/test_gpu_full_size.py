@@ -15,7 +15,7 @@ def test_cfg4_mistral_shaped_zipf():
 
 def test_cfg5_load_imbalance_stress():
     # automatic screening, as the benchmark runs it (it is on at this size)
-    run_layer(WORKLOADS["cfg5"], check_batches=(3,), check_steps={0, 63}, screening=1)
+    run_layer(WORKLOADS["cfg5"], check_batches=(3, 6), check_steps={0, 63}, screening=1)
 
 
 @pytest.mark.parametrize("layer", [0, 5])
@@ -36,7 +36,7 @@ def test_cfg3_whole_stack_in_one_call():
     from tests._harness import MIN_MARGIN, OracleCache, check_output, oracle_layer
 
     wl = WORKLOADS["cfg3"]
-    sampled, b_sel, steps = (0, 5), 1, 2
+    sampled, b_sels, steps = (0, 5, 17), (1, 3), 2
     cfgs = [ses.cfg_from_workload(wl, *layer_params(wl, r)) for r in range(wl.n_layers)]
     stack = ses.LayerStack(cfgs, steps)
     B = wl.batch
@@ -47,30 +47,38 @@ def test_cfg3_whole_stack_in_one_call():
             stack.layers[r].separate(ctx, ld.q_win, ld.k, ld.v)
             stack.layers[r].compress(ctx, ld.k, ld.v)
             if r in sampled:
-                refs[r] = oracle_layer(ld, b_sel, cfgs[r])
-                assert refs[r]["margin"] >= MIN_MARGIN
+                for b_sel in b_sels:
+                    refs[r, b_sel] = oracle_layer(ld, b_sel, cfgs[r])
+                    assert refs[r, b_sel]["margin"] >= MIN_MARGIN
             inputs.append([ld.decode_inputs(s) for s in range(steps)])
             del ld
-        stack.rebase()
-        caches = {r: OracleCache(refs[r]) for r in sampled}
+        stack.rebase(ctx)
+        caches = {key: OracleCache(ref) for key, ref in refs.items()}
         for s in range(steps):
             q, kn, vn = (torch.cat([inputs[r][s][j] for r in range(wl.n_layers)]) for j in range(3))
             out = stack.decode(ctx, q, kn, vn)
-            for r in sampled:
-                caches[r].append(to_numpy(kn[r * B + b_sel]), to_numpy(vn[r * B + b_sel]))
-                ref = caches[r].attend(to_numpy(q[r * B + b_sel]))
+            for (r, b_sel), cache in caches.items():
+                cache.append(to_numpy(kn[r * B + b_sel]), to_numpy(vn[r * B + b_sel]))
+                ref = cache.attend(to_numpy(q[r * B + b_sel]))
                 check_output(out[r * B + b_sel].cpu().numpy(), ref, wl.dtype, f"stack layer {r} step {s}")
         assert taskkv_last_async_error(ctx.handle) == 0
         lens = stack.lens.cpu().numpy().reshape(wl.n_layers, B, wl.n_kv_heads)
-        for r in sampled:
-            assert lens[r, b_sel].tolist() == [len(x) + steps for x in refs[r]["kept"]]
+        for (r, b_sel), ref in refs.items():
+            assert lens[r, b_sel].tolist() == [len(x) + steps for x in ref["kept"]]
         # every layer holds the budget of Eq. 17: about 40 % of its full cache
         per_layer = lens.reshape(wl.n_layers, -1).sum(axis=1) - steps * B * wl.n_kv_heads
         assert np.all(np.abs(per_layer / (B * wl.n_kv_heads * wl.ctx_len) - 0.4) < 0.002)
 
 
-@pytest.mark.parametrize("name", ["cfg5", "cfg4"])
-def test_outputs_are_consistent_for_every_unit(name):
+def _stack_layer_with(n_hetero):
+    """First layer of the 32-layer workload that marks this many heads."""
+    from taskkv_synth import layer_params
+    wl = WORKLOADS["cfg3"]
+    return next(r for r in range(wl.n_layers) if layer_params(wl, r)[0] == n_hetero)
+
+
+@pytest.mark.parametrize("name,n_het", [("cfg5", None), ("cfg4", None), ("cfg3", 1), ("cfg3", 2), ("cfg3", 3)])
+def test_outputs_are_consistent_for_every_unit(name, n_het):
     """Properties that hold at any size, checked for every unit of the full
     workload with library routines (the oracle above checks sampled batch
     elements value by value): the mask marks exactly the farthest heads of the
@@ -86,7 +94,8 @@ def test_outputs_are_consistent_for_every_unit(name):
     from taskkv_synth import make_layer
 
     wl = WORKLOADS[name]
-    ld = make_layer(wl, 0, "cuda:0")
+    ld = make_layer(wl, 0 if n_het is None else _stack_layer_with(n_het), "cuda:0")
+    assert n_het is None or ld.n_hetero == n_het
     cfg = ses.cfg_from_workload(wl, ld.n_hetero, ld.n_middle)
     B, H, G, N, d = wl.batch, wl.n_kv_heads, wl.group, wl.ctx_len, wl.head_dim
     s1, s2, k_mid, t = wl.n_sink, wl.n_recent, ld.n_middle, min(wl.top_t, N)

@@ -455,7 +455,7 @@ def test_layer_stack_decode_matches_per_layer_calls():
             for bufs in (a, b):
                 bufs.separate(ctx, ld.q_win, ld.k, ld.v)
                 bufs.compress(ctx, ld.k, ld.v)
-        stack.rebase()
+        stack.rebase(ctx)
         for step in range(wl.decode_steps):
             ins = [ld.decode_inputs(step) for ld in lds]
             ref = torch.cat([a.decode(ctx, *i).clone() for a, i in zip(solo, ins)])
@@ -534,3 +534,71 @@ def test_profiling_changes_no_output_and_times_the_kernel(dtype, ctx_len):
         assert launches == 5 and 0.0 < ms < wall_ms
         assert torch.equal(bufs.decode(ctx, q), plain)
         assert tk.taskkv_profile_read(ctx.handle) == (0.0, 0)
+
+
+def test_mask_with_more_full_heads_than_the_cfg_provides_for():
+    """taskkv_compress takes any mask.  One that marks every head while cfg says
+    none keeps everything does not fit the cache the cfg sizes: the units that
+    do not fit are left empty, flag 2 is raised, and the decode steps that
+    follow (append included) stay inside the buffers and end normally."""
+    import paper_2501_15113_amd as tk
+    ses = _session()
+    wl = small_workload(name="overmask", wid=159, ctx_len=3000, n_hetero=0, batch=2)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    bufs = ses.LayerBuffers(cfg, 2)
+    guard = 4096
+    kc = torch.full((bufs.capacity * wl.head_dim + guard,), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    vc = kc.clone()
+    bufs.k_cache, bufs.v_cache = kc[:bufs.capacity * wl.head_dim], vc[:bufs.capacity * wl.head_dim]
+    with ses.Context([cfg], 2) as ctx:
+        bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+        bufs.mask.fill_(1)
+        bufs.compress(ctx, ld.k, ld.v)
+        assert tk.taskkv_last_async_error(ctx.handle) == 2
+        offs, lens = bufs.offsets.cpu().numpy(), bufs.lens.cpu().numpy()
+        assert offs[-1] <= bufs.capacity and (np.diff(offs) >= 0).all()
+        fits = np.diff(offs) > 0
+        assert fits.any() and not fits.all()
+        assert (lens[fits] == wl.ctx_len).all() and (lens[~fits] == 0).all()
+        for step in range(2):
+            q, kn, vn = ld.decode_inputs(step)
+            out = bufs.decode(ctx, q, kn, vn)
+        torch.cuda.synchronize()
+        assert tk.taskkv_last_async_error(ctx.handle) == 1       # the empty units could not take the token
+        assert torch.isfinite(out).all()
+        lens2 = bufs.lens.cpu().numpy()
+        assert (lens2[fits] == wl.ctx_len + 2).all() and (lens2[~fits] == 0).all()
+        G = wl.group
+        o = out.view(-1, G, wl.head_dim).cpu()
+        assert not o[torch.as_tensor(~fits)].any() and o[torch.as_tensor(fits)].abs().max() > 0
+    # nothing was written past the capacity
+    assert (kc[bufs.capacity * wl.head_dim:] == 7.0).all() and (vc[bufs.capacity * wl.head_dim:] == 7.0).all()
+
+
+def test_compress_rejects_screened_scores_under_another_budget():
+    """Screened scores are exact only where the separator's own selection can
+    decide: compressing them with another middle budget is refused; with
+    screening off the same scores serve any budget."""
+    import paper_2501_15113_amd as tk
+    ses = _session()
+    wl = small_workload(name="rebudget", wid=162, ctx_len=4000, n_middle=100)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    other = ses.cfg_from_workload(wl, n_middle=50)
+    for mode, ok in ((2, False), (0, True)):
+        bufs, bufs2 = ses.LayerBuffers(cfg, 0), ses.LayerBuffers(other, 0)
+        with ses.Context([cfg], 0, screening=mode) as ctx:
+            bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+            bufs2.scores, bufs2.mask = bufs.scores, bufs.mask
+            if ok:
+                bufs2.compress(ctx, ld.k, ld.v)
+                ref = oracle_layer(ld, 0, other)
+                kept = bufs2.kept_idx.cpu().numpy().reshape(wl.batch, wl.n_kv_heads, -1)[0]
+                for h in range(wl.n_kv_heads):
+                    if not ref["mask"][h]:
+                        assert kept[h, :len(ref["kept"][h])].tolist() == ref["kept"][h].tolist()
+            else:
+                with pytest.raises(tk.TaskKVError, match="invalid argument"):
+                    bufs2.compress(ctx, ld.k, ld.v)
+            bufs.compress(ctx, ld.k, ld.v)
