@@ -189,6 +189,33 @@ int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void 
                        const int64_t *offsets, int32_t *lens, float *out, void *hip_stream);
 
 /*
+ * taskkv_decode_attn for callers that cannot allocate and hold no context:
+ * code whose stream is being captured into a HIP graph, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and append rule
+ * as taskkv_decode_attn, without the ctx: the kernels' scratch memory is a
+ * device array of TASKKV_STATIC_SCRATCH_BYTES that is part of the library's
+ * code object (each GPU the library runs on holds it from module load until the
+ * process ends).  The call allocates nothing and synchronises nothing; its
+ * first call on a device looks up the array's address on that device and the
+ * device's properties (make that call outside graph capture).
+ *   async_flag  device pointer to an int32 that receives the sticky condition
+ *               bits of taskkv_last_async_error (bit 1: append to a full unit),
+ *               OR-ed in by the kernels; the caller clears and reads it.  NULL:
+ *               the bits go to a word inside the scratch array and are lost.
+ * Returns TASKKV_EWORKSPACE when the step needs more scratch than the array
+ * holds (taskkv_workspace_bytes of a decode-only use: about
+ * (4096 + B*H_kv) * G * (d + 2) * 4 bytes for bf16 caches), before anything is
+ * enqueued.  The device that is current at the call is used.  All calls on one
+ * GPU share that GPU's array, which keeps the previous call's contents: calls
+ * that overlap in time on one GPU (two streams, two threads) race; calls on
+ * one stream, or ordered by events, do not.
+ */
+#define TASKKV_STATIC_SCRATCH_BYTES (24u << 20)
+int taskkv_decode_attn_static(const taskkv_layer_cfg *cfg, const void *q, const void *k_new, const void *v_new,
+                              void *k_cache, void *v_cache, int64_t capacity_tokens, const int64_t *offsets,
+                              int32_t *lens, float *out, int32_t *async_flag, void *hip_stream);
+
+/*
  * A decode step of a whole stack of layers in one call (the step of Sec. 5.5.3
  * for every layer at once; it serves callers that have all layers' queries at
  * hand, e.g. a benchmark or speculative pipelines -- in an ordinary decoder

@@ -15,6 +15,7 @@ EXPORTED_SYMBOLS = [
     "taskkv_compress", "taskkv_decode_attn", "taskkv_cache_export", "taskkv_last_async_error",
     "taskkv_profile_enable", "taskkv_profile_read", "taskkv_set_screening", "taskkv_set_stream_skew",
     "taskkv_set_stats_engine", "taskkv_stack_rebase", "taskkv_decode_attn_layers",
+    "taskkv_decode_attn_static",
 ]
 
 
@@ -85,6 +86,8 @@ def load_library():
     lib.taskkv_stack_rebase.restype = C.c_int
     lib.taskkv_decode_attn_layers.argtypes = [vp, cfgp, i32, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     lib.taskkv_decode_attn_layers.restype = C.c_int
+    lib.taskkv_decode_attn_static.argtypes = [cfgp, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, vp]
+    lib.taskkv_decode_attn_static.restype = C.c_int
     lib.taskkv_cache_export.argtypes = [vp, cfgp, vp, vp, i64, vp, vp, vp, vp]
     lib.taskkv_cache_export.restype = C.c_int
     lib.taskkv_last_async_error.argtypes = [vp, vp]
@@ -198,6 +201,18 @@ def taskkv_decode_attn(ctx, cfg, q, k_new, v_new, k_cache, v_cache, capacity_tok
         ctx, C.byref(cfg), _ptr(q, e), _ptr(k_new, e, allow_none=True), _ptr(v_new, e, allow_none=True),
         _ptr(k_cache, e), _ptr(v_cache, e), capacity_tokens, _ptr(offsets, torch.int64),
         _ptr(lens, torch.int32), _ptr(out, torch.float32), _stream(stream)), "taskkv_decode_attn")
+
+
+def taskkv_decode_attn_static(cfg, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens, out,
+                              async_flag=None, stream=None) -> None:
+    """taskkv_decode_attn without a ctx: scratch memory is the library's own fixed device array."""
+    import torch
+    e = _elem(cfg)
+    _check(load_library().taskkv_decode_attn_static(
+        C.byref(cfg), _ptr(q, e), _ptr(k_new, e, allow_none=True), _ptr(v_new, e, allow_none=True),
+        _ptr(k_cache, e), _ptr(v_cache, e), capacity_tokens, _ptr(offsets, torch.int64),
+        _ptr(lens, torch.int32), _ptr(out, torch.float32), _ptr(async_flag, torch.int32, allow_none=True),
+        _stream(stream)), "taskkv_decode_attn_static")
 
 
 def taskkv_stack_rebase(ctx, n_layers, units_per_layer, layer_offsets, layer_capacity_tokens, stacked_offsets,

@@ -2,6 +2,7 @@
 // kernel sequencing.  No entry point here synchronises the device or allocates,
 // except create / destroy / last_async_error / profile_read.
 #include <math.h>
+#include <mutex>
 #include <new>
 
 #include "taskkv_internal.h"
@@ -115,6 +116,49 @@ static size_t ws_decode(const Dims &d, int64_t capacity) {
          al(((size_t)d.units + 1) * sizeof(int32_t)) +
          al(stream_table_ints(d) * sizeof(int32_t));   // page prefix, wave range starts, first/last wave of each unit
 }
+
+static int decode_step(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q, const void *k_new,
+                       const void *v_new, void *k_cache, void *v_cache, int64_t capacity_tokens,
+                       const int64_t *offsets, int32_t *lens, float *out, void *hip_stream) {
+  Dims d;
+  if (!ctx || !resolve(cfg, d)) return TASKKV_EINVAL;
+  if (!q || !k_cache || !v_cache || !offsets || !lens || !out) return TASKKV_EINVAL;
+  if ((k_new == nullptr) != (v_new == nullptr)) return TASKKV_EINVAL;
+  if (capacity_tokens <= 0 || capacity_tokens % CHUNK) return TASKKV_EINVAL;
+  if (capacity_tokens / CHUNK > 0x7fffffff) return TASKKV_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
+  const size_t n_slots = decode_slots(d, capacity_tokens);
+  Carver cv(ctx->ws, ctx->ws_bytes);
+  float *pm = cv.take<float>(n_slots * d.G);
+  float *pl = cv.take<float>(n_slots * d.G);
+  float *po = cv.take<float>(n_slots * d.G * d.D);
+  int32_t *eff_len = cv.take<int32_t>((size_t)d.units + 1);
+  int32_t *page_prefix = cv.take<int32_t>(stream_table_ints(d));
+  if (!cv.ok) return TASKKV_EWORKSPACE;
+  if (cfg->dtype == TASKKV_BF16 && d.units <= STREAM_MAX_UNITS)
+    return launch_decode_stream(ctx, d, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens,
+                                eff_len, page_prefix, pm, pl, po, out, s);
+  return launch_decode(ctx, d, cfg->dtype, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets,
+                       lens, eff_len, pm, pl, po, out, s);
+}
+
+
+// ---- state of the entry point that allocates nothing (taskkv_decode_attn_static)
+// Its kernels' scratch -- partial results, per-step tables, the sticky flag --
+// lives in a device array of fixed size that every GPU the library runs on
+// holds from module load to process end.
+constexpr size_t STATIC_SCRATCH_BYTES = TASKKV_STATIC_SCRATCH_BYTES;
+constexpr size_t STATIC_FLAG_BYTES = 256;
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+struct StaticState {
+  bool ready;
+  int *own_flag;     // flag word inside the device's scratch array
+  taskkv_ctx ctx;    // a context whose workspace is the device's scratch array
+};
+static StaticState g_static[STATIC_MAX_DEVICES];
+static std::mutex g_static_mutex;
 
 int profile_harvest(taskkv_ctx *ctx) {
   for (int i = 0; i < ctx->n_events; ++i) {
@@ -333,27 +377,46 @@ int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k,
 int taskkv_decode_attn(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q, const void *k_new,
                        const void *v_new, void *k_cache, void *v_cache, int64_t capacity_tokens,
                        const int64_t *offsets, int32_t *lens, float *out, void *hip_stream) {
-  Dims d;
-  if (!ctx || !resolve(cfg, d)) return TASKKV_EINVAL;
-  if (!q || !k_cache || !v_cache || !offsets || !lens || !out) return TASKKV_EINVAL;
-  if ((k_new == nullptr) != (v_new == nullptr)) return TASKKV_EINVAL;
-  if (capacity_tokens <= 0 || capacity_tokens % CHUNK) return TASKKV_EINVAL;
-  if (capacity_tokens / CHUNK > 0x7fffffff) return TASKKV_EINVAL;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  if (capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
-  const size_t n_slots = decode_slots(d, capacity_tokens);
-  Carver cv(ctx->ws, ctx->ws_bytes);
-  float *pm = cv.take<float>(n_slots * d.G);
-  float *pl = cv.take<float>(n_slots * d.G);
-  float *po = cv.take<float>(n_slots * d.G * d.D);
-  int32_t *eff_len = cv.take<int32_t>((size_t)d.units + 1);
-  int32_t *page_prefix = cv.take<int32_t>(stream_table_ints(d));
-  if (!cv.ok) return TASKKV_EWORKSPACE;
-  if (cfg->dtype == TASKKV_BF16 && d.units <= STREAM_MAX_UNITS)
-    return launch_decode_stream(ctx, d, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens,
-                                eff_len, page_prefix, pm, pl, po, out, s);
-  return launch_decode(ctx, d, cfg->dtype, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets,
-                       lens, eff_len, pm, pl, po, out, s);
+  return decode_step(ctx, cfg, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens, out, hip_stream);
+}
+
+int taskkv_decode_attn_static(const taskkv_layer_cfg *cfg, const void *q, const void *k_new, const void *v_new,
+                              void *k_cache, void *v_cache, int64_t capacity_tokens, const int64_t *offsets,
+                              int32_t *lens, float *out, int32_t *async_flag, void *hip_stream) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return TASKKV_EHIP;
+  // one call at a time builds and uses a device's state (calls that overlap on
+  // one GPU would race on the scratch array anyway)
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticState &st = g_static[dev];
+  if (!st.ready) {
+    // the array's name is a host-side stand-in: its device address on the
+    // current GPU comes from the runtime, once per device
+    unsigned char *ptr = nullptr;
+    if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TASKKV_EHIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return TASKKV_EHIP;
+    taskkv_ctx &c = st.ctx;
+    c.device = dev;
+    c.ws = reinterpret_cast<char *>(ptr) + STATIC_FLAG_BYTES;
+    c.ws_bytes = STATIC_SCRATCH_BYTES - STATIC_FLAG_BYTES;
+    c.d_err = reinterpret_cast<int *>(ptr);   // zero when the module is loaded, like the whole array
+    c.profiling = 0;
+    c.n_events = c.events_created = 0;
+    c.prof_ms = 0.0;
+    c.prof_launches = 0;
+    c.n_cu = prop.multiProcessorCount;
+    c.screening = 1;
+    c.stats_engine = 1;
+    c.stream_skew = STREAM_SKEW_DEFAULT;
+    for (int i = 0; i < 4; ++i) c.stream_wg[i] = 0;
+    c.screened_scores = nullptr;
+    st.own_flag = c.d_err;
+    st.ready = true;
+  }
+  st.ctx.d_err = async_flag ? reinterpret_cast<int *>(async_flag) : st.own_flag;
+  return decode_step(&st.ctx, cfg, q, k_new, v_new, k_cache, v_cache, capacity_tokens, offsets, lens, out,
+                     hip_stream);
 }
 
 int taskkv_stack_rebase(taskkv_ctx *ctx, int32_t n_layers, int32_t units_per_layer, const int64_t *layer_offsets,
