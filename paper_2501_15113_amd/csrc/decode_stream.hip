@@ -52,12 +52,8 @@ struct StreamTables {
   }
 };
 
-#ifndef TASKKV_STREAM_WAVES_PER_SIMD
-#define TASKKV_STREAM_WAVES_PER_SIMD 1
-#endif
-
 template <int D, int NP, bool NT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(TASKKV_STREAM_WAVES_PER_SIMD)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1)))
 void decode_stream_kernel(
     const uint16_t *__restrict__ q, const uint16_t *__restrict__ k_new,
     const uint16_t *__restrict__ v_new, uint4 *kc, uint4 *vc, const int64_t *__restrict__ offsets,
@@ -276,10 +272,6 @@ void decode_stream_kernel(
   flush();
 }
 
-#ifndef TASKKV_COMBINE_UN
-#define TASKKV_COMBINE_UN 4
-#endif
-
 // Merge the partials of one (batch, query head): slots wave + unit for the waves
 // whose page ranges meet the unit.  One block of 1024 threads = NCL slot lanes x
 // D/4 channel lanes; slot lane c owns slots c, c+NCL, ... and requests UN of
@@ -291,7 +283,7 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
     const float *__restrict__ pm, const float *__restrict__ pl, const float *__restrict__ po,
     const int32_t *__restrict__ page_prefix, const int32_t *__restrict__ eff_len,
     int32_t *__restrict__ lens_out, float *__restrict__ out, int n_units, int Hq, int Hkv, int G, int W) {
-  constexpr int DL = D / 4, NCL = 1024 / DL, UN = TASKKV_COMBINE_UN;
+  constexpr int DL = D / 4, NCL = 1024 / DL, UN = 4;
   const int bq = blockIdx.x, tid = threadIdx.x;
   const int b = bq / Hq, hq = bq % Hq, h = hq / G, slot = hq % G;
   const int u = b * Hkv + h;
@@ -374,19 +366,13 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
 // heads, at one wave per SIMD (fitting two waves into the register file costs
 // spills and measured 5 % slower; 3 pages: 1 % slower).  Pages of 64-wide heads are
 // half the size (8 instructions): 3 of them measured 3 % faster than 2 or 4.
-#ifndef TASKKV_STREAM_NP64
-#define TASKKV_STREAM_NP64 3
-#endif
-#ifndef TASKKV_STREAM_NP
-#define TASKKV_STREAM_NP 2
-#endif
+template <int D>
+constexpr int stream_ring_pages() { return D == 64 ? 3 : 2; }
 // Fewest pages worth giving a wave: below this the launch is latency bound and
 // extra waves only add partials for the combine kernel to read (measured on
 // steps of 10-70 MB: 3 is 1-3 % faster than 4; with 2 the kernel itself gains
 // another 1.5 us but the combine kernel loses more).
-#ifndef TASKKV_STREAM_MIN_PAGES
-#define TASKKV_STREAM_MIN_PAGES 3
-#endif
+constexpr int STREAM_MIN_PAGES = 3;
 
 template <int D, bool NT>
 static void run_stream(taskkv_ctx *ctx, const Dims &dm, const uint16_t *q, const uint16_t *kn,
@@ -396,7 +382,7 @@ static void run_stream(taskkv_ctx *ctx, const Dims &dm, const uint16_t *q, const
   const int skew = (n_wg & 1) ? 0 : ctx->stream_skew;
   const dim3 grid(n_wg, (dm.G + 15) / 16), block(256);
   const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
-  launch_attention(ctx, decode_stream_kernel<D, (D == 64 ? TASKKV_STREAM_NP64 : TASKKV_STREAM_NP), NT>, grid, block,
+  launch_attention(ctx, decode_stream_kernel<D, stream_ring_pages<D>(), NT>, grid, block,
                    s, q, kn, vn, kc, vc, offsets, lens, eff_len, page_prefix, ctx->d_err, pm, pl, po, dm.units,
                    dm.Hq, dm.Hkv, dm.G, scale_log2, skew);
   combine_stream_kernel<D><<<dim3(dm.B * dm.Hq), dim3(1024), 0, s>>>(
@@ -414,11 +400,11 @@ int launch_decode_stream(taskkv_ctx *ctx, const Dims &dm, const void *q, const v
     int per_cu = 0;
     hipError_t e;
     if (dm.D == 64)
-      e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, TASKKV_STREAM_NP64, true>, 256, 0)
-             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, TASKKV_STREAM_NP64, false>, 256, 0);
+      e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, stream_ring_pages<64>(), true>, 256, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<64, stream_ring_pages<64>(), false>, 256, 0);
     else
-      e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<128, TASKKV_STREAM_NP, true>, 256, 0)
-             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<128, TASKKV_STREAM_NP, false>, 256, 0);
+      e = nt ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<128, stream_ring_pages<128>(), true>, 256, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_stream_kernel<128, stream_ring_pages<128>(), false>, 256, 0);
     if (e != hipSuccess || per_cu < 1) return TASKKV_EHIP;
     int n = ctx->n_cu * per_cu;
     ctx->stream_wg[variant] = n > STREAM_MAX_WG ? STREAM_MAX_WG : n;
@@ -426,7 +412,7 @@ int launch_decode_stream(taskkv_ctx *ctx, const Dims &dm, const void *q, const v
   int n_wg = ctx->stream_wg[variant];
   {
     // capacity / PAGE bounds the pages of a step from above
-    const int64_t want = (capacity / PAGE + 4 * TASKKV_STREAM_MIN_PAGES - 1) / (4 * TASKKV_STREAM_MIN_PAGES);
+    const int64_t want = (capacity / PAGE + 4 * STREAM_MIN_PAGES - 1) / (4 * STREAM_MIN_PAGES);
     if (want < n_wg) n_wg = want < 1 ? 1 : (int)want;
   }
   // The append is fused when one head slice covers the query group; otherwise
