@@ -119,7 +119,8 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5 (default cfg5: largest context, "
-                    "the load-imbalance stress case)")
+                    "the load-imbalance stress case); llama40 / llama60 / mistral40 / mistral60: 32-layer stacks "
+                    "on the paper's layer schedule at a 40 %% / 60 %% budget")
     ap.add_argument("--layer-batched", action="store_true",
                     help="workloads with several layers: keep all layers' caches in one allocation and "
                          "serve a decode step of the whole stack with one taskkv_decode_attn call")
@@ -164,7 +165,12 @@ def measure(args, workload, with_cpu_baseline, layer_batched, steps, warmup):
     torch.cuda.empty_cache()
     free0, _ = torch.cuda.mem_get_info()
 
-    layers = [make_layer(wl, r, dev) for r in range(wl.n_layers)]
+    plan = [None] * wl.n_layers
+    if wl.schedule is not None:
+        # stacks on the paper's layer schedule: per-layer counts from the library's plan (Eq. 16-17)
+        beta, m_top, frac = wl.schedule
+        plan = tk.taskkv_layer_plan(wl.n_kv_heads, beta, m_top, wl.n_layers, frac, wl.ctx_len, wl.n_sink, wl.n_recent)
+    layers = [make_layer(wl, r, dev, plan=plan[r]) for r in range(wl.n_layers)]
     torch.cuda.synchronize()
     torch.cuda.empty_cache()          # the generators' fp32 temporaries are not part of the path
     cfgs = [session.cfg_from_workload(wl, ld.n_hetero, ld.n_middle) for ld in layers]

@@ -108,6 +108,17 @@ int32_t taskkv_hetero_head_count(int32_t n_heads, double beta, int32_t m_top, in
 int32_t taskkv_middle_budget(int64_t layer_budget_tokens, int32_t ctx_len, int32_t n_heads,
                              int32_t n_hetero, int32_t n_sink, int32_t n_recent);
 
+/* Host only.  The plan of a stack of n_layers layers under one budget (Eq. 16 and
+ * Eq. 17 together, the operating points "KV cache budget 40 % / 60 %" of
+ * Sec. 5.4): every layer may hold B = floor(budget_frac * n_heads * ctx_len)
+ * tokens; layer r marks n_hetero[r] = f(r) heads (Eq. 16 with beta, m_top) and
+ * gives every other head n_middle[r] = k middle activations (Eq. 17 with B,
+ * n_sink, n_recent).  n_heads is the number of heads that are ranked (the KV
+ * heads).  n_hetero, n_middle: host arrays of n_layers entries.  The two
+ * values go into the layers' taskkv_layer_cfg.  budget_frac in [0, 1]. */
+int taskkv_layer_plan(int32_t n_heads, double beta, int32_t m_top, int32_t n_layers, double budget_frac,
+                      int32_t ctx_len, int32_t n_sink, int32_t n_recent, int32_t *n_hetero, int32_t *n_middle);
+
 /*
  * Semantic separator (paper Sec. 4.1, Eq. 12-15, Eq. 7-8, ranking paragraph).
  *   q_win   [B, H_q, L, d]  last L query rows of the prompt (dtype of cfg)

@@ -347,6 +347,20 @@ def hetero_head_count(n_heads, beta, m_top, layer, n_layers):
     return int(min(max(math.floor(f + 0.5), 0), n_heads))
 
 
+def layer_plan(n_heads, beta, m_top, n_layers, budget_frac, ctx_len, n_sink, n_recent):
+    """Sec. 4.1-4.2 put together for a stack of R layers under one budget: every
+    layer gets B = budget_frac * n * N tokens (the "KV cache budget" of Sec. 5.4,
+    a share of the full cache, floored to whole tokens); layer r marks f(r)
+    heads by Eq. 16 and gives each other head k(r) middle activations by Eq. 17.
+    Returns [(f(r), k(r)) for r in 0..R-1]."""
+    budget = int(math.floor(budget_frac * n_heads * ctx_len))
+    plan = []
+    for r in range(n_layers):
+        f = hetero_head_count(n_heads, beta, m_top, r, n_layers)
+        plan.append((f, middle_budget(budget, ctx_len, n_heads, f, n_sink, n_recent)))
+    return plan
+
+
 def middle_budget(layer_budget_tokens, ctx_len, n_heads, n_hetero, n_sink, n_recent):
     """Eq. 17: k = (B - N f(r)) / (n - f(r)) - s1 - s2, floored, clipped at 0."""
     if n_heads == n_hetero:

@@ -9,7 +9,7 @@ from .binding import (LayerCfg, TaskKVError, CHUNK_TOKENS, F32, BF16, PACK_SELEC
                       taskkv_cache_tokens, taskkv_hetero_head_count, taskkv_middle_budget,
                       taskkv_separate, taskkv_compress, taskkv_decode_attn, taskkv_cache_export,
                       taskkv_last_async_error, taskkv_profile_enable, taskkv_profile_read, taskkv_set_screening, taskkv_set_stream_skew, taskkv_set_stats_engine,
-                      taskkv_stack_rebase, taskkv_decode_attn_layers, taskkv_decode_attn_static,
+                      taskkv_stack_rebase, taskkv_decode_attn_layers, taskkv_decode_attn_static, taskkv_layer_plan,
                       EXPORTED_SYMBOLS)
 
 __all__ = [
@@ -19,5 +19,5 @@ __all__ = [
     "taskkv_cache_tokens", "taskkv_hetero_head_count", "taskkv_middle_budget", "taskkv_separate",
     "taskkv_compress", "taskkv_decode_attn", "taskkv_cache_export", "taskkv_last_async_error",
     "taskkv_profile_enable", "taskkv_profile_read", "taskkv_set_screening", "taskkv_set_stream_skew", "taskkv_set_stats_engine", "taskkv_stack_rebase", "taskkv_decode_attn_layers",
-    "taskkv_decode_attn_static", "EXPORTED_SYMBOLS",
+    "taskkv_decode_attn_static", "taskkv_layer_plan", "EXPORTED_SYMBOLS",
 ]

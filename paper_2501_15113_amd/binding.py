@@ -15,7 +15,7 @@ EXPORTED_SYMBOLS = [
     "taskkv_compress", "taskkv_decode_attn", "taskkv_cache_export", "taskkv_last_async_error",
     "taskkv_profile_enable", "taskkv_profile_read", "taskkv_set_screening", "taskkv_set_stream_skew",
     "taskkv_set_stats_engine", "taskkv_stack_rebase", "taskkv_decode_attn_layers",
-    "taskkv_decode_attn_static",
+    "taskkv_decode_attn_static", "taskkv_layer_plan",
 ]
 
 
@@ -76,6 +76,9 @@ def load_library():
     lib.taskkv_hetero_head_count.restype = i32
     lib.taskkv_middle_budget.argtypes = [i64, i32, i32, i32, i32, i32]
     lib.taskkv_middle_budget.restype = i32
+    lib.taskkv_layer_plan.argtypes = [i32, C.c_double, i32, i32, C.c_double, i32, i32, i32, C.POINTER(i32),
+                                      C.POINTER(i32)]
+    lib.taskkv_layer_plan.restype = C.c_int
     lib.taskkv_separate.argtypes = [vp, cfgp] + [vp] * 8
     lib.taskkv_separate.restype = C.c_int
     lib.taskkv_compress.argtypes = [vp, cfgp, vp, vp, vp, vp, vp, vp, i64, i32, vp, vp, vp, vp]
@@ -171,6 +174,14 @@ def taskkv_hetero_head_count(n_heads, beta, m_top, layer, n_layers) -> int:
 def taskkv_middle_budget(layer_budget_tokens, ctx_len, n_heads, n_hetero, n_sink, n_recent) -> int:
     return load_library().taskkv_middle_budget(layer_budget_tokens, ctx_len, n_heads, n_hetero, n_sink,
                                                n_recent)
+
+
+def taskkv_layer_plan(n_heads, beta, m_top, n_layers, budget_frac, ctx_len, n_sink, n_recent):
+    """[(n_hetero, n_middle)] of every layer of a stack under one budget (Eq. 16-17)."""
+    f, k = (C.c_int32 * n_layers)(), (C.c_int32 * n_layers)()
+    _check(load_library().taskkv_layer_plan(n_heads, beta, m_top, n_layers, budget_frac, ctx_len, n_sink,
+                                            n_recent, f, k), "taskkv_layer_plan")
+    return list(zip(list(f), list(k)))
 
 
 def taskkv_separate(ctx, cfg, q_win, k, v, scores, sem_vec, dist, hetero_mask, stream=None) -> None:

@@ -279,6 +279,19 @@ int32_t taskkv_middle_budget(int64_t layer_budget_tokens, int32_t ctx_len, int32
   return (int32_t)(q < 0 ? 0 : q);
 }
 
+int taskkv_layer_plan(int32_t n_heads, double beta, int32_t m_top, int32_t n_layers, double budget_frac,
+                      int32_t ctx_len, int32_t n_sink, int32_t n_recent, int32_t *n_hetero, int32_t *n_middle) {
+  if (n_heads < 1 || n_layers < 1 || ctx_len < 1 || n_sink < 0 || n_recent < 0 || m_top < 0 || !n_hetero || !n_middle)
+    return TASKKV_EINVAL;
+  if (!(beta >= 0.0) || !(budget_frac >= 0.0) || !(budget_frac <= 1.0)) return TASKKV_EINVAL;
+  const int64_t budget = (int64_t)floor(budget_frac * n_heads * ctx_len);
+  for (int r = 0; r < n_layers; ++r) {
+    n_hetero[r] = taskkv_hetero_head_count(n_heads, beta, m_top, r, n_layers);
+    n_middle[r] = taskkv_middle_budget(budget, ctx_len, n_heads, n_hetero[r], n_sink, n_recent);
+  }
+  return TASKKV_OK;
+}
+
 int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_win, const void *k,
                     const void *v, double *scores, double *sem_vec, double *dist,
                     uint8_t *hetero_mask, void *hip_stream) {

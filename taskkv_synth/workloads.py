@@ -45,6 +45,10 @@ class Workload:
     add_centre_head: int = 0
     pool_kernel: int = 1
     offset: float = 6.0
+    # stacks that follow the paper's layer schedule: (beta, m, budget share) of
+    # Sec. 5.4; the per-layer head counts and middle budgets are computed by the
+    # caller (library or oracle) and handed to make_layer
+    schedule: Tuple[float, int, float] = None
 
     @property
     def group(self) -> int:
@@ -73,6 +77,16 @@ WORKLOADS = {
 }
 
 
+# The two settings of Sec. 5.4 (beta = 0.25, m = 4 on the 32-head MHA model; beta = 0.3, m = 1 on the 32/8
+# GQA model; 16 sinks, 256 recent tokens, pooling width 7) at the budgets of Table 1, on a 32-layer stack
+# with a 32768-token prompt (the paper's latency experiment uses 30K tokens).
+for _tag, _hq, _hkv, _beta, _m in (("llama", 32, 32, 0.25, 4), ("mistral", 32, 8, 0.3, 1)):
+    for _pct in (40, 60):
+        WORKLOADS[f"{_tag}{_pct}"] = Workload(f"{_tag}{_pct}", 10 + len(WORKLOADS), 1, _hq, _hkv, 128, 32768, "bf16", 16, 256,
+                                              0, 0, 64, "scaled", n_layers=32, pool_kernel=7,
+                                              schedule=(_beta, _m, _pct / 100.0))
+
+
 def small_workload(name="small", **kw) -> Workload:
     """A reduced workload for parity sweeps; keyword overrides any field."""
     base = dict(name=name, wid=100, batch=2, n_q_heads=8, n_kv_heads=4, head_dim=128,
@@ -84,7 +98,10 @@ def small_workload(name="small", **kw) -> Workload:
 
 def layer_params(wl: Workload, layer: int) -> Tuple[int, int]:
     """(n_hetero, n_middle) of one layer.  Only the 32-layer workload varies:
-    its heterogeneous fraction is drawn U(0.1, 0.4) per layer."""
+    its heterogeneous fraction is drawn U(0.1, 0.4) per layer.  Workloads with a
+    `schedule` take theirs from the caller's plan instead (make_layer's `plan`)."""
+    if wl.schedule is not None:
+        raise ValueError(f"{wl.name}: per-layer counts come from the layer plan of the caller")
     if wl.name != "cfg3":
         return wl.n_hetero, wl.n_middle
     rs = np.random.RandomState(wl.seed * 1000 + layer)
@@ -131,13 +148,14 @@ class LayerData:
         return q.to(dt), kn.to(dt), vn.to(dt)
 
 
-def make_layer(wl: Workload, layer: int = 0, device="cpu", seed_bump: int = 0) -> LayerData:
+def make_layer(wl: Workload, layer: int = 0, device="cpu", seed_bump: int = 0, plan=None) -> LayerData:
     """Prefill-time tensors of one layer.  `seed_bump` selects another draw of
     the same recipe (used when a draw's decision margins are too small to be a
-    well-posed test, see the tests)."""
+    well-posed test, see the tests).  `plan` = (n_hetero, n_middle) of this
+    layer for workloads whose counts follow a layer schedule."""
     B, Hq, Hkv, d, N, L = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ctx_len, wl.obs_window
     G = wl.group
-    n_het, n_mid = layer_params(wl, layer)
+    n_het, n_mid = layer_params(wl, layer) if plan is None else plan
     dev = torch.device(device)
     g = _gen(dev, wl.seed, layer, 1, seed_bump)
 

@@ -46,6 +46,15 @@ def test_budget_helpers_match_oracle():
         assert tk.taskkv_middle_budget(*args) == orc.middle_budget(*args)
 
 
+def test_layer_plan_matches_oracle():
+    for n, beta, m, R, frac, N, s1, s2 in [(32, 0.25, 4, 32, 0.4, 30000, 16, 256), (8, 0.3, 1, 32, 0.6, 32768, 16, 256),
+                                           (8, 0.3, 1, 32, 0.4, 16384, 4, 128), (8, 0.5, 4, 4, 0.4, 1000, 4, 8),
+                                           (4, 0.5, 0, 1, 1.0, 77, 0, 0), (8, 0.3, 1, 7, 0.123, 5001, 3, 9)]:
+        assert tk.taskkv_layer_plan(n, beta, m, R, frac, N, s1, s2) == orc.layer_plan(n, beta, m, R, frac, N, s1, s2)
+    with pytest.raises(tk.TaskKVError):
+        tk.taskkv_layer_plan(8, 0.3, 1, 32, 1.5, 1000, 4, 8)
+
+
 def _cfg(**kw):
     base = dict(batch=2, n_q_heads=8, n_kv_heads=4, head_dim=128, ctx_len=5000, n_sink=4, n_recent=32,
                 n_middle=64, n_hetero=1, dtype=tk.BF16)

@@ -16,6 +16,13 @@ SOURCE = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))
 
 # (what is planted, text in the oracle, replacement); the text must occur once
 MISTAKES = [
+    ("layer plan budgets the whole cache instead of the stated share",
+     "budget = int(math.floor(budget_frac * n_heads * ctx_len))", "budget = int(math.floor(n_heads * ctx_len))"),
+    ("layer plan takes the budget per head",
+     "budget = int(math.floor(budget_frac * n_heads * ctx_len))", "budget = int(math.floor(budget_frac * ctx_len))"),
+    ("layer plan gives every layer the first layer's head count",
+     "f = hetero_head_count(n_heads, beta, m_top, r, n_layers)\n        plan.append",
+     "f = hetero_head_count(n_heads, beta, m_top, 0, n_layers)\n        plan.append"),
     ("causal mask of the window hides the diagonal too",
      "hidden = j > (N - L + i)", "hidden = j >= (N - L + i)"),
     ("query head mapped to its KV head by modulo",

@@ -399,3 +399,23 @@ def test_compressed_cache_groups_and_means():
     b3 = p3[s1:s1 + n].tolist() + [N - s2]
     np.testing.assert_allclose((c32[s1:s1 + n].astype(np.float64) * np.diff(b3)[:, None]).sum(axis=0),
                                k32[s1:N - s2].astype(np.float64).sum(axis=0), rtol=1e-6, atol=1e-6)
+
+
+def test_layer_plan_spends_the_budget_in_every_layer():
+    """Eq. 16 and Eq. 17 together: with f(r) full heads and k(r) middle tokens
+    for each other head a layer holds f N + (n - f)(s1 + s2 + k) tokens, which
+    is the layer budget up to the flooring of Eq. 17 (less than one token per
+    compressed head) -- for the two settings of Sec. 5.4 at both budgets of
+    Table 1, and the head counts run from n*beta down to m."""
+    for n, beta, m in ((32, 0.25, 4), (8, 0.3, 1)):
+        for frac in (0.4, 0.6):
+            N, s1, s2, R = 30000, 16, 256, 32
+            plan = orc.layer_plan(n, beta, m, R, frac, N, s1, s2)
+            assert len(plan) == R
+            assert plan[0][0] == math.floor(n * beta + 0.5) and plan[-1][0] == m
+            assert all(a[0] >= b[0] for a, b in zip(plan, plan[1:]))          # fewer marked heads with depth
+            for f, k in plan:
+                held = f * N + (n - f) * (s1 + s2 + k)
+                assert k > 0 and frac * n * N - (n - f) - 1 < held <= frac * n * N
+    # a budget that the marked heads alone exhaust leaves no middle tokens
+    assert all(k == 0 for _, k in orc.layer_plan(8, 0.5, 4, 4, 0.4, 1000, 4, 8))
