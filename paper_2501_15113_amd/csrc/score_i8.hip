@@ -8,23 +8,27 @@
 // bf16 operands, however, make the dot products exactly computable in
 // integers: an element is +-M * 2^(e - 134) with an 8-bit M.  Every row (of
 // the window and of K) gets its own exponent E = the largest e of the row, and
-// an element is placed on the row's grid as H = M << (e - E + 20), a number
-// below 2^28 (the largest element of the row has its top bit at bit 27).  The
-// signed value S = +-H is cut into the four digits of its two's complement
-// form, three of 0 ... 127 and the signed top one (S >> 21, -128 ... 127), and
+// an element is placed on the row's grid as H = M << (e - E + 22), a number
+// below 2^30.  The signed value S = +-H is cut into four balanced base-256
+// digits, d0 ... d2 in -128 ... 127 and d3 in -64 ... 64 with
+// S = d0 + 256 d1 + 256^2 d2 + 256^3 d3: they are the bytes of
+// (S + 0x00808080) xor 0x00808080 -- two integer instructions per element for
+// all four digits, where shifting and masking each digit out took twelve -- and
 //
-//   sum_c Sq[c] Sk[c] = sum_{a,b} 128^(a+b) sum_c dq_a[c] dk_b[c],
+//   sum_c Sq[c] Sk[c] = sum_{a,b} 256^(a+b) sum_c dq_a[c] dk_b[c],
 //
 // where each inner sum is a v_mfma_i32_32x32x32_i8 contraction with exact
-// int32 accumulation (|sum| <= 4 * 128 * 128 * 127 < 2^23 per class a+b; the 32x32x32
+// int32 accumulation (a class a+b sums at most four digit pairs over d <= 128
+// channels: below 2^23, and 256 x a class plus the next one stays below 2^31
+// because the top digits are at most 64; the 32x32x32
 // shape issues at twice the rate of 16x16x64 on this part: 4.8 against 2.7
 // POP/s measured).  The seven class sums are combined in fp64 by Horner's rule
 // from the top class down (rounding 1e-16) and scaled by the two row factors
-// 2^(E - 154): the logit is then the exact dot product, rounded a few times in
+// 2^(E - 156): the logit is then the exact dot product, rounded a few times in
 // fp64, like the plain fp64 definition.
 //
-// Elements more than 20 binary orders below their row's largest do not fit the
-// window.  They are rare (Gaussian bf16 data has them at a rate of a few 1e-6
+// Elements more than 22 binary orders below their row's largest do not fit the
+// window.  They are rare (Gaussian bf16 data has them at a rate of about 1e-6
 // per element) and handled without approximation.  With x = xh + r (the part
 // inside the window and the remainder),
 //
@@ -60,32 +64,37 @@ __device__ __forceinline__ void bf16_fields(uint32_t b, int &e, int &M, bool &ne
   e = ef ? ef : 1;
   neg = (b & 0x8000u) != 0;
 }
-// Part of an element inside the 28-bit window of a row with exponent E.
+constexpr int I8_SHIFT = 22;               // the largest element of a row has its top bit at bit 29
+constexpr int I8_GRID = 134 + I8_SHIFT;     // an element times 2^(I8_GRID - E) is its integer on the row's grid
+// Part of an element inside the 30-bit window of a row with exponent E.
 __device__ __forceinline__ uint32_t window_part(int M, int e, int E) {
-  const int sh = e - E + 20;   // <= 20
+  const int sh = e - E + I8_SHIFT;   // <= I8_SHIFT
   const uint32_t up = (uint32_t)M << (sh & 31), down = (uint32_t)M >> min(-sh, 31);
   return sh >= 0 ? up : down;   // both computed: no branch per element
 }
 __device__ __forceinline__ bool fits_window(int M, int e, int E) {
-  const int sh = e - E + 20;
+  const int sh = e - E + I8_SHIFT;
   const int back = min(-sh, 31);
   return sh >= 0 || (((uint32_t)M >> back) << back) == (uint32_t)M;
 }
 __device__ __forceinline__ double bf16_to_double(uint32_t b) { return (double)__uint_as_float(b << 16); }
 
-// exp(x) for x <= 0 to a relative 2e-13: x = (256 n + j) ln2 / 256 + r with
-// |r| <= ln2 / 512, exp(x) = 2^n * 2^(j/256) * e^r; 2^(j/256) from a table of
-// 256 doubles, e^r - 1 from three terms (r^4 / 24 < 1.5e-13).  Eleven fp64
-// operations where the library routine takes about twice as many; the row
-// statistics need one exponential per logit, which is what bounds the kernel.
-// Arguments known to be finite need no clamp (any size: a huge negative one
-// ends as 2^(-large) = 0); -inf does, e^-800 underflows to 0.
+// Exponentials of the row statistics.  Logits are kept in units of ln 2 / 256
+// (the factor is folded into the rows' scale factors), so that for an argument
+// x <= 0 in those units  2^(x / 256) = 2^n * 2^(j / 256) * e^(r ln2 / 256)  with
+// 256 n + j = rint(x) and r = x - rint(x), |r| <= 1/2, exact: 2^(j/256) from a
+// table of 256 doubles, e^(r ln2/256) - 1 from three terms (the fourth is below
+// 1.5e-13).  Nine fp64 operations where the library routine takes about twice
+// as many; the row statistics need one exponential per logit, which is what
+// bounds the kernel.  Arguments known to be finite need no clamp (any size: a
+// huge negative one ends as 2^(-large) = 0); -inf does.
 constexpr int EXP_TAB = 256;
+constexpr double EXP_UNITS = 369.3299304675746322841407;   // 256 / ln 2: units per natural unit
 
-// carry * exp(x0) + sum of exp(x[v]) over sixteen arguments, all <= 0, in three
-// sweeps -- range reduction, table reads, polynomial -- so that the seventeen
-// table reads are in flight together instead of each being waited for where
-// it is used.  x0 may be -inf (clamped); CLAMP says whether x[] may be.
+// carry * 2^(x0/256) + sum of 2^(x[v]/256) over sixteen arguments, all <= 0, in
+// three sweeps -- range reduction, table reads, polynomial -- so that the
+// seventeen table reads are in flight together instead of each being waited
+// for where it is used.  x0 may be -inf (clamped); CLAMP says whether x[] may be.
 template <bool CLAMP>
 __device__ __forceinline__ double exp_sum17(double carry, double x0, const double (&x)[16], const double *tab) {
   double r[17];
@@ -93,10 +102,9 @@ __device__ __forceinline__ double exp_sum17(double carry, double x0, const doubl
 #pragma unroll
   for (int v = 0; v < 17; ++v) {
     double xv = v == 16 ? x0 : x[v];
-    if (CLAMP || v == 16) xv = fmax(xv, -800.0);
-    const double kf = rint(xv * 369.3299304675746322841407);   // 256 / ln 2
-    // minus kf * ln2 / 256 in two parts: the high one has 32 significant bits
-    r[v] = fma(kf, -7.453964567463233203210912e-13, fma(kf, -0.00270760617331688990816474, xv));
+    if (CLAMP || v == 16) xv = fmax(xv, -300000.0);   // 2^-1171 = 0
+    const double kf = rint(xv);
+    r[v] = xv - kf;
     ki[v] = (int)kf;
   }
   double y[17];
@@ -105,8 +113,9 @@ __device__ __forceinline__ double exp_sum17(double carry, double x0, const doubl
   __builtin_amdgcn_sched_barrier(0);   // the compiler would otherwise move every read down to its use
 #pragma unroll
   for (int v = 0; v < 17; ++v) {
-    const double q = fma(r[v], 1.66666666666666657415e-01, 0.5) * r[v];
-    r[v] = fma(q, r[v], r[v]);         // e^r - 1
+    // e^(r c) - 1 with c = ln2 / 256: r (c + r (c^2/2 + r c^3/6))
+    const double q = fma(r[v], 3.308302680541371e-09, 3.665565596910106e-06);
+    r[v] = fma(q, r[v], 0.0027076061740622863) * r[v];
   }
   __builtin_amdgcn_sched_barrier(0);
   double sum = 0.0;
@@ -119,27 +128,34 @@ __device__ __forceinline__ double exp_sum17(double carry, double x0, const doubl
 }
 
 // 16 elements (8 dwords of bf16 pairs) -> four 16-byte digit vectors; returns
-// whether every element fits the window.  An element times 2^(154 - E) is below
-// 2^28 in magnitude, so the scaling and the conversion to an integer S (towards
-// zero: the magnitude keeps window_part's bits) are exact float operations, and
-// the element fits when converting back returns the scaled value.  Digits are
-// those of S in two's complement: three of 0 ... 127 and the signed top one,
-// S >> 21 in -128 ... 127, so that S = sum of digit_t 128^t whatever the sign.
+// whether every element fits the window.  An element times 2^(I8_GRID - E) is
+// below 2^30 in magnitude, so the scaling and the conversion to an integer S
+// (towards zero: the magnitude keeps window_part's bits) are exact float
+// operations, and the element fits when converting back returns the scaled
+// value.  The four balanced digits of S are the bytes of
+// (S + 0x00808080) ^ 0x00808080; two rounds of byte permutes turn the four
+// elements' digit bytes into one dword per digit.
 __device__ __forceinline__ bool digits_of(const uint32_t (&w)[8], int E, v4i (&dig)[4]) {
   bool all_fit = true;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) dig[t] = v4i{0, 0, 0, 0};
+  for (int x4 = 0; x4 < 4; ++x4) {
+    uint32_t dd[4];
 #pragma unroll
-  for (int x = 0; x < 16; ++x) {
-    const float val = __uint_as_float((x & 1) ? (w[x >> 1] & 0xffff0000u) : (w[x >> 1] << 16));
-    const float scaled = ldexpf(val, 154 - E);
-    const int S = (int)scaled;
-    all_fit = all_fit && (float)S == scaled;
-    const int sh = 8 * (x & 3);
-    dig[0][x >> 2] |= (S & 127) << sh;
-    dig[1][x >> 2] |= ((S >> 7) & 127) << sh;
-    dig[2][x >> 2] |= ((S >> 14) & 127) << sh;
-    dig[3][x >> 2] |= (int)(((uint32_t)(S >> 21) & 0xffu) << sh);
+    for (int i = 0; i < 4; ++i) {
+      const int x = 4 * x4 + i;
+      const float val = __uint_as_float((x & 1) ? (w[x >> 1] & 0xffff0000u) : (w[x >> 1] << 16));
+      const float scaled = ldexpf(val, I8_GRID - E);
+      const int S = (int)scaled;
+      all_fit = all_fit && (float)S == scaled;
+      dd[i] = (uint32_t)(S + 0x00808080) ^ 0x00808080u;
+    }
+    // byte t of dd[i] -> byte i of digit t (v_perm_b32: selectors 0-3 take bytes of the second operand, 4-7 of the first)
+    const uint32_t a01 = __builtin_amdgcn_perm(dd[1], dd[0], 0x05010400u), b01 = __builtin_amdgcn_perm(dd[1], dd[0], 0x07030602u);
+    const uint32_t a23 = __builtin_amdgcn_perm(dd[3], dd[2], 0x05010400u), b23 = __builtin_amdgcn_perm(dd[3], dd[2], 0x07030602u);
+    dig[0][x4] = (int)__builtin_amdgcn_perm(a23, a01, 0x05040100u);
+    dig[1][x4] = (int)__builtin_amdgcn_perm(a23, a01, 0x07060302u);
+    dig[2][x4] = (int)__builtin_amdgcn_perm(b23, b01, 0x05040100u);
+    dig[3][x4] = (int)__builtin_amdgcn_perm(b23, b01, 0x07060302u);
   }
   return all_fit;
 }
@@ -157,7 +173,7 @@ __device__ __forceinline__ int row_exponent_of(const uint32_t (&w)[8]) {
 
 // Window rows [row0, row0 + R) of every unit -> digit vectors in operand
 // layout qdig[unit][rb][ks][t][lane] (rb: 32-row block, ks: 32 channels), the
-// row factors gq = scale * 2^(E - 126) (that is scale * 2^56 * 2^(E - 182)),
+// row factors gq = (256 / ln 2) * scale * 2^(E - 126) (logits come out in units of ln 2 / 256),
 // and the list of remainders.  One wave per (unit, 32-row block).
 template <int D>
 __global__ __launch_bounds__(64) void q_digits_kernel(const uint16_t *__restrict__ q, v4i *__restrict__ qdig,
@@ -208,7 +224,7 @@ __global__ __launch_bounds__(64) void q_digits_kernel(const uint16_t *__restrict
         bool neg;
         bf16_fields(b, e, M, neg);
         if (fits_window(M, e, E)) continue;
-        const double kept = ldexp((double)window_part(M, e, E), E - 154);
+        const double kept = ldexp((double)window_part(M, e, E), E - I8_GRID);
         const double rem = bf16_to_double(b) - (neg ? -kept : kept);
         const int at = atomicAdd(qcnt + unit, 1);
         if (at < I8_QCAP) {
@@ -221,7 +237,7 @@ __global__ __launch_bounds__(64) void q_digits_kernel(const uint16_t *__restrict
       }
     }
   }
-  if (half == 0) gq[(size_t)unit * dm.Rpad + r] = ldexp(dm.scale, E - 126);
+  if (half == 0) gq[(size_t)unit * dm.Rpad + r] = ldexp(dm.scale * EXP_UNITS, E - 126);
 }
 
 __global__ void zero_i32_kernel(int32_t *p, int n) {
@@ -243,6 +259,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, half = l >> 5;
   const int N = dm.N, NK = dm.n_keys, L = dm.L, R = dm.R, Rpad = dm.Rpad, row0 = dm.row0;
   const int n_rb = Rpad / 32;
+  const double unit_scale = dm.scale * EXP_UNITS;   // logits are kept in units of ln 2 / 256
   const uint16_t *kb = k + (size_t)unit * N * D;
   const double *qdu = qd + (size_t)unit * Rpad * D;
   const int n_tiny_all = qcnt[unit];
@@ -337,7 +354,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
         const int tile = ck >> 5, ks = cseg >> 1, lane = (ck & 31) + 32 * (cseg & 1);
 #pragma unroll
         for (int t = 0; t < 4; ++t) s_dig[buf][tile][ks][t][lane] = dig[t];
-        if (cseg == 0) s_ek[buf][ck] = E - 182;
+        if (cseg == 0) s_ek[buf][ck] = E - (2 * I8_GRID - 126);   // with the row factor: 2^(Eq - I8_GRID) 2^(Ek - I8_GRID)
       }
       // remainders of the elements that do not fit: the wave's own short list,
       // filled lane by lane (no atomics, nothing to reset); a count above the
@@ -354,7 +371,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
             bf16_fields(b, e, M, neg);
             if (fits_window(M, e, E)) continue;
             if (cnt < I8_KCAP) {
-              const double kept = ldexp((double)window_part(M, e, E), E - 154);
+              const double kept = ldexp((double)window_part(M, e, E), E - I8_GRID);
               QTiny ent;
               ent.row = ck;
               ent.c = cseg * 16 + x;
@@ -421,7 +438,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
               for (int t = 0; t < 4; ++t) ka[ks][t] = s_dig[buf][tile][ks][t][l];
           }
           // classes a + b = 6 ... 0: Horner from the top class down, two classes
-          // joined in int32 (|class sum| < 2^23) before every fp64 step.
+          // joined in int32 (256 x a class sum plus the next stays below 2^31) before every fp64 step.
           // (Interleaving the instructions of two classes, so that no two
           // consecutive ones accumulate into the same registers, was measured
           // 4 % slower: the second register block costs more than it hides.)
@@ -456,20 +473,20 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
               if (KZ && QZ && cls == 1) {
                 // classes 1 and 0 are empty
 #pragma unroll
-                for (int v = 0; v < 16; ++v) t16[v] *= 16384.0;
+                for (int v = 0; v < 16; ++v) t16[v] *= 65536.0;
               } else if ((KZ || QZ) && cls == 1) {
                 const v16i hi = class_sum(1, zero);   // class 0 is empty
 #pragma unroll
-                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)(hi[v] * 128));
+                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 65536.0, (double)(hi[v] * 256));
               } else {
-                // the lower class is accumulated on top of 128 x the upper one: one
+                // the lower class is accumulated on top of 256 x the upper one: one
                 // accumulator block instead of two
                 v16i acc = class_sum(cls, zero);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] *= 128;
+                for (int v = 0; v < 16; ++v) acc[v] *= 256;
                 acc = class_sum(cls - 1, acc);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 16384.0, (double)acc[v]);
+                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 65536.0, (double)acc[v]);
               }
             }
           };
@@ -510,7 +527,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
               const int j = jl + 8 * (v >> 2) + (v & 3);
-              if (j < NK) t16[v] += ent.r * dm.scale * bf16_to_double(kb[(size_t)j * D + ent.c]);
+              if (j < NK) t16[v] += ent.r * unit_scale * bf16_to_double(kb[(size_t)j * D + ent.c]);
             }
           }
           // remainders of key elements that did not fit: qh[c] * r
@@ -527,7 +544,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
                   if (q2.row == row && q2.c == ent.c) qh -= q2.r;
                 }
                 const int vv = 4 * (kk >> 3) + (kk & 3);
-                const double add = qh * ent.r * dm.scale;
+                const double add = qh * ent.r * unit_scale;
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
                   if (v == vv) t16[v] += add;
@@ -547,7 +564,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
             }
           }
 #pragma unroll
-          for (int v = 0; v < 16; ++v) t16[v] *= dm.scale;
+          for (int v = 0; v < 16; ++v) t16[v] *= unit_scale;
         }
         // the tile's visible logits join the running statistics at once:
         // seventeen exponentials for sixteen logits, no per-logit selects
@@ -596,11 +613,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   if (have) {
     const double mo = __shfl_xor(m, 32), lo = __shfl_xor(ls, 32);
     const double mn = fmax(m, mo);
-    if (mn > -INFINITY) ls = ls * exp(m - mn) + lo * exp(mo - mn);
+    if (mn > -INFINITY) ls = ls * exp2((m - mn) * (1.0 / 256)) + lo * exp2((mo - mn) * (1.0 / 256));
     m = mn;
     if (half == 0) {
       double *pp = part + ((size_t)unit * gridDim.x + blockIdx.x) * Rpad * 2;
-      pp[2 * row] = m;
+      pp[2 * row] = m * (1.0 / EXP_UNITS);   // back to natural units
       pp[2 * row + 1] = ls;
     }
   }
