@@ -79,25 +79,41 @@ static int64_t cache_tokens(const Dims &d, int reserve) {
 
 static size_t al(size_t b) { return (b + 255) & ~size_t(255); }
 
+// What the screening pass of the separator leaves for the compressor; both
+// carve it first, so it sits at the start of the workspace.
+static size_t ws_screen_state(const Dims &d) {
+  return al((size_t)d.units * d.N * sizeof(int32_t)) +                 // columns to recompute
+         al((size_t)d.units * 2 * sizeof(int32_t)) +                   // their count
+         al((size_t)d.units * MSEL_MAX_SLICES * sizeof(int)) +         // middle columns above the band, per slice
+         al((size_t)d.units * sizeof(int));                            // which units have those counts
+}
+static void carve_screen_state(Carver &cv, const Dims &d, ScreenBufs &scr) {
+  scr.band_idx = cv.take<int32_t>((size_t)d.units * d.N);
+  scr.band_cnt = cv.take<int32_t>((size_t)d.units * 2);
+  scr.above_band = cv.take<int>((size_t)d.units * MSEL_MAX_SLICES);
+  scr.list_ok = cv.take<int>((size_t)d.units);
+}
+
 static size_t ws_separate(const Dims &d) {
   const int n_chunks = score_parts(d);
-  size_t b = 0;
+  size_t b = ws_screen_state(d);
   b += al((size_t)d.units * d.Rpad * d.D * sizeof(double));           // window rows in fp64
   b += al((size_t)d.units * n_chunks * d.Rpad * 2 * sizeof(double));  // per-chunk row stats
   b += al((size_t)d.units * d.Rpad * 2 * sizeof(double));             // row stats
   b += al((size_t)d.units * d.T * sizeof(int32_t));                   // top-t picks
-  b += al((size_t)d.units * d.N * sizeof(int32_t));                   // screening: columns to recompute
-  b += 2 * al((size_t)d.units * sizeof(unsigned long long));          // their count, key norms
+  b += al((size_t)d.units * sizeof(unsigned long long));              // key norms
   b += al((size_t)d.units * d.Rpad * d.D * 4);                        // int8 pass: digits of the window rows
   b += al((size_t)d.units * d.Rpad * sizeof(double));                 //   row factors
   b += al((size_t)d.units * I8_QCAP * sizeof(QTiny));                 //   remainders that do not fit
   b += al((size_t)d.units * sizeof(int32_t));                         //   their count
+  b += msel_workspace_bytes(d);                                       // sliced selections
   return b;
 }
 static size_t ws_compress(const Dims &d, int dtype) {
-  size_t b = d.pool > 1 ? al((size_t)d.units * d.N * sizeof(double)) : 0;
+  size_t b = ws_screen_state(d) + (d.pool > 1 ? al((size_t)d.units * d.N * sizeof(double)) : 0);
   if (d.pack_mode == TASKKV_PACK_COMPRESSED)
     b += 2 * al((size_t)d.units * d.k * d.D * (dtype == TASKKV_F32 ? 4 : 2));
+  b += msel_workspace_bytes(d);
   return b;
 }
 // Partial slots a decode call needs: one per chunk for the chunk-grid kernels,
@@ -130,6 +146,7 @@ static int decode_step(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void 
   if (capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
   const size_t n_slots = decode_slots(d, capacity_tokens);
   Carver cv(ctx->ws, ctx->ws_bytes);
+  ctx->screened_list = 0;   // the workspace is reused
   float *pm = cv.take<float>(n_slots * d.G);
   float *pl = cv.take<float>(n_slots * d.G);
   float *po = cv.take<float>(n_slots * d.G * d.D);
@@ -213,6 +230,7 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
   c->stream_skew = STREAM_SKEW_DEFAULT;
   for (int i = 0; i < 4; ++i) c->stream_wg[i] = 0;
   c->screened_scores = nullptr;
+  c->screened_list = 0;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) {
     delete c;
@@ -301,13 +319,12 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int n_parts = score_parts(d);
   Carver cv(ctx->ws, ctx->ws_bytes);
+  ScreenBufs scr;
+  carve_screen_state(cv, d, scr);
   double *qd = cv.take<double>((size_t)d.units * d.Rpad * d.D);
   double *part = cv.take<double>((size_t)d.units * n_parts * d.Rpad * 2);
   double *stats = cv.take<double>((size_t)d.units * d.Rpad * 2);
   int32_t *top_idx = cv.take<int32_t>((size_t)d.units * d.T);
-  ScreenBufs scr;
-  scr.band_idx = cv.take<int32_t>((size_t)d.units * d.N);
-  scr.band_cnt = cv.take<int32_t>((size_t)d.units * 2);
   scr.knorm = cv.take<unsigned long long>((size_t)d.units);
   scr.mode = ctx->screening;
   scr.n_cu = ctx->n_cu;
@@ -317,18 +334,32 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   i8.qtiny = cv.take<QTiny>((size_t)d.units * I8_QCAP);
   i8.qcnt = cv.take<int32_t>((size_t)d.units);
   i8.prof = ctx;
+  MSelBufs mb;
+  const bool sliced = msel_carve(cv, d, mb);
+  scr.msel = sliced ? &mb : nullptr;
   if (!cv.ok) return TASKKV_EWORKSPACE;
+  ctx->screened_list = 0;
   if (scores_screened(d, cfg->dtype, &scr)) {
     ctx->screened_scores = scores;
-    const int sel[6] = {cfg->ctx_len, cfg->n_sink, cfg->n_recent, cfg->n_middle, cfg->pack_mode, cfg->pool_kernel};
-    for (int i = 0; i < 6; ++i) ctx->screened_sel[i] = sel[i];
+    ctx->screened_list = band_is_sliced(d, &scr) ? 1 : 0;
+    const int sel[8] = {cfg->ctx_len, cfg->n_sink, cfg->n_recent, cfg->n_middle, cfg->pack_mode, cfg->pool_kernel,
+                        cfg->batch, cfg->n_kv_heads};
+    for (int i = 0; i < 8; ++i) ctx->screened_sel[i] = sel[i];
   } else if (ctx->screened_scores == scores) {
     ctx->screened_scores = nullptr;
   }
   int rc = launch_scores(d, cfg->dtype, q_win, k, qd, part, stats, scores, ctx->screening ? &scr : nullptr,
                          ctx->stats_engine ? &i8 : nullptr, s);
   if (rc) return rc;
-  rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, 0, s);
+  // Eq. 14.  After screening, the t best columns are among the listed ones (an
+  // unlisted column is provably below the threshold): a few hundred candidates
+  // instead of N.
+  if (ctx->screening && scores_screened(d, cfg->dtype, &scr))
+    rc = launch_select_listed(d, scores, scr.band_idx, scr.band_cnt, d.T, top_idx, s);
+  else if (sliced && msel_pays(d, ctx->n_cu, 0, d.N, d.T))
+    rc = launch_select_sliced(d, ctx->n_cu, mb, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, s);
+  else
+    rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, 0, nullptr, s);
   if (rc) return rc;
   return launch_semvec_mask(d, cfg->dtype, scores, v, top_idx, sem_vec, dist, hetero_mask, s);
 }
@@ -346,12 +377,17 @@ int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k,
   if (capacity_tokens / PAGE > 0x7fffffff) return TASKKV_EINVAL;
   if (scores == ctx->screened_scores) {
     // screened scores are exact only where the separator's own budget can decide
-    const int sel[6] = {cfg->ctx_len, cfg->n_sink, cfg->n_recent, cfg->n_middle, cfg->pack_mode, cfg->pool_kernel};
-    for (int i = 0; i < 6; ++i)
+    const int sel[8] = {cfg->ctx_len, cfg->n_sink, cfg->n_recent, cfg->n_middle, cfg->pack_mode, cfg->pool_kernel,
+                        cfg->batch, cfg->n_kv_heads};
+    for (int i = 0; i < 8; ++i)
       if (sel[i] != ctx->screened_sel[i]) return TASKKV_EINVAL;
   }
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   Carver cv(ctx->ws, ctx->ws_bytes);
+  ScreenBufs scr;
+  carve_screen_state(cv, d, scr);   // still as the separator left it, if this call follows it
+  const bool from_band = scores == ctx->screened_scores && ctx->screened_list;
+  ctx->screened_list = 0;           // the rest of the workspace is reused below
   const double *sel_scores = scores;
   int rc = TASKKV_OK;
   if (d.pool > 1 && d.pack_mode == TASKKV_PACK_SELECTIVE) {
@@ -373,8 +409,18 @@ int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k,
     // score (count 0) and get sinks + recent from the same kernel
     const int count = d.pack_mode == TASKKV_PACK_SELECTIVE ? d.k : 0;
     const int gap = d.pack_mode == TASKKV_PACK_COMPRESSED ? d.k : 0;  // filled with group positions below
-    rc = launch_select(d, sel_scores, hetero_mask, d.s1, d.N - d.s2, count, d.s1, gap, d.s2, kept_idx,
-                       d.row_stride, d.keep_all, s);
+    MSelBufs mb;
+    const bool sliced = msel_carve(cv, d, mb);
+    if (!cv.ok) return TASKKV_EWORKSPACE;
+    if (sliced && from_band && d.pool == 1 && !d.keep_all && msel_pays(d, ctx->n_cu, d.s1, d.N - d.s2, count))
+      rc = launch_select_from_band(d, ctx->n_cu, mb, sel_scores, hetero_mask, scr.band_idx, scr.band_cnt,
+                                   scr.above_band, scr.list_ok, kept_idx, s);
+    else if (sliced && !d.keep_all && msel_pays(d, ctx->n_cu, d.s1, d.N - d.s2, count))
+      rc = launch_select_sliced(d, ctx->n_cu, mb, sel_scores, hetero_mask, d.s1, d.N - d.s2, count, d.s1, gap, d.s2,
+                                kept_idx, d.row_stride, s);
+    else
+      rc = launch_select(d, sel_scores, hetero_mask, d.s1, d.N - d.s2, count, d.s1, gap, d.s2, kept_idx,
+                         d.row_stride, d.keep_all, nullptr, s);
     if (rc) return rc;
   }
   if (comp_k) {
@@ -424,6 +470,7 @@ int taskkv_decode_attn_static(const taskkv_layer_cfg *cfg, const void *q, const 
     c.stream_skew = STREAM_SKEW_DEFAULT;
     for (int i = 0; i < 4; ++i) c.stream_wg[i] = 0;
     c.screened_scores = nullptr;
+    c.screened_list = 0;
     st.own_flag = c.d_err;
     st.ready = true;
   }

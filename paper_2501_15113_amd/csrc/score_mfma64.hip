@@ -398,7 +398,11 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     // part in a decision (any number of them: the grid covers all N)
     int rc = launch_screen(dm, q_win, k, stats, scores, cpw, s);
     if (rc) return rc;
-    rc = launch_band(dm, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt, s);
+    if (band_is_sliced(dm, scr))
+      rc = launch_band_sliced(dm, scr->n_cu, *scr->msel, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt,
+                              scr->above_band, scr->list_ok, s);
+    else
+      rc = launch_band(dm, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt, nullptr, nullptr, s);
     if (rc) return rc;
     // The listed columns of a unit make about twenty 16-key tasks of some ten
     // microseconds each (a chain of dependent loads, 64 fp64 matrix instructions,
@@ -416,6 +420,10 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
 // Whether the column means of this layer go through the fp32 screening pass:
 // it pays once the fp64 column pass is large compared with the extra launches
 // (mode 1 = decide here, 2 = whenever possible).
+bool band_is_sliced(const Dims &dm, const ScreenBufs *scr) {
+  return scr != nullptr && scr->msel != nullptr && msel_pays(dm, scr->n_cu, 0, dm.N, dm.T);
+}
+
 bool scores_screened(const Dims &dm, int dtype, const ScreenBufs *scr) {
   const int n_groups = (dm.Rtot + ROW_GROUP - 1) / ROW_GROUP;
   const bool big = (double)dm.units * dm.Rtot * dm.N >= 3e7;   // measured: loses at 8e6, wins at 7e7

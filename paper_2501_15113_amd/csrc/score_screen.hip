@@ -22,6 +22,7 @@
 // 2e-5 + R * 1.2e-7.  band_kernel evaluates the bound from the measured norms.
 #include <math.h>
 
+#include "band_common.h"
 #include "lane_ops.h"
 #include "select_common.h"
 
@@ -195,59 +196,27 @@ __global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ s
                                                     const double *__restrict__ qd,
                                                     const unsigned long long *__restrict__ knorm,
                                                     int32_t *__restrict__ band_idx,
-                                                    int32_t *__restrict__ band_cnt, Dims dm) {
-  const int unit = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int N = dm.N, D = dm.D;
+                                                    int32_t *__restrict__ band_cnt, Dims dm,
+                                                    const int *__restrict__ only_flagged,
+                                                    int *__restrict__ sliced_ok) {
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  if (only_flagged && !only_flagged[unit]) return;
+  if (sliced_ok && tid == 0) sliced_ok[unit] = 0;   // this unit's list has no per-slice counts
+  const int N = dm.N;
   const double *sc = scores + (size_t)unit * N;
   __shared__ RadixScratch rs;
   __shared__ int s_cnt[32];
   __shared__ double s_q[16];
 
-  // largest squared norm of a window row
-  double qmax = 0.0;
-  for (int r0 = wv; r0 < dm.R; r0 += 16 * 8) {
-    // eight rows of the wave at a time: sixteen loads in flight, not two
-    double e[8][2];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = r0 + 16 * i;
-      const double *row = qd + ((size_t)unit * dm.Rpad + (r < dm.R ? r : r0)) * D;
-      e[i][0] = row[lane];
-      e[i][1] = D > 64 ? row[64 + lane] : 0.0;
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      double ss = fma(e[i][0], e[i][0], e[i][1] * e[i][1]);
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-      qmax = fmax(qmax, ss);   // a row past R repeats row r0
-    }
-  }
-  if (lane == 0) s_q[wv] = qmax;
-  __syncthreads();
-  qmax = 0.0;
-  for (int i = 0; i < 16; ++i) qmax = fmax(qmax, s_q[i]);
+  const double qmax = max_row_norm2(qd, unit, dm, s_q);
   const double kmax = __longlong_as_double((long long)knorm[unit]);
-  const double gamma = 4.0 * D * 5.9604644775390625e-08;   // 4 d 2^-24
-  const double eps = dm.scale * gamma * sqrt(qmax) * sqrt(kmax) + 2e-5 + dm.R * 1.2e-7;
-  const double w3 = 3.0 * eps;
-
   int unused;
   const double tau_t = __longlong_as_double((long long)radix_threshold(sc, 0, N, dm.T, rs, unused));
-  const bool middle = dm.pack_mode == TASKKV_PACK_SELECTIVE && !dm.keep_all && dm.k > 0 &&
-                      dm.k < N - dm.s1 - dm.s2;
   double tau_k = 0.0;
-  if (middle)
+  if (band_has_middle(dm))
     tau_k = __longlong_as_double((long long)radix_threshold(sc, dm.s1, N - dm.s2, dm.k, rs, unused));
-  // values below 1e-30 may have been flushed to zero by the fp32 pass: treat them as ties
-  const double lo_t = w3 >= 1.0 ? -1.0 : tau_t * (1.0 - w3) - 1e-30;
-  const double lo_k = w3 >= 1.0 ? -1.0 : tau_k * (1.0 - w3) - 1e-30, hi_k = w3 >= 1.0 ? INFINITY : tau_k * (1.0 + w3) + 1e-30;
-
-  const int listed = list_ascending(sc, 0, N, 0, band_idx + (size_t)unit * N, s_cnt, [&](int j, double x) {
-    bool in = x >= lo_t;
-    if (middle && j >= dm.s1 && j < N - dm.s2) in = in || (x >= lo_k && x <= hi_k);
-    return in ? 1 : 0;
-  });
+  const InBand band = band_limits(dm, qmax, kmax, tau_t, tau_k);
+  const int listed = list_ascending(sc, 0, N, 0, band_idx + (size_t)unit * N, s_cnt, band);
   if (tid == 0) band_cnt[unit] = listed;
 }
 
@@ -318,8 +287,9 @@ int launch_screen(const Dims &dm, const void *q_win, const void *k, const double
 }
 
 int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
-                int32_t *band_idx, int32_t *band_cnt, hipStream_t s) {
-  band_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, band_idx, band_cnt, dm);
+                int32_t *band_idx, int32_t *band_cnt, const int *only_flagged, int *sliced_ok, hipStream_t s) {
+  band_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, band_idx, band_cnt, dm, only_flagged,
+                                                   sliced_ok);
   return hip_ok(hipGetLastError());
 }
 

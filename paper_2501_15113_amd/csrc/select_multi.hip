@@ -1,0 +1,613 @@
+// The selections of select.hip and the band of score_screen.hip with a unit's
+// scores cut into slices that several blocks sweep at once.
+//
+// A sweep over the scores of all units is a pass over up to 64 MB; with one
+// block per unit a selection takes six to eight of them, each at the speed of
+// 8-64 blocks.  Here every phase is a kernel of S blocks per unit, a selection
+// reads the scores three times (four when they crowd into few bins), and both
+// thresholds of the band come out of the same reads:
+//   clear    the per-unit histograms and counters;
+//   hist1    12-bit digit histogram (bits 48-59 of the fp64 pattern: sixteen
+//            bins per octave over [2^-255, 2), anything smaller in bin 0,
+//            anything larger in bin 4095) of a slice, added to the unit's;
+//   hist2    only where the bin that holds the wanted rank has more entries
+//            than the candidate list takes: histogram of the next twelve bits
+//            of that bin's entries;
+//   gather   every block finds the wanted bin from the unit's histograms,
+//            appends its slice's entries of that bin (pattern and position) to
+//            the unit's candidate list and counts its entries in higher bins;
+//   settle   one block per unit settles the remaining digits on the candidate
+//            list -> threshold pattern and how many entries equal to it are
+//            taken; the candidates' positions give every slice's share;
+//   write    every block lists its slice's picks behind those of the slices
+//            before it (ascending positions, ties to the lower index).
+// The band's list is written slice by slice into the row and closed up by one
+// more small kernel, which saves a counting pass.
+// Results do not depend on the order in which blocks run: histograms and
+// candidate lists are only counted, never read in order.  A unit whose wanted
+// rank falls into one of the two mixed end bins, or whose wanted bin still
+// holds too many entries after the second digit (thousands of equal scores),
+// is flagged and redone by the one-block kernel afterwards.
+#include <math.h>
+
+#include "band_common.h"
+#include "select_common.h"
+
+namespace taskkv {
+
+// View of a list of fp64 bit patterns as scores.
+struct KeyArray {
+  const unsigned long long *k;
+  __device__ __forceinline__ double operator[](int j) const { return __longlong_as_double((long long)k[j]); }
+};
+__device__ __forceinline__ int position_of(const KeyArray &, int j) { return j; }
+
+// Entries per slice when [0, N) is cut into S slices (whole rounds of 64).
+__host__ __device__ __forceinline__ int slice_len(int N, int S) { return (((N + S - 1) / S) + 63) & ~63; }
+__device__ __forceinline__ void slice_of(int N, int s, int S, int &a, int &b) {
+  const int seg = slice_len(N, S);
+  a = min(N, s * seg);
+  b = min(N, a + seg);
+}
+
+__device__ __forceinline__ size_t counts_at(int unit, int s) { return ((size_t)unit * MSEL_MAX_SLICES + s) * 2; }
+__device__ __forceinline__ size_t hist_at(int level, int sel, int unit, int units) {
+  return ((size_t)(level * 2 + sel) * units + unit) * 4096;
+}
+
+// Scores a thread holds per round of a slice's sweep: a slice of the named
+// workloads is one round, and its loads are issued before the block's
+// preparations (clearing LDS, looking up the wanted bin) so that both overlap.
+constexpr int SLICE_U = 16;
+
+constexpr unsigned long long DIGIT1_BASE = 0x3000ull;   // leading 16 bits of 2^-255
+__device__ __forceinline__ int digit1(uint64_t key) {
+  const long long d = (long long)(key >> 48) - (long long)DIGIT1_BASE;
+  return d < 0 ? 0 : (d > 4095 ? 4095 : (int)d);
+}
+__device__ __forceinline__ int digit2(uint64_t key) { return (int)(key >> 36) & 4095; }
+
+// LDS of a block that looks up a wanted bin.
+struct PickScratch {
+  unsigned hist12[4096];
+  int wsum[16];
+  int bin, rem;
+};
+
+// What a unit's histograms say about one selection: the digits of the wanted
+// entry known so far, its rank among the entries that share them and how many
+// those are.  Every block of the unit derives the same answer.
+struct Wanted {
+  uint64_t pat, known;
+  int rem, n;
+  bool redo;     // leave the unit to the one-block kernel
+  bool level2;   // the second digit is needed (and, after hist2, known)
+};
+
+// Level 1 only.  All 1024 threads; ps is overwritten.
+__device__ __forceinline__ Wanted wanted_level1(const MSelBufs &mb, int sel, int unit, int units, PickScratch &ps) {
+  const int tid = threadIdx.x;
+  __syncthreads();
+  const unsigned *h = mb.hist + hist_at(0, sel, unit, units);
+  for (int i = tid; i < 4096; i += 1024) ps.hist12[i] = h[i];
+  __syncthreads();
+  pick_bin12(ps, mb.count[sel]);
+  Wanted w;
+  const int bin = ps.bin;
+  w.n = (int)ps.hist12[bin];
+  w.rem = ps.rem;
+  w.pat = (DIGIT1_BASE + (unsigned long long)bin) << 48;
+  w.known = 0xffffull << 48;
+  w.redo = bin == 0 || bin == 4095 || w.n == 0;
+  w.level2 = !w.redo && w.n > MSEL_CAND;
+  return w;
+}
+
+// Both levels.
+__device__ __forceinline__ Wanted wanted_bin(const MSelBufs &mb, int sel, int unit, int units, PickScratch &ps) {
+  Wanted w = wanted_level1(mb, sel, unit, units, ps);
+  if (!w.level2) return w;   // the same in every thread
+  const int tid = threadIdx.x;
+  __syncthreads();
+  const unsigned *h = mb.hist + hist_at(1, sel, unit, units);
+  for (int i = tid; i < 4096; i += 1024) ps.hist12[i] = h[i];
+  __syncthreads();
+  pick_bin12(ps, w.rem);
+  const int bin = ps.bin;
+  w.n = (int)ps.hist12[bin];
+  w.rem = ps.rem;
+  w.pat |= (unsigned long long)bin << 36;
+  w.known |= 0xfffull << 36;
+  w.redo = w.n == 0 || w.n > MSEL_CAND;
+  return w;
+}
+
+__global__ void msel_clear_kernel(MSelBufs mb, int units) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (size_t)4 * units * 4096) mb.hist[i] = 0u;
+  if (i < (size_t)2 * units) mb.n_cand[i] = 0;
+  if (i < (size_t)units) mb.flag[i] = 0;
+}
+
+__global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restrict__ scores,
+                                                          const uint8_t *__restrict__ skip, MSelBufs mb, int N) {
+  const int s = blockIdx.x, unit = blockIdx.y, units = gridDim.y, tid = threadIdx.x;
+  if (skip && skip[unit]) return;
+  const double *sc = scores + (size_t)unit * N;
+  int a, b;
+  slice_of(N, s, mb.S, a, b);
+  if (a >= b) return;
+  __shared__ unsigned h[2][4096];
+  const bool two = mb.nsel > 1;
+  for (int j0 = a; j0 < b; j0 += SLICE_U * 1024) {
+    uint64_t key[SLICE_U];
+#pragma unroll
+    for (int r = 0; r < SLICE_U; ++r) key[r] = score_key(sc[min(j0 + r * 1024 + tid, b - 1)]);
+    if (j0 == a) {   // with the first loads in flight
+      for (int i = tid; i < 2 * 4096; i += 1024) h[0][i] = 0;
+      __syncthreads();
+    }
+#pragma unroll
+    for (int r = 0; r < SLICE_U; ++r) {
+      const int j = j0 + r * 1024 + tid;
+      if (j < b) {
+        const int d = digit1(key[r]);
+        if (j >= mb.lo[0] && j < mb.hi[0]) atomicAdd(&h[0][d], 1u);
+        if (two && j >= mb.lo[1] && j < mb.hi[1]) atomicAdd(&h[1][d], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  for (int sel = 0; sel < mb.nsel; ++sel) {
+    unsigned *g = mb.hist + hist_at(0, sel, unit, units);
+    for (int i = tid; i < 4096; i += 1024)
+      if (h[sel][i]) atomicAdd(&g[i], h[sel][i]);
+  }
+}
+
+__global__ __launch_bounds__(1024) void msel_hist2_kernel(const double *__restrict__ scores,
+                                                          const uint8_t *__restrict__ skip, MSelBufs mb, int N) {
+  const int s = blockIdx.x, unit = blockIdx.y, units = gridDim.y, tid = threadIdx.x;
+  if (skip && skip[unit]) return;
+  __shared__ PickScratch ps;
+  __shared__ unsigned h[2][4096];
+  Wanted w[2];
+  w[0] = wanted_level1(mb, 0, unit, units, ps);
+  w[1] = w[0];
+  w[1].level2 = false;
+  if (mb.nsel > 1) w[1] = wanted_level1(mb, 1, unit, units, ps);
+  // a unit that will be redone anyway needs no second digit
+  if (w[0].redo || (mb.nsel > 1 && w[1].redo) || (!w[0].level2 && !w[1].level2)) return;
+  const double *sc = scores + (size_t)unit * N;
+  int a, b;
+  slice_of(N, s, mb.S, a, b);
+  if (a >= b) return;
+  for (int i = tid; i < 2 * 4096; i += 1024) h[0][i] = 0;
+  __syncthreads();
+  for (int j0 = a; j0 < b; j0 += SWEEP_U * 1024) {
+    uint64_t key[SWEEP_U];
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) key[r] = score_key(sc[min(j0 + r * 1024 + tid, b - 1)]);
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) {
+      const int j = j0 + r * 1024 + tid;
+      if (j < b) {
+#pragma unroll
+        for (int sel = 0; sel < 2; ++sel)
+          if (w[sel].level2 && j >= mb.lo[sel] && j < mb.hi[sel] && (key[r] & w[sel].known) == w[sel].pat)
+            atomicAdd(&h[sel][digit2(key[r])], 1u);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int sel = 0; sel < 2; ++sel) {
+    if (sel >= mb.nsel || !w[sel].level2) continue;
+    unsigned *g = mb.hist + hist_at(1, sel, unit, units);
+    for (int i = tid; i < 4096; i += 1024)
+      if (h[sel][i]) atomicAdd(&g[i], h[sel][i]);
+  }
+}
+
+__global__ __launch_bounds__(1024) void msel_gather_kernel(const double *__restrict__ scores,
+                                                           const uint8_t *__restrict__ skip, MSelBufs mb, int N) {
+  const int s = blockIdx.x, unit = blockIdx.y, units = gridDim.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  if (skip && skip[unit]) return;
+  __shared__ PickScratch ps;
+  __shared__ int s_w[16];
+  __shared__ int s_base;
+  const double *sc = scores + (size_t)unit * N;
+  const uint64_t below = (1ull << lane) - 1ull;
+  int a, b;
+  slice_of(N, s, mb.S, a, b);
+  Wanted w[2];
+  int above = 0;   // entries of selection 0 in higher bins, counted per wave
+  for (int j0 = a; j0 < b; j0 += SLICE_U * 1024) {
+    const int jw = j0 + wv * 64 * SLICE_U;
+    uint64_t key[SLICE_U];
+#pragma unroll
+    for (int r = 0; r < SLICE_U; ++r) key[r] = score_key(sc[min(jw + 64 * r + lane, b - 1)]);
+    if (j0 == a) {   // with the first loads in flight
+      w[0] = wanted_bin(mb, 0, unit, units, ps);
+      w[1] = w[0];
+      if (mb.nsel > 1) w[1] = wanted_bin(mb, 1, unit, units, ps);
+      if (w[0].redo || w[1].redo) {   // the same for every block of the unit
+        if (s == 0 && tid == 0) mb.flag[unit] = 1;
+        return;
+      }
+      if (s == 0 && tid == 0) {
+#pragma unroll
+        for (int sel = 0; sel < 2; ++sel) {
+          if (sel >= mb.nsel) break;
+          mb.take[sel * units + unit] = w[sel].rem;
+          mb.wpat[sel * units + unit] = w[sel].pat;
+          mb.wshift[sel * units + unit] = w[sel].level2 ? 24 : 36;
+        }
+      }
+    }
+#pragma unroll
+    for (int sel = 0; sel < 2; ++sel) {
+      if (sel >= mb.nsel) break;
+      const size_t su = (size_t)sel * units + unit;
+      uint64_t hit[SLICE_U];
+      int n_hit = 0;
+#pragma unroll
+      for (int r = 0; r < SLICE_U; ++r) {
+        const int j = jw + 64 * r + lane;
+        const bool in = j < b && j >= mb.lo[sel] && j < mb.hi[sel];
+        const uint64_t part = key[r] & w[sel].known;
+        hit[r] = __ballot(in && part == w[sel].pat);
+        n_hit += __popcll(hit[r]);
+        if (sel == 0) above += __popcll(__ballot(in && part > w[0].pat));
+      }
+      __syncthreads();   // s_w, s_base may still be read from the round before
+      if (lane == 0) s_w[wv] = n_hit;
+      __syncthreads();
+      if (tid == 0) {
+        int tot = 0;
+        for (int i = 0; i < 16; ++i) tot += s_w[i];
+        s_base = tot ? atomicAdd(&mb.n_cand[su], tot) : 0;   // one atomic per block and round
+      }
+      __syncthreads();
+      int at = s_base;
+      for (int i = 0; i < wv; ++i) at += s_w[i];
+#pragma unroll
+      for (int r = 0; r < SLICE_U; ++r) {
+        if ((hit[r] >> lane) & 1ull) {
+          const size_t p = su * MSEL_CAND + at + __popcll(hit[r] & below);
+          mb.cand_key[p] = key[r];
+          mb.cand_idx[p] = jw + 64 * r + lane;
+        }
+        at += __popcll(hit[r]);
+      }
+    }
+  }
+  __syncthreads();
+  if (lane == 0) s_w[wv] = above;
+  __syncthreads();
+  if (tid == 0) {
+    int tot = 0;
+    for (int i = 0; i < 16; ++i) tot += s_w[i];
+    mb.n_above[(size_t)unit * MSEL_MAX_SLICES + s] = tot;
+  }
+}
+
+// Threshold of one selection of a unit from its candidate list: the pattern of
+// the wanted entry and how many entries equal to it are taken.  The list's
+// entries share their leading digits; the others are settled in LDS.  All 1024
+// threads.
+__device__ __forceinline__ uint64_t settle(const MSelBufs &mb, size_t su, RadixScratch &rs, int &take_equal) {
+  const KeyArray view{mb.cand_key + su * MSEL_CAND};
+  const int shift = mb.wshift[su], n = mb.n_cand[su];
+  return radix_finish(view, 0, n, rs, mb.wpat[su], ~0ull << (shift + 12), shift, mb.take[su], n, take_equal);
+}
+
+// One block per unit and threshold.  Selection: the threshold, and the picks
+// of every slice (entries in higher bins + candidates above / at the
+// threshold).  Band: the threshold, and with the first one the largest squared
+// norm of a window row.
+template <bool BAND>
+__global__ __launch_bounds__(1024) void msel_settle_kernel(const uint8_t *__restrict__ skip, MSelBufs mb, Dims dm,
+                                                           const double *__restrict__ qd) {
+  const int unit = blockIdx.x, units = gridDim.x, sel = blockIdx.y, tid = threadIdx.x;
+  if ((skip && skip[unit]) || mb.flag[unit]) return;
+  __shared__ RadixScratch rs;
+  int take_equal;
+  const uint64_t pat = settle(mb, (size_t)sel * units + unit, rs, take_equal);
+  if (!BAND) {
+    __shared__ int c[2 * MSEL_MAX_SLICES];
+    if (tid < 2 * MSEL_MAX_SLICES) c[tid] = 0;
+    __syncthreads();
+    const int seg = slice_len(dm.N, mb.S), n = mb.n_cand[unit];
+    for (int i = tid; i < n; i += 1024) {
+      const uint64_t key = mb.cand_key[(size_t)unit * MSEL_CAND + i];
+      const int sl = mb.cand_idx[(size_t)unit * MSEL_CAND + i] / seg;
+      if (key > pat) atomicAdd(&c[sl], 1);
+      else if (key == pat) atomicAdd(&c[MSEL_MAX_SLICES + sl], 1);
+    }
+    __syncthreads();
+    if (tid < mb.S) {
+      mb.counts[counts_at(unit, tid)] = mb.n_above[(size_t)unit * MSEL_MAX_SLICES + tid] + c[tid];
+      mb.counts[counts_at(unit, tid) + 1] = c[MSEL_MAX_SLICES + tid];
+    }
+    if (tid == 0) {
+      mb.pat[unit] = pat;
+      mb.take_final[unit] = take_equal;
+    }
+  } else {
+    if (tid == 0) mb.band[(size_t)sel * units + unit] = __longlong_as_double((long long)pat);
+    if (sel == 0) {
+      __shared__ double s_q[16];
+      const double qmax = max_row_norm2(qd, unit, dm, s_q);
+      if (tid == 0) mb.band[(size_t)2 * units + unit] = qmax;
+    }
+  }
+}
+
+// 1 = above the threshold, 2 = equal to it.
+struct AboveOrAt {
+  uint64_t pat;
+  __device__ __forceinline__ int operator()(int, double x) const {
+    const uint64_t key = score_key(x);
+    return key > pat ? 1 : (key == pat ? 2 : 0);
+  }
+};
+
+// Row layout as select_kernel writes it: [0, prefix) ++ picks ++ gap ++ [N - suffix, N) ++ -1 padding.
+__global__ __launch_bounds__(1024) void msel_write_kernel(const double *__restrict__ scores,
+                                                          const uint8_t *__restrict__ skip, MSelBufs mb, int N,
+                                                          int prefix, int gap, int suffix, int32_t *__restrict__ out,
+                                                          int out_stride) {
+  const int s = blockIdx.x, unit = blockIdx.y, tid = threadIdx.x;
+  int32_t *orow = out + (size_t)unit * out_stride;
+  if (skip && skip[unit]) {
+    if (s == 0)
+      for (int i = tid; i < out_stride; i += 1024) orow[i] = -1;
+    return;
+  }
+  if (mb.flag[unit]) return;
+  __shared__ int s_cnt[32];
+  int base1 = 0, base2 = 0;
+  for (int x = 0; x < s; ++x) {
+    base1 += mb.counts[counts_at(unit, x)];
+    base2 += mb.counts[counts_at(unit, x) + 1];
+  }
+  int a, b;
+  slice_of(N, s, mb.S, a, b);
+  a = max(a, mb.lo[0]);
+  b = min(b, mb.hi[0]);
+  int unused;
+  list_chunked(scores + (size_t)unit * N, a, b, mb.take_final[unit], orow + prefix, s_cnt, AboveOrAt{mb.pat[unit]},
+               base1, base2, unused);
+  if (s == 0) {
+    const int count = mb.count[0];
+    for (int i = tid; i < prefix; i += 1024) orow[i] = i;
+    for (int i = tid; i < suffix; i += 1024) orow[prefix + count + gap + i] = N - suffix + i;
+    for (int i = prefix + count + gap + suffix + tid; i < out_stride; i += 1024) orow[i] = -1;
+  }
+}
+
+// The band's columns of a slice, listed from the slice's first slot of the row.
+__global__ __launch_bounds__(1024) void mband_write_kernel(const double *__restrict__ scores,
+                                                           const unsigned long long *__restrict__ knorm, MSelBufs mb,
+                                                           Dims dm, int32_t *__restrict__ band_idx,
+                                                           int *__restrict__ above_band) {
+  const int s = blockIdx.x, unit = blockIdx.y, units = gridDim.y, tid = threadIdx.x;
+  if (mb.flag[unit]) return;
+  __shared__ int s_cnt[32];
+  const InBand band = band_limits(dm, mb.band[(size_t)2 * units + unit], __longlong_as_double((long long)knorm[unit]),
+                                  mb.band[unit], mb.nsel > 1 ? mb.band[(size_t)units + unit] : 0.0);
+  int a, b;
+  slice_of(dm.N, s, mb.S, a, b);
+  int n_above;
+  const int n = list_chunked(scores + (size_t)unit * dm.N, a, b, 0, band_idx + (size_t)unit * dm.N + a, s_cnt, band, 0,
+                             0, n_above);
+  if (tid == 0) {
+    mb.counts[counts_at(unit, s)] = n;
+    above_band[(size_t)unit * MSEL_MAX_SLICES + s] = n_above;
+  }
+}
+
+// Closes the gaps between the slices' lists of a row (a list only ever moves
+// towards the row's start, chunk by chunk through registers).
+__global__ __launch_bounds__(1024) void mband_close_kernel(MSelBufs mb, int N, int32_t *__restrict__ band_idx,
+                                                           int32_t *__restrict__ band_cnt, int *__restrict__ list_ok) {
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  if (mb.flag[unit]) return;   // the one-block kernel that redoes the unit says so in list_ok
+  if (tid == 0) list_ok[unit] = 1;
+  int32_t *row = band_idx + (size_t)unit * N;
+  const int seg = slice_len(N, mb.S);
+  int total = mb.counts[counts_at(unit, 0)];
+  for (int s = 1; s < mb.S; ++s) {
+    const int c = mb.counts[counts_at(unit, s)];
+    const int32_t *src = row + min(N, s * seg);
+    int32_t *dst = row + total;
+    if (dst != src) {
+      for (int off = 0; off < c; off += 1024) {
+        const int32_t v = off + tid < c ? src[off + tid] : 0;
+        __syncthreads();
+        if (off + tid < c) dst[off + tid] = v;
+        __syncthreads();
+      }
+    }
+    total += c;
+  }
+  if (tid == 0) band_cnt[unit] = total;
+}
+
+// ---- launchers
+static int msel_slices(const Dims &dm, int n_cu) {
+  const int S = 2 * n_cu / dm.units;
+  return S < 1 ? 1 : (S > MSEL_MAX_SLICES ? MSEL_MAX_SLICES : S);
+}
+static bool msel_sized(const Dims &dm) { return dm.N >= MSEL_MIN_RANGE && dm.units <= MSEL_MAX_UNITS; }
+
+// Long ranges on few units; elsewhere the extra launches cost more than the
+// idle compute units.
+bool msel_pays(const Dims &dm, int n_cu, int lo, int hi, int count) {
+  return msel_sized(dm) && hi - lo >= MSEL_MIN_RANGE && count > 0 && count < hi - lo && msel_slices(dm, n_cu) >= 2;
+}
+
+static size_t al256(size_t b) { return (b + 255) & ~size_t(255); }
+
+size_t msel_workspace_bytes(const Dims &dm) {
+  if (!msel_sized(dm)) return 0;
+  const size_t u = dm.units;
+  return al256(4 * u * 4096 * 4) + al256(2 * u * MSEL_CAND * 8) + al256(2 * u * MSEL_CAND * 4) + 3 * al256(2 * u * 4) + al256(2 * u * 8) +
+         al256(u * 4) + al256(u * MSEL_MAX_SLICES * 4) + al256(u * 8) + al256(u * 4) +
+         al256(u * MSEL_MAX_SLICES * 2 * 4) + al256(u * 3 * 8);
+}
+
+bool msel_carve(Carver &cv, const Dims &dm, MSelBufs &mb) {
+  mb.hist = nullptr;
+  if (!msel_sized(dm)) return false;
+  const size_t u = dm.units;
+  mb.hist = cv.take<unsigned>(4 * u * 4096);
+  mb.cand_key = cv.take<unsigned long long>(2 * u * MSEL_CAND);
+  mb.cand_idx = cv.take<int32_t>(2 * u * MSEL_CAND);
+  mb.n_cand = cv.take<int>(2 * u);
+  mb.take = cv.take<int>(2 * u);
+  mb.wpat = cv.take<unsigned long long>(2 * u);
+  mb.wshift = cv.take<int>(2 * u);
+  mb.flag = cv.take<int>(u);
+  mb.n_above = cv.take<int>(u * MSEL_MAX_SLICES);
+  mb.pat = cv.take<unsigned long long>(u);
+  mb.take_final = cv.take<int>(u);
+  mb.counts = cv.take<int>(u * MSEL_MAX_SLICES * 2);
+  mb.band = cv.take<double>(u * 3);
+  return cv.ok;
+}
+
+// clear, hist1, hist2, gather
+static void msel_candidates(const Dims &dm, const double *scores, const uint8_t *skip, const MSelBufs &mb,
+                            hipStream_t s) {
+  const size_t n = (size_t)4 * dm.units * 4096;
+  msel_clear_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(mb, dm.units);
+  const dim3 grid(mb.S, dm.units), block(1024);
+  msel_hist1_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
+  msel_hist2_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
+  msel_gather_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
+}
+
+int launch_select_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const uint8_t *skip_mask, int lo,
+                         int hi, int count, int prefix, int gap, int suffix, int32_t *out, int out_stride,
+                         hipStream_t s) {
+  mb.S = msel_slices(dm, n_cu);
+  mb.nsel = 1;
+  mb.lo[0] = lo; mb.hi[0] = hi; mb.count[0] = count;
+  mb.lo[1] = mb.hi[1] = mb.count[1] = 0;
+  msel_candidates(dm, scores, skip_mask, mb, s);
+  msel_settle_kernel<false><<<dim3(dm.units), dim3(1024), 0, s>>>(skip_mask, mb, dm, nullptr);
+  msel_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, skip_mask, mb, dm.N, prefix, gap, suffix, out,
+                                                             out_stride);
+  int rc = hip_ok(hipGetLastError());
+  if (rc) return rc;
+  return launch_select(dm, scores, skip_mask, lo, hi, count, prefix, gap, suffix, out, out_stride, 0, mb.flag, s);
+}
+
+int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *qd,
+                       const unsigned long long *knorm, int32_t *band_idx, int32_t *band_cnt, int *above_band,
+                       int *list_ok, hipStream_t s) {
+  mb.S = msel_slices(dm, n_cu);
+  mb.nsel = band_has_middle(dm) ? 2 : 1;
+  mb.lo[0] = 0; mb.hi[0] = dm.N; mb.count[0] = dm.T;
+  mb.lo[1] = dm.s1; mb.hi[1] = dm.N - dm.s2; mb.count[1] = dm.k;
+  msel_candidates(dm, scores, nullptr, mb, s);
+  msel_settle_kernel<true><<<dim3(dm.units, mb.nsel), dim3(1024), 0, s>>>(nullptr, mb, dm, qd);
+  mband_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, knorm, mb, dm, band_idx, above_band);
+  mband_close_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(mb, dm.N, band_idx, band_cnt, list_ok);
+  int rc = hip_ok(hipGetLastError());
+  if (rc) return rc;
+  return launch_band(dm, scores, qd, knorm, band_idx, band_cnt, mb.flag, list_ok, s);
+}
+
+// One block per unit: the middle threshold from the band's list.  The columns
+// of the middle that the list leaves out are either above the band (counted
+// per slice when the list was written) or below it, so the k-th largest score
+// of the middle is the (k - columns above)-th largest of the listed ones.
+__global__ __launch_bounds__(1024) void mlist_settle_kernel(const double *__restrict__ scores,
+                                                            const uint8_t *__restrict__ skip, MSelBufs mb, Dims dm,
+                                                            const int32_t *__restrict__ band_idx,
+                                                            const int32_t *__restrict__ band_cnt,
+                                                            const int *__restrict__ above_band,
+                                                            const int *__restrict__ list_ok) {
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  if (skip && skip[unit]) {
+    if (tid == 0) mb.flag[unit] = 0;
+    return;
+  }
+  if (!list_ok[unit]) {
+    if (tid == 0) mb.flag[unit] = 1;
+    return;
+  }
+  const int N = dm.N;
+  const double *sc = scores + (size_t)unit * N;
+  const int32_t *list = band_idx + (size_t)unit * N;
+  const int n = band_cnt[unit];
+  // the listed columns of the middle: entries [ia, ib) of the ascending list
+  int ia = 0, ib = 0;
+  {
+    int lo = 0, hi = n;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (list[mid] < dm.s1) lo = mid + 1; else hi = mid;
+    }
+    ia = lo;
+    hi = n;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (list[mid] < N - dm.s2) lo = mid + 1; else hi = mid;
+    }
+    ib = lo;
+  }
+  int above = 0;
+  for (int x = 0; x < mb.S; ++x) above += above_band[(size_t)unit * MSEL_MAX_SLICES + x];
+  const int need = dm.k - above;
+  if (need < 1 || need > ib - ia) {   // not while the band's bound holds; the full selection decides then
+    if (tid == 0) mb.flag[unit] = 1;
+    return;
+  }
+  __shared__ RadixScratch rs;
+  __shared__ int c[2 * MSEL_MAX_SLICES];
+  int take_equal;
+  const ListedScores view{sc, list};
+  const uint64_t pat = radix_threshold(view, ia, ib, need, rs, take_equal);
+  if (tid < 2 * MSEL_MAX_SLICES) c[tid] = 0;
+  __syncthreads();
+  const int seg = slice_len(N, mb.S);
+  for (int i = ia + tid; i < ib; i += 1024) {
+    const int j = list[i];
+    const uint64_t key = score_key(sc[j]);
+    if (key > pat) atomicAdd(&c[j / seg], 1);
+    else if (key == pat) atomicAdd(&c[MSEL_MAX_SLICES + j / seg], 1);
+  }
+  __syncthreads();
+  if (tid < mb.S) {
+    mb.counts[counts_at(unit, tid)] = above_band[(size_t)unit * MSEL_MAX_SLICES + tid] + c[tid];
+    mb.counts[counts_at(unit, tid) + 1] = c[MSEL_MAX_SLICES + tid];
+  }
+  if (tid == 0) {
+    mb.pat[unit] = pat;
+    mb.take_final[unit] = take_equal;
+    mb.flag[unit] = 0;
+  }
+}
+
+int launch_select_from_band(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const uint8_t *skip_mask,
+                            const int32_t *band_idx, const int32_t *band_cnt, const int *above_band,
+                            const int *list_ok, int32_t *out, hipStream_t s) {
+  mb.S = msel_slices(dm, n_cu);
+  mb.nsel = 1;
+  mb.lo[0] = dm.s1; mb.hi[0] = dm.N - dm.s2; mb.count[0] = dm.k;
+  mb.lo[1] = mb.hi[1] = mb.count[1] = 0;
+  mlist_settle_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, skip_mask, mb, dm, band_idx, band_cnt, above_band,
+                                                           list_ok);
+  msel_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, skip_mask, mb, dm.N, dm.s1, 0, dm.s2, out,
+                                                             dm.row_stride);
+  int rc = hip_ok(hipGetLastError());
+  if (rc) return rc;
+  return launch_select(dm, scores, skip_mask, dm.s1, dm.N - dm.s2, dm.k, dm.s1, 0, dm.s2, out, dm.row_stride, 0,
+                       mb.flag, s);
+}
+
+}  // namespace taskkv

@@ -54,7 +54,8 @@ struct taskkv_ctx {
   // what the last taskkv_separate screened its scores for: off the listed
   // columns they are fp32 values, good only for this selection
   const double *screened_scores;
-  int screened_sel[6];   // ctx_len, n_sink, n_recent, n_middle, pack_mode, pool_kernel
+  int screened_list;     // the band lists of that call are still in the workspace, with per-slice counts
+  int screened_sel[8];   // ctx_len, n_sink, n_recent, n_middle, pack_mode, pool_kernel, batch, n_kv_heads
 };
 
 namespace taskkv {
@@ -100,6 +101,10 @@ struct ScreenBufs {
   unsigned long long *knorm;   // [units] max squared key norm (bit pattern of a double)
   int mode;                    // 1 = when it pays, 2 = whenever the inputs allow
   int n_cu;                    // compute units of the device
+  const struct MSelBufs *msel; // buffers of the sliced band kernels, or null
+  // what the sliced band kernels leave for the middle pick of the compressor:
+  int *above_band;             // [units][MSEL_MAX_SLICES] middle columns of a slice above the band
+  int *list_ok;                // [units] 1 = the unit's list and counts come from the sliced kernels
 };
 // Buffers of the int8 row-statistics pass (see score_i8.hip).
 constexpr int I8_QCAP = 4096;   // listed window-row remainders per unit
@@ -122,14 +127,56 @@ bool screen_supported(const Dims &dm, int dtype);
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);
 int launch_screen(const Dims &dm, const void *q_win, const void *k, const double *stats, double *scores,
                   int chunks_per_wg, hipStream_t s);
+// Buffers of the selections whose sweeps are cut into slices (see select_multi.hip).
+constexpr int MSEL_MAX_SLICES = 32;    // blocks that share a unit
+constexpr int MSEL_MAX_UNITS = 256;    // beyond this one block per unit fills the chip anyway
+constexpr int MSEL_MIN_RANGE = 32768;  // shorter ranges do not pay for the extra launches
+constexpr int MSEL_CAND = 4096;        // entries of the wanted bin a unit's candidate list takes
+struct MSelBufs {
+  unsigned *hist;                // [2 levels][2][units][4096] digit histograms
+  unsigned long long *cand_key;  // [2][units][MSEL_CAND] bit patterns in the wanted bin
+  int32_t *cand_idx;             // [2][units][MSEL_CAND] and their positions
+  int *n_cand, *take;            // [2][units] their number, rank of the wanted entry among them
+  unsigned long long *wpat;      // [2][units] the digits they share
+  int *wshift;                   // [2][units] position of the first digit they may differ in
+  int *flag;                     // [units] 1 = redo this unit with one block
+  int *n_above;                  // [units][MSEL_MAX_SLICES] entries of a slice in bins above the wanted one
+  unsigned long long *pat;       // [units] threshold pattern
+  int *take_final;               // [units] entries equal to it that are taken
+  int *counts;                   // [units][MSEL_MAX_SLICES][2] picks of every slice: above / at the threshold
+  double *band;                  // [3][units] band: the two thresholds, largest squared window-row norm
+  int S, nsel;                   // slices per unit, thresholds wanted (1 or 2)
+  int lo[2], hi[2], count[2];    // range and rank of each
+};
+size_t msel_workspace_bytes(const Dims &dm);
+// false when the workspace was not sized for the sliced kernels
+bool msel_carve(Carver &cv, const Dims &dm, MSelBufs &mb);
+bool msel_pays(const Dims &dm, int n_cu, int lo, int hi, int count);
+int launch_select_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const uint8_t *skip_mask, int lo,
+                         int hi, int count, int prefix, int gap, int suffix, int32_t *out, int out_stride,
+                         hipStream_t s);
+int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *qd,
+                       const unsigned long long *knorm, int32_t *band_idx, int32_t *band_cnt, int *above_band,
+                       int *list_ok, hipStream_t s);
+// The middle pick on screened scores whose band lists are still there: the
+// threshold is one of the listed columns, so no sweep is needed to find it.
+int launch_select_from_band(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const uint8_t *skip_mask,
+                            const int32_t *band_idx, const int32_t *band_cnt, const int *above_band,
+                            const int *list_ok, int32_t *out, hipStream_t s);
+// only_flagged: when given, units whose entry is 0 are left alone; sliced_ok:
+// when given, the entry of every unit the kernel lists is set to 0
 int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
-                int32_t *band_idx, int32_t *band_cnt, hipStream_t s);
+                int32_t *band_idx, int32_t *band_cnt, const int *only_flagged, int *sliced_ok, hipStream_t s);
+bool band_is_sliced(const Dims &dm, const struct ScreenBufs *scr);
 bool scores_screened(const Dims &dm, int dtype, const ScreenBufs *scr);
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
                   double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8, hipStream_t s);
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
                   int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
-                  hipStream_t s);
+                  const int *only_flagged, hipStream_t s);
+// top `count` among the columns an ascending per-unit list names ([units][N] entries, n_listed[unit] used)
+int launch_select_listed(const Dims &dm, const double *scores, const int32_t *listed, const int32_t *n_listed,
+                         int count, int32_t *out, hipStream_t s);
 int launch_pool(const Dims &dm, const double *scores, double *pooled, hipStream_t s);
 int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const void *v,
                        const int32_t *top_idx, double *sem_vec, double *dist, uint8_t *mask,

@@ -295,15 +295,18 @@ def test_duplicated_keys_tie_to_lower_index():
     run_layer(small_workload(name="dups", wid=153, ctx_len=1000, n_middle=120), mutate=dup)
 
 
+@pytest.mark.parametrize("ctx_len", [9000, 40000])
 @pytest.mark.parametrize("n_middle", [40, 700])
-def test_compress_on_scores_of_any_magnitude(n_middle):
+def test_compress_on_scores_of_any_magnitude(n_middle, ctx_len):
     """taskkv_compress ranks whatever non-negative scores the caller hands over:
     zeros, denormals, values whose leading bits differ (the selection's first
     sweep assumes a common leading nibble and must notice when there is none),
-    and long runs of equal values."""
+    and long runs of equal values.  The longer context is past the length from
+    which several blocks share a unit's selection: rows with one leading nibble
+    and few equal values go through the sliced kernels, the others fall back."""
     from oracle import taskkv_oracle as orc
     ses = _session()
-    wl = small_workload(name="magnitudes", wid=159, batch=2, ctx_len=9000, n_middle=n_middle, n_hetero=1)   # more than the selection keeps in LDS
+    wl = small_workload(name="magnitudes", wid=159, batch=2, ctx_len=ctx_len, n_middle=n_middle, n_hetero=1)   # more than the selection keeps in LDS
     ld = make_layer(wl, 0, "cuda:0")
     cfg = ses.cfg_from_workload(wl)
     bufs = ses.LayerBuffers(cfg, 0)
@@ -318,6 +321,8 @@ def test_compress_on_scores_of_any_magnitude(n_middle):
     sc[0, 3, rng.integers(0, N, 20)] = 0.5
     sc[1, 0, :] = 0.0
     sc[1, 1, :] = np.floor(rng.random(N) * 8) / 8                         # eight distinct values
+    sc[1, 2, :] = 1.0 + rng.random(N) * 1e-6                              # all in one bin of the leading digits
+    sc[1, 3, :] = 0.5 + np.floor(rng.random(N) * 1000) / 4000             # a thousand values, each many times
     mask = np.zeros((B, H), dtype=np.uint8)
     mask[:, H - 1 if n_middle == 40 else 0] = 1
     with ses.Context([cfg], 0) as ctx:
@@ -413,7 +418,9 @@ def test_empty_units_give_zero_output():
 
 
 @pytest.mark.parametrize("kw", [dict(), dict(recipe="zipf", ctx_len=5000, n_middle=300, top_t=200),
-                                dict(ctx_len=9000, n_q_heads=32, n_kv_heads=4, obs_window=32, n_middle=500)])
+                                dict(ctx_len=9000, n_q_heads=32, n_kv_heads=4, obs_window=32, n_middle=500),
+                                # long enough for the selections that several blocks share
+                                dict(batch=1, ctx_len=34000, n_middle=900, top_t=256)])
 def test_screening_changes_no_decision(kw):
     """With and without the fp32 screening pass: identical mask, kept indices and
     top-t vectors; without it every score is fp64-exact."""
