@@ -359,7 +359,7 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   else if (sliced && msel_pays(d, ctx->n_cu, 0, d.N, d.T))
     rc = launch_select_sliced(d, ctx->n_cu, mb, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, s);
   else
-    rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, 0, nullptr, s);
+    rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, 0, s);
   if (rc) return rc;
   return launch_semvec_mask(d, cfg->dtype, scores, v, top_idx, sem_vec, dist, hetero_mask, s);
 }
@@ -420,7 +420,7 @@ int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k,
                                 kept_idx, d.row_stride, s);
     else
       rc = launch_select(d, sel_scores, hetero_mask, d.s1, d.N - d.s2, count, d.s1, gap, d.s2, kept_idx,
-                         d.row_stride, d.keep_all, nullptr, s);
+                         d.row_stride, d.keep_all, s);
     if (rc) return rc;
   }
   if (comp_k) {

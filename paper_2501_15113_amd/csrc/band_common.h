@@ -4,6 +4,7 @@
 
 #include <math.h>
 
+#include "select_common.h"
 #include "taskkv_internal.h"
 
 namespace taskkv {
@@ -58,8 +59,12 @@ __host__ __device__ __forceinline__ bool band_has_middle(const Dims &dm) {
 
 // The band around the two thresholds: three times the relative error bound of
 // the fp32 scores, from the measured norms (qmax, kmax: largest squared norms
-// of a window row and of a key).
-__device__ __forceinline__ InBand band_limits(const Dims &dm, double qmax, double kmax, double tau_t, double tau_k) {
+// of a window row and of a key).  The thresholds of the fp32 scores may be
+// given as brackets: tau_t is any value at or below the top-t threshold, and
+// the middle threshold lies in [tau_k_lo, tau_k_hi]; a wider bracket lists more
+// columns and loses nothing.
+__device__ __forceinline__ InBand band_limits(const Dims &dm, double qmax, double kmax, double tau_t, double tau_k_lo,
+                                              double tau_k_hi) {
   const double gamma = 4.0 * dm.D * 5.9604644775390625e-08;   // 4 d 2^-24
   const double eps = dm.scale * gamma * sqrt(qmax) * sqrt(kmax) + 2e-5 + dm.R * 1.2e-7;
   const double w3 = 3.0 * eps;
@@ -67,11 +72,29 @@ __device__ __forceinline__ InBand band_limits(const Dims &dm, double qmax, doubl
   InBand b;
   // values below 1e-30 may have been flushed to zero by the fp32 pass: treat them as ties
   b.lo_t = w3 >= 1.0 ? -1.0 : tau_t * (1.0 - w3) - 1e-30;
-  b.lo_k = w3 >= 1.0 ? -1.0 : tau_k * (1.0 - w3) - 1e-30;
-  b.hi_k = w3 >= 1.0 ? INFINITY : tau_k * (1.0 + w3) + 1e-30;
+  b.lo_k = w3 >= 1.0 ? -1.0 : tau_k_lo * (1.0 - w3) - 1e-30;
+  b.hi_k = w3 >= 1.0 ? INFINITY : tau_k_hi * (1.0 + w3) + 1e-30;
   b.m0 = middle ? dm.s1 : 0;
   b.m1 = middle ? dm.N - dm.s2 : 0;
   return b;
+}
+
+// One block lists the band of one unit: error bound, the two thresholds of the
+// fp32 scores, the columns to recompute (ascending) and their number.  All
+// 1024 threads; s_cnt: 32 ints, s_q: 16 doubles of LDS.
+__device__ __forceinline__ void band_of_unit(const double *__restrict__ sc, const double *__restrict__ qd, double kmax,
+                                             int unit, const Dims &dm, int32_t *__restrict__ list,
+                                             int32_t *__restrict__ count, RadixScratch &rs, int *s_cnt, double *s_q) {
+  const int N = dm.N;
+  const double qmax = max_row_norm2(qd, unit, dm, s_q);
+  int unused;
+  const double tau_t = __longlong_as_double((long long)radix_threshold(sc, 0, N, dm.T, rs, unused));
+  double tau_k = 0.0;
+  if (band_has_middle(dm))
+    tau_k = __longlong_as_double((long long)radix_threshold(sc, dm.s1, N - dm.s2, dm.k, rs, unused));
+  const InBand band = band_limits(dm, qmax, kmax, tau_t, tau_k, tau_k);
+  const int listed = list_ascending(sc, 0, N, 0, list, s_cnt, band);
+  if (threadIdx.x == 0) *count = listed;
 }
 
 }  // namespace taskkv

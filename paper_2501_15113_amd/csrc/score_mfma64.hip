@@ -402,7 +402,7 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
       rc = launch_band_sliced(dm, scr->n_cu, *scr->msel, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt,
                               scr->above_band, scr->list_ok, s);
     else
-      rc = launch_band(dm, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt, nullptr, nullptr, s);
+      rc = launch_band(dm, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt, s);
     if (rc) return rc;
     // The listed columns of a unit make about twenty 16-key tasks of some ten
     // microseconds each (a chain of dependent loads, 64 fp64 matrix instructions,

@@ -196,28 +196,13 @@ __global__ __launch_bounds__(1024) void band_kernel(const double *__restrict__ s
                                                     const double *__restrict__ qd,
                                                     const unsigned long long *__restrict__ knorm,
                                                     int32_t *__restrict__ band_idx,
-                                                    int32_t *__restrict__ band_cnt, Dims dm,
-                                                    const int *__restrict__ only_flagged,
-                                                    int *__restrict__ sliced_ok) {
-  const int unit = blockIdx.x, tid = threadIdx.x;
-  if (only_flagged && !only_flagged[unit]) return;
-  if (sliced_ok && tid == 0) sliced_ok[unit] = 0;   // this unit's list has no per-slice counts
-  const int N = dm.N;
-  const double *sc = scores + (size_t)unit * N;
+                                                    int32_t *__restrict__ band_cnt, Dims dm) {
+  const int unit = blockIdx.x;
   __shared__ RadixScratch rs;
   __shared__ int s_cnt[32];
   __shared__ double s_q[16];
-
-  const double qmax = max_row_norm2(qd, unit, dm, s_q);
-  const double kmax = __longlong_as_double((long long)knorm[unit]);
-  int unused;
-  const double tau_t = __longlong_as_double((long long)radix_threshold(sc, 0, N, dm.T, rs, unused));
-  double tau_k = 0.0;
-  if (band_has_middle(dm))
-    tau_k = __longlong_as_double((long long)radix_threshold(sc, dm.s1, N - dm.s2, dm.k, rs, unused));
-  const InBand band = band_limits(dm, qmax, kmax, tau_t, tau_k);
-  const int listed = list_ascending(sc, 0, N, 0, band_idx + (size_t)unit * N, s_cnt, band);
-  if (tid == 0) band_cnt[unit] = listed;
+  band_of_unit(scores + (size_t)unit * dm.N, qd, __longlong_as_double((long long)knorm[unit]), unit, dm,
+               band_idx + (size_t)unit * dm.N, band_cnt + unit, rs, s_cnt, s_q);
 }
 
 __global__ void zero_u64_kernel(unsigned long long *p, int n) {
@@ -287,9 +272,8 @@ int launch_screen(const Dims &dm, const void *q_win, const void *k, const double
 }
 
 int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
-                int32_t *band_idx, int32_t *band_cnt, const int *only_flagged, int *sliced_ok, hipStream_t s) {
-  band_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, band_idx, band_cnt, dm, only_flagged,
-                                                   sliced_ok);
+                int32_t *band_idx, int32_t *band_cnt, hipStream_t s) {
+  band_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, band_idx, band_cnt, dm);
   return hip_ok(hipGetLastError());
 }
 

@@ -9,8 +9,6 @@
 
 namespace taskkv {
 
-__device__ __forceinline__ uint64_t key_of(double x) { return score_key(x); }
-
 // Average pooling of the selection scores: stride 1, zero padding, fixed
 // divisor (Sec. 5.4 names only the kernel size).
 __global__ void pool_kernel(const double *__restrict__ c, double *__restrict__ p, int N, int width) {
@@ -27,47 +25,24 @@ __global__ void pool_kernel(const double *__restrict__ c, double *__restrict__ p
   p[(size_t)unit * N + j] = acc / (double)width;
 }
 
-// One block per unit.  Picks the `count` largest scores inside [lo, hi) by
-// (score desc, index asc) with an 8-bit radix select on the 64-bit patterns,
-// then writes  [0, prefix) ++ picks ascending ++ (gap slots left for the caller)
-// ++ [N - suffix, N)  and pads the row with -1.  Units flagged in `skip` get an
-// all -1 row; with `only_flagged`, units whose entry is 0 are left alone.  With a list of columns (`listed`, `n_listed` per unit, ascending)
-// the picks are taken among the listed columns only: [lo, hi) is ignored.
+// One block per unit (see select_of_unit).  Units flagged in `skip` get an all
+// -1 row.
 __global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__ scores,
                                                       const uint8_t *__restrict__ skip, int skip_all,
                                                       int N, int lo, int hi, int count, int prefix,
                                                       int gap, int suffix, int32_t *__restrict__ out,
                                                       int out_stride, const int32_t *__restrict__ listed,
-                                                      const int32_t *__restrict__ n_listed,
-                                                      const int *__restrict__ only_flagged) {
+                                                      const int32_t *__restrict__ n_listed) {
   const int unit = blockIdx.x, tid = threadIdx.x;
-  if (only_flagged && !only_flagged[unit]) return;
   int32_t *orow = out + (size_t)unit * out_stride;
   if (skip_all || (skip && skip[unit])) {
     for (int i = tid; i < out_stride; i += 1024) orow[i] = -1;
     return;
   }
-  const double *sc = scores + (size_t)unit * N;
   __shared__ RadixScratch rs;
   __shared__ int s_cnt[32];
-
-  if (count > 0) {
-    // pat = the count-th largest score; `remaining` of the entries equal to it
-    // are taken, lowest index first.
-    auto pick = [&](auto view, int a, int b) {
-      int remaining;
-      const uint64_t pat = radix_threshold(view, a, b, count, rs, remaining);
-      list_ascending(view, a, b, remaining, orow + prefix, s_cnt, [&](int, double x) {
-        const uint64_t key = key_of(x);
-        return key > pat ? 1 : (key == pat ? 2 : 0);
-      });
-    };
-    if (listed != nullptr) pick(ListedScores{sc, listed + (size_t)unit * N}, 0, n_listed[unit]);
-    else pick(sc, lo, hi);
-  }
-  for (int i = tid; i < prefix; i += 1024) orow[i] = i;
-  for (int i = tid; i < suffix; i += 1024) orow[prefix + count + gap + i] = N - suffix + i;
-  for (int i = prefix + count + gap + suffix + tid; i < out_stride; i += 1024) orow[i] = -1;
+  select_of_unit(scores + (size_t)unit * N, orow, N, lo, hi, count, prefix, gap, suffix, out_stride,
+                 listed ? listed + (size_t)unit * N : nullptr, listed ? n_listed[unit] : 0, rs, s_cnt);
 }
 
 __device__ __forceinline__ double elem_to_double(float x) { return (double)x; }
@@ -166,16 +141,16 @@ __global__ __launch_bounds__(256) void dist_mask_kernel(const double *__restrict
 
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
                   int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
-                  const int *only_flagged, hipStream_t s) {
+                  hipStream_t s) {
   select_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, skip_mask, skip_all, dm.N, lo, hi, count, prefix, gap,
-                                                     suffix, out, out_stride, nullptr, nullptr, only_flagged);
+                                                     suffix, out, out_stride, nullptr, nullptr);
   return hip_ok(hipGetLastError());
 }
 
 int launch_select_listed(const Dims &dm, const double *scores, const int32_t *listed, const int32_t *n_listed,
                          int count, int32_t *out, hipStream_t s) {
   select_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, nullptr, 0, dm.N, 0, 0, count, 0, 0, 0, out, count,
-                                                     listed, n_listed, nullptr);
+                                                     listed, n_listed);
   return hip_ok(hipGetLastError());
 }
 

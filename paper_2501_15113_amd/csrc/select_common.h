@@ -43,26 +43,24 @@ constexpr int SWEEP_U = 8;
 constexpr int RADIX_CAND = 4096;
 struct RadixScratch {
   uint64_t found;
-  int bin, rem, n;
+  int bin, rem, n_bin, n;
   unsigned top_and, top_or;   // bits 60-63 of every key, and-ed / or-ed
   int wsum[16];
-  unsigned hist12[4096];
+  alignas(16) unsigned hist12[4096];   // read four bins at a time
   uint64_t cand[RADIX_CAND];
 };
 
-// The bin of rs.hist12 (filled, 4096 bins of a 12-bit digit) that holds the
-// remaining-th largest entry -> rs.bin, and its rank inside the bin -> rs.rem.
-// Thread i owns bins 4095 - 4 i ... 4092 - 4 i; a block scan gives the count
-// above them.  Called by all 1024 threads; ends with a barrier.
+// The bin of `hist` (4096 bins of a 12-bit digit, in LDS or in global memory)
+// that holds the remaining-th largest entry -> rs.bin, its rank inside the bin
+// -> rs.rem, the bin's count -> rs.n_bin.  Thread i owns bins 4095 - 4 i ...
+// 4092 - 4 i; a block scan gives the count above them.  Called by all 1024
+// threads; ends with a barrier.
 template <typename RS>
-__device__ __forceinline__ void pick_bin12(RS &rs, int remaining) {
+__device__ __forceinline__ void pick_bin12(const unsigned *hist, RS &rs, int remaining) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  int c[4], own = 0;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    c[q] = (int)rs.hist12[4095 - 4 * tid - q];
-    own += c[q];
-  }
+  const uint4 mine = *reinterpret_cast<const uint4 *>(hist + 4092 - 4 * tid);
+  const int c[4] = {(int)mine.w, (int)mine.z, (int)mine.y, (int)mine.x};   // highest bin first
+  const int own = c[0] + c[1] + c[2] + c[3];
   int incl = own;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
@@ -83,6 +81,7 @@ __device__ __forceinline__ void pick_bin12(RS &rs, int remaining) {
     }
     rs.bin = 4095 - 4 * tid - q;
     rs.rem = remaining - cum;
+    rs.n_bin = c[q];
   }
   __syncthreads();
 }
@@ -161,8 +160,8 @@ __device__ __forceinline__ uint64_t radix_finish(SC sc, int lo, int hi, RadixScr
       }
     }
     __syncthreads();
-    pick_bin12(rs, remaining);
-    n_match = (int)rs.hist12[rs.bin];   // entries that share all digits known after this pass
+    pick_bin12(rs.hist12, rs, remaining);
+    n_match = rs.n_bin;   // entries that share all digits known after this pass
     pat |= (uint64_t)rs.bin << shift;
     known |= 0xfffull << shift;
     remaining = rs.rem;
@@ -228,7 +227,7 @@ __device__ __forceinline__ uint64_t radix_threshold(SC sc, int lo, int hi, int c
     __syncthreads();
     const bool common = rs.top_and == rs.top_or;
     if (common) {
-      pick_bin12(rs, remaining);
+      pick_bin12(rs.hist12, rs, remaining);
       pat = ((uint64_t)rs.top_and << 60) | ((uint64_t)rs.bin << 48);
       known = 0xffffull << 48;
     } else {
@@ -246,13 +245,13 @@ __device__ __forceinline__ uint64_t radix_threshold(SC sc, int lo, int hi, int c
           hist_add_merged(rs.hist12, j0 + r * 1024 + tid < hi, (unsigned)(key[r] >> 60));
       }
       __syncthreads();
-      pick_bin12(rs, remaining);
+      pick_bin12(rs.hist12, rs, remaining);
       pat = (uint64_t)rs.bin << 60;
       known = 0xfull << 60;
       shift = 48;
     }
     remaining = rs.rem;
-    n_match = (int)rs.hist12[rs.bin];
+    n_match = rs.n_bin;
     __syncthreads();
   }
   return radix_finish(sc, lo, hi, rs, pat, known, shift, remaining, n_match, take_equal);
@@ -415,6 +414,42 @@ __device__ __forceinline__ void count_classes(SC sc, int lo, int hi, int *s_cnt,
     n1 += s_cnt[w];
     n2 += s_cnt[16 + w];
   }
+}
+
+// 1 = above the threshold, 2 = equal to it.
+struct AboveOrAt {
+  uint64_t pat;
+  __device__ __forceinline__ int operator()(int, double x) const {
+    const uint64_t key = score_key(x);
+    return key > pat ? 1 : (key == pat ? 2 : 0);
+  }
+};
+
+// One block selects for one unit: the `count` largest scores inside [lo, hi) by
+// (score desc, index asc), written as  [0, prefix) ++ picks ascending ++ (gap
+// slots left for the caller) ++ [N - suffix, N)  with the rest of the row -1.
+// With a list of columns (`listed`, n_listed of them, ascending) the picks are
+// taken among the listed columns only: [lo, hi) is ignored.  All 1024 threads;
+// s_cnt: 32 ints of LDS.
+__device__ __forceinline__ void select_of_unit(const double *__restrict__ sc, int32_t *__restrict__ orow, int N, int lo,
+                                               int hi, int count, int prefix, int gap, int suffix, int out_stride,
+                                               const int32_t *__restrict__ listed, int n_listed, RadixScratch &rs,
+                                               int *s_cnt) {
+  const int tid = threadIdx.x;
+  if (count > 0) {
+    // pat = the count-th largest score; `remaining` of the entries equal to it
+    // are taken, lowest index first.
+    auto pick = [&](auto view, int a, int b) {
+      int remaining;
+      const uint64_t pat = radix_threshold(view, a, b, count, rs, remaining);
+      list_ascending(view, a, b, remaining, orow + prefix, s_cnt, AboveOrAt{pat});
+    };
+    if (listed != nullptr) pick(ListedScores{sc, listed}, 0, n_listed);
+    else pick(sc, lo, hi);
+  }
+  for (int i = tid; i < prefix; i += 1024) orow[i] = i;
+  for (int i = tid; i < suffix; i += 1024) orow[prefix + count + gap + i] = N - suffix + i;
+  for (int i = prefix + count + gap + suffix + tid; i < out_stride; i += 1024) orow[i] = -1;
 }
 
 }  // namespace taskkv

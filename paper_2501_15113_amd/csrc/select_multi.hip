@@ -3,16 +3,16 @@
 //
 // A sweep over the scores of all units is a pass over up to 64 MB; with one
 // block per unit a selection takes six to eight of them, each at the speed of
-// 8-64 blocks.  Here every phase is a kernel of S blocks per unit, a selection
-// reads the scores three times (four when they crowd into few bins), and both
-// thresholds of the band come out of the same reads:
+// 8-64 blocks.  Here every phase is a kernel of S blocks per unit and the
+// scores are read three or four times:
 //   clear    the per-unit histograms and counters;
 //   hist1    12-bit digit histogram (bits 48-59 of the fp64 pattern: sixteen
 //            bins per octave over [2^-255, 2), anything smaller in bin 0,
 //            anything larger in bin 4095) of a slice, added to the unit's;
-//   hist2    only where the bin that holds the wanted rank has more entries
-//            than the candidate list takes: histogram of the next twelve bits
-//            of that bin's entries;
+//   hist2    histogram of the next twelve bits of the entries in the bin that
+//            holds the wanted rank.
+// A selection (top-t of unscreened scores, the middle pick) skips hist2 unless
+// the wanted bin has more entries than the candidate list takes, and goes on:
 //   gather   every block finds the wanted bin from the unit's histograms,
 //            appends its slice's entries of that bin (pattern and position) to
 //            the unit's candidate list and counts its entries in higher bins;
@@ -21,13 +21,23 @@
 //            taken; the candidates' positions give every slice's share;
 //   write    every block lists its slice's picks behind those of the slices
 //            before it (ascending positions, ties to the lower index).
-// The band's list is written slice by slice into the row and closed up by one
-// more small kernel, which saves a counting pass.
+// The band of the screening pass wants two thresholds at once (top-t and the
+// middle pick, from the same reads) but only to within a fraction of its own
+// width: the two digits bracket each to 2^-16 of itself, so it goes on with
+//   brackets the wanted bins of both levels -> the brackets, and the largest
+//            window-row norm for the error bound;
+//   write    every block lists its slice's band columns from the slice's first
+//            slot of the row and counts the middle columns above the band;
+//   close    one block per unit closes the gaps between the slices' lists.
+// The compressor's middle pick on screened scores then needs no sweep to find
+// its threshold: every middle column the band leaves out is above it (counted)
+// or below it, so the threshold is the (k - columns above)-th largest listed
+// score (mlist_settle), and `write` lists the picks.
 // Results do not depend on the order in which blocks run: histograms and
 // candidate lists are only counted, never read in order.  A unit whose wanted
 // rank falls into one of the two mixed end bins, or whose wanted bin still
 // holds too many entries after the second digit (thousands of equal scores),
-// is flagged and redone by the one-block kernel afterwards.
+// is flagged and left to one block, as in the one-block kernels.
 #include <math.h>
 
 #include "band_common.h"
@@ -69,9 +79,8 @@ __device__ __forceinline__ int digit2(uint64_t key) { return (int)(key >> 36) & 
 
 // LDS of a block that looks up a wanted bin.
 struct PickScratch {
-  unsigned hist12[4096];
   int wsum[16];
-  int bin, rem;
+  int bin, rem, n_bin;
 };
 
 // What a unit's histograms say about one selection: the digits of the wanted
@@ -86,20 +95,16 @@ struct Wanted {
 
 // Level 1 only.  All 1024 threads; ps is overwritten.
 __device__ __forceinline__ Wanted wanted_level1(const MSelBufs &mb, int sel, int unit, int units, PickScratch &ps) {
-  const int tid = threadIdx.x;
-  __syncthreads();
-  const unsigned *h = mb.hist + hist_at(0, sel, unit, units);
-  for (int i = tid; i < 4096; i += 1024) ps.hist12[i] = h[i];
-  __syncthreads();
-  pick_bin12(ps, mb.count[sel]);
+  __syncthreads();   // ps may still be read from the call before
+  pick_bin12(mb.hist + hist_at(0, sel, unit, units), ps, mb.count[sel]);
   Wanted w;
   const int bin = ps.bin;
-  w.n = (int)ps.hist12[bin];
+  w.n = ps.n_bin;
   w.rem = ps.rem;
   w.pat = (DIGIT1_BASE + (unsigned long long)bin) << 48;
   w.known = 0xffffull << 48;
   w.redo = bin == 0 || bin == 4095 || w.n == 0;
-  w.level2 = !w.redo && w.n > MSEL_CAND;
+  w.level2 = !w.redo && (w.n > MSEL_CAND || mb.bracket);
   return w;
 }
 
@@ -107,18 +112,13 @@ __device__ __forceinline__ Wanted wanted_level1(const MSelBufs &mb, int sel, int
 __device__ __forceinline__ Wanted wanted_bin(const MSelBufs &mb, int sel, int unit, int units, PickScratch &ps) {
   Wanted w = wanted_level1(mb, sel, unit, units, ps);
   if (!w.level2) return w;   // the same in every thread
-  const int tid = threadIdx.x;
   __syncthreads();
-  const unsigned *h = mb.hist + hist_at(1, sel, unit, units);
-  for (int i = tid; i < 4096; i += 1024) ps.hist12[i] = h[i];
-  __syncthreads();
-  pick_bin12(ps, w.rem);
-  const int bin = ps.bin;
-  w.n = (int)ps.hist12[bin];
+  pick_bin12(mb.hist + hist_at(1, sel, unit, units), ps, w.rem);
+  w.n = ps.n_bin;
   w.rem = ps.rem;
-  w.pat |= (unsigned long long)bin << 36;
+  w.pat |= (unsigned long long)ps.bin << 36;
   w.known |= 0xfffull << 36;
-  w.redo = w.n == 0 || w.n > MSEL_CAND;
+  w.redo = w.n == 0 || (w.n > MSEL_CAND && !mb.bracket);
   return w;
 }
 
@@ -302,56 +302,55 @@ __device__ __forceinline__ uint64_t settle(const MSelBufs &mb, size_t su, RadixS
   return radix_finish(view, 0, n, rs, mb.wpat[su], ~0ull << (shift + 12), shift, mb.take[su], n, take_equal);
 }
 
-// One block per unit and threshold.  Selection: the threshold, and the picks
-// of every slice (entries in higher bins + candidates above / at the
-// threshold).  Band: the threshold, and with the first one the largest squared
-// norm of a window row.
-template <bool BAND>
-__global__ __launch_bounds__(1024) void msel_settle_kernel(const uint8_t *__restrict__ skip, MSelBufs mb, Dims dm,
-                                                           const double *__restrict__ qd) {
-  const int unit = blockIdx.x, units = gridDim.x, sel = blockIdx.y, tid = threadIdx.x;
+// One block per unit: the threshold, and the picks of every slice (entries in
+// higher bins + candidates above / at the threshold).
+__global__ __launch_bounds__(1024) void msel_settle_kernel(const uint8_t *__restrict__ skip, MSelBufs mb, Dims dm) {
+  const int unit = blockIdx.x, tid = threadIdx.x;
   if ((skip && skip[unit]) || mb.flag[unit]) return;
   __shared__ RadixScratch rs;
+  __shared__ int c[2 * MSEL_MAX_SLICES];
   int take_equal;
-  const uint64_t pat = settle(mb, (size_t)sel * units + unit, rs, take_equal);
-  if (!BAND) {
-    __shared__ int c[2 * MSEL_MAX_SLICES];
-    if (tid < 2 * MSEL_MAX_SLICES) c[tid] = 0;
-    __syncthreads();
-    const int seg = slice_len(dm.N, mb.S), n = mb.n_cand[unit];
-    for (int i = tid; i < n; i += 1024) {
-      const uint64_t key = mb.cand_key[(size_t)unit * MSEL_CAND + i];
-      const int sl = mb.cand_idx[(size_t)unit * MSEL_CAND + i] / seg;
-      if (key > pat) atomicAdd(&c[sl], 1);
-      else if (key == pat) atomicAdd(&c[MSEL_MAX_SLICES + sl], 1);
-    }
-    __syncthreads();
-    if (tid < mb.S) {
-      mb.counts[counts_at(unit, tid)] = mb.n_above[(size_t)unit * MSEL_MAX_SLICES + tid] + c[tid];
-      mb.counts[counts_at(unit, tid) + 1] = c[MSEL_MAX_SLICES + tid];
-    }
-    if (tid == 0) {
-      mb.pat[unit] = pat;
-      mb.take_final[unit] = take_equal;
-    }
-  } else {
-    if (tid == 0) mb.band[(size_t)sel * units + unit] = __longlong_as_double((long long)pat);
-    if (sel == 0) {
-      __shared__ double s_q[16];
-      const double qmax = max_row_norm2(qd, unit, dm, s_q);
-      if (tid == 0) mb.band[(size_t)2 * units + unit] = qmax;
-    }
+  const uint64_t pat = settle(mb, unit, rs, take_equal);
+  if (tid < 2 * MSEL_MAX_SLICES) c[tid] = 0;
+  __syncthreads();
+  const int seg = slice_len(dm.N, mb.S), n = mb.n_cand[unit];
+  for (int i = tid; i < n; i += 1024) {
+    const uint64_t key = mb.cand_key[(size_t)unit * MSEL_CAND + i];
+    const int sl = mb.cand_idx[(size_t)unit * MSEL_CAND + i] / seg;
+    if (key > pat) atomicAdd(&c[sl], 1);
+    else if (key == pat) atomicAdd(&c[MSEL_MAX_SLICES + sl], 1);
+  }
+  __syncthreads();
+  if (tid < mb.S) {
+    mb.counts[counts_at(unit, tid)] = mb.n_above[(size_t)unit * MSEL_MAX_SLICES + tid] + c[tid];
+    mb.counts[counts_at(unit, tid) + 1] = c[MSEL_MAX_SLICES + tid];
+  }
+  if (tid == 0) {
+    mb.pat[unit] = pat;
+    mb.take_final[unit] = take_equal;
   }
 }
 
-// 1 = above the threshold, 2 = equal to it.
-struct AboveOrAt {
-  uint64_t pat;
-  __device__ __forceinline__ int operator()(int, double x) const {
-    const uint64_t key = score_key(x);
-    return key > pat ? 1 : (key == pat ? 2 : 0);
+// The band needs no exact thresholds of the fp32 scores, only brackets: the
+// two digits of the histograms place each within 2^-16 of itself, less than
+// the band's own width.  Three blocks per unit: the two brackets and the largest
+// squared norm of a window row.
+__global__ __launch_bounds__(1024) void mband_brackets_kernel(MSelBufs mb, Dims dm, const double *__restrict__ qd) {
+  const int unit = blockIdx.x, units = gridDim.x, what = blockIdx.y, tid = threadIdx.x;
+  if (what == 2) {
+    __shared__ double s_q[16];
+    const double qmax = max_row_norm2(qd, unit, dm, s_q);
+    if (tid == 0) mb.band[(size_t)2 * units + unit] = qmax;
+    return;
   }
-};
+  if (what >= mb.nsel) return;
+  __shared__ PickScratch ps;
+  const Wanted w = wanted_bin(mb, what, unit, units, ps);
+  if (tid == 0) {
+    if (w.redo) mb.flag[unit] = 1;
+    mb.band[(size_t)what * units + unit] = __longlong_as_double((long long)w.pat);   // the bracket's lower end
+  }
+}
 
 // Row layout as select_kernel writes it: [0, prefix) ++ picks ++ gap ++ [N - suffix, N) ++ -1 padding.
 __global__ __launch_bounds__(1024) void msel_write_kernel(const double *__restrict__ scores,
@@ -365,8 +364,14 @@ __global__ __launch_bounds__(1024) void msel_write_kernel(const double *__restri
       for (int i = tid; i < out_stride; i += 1024) orow[i] = -1;
     return;
   }
-  if (mb.flag[unit]) return;
   __shared__ int s_cnt[32];
+  if (mb.flag[unit]) {   // the sliced kernels gave up on this unit: its first block selects alone
+    __shared__ RadixScratch rs;
+    if (s == 0)
+      select_of_unit(scores + (size_t)unit * N, orow, N, mb.lo[0], mb.hi[0], mb.count[0], prefix, gap, suffix,
+                     out_stride, nullptr, 0, rs, s_cnt);
+    return;
+  }
   int base1 = 0, base2 = 0;
   for (int x = 0; x < s; ++x) {
     base1 += mb.counts[counts_at(unit, x)];
@@ -395,8 +400,11 @@ __global__ __launch_bounds__(1024) void mband_write_kernel(const double *__restr
   const int s = blockIdx.x, unit = blockIdx.y, units = gridDim.y, tid = threadIdx.x;
   if (mb.flag[unit]) return;
   __shared__ int s_cnt[32];
-  const InBand band = band_limits(dm, mb.band[(size_t)2 * units + unit], __longlong_as_double((long long)knorm[unit]),
-                                  mb.band[unit], mb.nsel > 1 ? mb.band[(size_t)units + unit] : 0.0);
+  const uint64_t rest = (1ull << 36) - 1ull;   // the digits the brackets leave open
+  const double tau_k = mb.nsel > 1 ? mb.band[(size_t)units + unit] : 0.0;
+  const InBand band =
+      band_limits(dm, mb.band[(size_t)2 * units + unit], __longlong_as_double((long long)knorm[unit]), mb.band[unit],
+                  tau_k, __longlong_as_double((long long)(score_key(tau_k) | rest)));
   int a, b;
   slice_of(dm.N, s, mb.S, a, b);
   int n_above;
@@ -410,11 +418,21 @@ __global__ __launch_bounds__(1024) void mband_write_kernel(const double *__restr
 
 // Closes the gaps between the slices' lists of a row (a list only ever moves
 // towards the row's start, chunk by chunk through registers).
-__global__ __launch_bounds__(1024) void mband_close_kernel(MSelBufs mb, int N, int32_t *__restrict__ band_idx,
+__global__ __launch_bounds__(1024) void mband_close_kernel(const double *__restrict__ scores,
+                                                           const double *__restrict__ qd,
+                                                           const unsigned long long *__restrict__ knorm, MSelBufs mb,
+                                                           Dims dm, int32_t *__restrict__ band_idx,
                                                            int32_t *__restrict__ band_cnt, int *__restrict__ list_ok) {
-  const int unit = blockIdx.x, tid = threadIdx.x;
-  if (mb.flag[unit]) return;   // the one-block kernel that redoes the unit says so in list_ok
-  if (tid == 0) list_ok[unit] = 1;
+  const int unit = blockIdx.x, tid = threadIdx.x, N = dm.N;
+  if (tid == 0) list_ok[unit] = mb.flag[unit] ? 0 : 1;
+  if (mb.flag[unit]) {   // the sliced kernels gave up on this unit: one block lists its band, without slice counts
+    __shared__ RadixScratch rs;
+    __shared__ int s_cnt[32];
+    __shared__ double s_q[16];
+    band_of_unit(scores + (size_t)unit * N, qd, __longlong_as_double((long long)knorm[unit]), unit, dm,
+                 band_idx + (size_t)unit * N, band_cnt + unit, rs, s_cnt, s_q);
+    return;
+  }
   int32_t *row = band_idx + (size_t)unit * N;
   const int seg = slice_len(N, mb.S);
   int total = mb.counts[counts_at(unit, 0)];
@@ -478,15 +496,18 @@ bool msel_carve(Carver &cv, const Dims &dm, MSelBufs &mb) {
   return cv.ok;
 }
 
-// clear, hist1, hist2, gather
-static void msel_candidates(const Dims &dm, const double *scores, const uint8_t *skip, const MSelBufs &mb,
+static void msel_histograms(const Dims &dm, const double *scores, const uint8_t *skip, const MSelBufs &mb,
                             hipStream_t s) {
   const size_t n = (size_t)4 * dm.units * 4096;
   msel_clear_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(mb, dm.units);
   const dim3 grid(mb.S, dm.units), block(1024);
   msel_hist1_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
   msel_hist2_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
-  msel_gather_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
+}
+static void msel_candidates(const Dims &dm, const double *scores, const uint8_t *skip, const MSelBufs &mb,
+                            hipStream_t s) {
+  msel_histograms(dm, scores, skip, mb, s);
+  msel_gather_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, skip, mb, dm.N);
 }
 
 int launch_select_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const uint8_t *skip_mask, int lo,
@@ -494,15 +515,14 @@ int launch_select_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *sc
                          hipStream_t s) {
   mb.S = msel_slices(dm, n_cu);
   mb.nsel = 1;
+  mb.bracket = 0;
   mb.lo[0] = lo; mb.hi[0] = hi; mb.count[0] = count;
   mb.lo[1] = mb.hi[1] = mb.count[1] = 0;
   msel_candidates(dm, scores, skip_mask, mb, s);
-  msel_settle_kernel<false><<<dim3(dm.units), dim3(1024), 0, s>>>(skip_mask, mb, dm, nullptr);
+  msel_settle_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(skip_mask, mb, dm);
   msel_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, skip_mask, mb, dm.N, prefix, gap, suffix, out,
                                                              out_stride);
-  int rc = hip_ok(hipGetLastError());
-  if (rc) return rc;
-  return launch_select(dm, scores, skip_mask, lo, hi, count, prefix, gap, suffix, out, out_stride, 0, mb.flag, s);
+  return hip_ok(hipGetLastError());
 }
 
 int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *qd,
@@ -512,13 +532,12 @@ int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scor
   mb.nsel = band_has_middle(dm) ? 2 : 1;
   mb.lo[0] = 0; mb.hi[0] = dm.N; mb.count[0] = dm.T;
   mb.lo[1] = dm.s1; mb.hi[1] = dm.N - dm.s2; mb.count[1] = dm.k;
-  msel_candidates(dm, scores, nullptr, mb, s);
-  msel_settle_kernel<true><<<dim3(dm.units, mb.nsel), dim3(1024), 0, s>>>(nullptr, mb, dm, qd);
+  mb.bracket = 1;
+  msel_histograms(dm, scores, nullptr, mb, s);
+  mband_brackets_kernel<<<dim3(dm.units, 3), dim3(1024), 0, s>>>(mb, dm, qd);
   mband_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, knorm, mb, dm, band_idx, above_band);
-  mband_close_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(mb, dm.N, band_idx, band_cnt, list_ok);
-  int rc = hip_ok(hipGetLastError());
-  if (rc) return rc;
-  return launch_band(dm, scores, qd, knorm, band_idx, band_cnt, mb.flag, list_ok, s);
+  mband_close_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, mb, dm, band_idx, band_cnt, list_ok);
+  return hip_ok(hipGetLastError());
 }
 
 // One block per unit: the middle threshold from the band's list.  The columns
@@ -598,16 +617,14 @@ int launch_select_from_band(const Dims &dm, int n_cu, MSelBufs mb, const double 
                             const int *list_ok, int32_t *out, hipStream_t s) {
   mb.S = msel_slices(dm, n_cu);
   mb.nsel = 1;
+  mb.bracket = 0;
   mb.lo[0] = dm.s1; mb.hi[0] = dm.N - dm.s2; mb.count[0] = dm.k;
   mb.lo[1] = mb.hi[1] = mb.count[1] = 0;
   mlist_settle_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, skip_mask, mb, dm, band_idx, band_cnt, above_band,
                                                            list_ok);
   msel_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, skip_mask, mb, dm.N, dm.s1, 0, dm.s2, out,
                                                              dm.row_stride);
-  int rc = hip_ok(hipGetLastError());
-  if (rc) return rc;
-  return launch_select(dm, scores, skip_mask, dm.s1, dm.N - dm.s2, dm.k, dm.s1, 0, dm.s2, out, dm.row_stride, 0,
-                       mb.flag, s);
+  return hip_ok(hipGetLastError());
 }
 
 }  // namespace taskkv

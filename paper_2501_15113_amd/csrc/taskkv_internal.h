@@ -144,7 +144,8 @@ struct MSelBufs {
   unsigned long long *pat;       // [units] threshold pattern
   int *take_final;               // [units] entries equal to it that are taken
   int *counts;                   // [units][MSEL_MAX_SLICES][2] picks of every slice: above / at the threshold
-  double *band;                  // [3][units] band: the two thresholds, largest squared window-row norm
+  double *band;                  // [3][units] band: brackets of the two thresholds, largest squared window-row norm
+  int bracket;                   // 1 = the thresholds are wanted to their second digit only (the band's)
   int S, nsel;                   // slices per unit, thresholds wanted (1 or 2)
   int lo[2], hi[2], count[2];    // range and rank of each
 };
@@ -163,17 +164,15 @@ int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scor
 int launch_select_from_band(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const uint8_t *skip_mask,
                             const int32_t *band_idx, const int32_t *band_cnt, const int *above_band,
                             const int *list_ok, int32_t *out, hipStream_t s);
-// only_flagged: when given, units whose entry is 0 are left alone; sliced_ok:
-// when given, the entry of every unit the kernel lists is set to 0
 int launch_band(const Dims &dm, const double *scores, const double *qd, const unsigned long long *knorm,
-                int32_t *band_idx, int32_t *band_cnt, const int *only_flagged, int *sliced_ok, hipStream_t s);
+                int32_t *band_idx, int32_t *band_cnt, hipStream_t s);
 bool band_is_sliced(const Dims &dm, const struct ScreenBufs *scr);
 bool scores_screened(const Dims &dm, int dtype, const ScreenBufs *scr);
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,
                   double *stats, double *scores, const ScreenBufs *scr, const I8Bufs *i8, hipStream_t s);
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
                   int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
-                  const int *only_flagged, hipStream_t s);
+                  hipStream_t s);
 // top `count` among the columns an ascending per-unit list names ([units][N] entries, n_listed[unit] used)
 int launch_select_listed(const Dims &dm, const double *scores, const int32_t *listed, const int32_t *n_listed,
                          int count, int32_t *out, hipStream_t s);
