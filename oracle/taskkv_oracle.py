@@ -193,23 +193,25 @@ def kept_tokens_no_cache(N, is_hetero, n_sink, n_recent, n_extra):
 
 
 def round_to_storage(x, dtype):
-    """fp64 -> storage dtype with one round-to-nearest-even.  "f32": IEEE
-    conversion.  "bf16": returned as float32 holding bf16-representable values
-    (normal range assumed; the means of cached values are)."""
+    """fp64 -> storage dtype, round to nearest, ties to even.  "f32": IEEE
+    conversion.  "bf16": written out as the choice between the two bf16
+    neighbours of each value (bf16 = 8 significant bits, so the neighbours of
+    a = m * 2^E, 0.5 <= m < 1, are the multiples of 2^(E-8) around it); returned
+    as float32 holding bf16-representable values (normal range assumed; the
+    means of cached values are)."""
     x = _f64(x)
     if dtype == "f32":
         return x.astype(np.float32)
-    u = x.view(np.uint64) if x.flags["C_CONTIGUOUS"] else np.ascontiguousarray(x).view(np.uint64)
-    sign = (u >> np.uint64(63)).astype(np.uint32)
-    mag = u & np.uint64(0x7FFFFFFFFFFFFFFF)
-    lsb = (mag >> np.uint64(45)) & np.uint64(1)
-    mag = (mag + np.uint64((1 << 44) - 1) + lsb) >> np.uint64(45)        # 11-bit exponent + 7-bit mantissa
-    exp64 = (mag >> np.uint64(7)).astype(np.int64)
-    mant = (mag & np.uint64(0x7F)).astype(np.uint32)
-    exp32 = np.where(exp64 == 0, 0, exp64 - 896).astype(np.uint32)
-    mant = np.where(exp64 == 0, 0, mant).astype(np.uint32)
-    bits = (sign << np.uint32(31)) | (exp32 << np.uint32(23)) | (mant << np.uint32(16))
-    return bits.astype(np.uint32).view(np.float32).reshape(x.shape)
+    a = np.abs(x)
+    _, E = np.frexp(a)                               # a = m * 2^E
+    ulp = np.ldexp(1.0, E - 8)                       # spacing of bf16 values in [2^(E-1), 2^E)
+    steps = np.floor(a / ulp)                        # exact: a / ulp < 2^8 and ulp is a power of two
+    below, above = steps * ulp, (steps + 1.0) * ulp
+    d_below, d_above = a - below, above - a          # exact differences
+    take_above = (d_above < d_below) | ((d_above == d_below) & (np.mod(steps, 2.0) == 1.0))
+    nearest = np.where(take_above, above, below)
+    nearest = np.where(a == 0.0, 0.0, nearest)
+    return np.copysign(nearest, x).astype(np.float32)
 
 
 def compressed_cache(k, v, is_hetero, n_sink, n_recent, n_groups, dtype):

@@ -84,9 +84,13 @@ MISTAKES = [
     ("groups start one token late",
      "a, b = lo + (g * M) // n, lo + ((g + 1) * M) // n", "a, b = lo + (g * M) // n + (g > 0), lo + ((g + 1) * M) // n"),
     ("bf16 rounding breaks ties upwards",
-     "mag = (mag + np.uint64((1 << 44) - 1) + lsb) >> np.uint64(45)", "mag = (mag + np.uint64(1 << 44)) >> np.uint64(45)"),
+     "take_above = (d_above < d_below) | ((d_above == d_below) & (np.mod(steps, 2.0) == 1.0))",
+     "take_above = d_above <= d_below"),
     ("bf16 conversion truncates",
-     "mag = (mag + np.uint64((1 << 44) - 1) + lsb) >> np.uint64(45)", "mag = mag >> np.uint64(45)"),
+     "take_above = (d_above < d_below) | ((d_above == d_below) & (np.mod(steps, 2.0) == 1.0))",
+     "take_above = np.zeros(a.shape, dtype=bool)"),
+    ("bf16 spacing of the next binade",
+     "ulp = np.ldexp(1.0, E - 8)", "ulp = np.ldexp(1.0, E - 7)"),
     ("decode maps query heads by modulo",
      "        h = qi // G\n", "        h = qi % hkv\n"),
     ("decode logits not scaled",
