@@ -113,6 +113,48 @@ def cpu_baseline(wl, layers, budget_s=5.0):
                     "core in both legs, only the library routines inside use the pool"}
 
 
+def exact_vector_leg(ctx_len=8192, reps=3):
+    """The window approximation against the definition it replaces (Eq. 12-15 against Eq. 1-2) on the
+    8192-token workload's shapes: the separator with the workload's window (L, t), and with L = N, t = N,
+    where its vector is the exact one.  Both on the same queries (the window is their last L rows)."""
+    import dataclasses
+    import torch
+    from paper_2501_15113_amd import session
+    from taskkv_synth import WORKLOADS, make_layer
+
+    base = WORKLOADS["cfg2"]
+    wl_full = dataclasses.replace(base, name="cfg2_exact", ctx_len=ctx_len, obs_window=ctx_len, top_t=ctx_len)
+    wl_win = dataclasses.replace(base, name="cfg2_window", ctx_len=ctx_len)
+    ld = make_layer(wl_full, 0, "cuda:0")
+    q_win = ld.q_win[:, :, ctx_len - wl_win.obs_window:, :].contiguous()
+    res = {}
+    for tag, wl, q in (("exact", wl_full, ld.q_win), ("window", wl_win, q_win)):
+        cfg = session.cfg_from_workload(wl)
+        bufs = session.LayerBuffers(cfg, 0)
+        with session.Context([cfg], 0) as ctx:
+            bufs.separate(ctx, q, ld.k, ld.v)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                bufs.separate(ctx, q, ld.k, ld.v)
+            e1.record()
+            torch.cuda.synchronize()
+        res[tag] = (bufs.sem_vec[0].clone(), bufs.mask[0].clone(), e0.elapsed_time(e1) / reps)
+    v, vw = res["exact"][0], res["window"][0]
+    rel = ((vw - v).norm(dim=1) / v.norm(dim=1)).cpu()
+    cos = ((vw * v).sum(dim=1) / (vw.norm(dim=1) * v.norm(dim=1))).cpu()
+    agree = int((res["exact"][1] == res["window"][1]).sum().item())
+    return {"workload": f"cfg2 shapes, batch 1, N={ctx_len}: window L={wl_win.obs_window}, t={wl_win.top_t} "
+                        f"against L=N, t=N",
+            "rel_err_mean": float(rel.mean()), "rel_err_max": float(rel.max()),
+            "cosine_mean": float(cos.mean()), "cosine_min": float(cos.min()),
+            "note": "Eq. 15 sums the top-t tokens' share of the attention mass only, so the window's vector is "
+                    "shorter than the exact one by about that share; the head ranking is what it has to keep",
+            "mask_agreement": f"{agree}/{wl_win.n_kv_heads} heads",
+            "separator_ms_exact": res["exact"][2], "separator_ms_window": res["window"][2]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -145,6 +187,7 @@ def main():
         out["also_cfg4"] = pick(measure(args, "cfg4", False, False, k_extra, w_extra))
         out["also_cfg3"] = {"per_layer": pick(measure(args, "cfg3", False, False, min(k_extra, 3), w_extra)),
                             "stacked": pick(measure(args, "cfg3", False, True, min(k_extra, 3), w_extra))}
+        out["exact_semantic_vector"] = exact_vector_leg()
     print(json.dumps(out))
 
 

@@ -177,6 +177,44 @@ def test_full_window_reproduces_exact_semantic_vector():
         np.testing.assert_allclose(sem[h], orc.full_semantic_vector(q[h], k[h], v[h]), rtol=1e-9, atol=1e-13)
 
 
+def test_window_approximation_against_the_exact_vector():
+    """Eq. 12-15 against Eq. 1-2 on the 8192-token workload's head shapes at
+    N = 2048: the separator with the workload's window (last 32 queries, top
+    256 tokens) and with L = N, t = N on the same queries.  Both runs match the
+    oracle; the relative error of the window's vectors and the heads on which
+    the two masks agree are the oracle's, i.e. properties of the method on
+    this seeded data and not of the kernels."""
+    import dataclasses
+    from oracle import taskkv_oracle as orc
+    from taskkv_synth import WORKLOADS
+    ses = _session()
+    N = 2048
+    base = WORKLOADS["cfg2"]
+    wl_full = dataclasses.replace(base, name="exact2k", ctx_len=N, obs_window=N, top_t=N)
+    wl_win = dataclasses.replace(base, name="window2k", ctx_len=N)
+    ld = make_layer(wl_full, 0, "cuda:0")
+    q_win = ld.q_win[:, :, N - wl_win.obs_window:, :].contiguous()
+    got, ref = {}, {}
+    for tag, wl, q in (("exact", wl_full, ld.q_win), ("window", wl_win, q_win)):
+        cfg = ses.cfg_from_workload(wl)
+        bufs = ses.LayerBuffers(cfg, 0)
+        with ses.Context([cfg], 0) as ctx:
+            bufs.separate(ctx, q, ld.k, ld.v)
+            torch.cuda.synchronize()
+        got[tag] = (bufs.sem_vec[0].cpu().numpy(), bufs.mask[0].cpu().numpy())
+        sep = orc.separate(to_numpy(q[0]), to_numpy(ld.k[0]), to_numpy(ld.v[0]), cfg.top_t, cfg.n_hetero,
+                           bool(cfg.add_centre_head))
+        ref[tag] = (sep["sem_vec"], sep["mask"])
+        np.testing.assert_allclose(got[tag][0], ref[tag][0], rtol=1e-9, atol=1e-13)
+        assert (got[tag][1] == ref[tag][1]).all()
+    rel = lambda r: np.linalg.norm(r["window"][0] - r["exact"][0], axis=1) / np.linalg.norm(r["exact"][0], axis=1)
+    np.testing.assert_allclose(rel(got), rel(ref), rtol=1e-7)
+    agree = int((got["window"][1] == got["exact"][1]).sum())
+    assert agree == int((ref["window"][1] == ref["exact"][1]).sum())
+    # what the approximation is for: the heads it marks are the heads the exact vectors mark
+    assert agree == wl_win.n_kv_heads, (agree, rel(got))
+
+
 # ------------------------------------------------------------------ ablation pack modes (Sec. 6.2)
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("kw", [
