@@ -129,9 +129,15 @@ int taskkv_layer_plan(int32_t n_heads, double beta, int32_t m_top, int32_t n_lay
  *                             token that can take part in a decision (the top-t
  *                             tokens and all tokens whose score is next to the
  *                             top-t or middle-activation threshold); with bf16
- *                             inputs the remaining tokens carry an fp32-accurate
- *                             value (relative error below ~1e-3) unless
- *                             screening is switched off (taskkv_set_screening)
+ *                             inputs the remaining tokens carry an fp32 value
+ *                             whose relative error is bounded by eps =
+ *                             scale * 4 d 2^-24 * max|q_i| * max|k_j| + 2e-5 +
+ *                             G L 1.2e-7 (about 1e-3 on the named workloads;
+ *                             the tests check 5e-3) unless screening is
+ *                             switched off (taskkv_set_screening).  Such scores
+ *                             are good for the selections of this cfg only,
+ *                             and taskkv_compress assumes that the array still
+ *                             holds what this call wrote
  *   sem_vec [B, H_kv, d] f64  v' of Eq. 15 over the top-t tokens of Eq. 14
  *   dist    [B, H_kv]    f64  L2 distance of v' from the mean over heads (Eq. 7-8)
  *   hetero_mask [B, H_kv] u8  1 = heterogeneous (keeps its full cache)
@@ -161,13 +167,17 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
  *                              TASKKV_PACK_COMPRESSED mode a compensation token is
  *                              listed by the first position of its group
  * capacity_tokens must be >= taskkv_cache_tokens(cfg, reserve_decode_tokens)
- * (else TASKKV_ECAPACITY).  cfg must name the same ctx_len, n_sink, n_recent,
- * n_middle, pack_mode and pool_kernel as the taskkv_separate call that produced
- * `scores` whenever that call screened them (see taskkv_set_screening): the
- * fp32 values off the decision columns are good for that selection only.  The
- * library checks this for the scores buffer of the ctx's last screening
- * taskkv_separate and returns TASKKV_EINVAL on a mismatch; switch screening off
- * to compress one set of scores under several budgets.  Middle tokens are the n_middle best of the pooled
+ * (else TASKKV_ECAPACITY).  cfg must name the same batch, n_kv_heads, ctx_len,
+ * n_sink, n_recent, n_middle, pack_mode and pool_kernel as the taskkv_separate
+ * call that produced `scores` whenever that call screened them (see
+ * taskkv_set_screening): the fp32 values off the decision columns are good for
+ * that selection only.  The library checks this for the scores buffer of the
+ * ctx's last screening taskkv_separate and returns TASKKV_EINVAL on a mismatch;
+ * switch screening off to compress one set of scores under several budgets, or
+ * to edit them between the two calls (when no other call on the ctx came in
+ * between, the middle pick reuses the column lists that call left in the
+ * workspace and relies on `scores` being unchanged).
+ * Middle tokens are the n_middle best of the pooled
  * scores inside [s1, N - s2), ties to the lower index; rows are copied
  * bit-for-bit; slots past a unit's length are zero-filled.  In
  * TASKKV_PACK_COMPRESSED mode group g of n covers middle offsets
@@ -284,8 +294,11 @@ int taskkv_set_screening(taskkv_ctx *ctx, int mode);
 /* Row maxima and softmax denominators of the window scores (Eq. 12) are needed
  * to fp64 accuracy.  For bf16 inputs they come from exact integer dot products
  * on the int8 matrix cores (engine 1, default); engine 0 uses the fp64 matrix
- * instruction, as fp32 inputs always do.  Both give the same decisions and
- * scores that agree to fp64 rounding. */
+ * instruction, as fp32 inputs always do.  Engine 1 evaluates its exponentials
+ * from a table and a cubic (relative error 2e-13), so the two engines' scores
+ * agree to about 1e-13 relative, not to the last bit; decisions (top-t, middle
+ * pick, head ranking) are the same wherever the margin between the competing
+ * values exceeds that (the parity tests demand 1e-9 of their inputs). */
 int taskkv_set_stats_engine(taskkv_ctx *ctx, int engine);
 
 /* Decode attention (Eq. 1 on the kept keys) deals the pages of a step to the
