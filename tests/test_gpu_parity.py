@@ -647,3 +647,28 @@ def test_compress_rejects_screened_scores_under_another_budget():
                 with pytest.raises(tk.TaskKVError, match="invalid argument"):
                     bufs2.compress(ctx, ld.k, ld.v)
             bufs.compress(ctx, ld.k, ld.v)
+
+
+def test_middle_pick_with_and_without_the_separators_column_lists():
+    """On a long screened layer the compressor takes its middle threshold from
+    the column lists the separator left in the workspace.  A decode call on the
+    same ctx in between overwrites them: the compressor must notice and select
+    from the scores alone, with the same result."""
+    ses = _session()
+    wl = small_workload(name="lists", wid=163, batch=1, ctx_len=36000, n_middle=1500, top_t=256, decode_steps=2)
+    ld = make_layer(wl, 0, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    direct, detour = ses.LayerBuffers(cfg, 2), ses.LayerBuffers(cfg, 2)
+    with ses.Context([cfg], 2, screening=2) as ctx:
+        direct.separate(ctx, ld.q_win, ld.k, ld.v)
+        direct.compress(ctx, ld.k, ld.v)
+        detour.separate(ctx, ld.q_win, ld.k, ld.v)
+        direct.decode(ctx, *ld.decode_inputs(0))          # reuses the workspace
+        detour.compress(ctx, ld.k, ld.v)
+        torch.cuda.synchronize()
+    assert torch.equal(direct.kept_idx, detour.kept_idx) and torch.equal(direct.mask, detour.mask)
+    ref = oracle_layer(ld, 0, cfg)
+    kept = detour.kept_idx.cpu().numpy().reshape(wl.batch, wl.n_kv_heads, -1)[0]
+    for h in range(wl.n_kv_heads):
+        if not ref["mask"][h]:
+            assert kept[h, :len(ref["kept"][h])].tolist() == ref["kept"][h].tolist()
