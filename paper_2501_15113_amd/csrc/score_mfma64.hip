@@ -56,51 +56,49 @@ __global__ void q_to_f64_kernel(const T *__restrict__ q, double *__restrict__ qd
   qd[idx] = val;
 }
 
-// Fixed-order merge of the per-part row statistics.  Eight adjacent lanes share
-// a row: lane i of them merges the parts i, i + 8, ... (records requested four
-// at a time: the loop is bound by memory latency), then the eight results are
-// merged in a fixed tree.  Launched with 1024 threads: 128 rows at a time.
+// Fixed-order merge of the per-part row statistics.  A wave shares a row: lane
+// i merges the parts i, i + 64, ... (records requested four at a time: the loop
+// is bound by memory latency), then the 64 results are merged in a fixed tree.
+// Launched with 1024 threads: 16 rows per block.
 __global__ __launch_bounds__(1024) void merge_stats_kernel(const double *__restrict__ part,
                                                            double *__restrict__ stats, int Rpad, int n_parts) {
-  const int unit = blockIdx.x, sub = threadIdx.x & 7;
-  for (int r0 = 0; r0 < Rpad; r0 += 128) {
-    const int r = r0 + (threadIdx.x >> 3);
-    const bool live = r < Rpad;
-    double m = -INFINITY, l = 0.0;
-    for (int c0 = sub; c0 < n_parts; c0 += 32) {
-      double mc[4], lc[4];
+  const int unit = blockIdx.x, sub = threadIdx.x & 63;
+  const int r = blockIdx.y * 16 + (threadIdx.x >> 6);
+  if (r >= Rpad) return;   // whole waves
+  double m = -INFINITY, l = 0.0;
+  for (int c0 = sub; c0 < n_parts; c0 += 256) {
+    double mc[4], lc[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const bool ok = live && c0 + 8 * u < n_parts;
-        const double *pp = part + (((size_t)unit * n_parts + (ok ? c0 + 8 * u : 0)) * Rpad + (live ? r : 0)) * 2;
-        mc[u] = ok ? pp[0] : -INFINITY;
-        lc[u] = ok ? pp[1] : 0.0;
-      }
-      double mn = m;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) mn = fmax(mn, mc[u]);
-      if (mn > -INFINITY) {
-        double sum = l * exp(m - mn);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) sum += lc[u] * exp(mc[u] - mn);
-        l = sum;
-        m = mn;
-      }
+    for (int u = 0; u < 4; ++u) {
+      const bool ok = c0 + 64 * u < n_parts;
+      const double *pp = part + (((size_t)unit * n_parts + (ok ? c0 + 64 * u : 0)) * Rpad + r) * 2;
+      mc[u] = ok ? pp[0] : -INFINITY;
+      lc[u] = ok ? pp[1] : 0.0;
     }
+    double mn = m;
 #pragma unroll
-    for (int off = 1; off < 8; off <<= 1) {
-      const double mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
-      const double mn = fmax(m, mo);
-      // both partners form the same sum: the lower lane's term first
-      const bool low = (sub & off) == 0;
-      const double a = low ? l : lo, am = low ? m : mo, b = low ? lo : l, bm = low ? mo : m;
-      if (mn > -INFINITY) l = a * exp(am - mn) + b * exp(bm - mn);
+    for (int u = 0; u < 4; ++u) mn = fmax(mn, mc[u]);
+    if (mn > -INFINITY) {
+      double sum = l * exp(m - mn);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sum += lc[u] * exp(mc[u] - mn);
+      l = sum;
       m = mn;
     }
-    if (live && sub == 0) {
-      stats[((size_t)unit * Rpad + r) * 2] = m;
-      stats[((size_t)unit * Rpad + r) * 2 + 1] = l;
-    }
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const double mo = __shfl_xor(m, off), lo = __shfl_xor(l, off);
+    const double mn = fmax(m, mo);
+    // both partners form the same sum: the lower lane's term first
+    const bool low = (sub & off) == 0;
+    const double a = low ? l : lo, am = low ? m : mo, b = low ? lo : l, bm = low ? mo : m;
+    if (mn > -INFINITY) l = a * exp(am - mn) + b * exp(bm - mn);
+    m = mn;
+  }
+  if (sub == 0) {
+    stats[((size_t)unit * Rpad + r) * 2] = m;
+    stats[((size_t)unit * Rpad + r) * 2 + 1] = l;
   }
 }
 
@@ -383,11 +381,11 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
       // bf16 inputs: exact integer dot products on the int8 matrix cores
       int rc = launch_i8_stats(dm, q_win, k, qd, *i8b, part, screen ? scr->knorm : nullptr, n_wg, cpw * SKC, s);
       if (rc) return rc;
-      merge_stats_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_wg);
+      merge_stats_kernel<<<dim3(dm.units, (dm.Rpad + 15) / 16), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_wg);
     } else {
       score_mfma64_kernel<T, D, 0, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
                                                                 nullptr);
-      merge_stats_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_parts);
+      merge_stats_kernel<<<dim3(dm.units, (dm.Rpad + 15) / 16), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_parts);
     }
     if (!screen) {
       score_mfma64_kernel<T, D, 1, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,

@@ -435,9 +435,12 @@ __global__ __launch_bounds__(1024) void mband_close_kernel(const double *__restr
   }
   int32_t *row = band_idx + (size_t)unit * N;
   const int seg = slice_len(N, mb.S);
-  int total = mb.counts[counts_at(unit, 0)];
+  __shared__ int s_n[MSEL_MAX_SLICES];   // one trip to memory for all counts
+  if (tid < mb.S) s_n[tid] = mb.counts[counts_at(unit, tid)];
+  __syncthreads();
+  int total = s_n[0];
   for (int s = 1; s < mb.S; ++s) {
-    const int c = mb.counts[counts_at(unit, s)];
+    const int c = s_n[s];
     const int32_t *src = row + min(N, s * seg);
     int32_t *dst = row + total;
     if (dst != src) {
