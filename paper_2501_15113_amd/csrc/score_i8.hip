@@ -630,11 +630,12 @@ bool i8_stats_supported(const Dims &dm, int dtype) {
 // Row statistics of one row group: digits of the window rows, then the
 // statistics partials; n_wg key ranges of keys_per_wg keys each.
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
-                    double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, hipStream_t s) {
+                    double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, bool qcnt_zeroed,
+                    hipStream_t s) {
   const int n_rb = dm.Rpad / 32;
   auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
   auto qdig = static_cast<v4i *>(bufs.qdig);
-  zero_i32_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(bufs.qcnt, dm.units);
+  if (!qcnt_zeroed) zero_i32_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(bufs.qcnt, dm.units);
   const bool small = n_rb <= 4;   // at most 128 window rows: blocks of four waves
   const int rows_per_block = small ? 128 : 256;
   const dim3 grid(n_wg, dm.units, (dm.Rpad + rows_per_block - 1) / rows_per_block);

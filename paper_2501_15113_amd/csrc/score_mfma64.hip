@@ -37,9 +37,13 @@ __device__ __forceinline__ float elem_to_float(uint16_t x) { return __uint_as_fl
 
 // Rows [row0, row0 + R) of the flattened window (row = g*L + i) of every unit
 // -> qd [unit][Rpad][D] fp64, zero padded.
+// Also clears the words of `zeros` (counters and histograms of the kernels
+// that follow on the stream).
 template <typename T>
-__global__ void q_to_f64_kernel(const T *__restrict__ q, double *__restrict__ qd, Dims dm) {
+__global__ void q_to_f64_kernel(const T *__restrict__ q, double *__restrict__ qd, Dims dm, ZeroList zeros) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (int z = 0; z < zeros.count; ++z)
+    for (size_t i = idx; i < zeros.n[z]; i += (size_t)gridDim.x * blockDim.x) zeros.p[z][i] = 0u;
   size_t total = (size_t)dm.units * dm.Rpad * dm.D;
   if (idx >= total) return;
   int c = idx % dm.D;
@@ -352,8 +356,15 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
   // the int8 statistics pass reads every key anyway and leaves the key norms
   // the screening pass needs; otherwise they get a pass of their own
   const bool i8 = i8b != nullptr && i8_stats_supported(dm_all, dtype);
-  if (screen) {
-    int rc = i8 ? launch_zero_u64(scr->knorm, dm_all.units, s) : launch_key_norms(dm_all, k, scr->knorm, s);
+  // counters and histograms of the kernels below are cleared by the first
+  // kernel of the sequence instead of by launches of their own
+  ZeroList zeros;
+  if (i8) zeros.add(i8b->qcnt, (size_t)dm_all.units);
+  if (screen && i8) zeros.add(scr->knorm, (size_t)2 * dm_all.units);
+  const bool sliced_band = screen && band_is_sliced(dm_all, scr);
+  if (sliced_band) msel_zero_words(dm_all, *scr->msel, zeros);
+  if (screen && !i8) {
+    int rc = launch_key_norms(dm_all, k, scr->knorm, s);
     if (rc) return rc;
   }
   for (int grp = 0; grp < n_groups; ++grp) {
@@ -371,7 +382,8 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
       dm.n_keys = (int)(vis < dm.N ? vis : dm.N);
     }
     const size_t total = (size_t)dm.units * dm.Rpad * dm.D;
-    q_to_f64_kernel<T><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(q_win, qd, dm);
+    q_to_f64_kernel<T><<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(q_win, qd, dm,
+                                                                                    grp == 0 ? zeros : ZeroList());
     const int n_chunks = (dm.n_keys + SKC - 1) / SKC;
     const int n_wg = (n_chunks + cpw - 1) / cpw;
     const int n_pairs = dm.Rpad / 32;
@@ -379,7 +391,7 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     const dim3 grid(n_wg, dm.units), block(64 * SNW);
     if (i8) {
       // bf16 inputs: exact integer dot products on the int8 matrix cores
-      int rc = launch_i8_stats(dm, q_win, k, qd, *i8b, part, screen ? scr->knorm : nullptr, n_wg, cpw * SKC, s);
+      int rc = launch_i8_stats(dm, q_win, k, qd, *i8b, part, screen ? scr->knorm : nullptr, n_wg, cpw * SKC, grp == 0, s);
       if (rc) return rc;
       merge_stats_kernel<<<dim3(dm.units, (dm.Rpad + 15) / 16), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_wg);
     } else {
@@ -396,9 +408,9 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     // part in a decision (any number of them: the grid covers all N)
     int rc = launch_screen(dm, q_win, k, stats, scores, cpw, s);
     if (rc) return rc;
-    if (band_is_sliced(dm, scr))
+    if (sliced_band)
       rc = launch_band_sliced(dm, scr->n_cu, *scr->msel, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt,
-                              scr->above_band, scr->list_ok, s);
+                              scr->above_band, scr->list_ok, true, s);
     else
       rc = launch_band(dm, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt, s);
     if (rc) return rc;

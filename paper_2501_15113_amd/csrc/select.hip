@@ -65,20 +65,21 @@ __global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__
   const int32_t *idx = top_idx + (size_t)unit * dm.T;
   __shared__ double red[16][128];
   double acc = 0.0;
-  for (int n0 = grp; n0 < dm.T; n0 += 4 * n_grp) {
-    // four picks of the group at a time: their index, score and value loads
+  constexpr int U = 16;
+  for (int n0 = grp; n0 < dm.T; n0 += U * n_grp) {
+    // sixteen picks of the group at a time: their index, score and value loads
     // overlap instead of forming one chain per pick
-    int j[4];
+    int j[U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) j[u] = n0 + u * n_grp < dm.T ? idx[n0 + u * n_grp] : -1;
-    double w[4], x[4];
+    for (int u = 0; u < U; ++u) j[u] = n0 + u * n_grp < dm.T ? idx[n0 + u * n_grp] : -1;
+    double w[U], x[U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       w[u] = j[u] >= 0 ? sc[j[u]] : 0.0;
       x[u] = j[u] >= 0 ? elem_to_double(vb[(size_t)j[u] * D + c]) : 0.0;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) acc += w[u] * x[u];   // same order as one pick at a time
+    for (int u = 0; u < U; ++u) acc += w[u] * x[u];   // same order as one pick at a time
   }
   red[grp][c] = acc;
   __syncthreads();

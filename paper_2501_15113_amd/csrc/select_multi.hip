@@ -499,10 +499,17 @@ bool msel_carve(Carver &cv, const Dims &dm, MSelBufs &mb) {
   return cv.ok;
 }
 
+// What msel_clear_kernel clears.
+void msel_zero_words(const Dims &dm, const MSelBufs &mb, ZeroList &z) {
+  z.add(mb.hist, (size_t)4 * dm.units * 4096);
+  z.add(mb.n_cand, (size_t)2 * dm.units);
+  z.add(mb.flag, (size_t)dm.units);
+}
+
 static void msel_histograms(const Dims &dm, const double *scores, const uint8_t *skip, const MSelBufs &mb,
-                            hipStream_t s) {
+                            hipStream_t s, bool cleared = false) {
   const size_t n = (size_t)4 * dm.units * 4096;
-  msel_clear_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(mb, dm.units);
+  if (!cleared) msel_clear_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(mb, dm.units);
   const dim3 grid(mb.S, dm.units), block(1024);
   msel_hist1_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
   msel_hist2_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
@@ -530,13 +537,13 @@ int launch_select_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *sc
 
 int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *qd,
                        const unsigned long long *knorm, int32_t *band_idx, int32_t *band_cnt, int *above_band,
-                       int *list_ok, hipStream_t s) {
+                       int *list_ok, bool cleared, hipStream_t s) {
   mb.S = msel_slices(dm, n_cu);
   mb.nsel = band_has_middle(dm) ? 2 : 1;
   mb.lo[0] = 0; mb.hi[0] = dm.N; mb.count[0] = dm.T;
   mb.lo[1] = dm.s1; mb.hi[1] = dm.N - dm.s2; mb.count[1] = dm.k;
   mb.bracket = 1;
-  msel_histograms(dm, scores, nullptr, mb, s);
+  msel_histograms(dm, scores, nullptr, mb, s, cleared);
   mband_brackets_kernel<<<dim3(dm.units, 3), dim3(1024), 0, s>>>(mb, dm, qd);
   mband_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, knorm, mb, dm, band_idx, above_band);
   mband_close_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, mb, dm, band_idx, band_cnt, list_ok);

@@ -91,6 +91,19 @@ __device__ __forceinline__ int find_unit(const int64_t *__restrict__ offsets, in
   return lo;
 }
 
+// Words a kernel at the head of a sequence sets to zero for the kernels behind
+// it (counters, histograms), which saves them a launch of their own.
+struct ZeroList {
+  uint32_t *p[6];
+  size_t n[6];   // 32-bit words
+  int count;
+  ZeroList() : count(0) {}
+  void add(void *ptr, size_t words) {
+    p[count] = static_cast<uint32_t *>(ptr);
+    n[count++] = words;
+  }
+};
+
 // ---- launchers (each validates nothing; api.hip has checked the arguments) ----
 int score_parts(const Dims &dm);
 int score_rows_padded(const Dims &dm);
@@ -120,8 +133,10 @@ struct I8Bufs {
   taskkv_ctx *prof; // ctx whose profiling hook may time the statistics kernel (or null)
 };
 bool i8_stats_supported(const Dims &dm, int dtype);
+// qcnt_zeroed: bufs.qcnt has been set to zero by an earlier kernel on the stream
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
-                    double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, hipStream_t s);
+                    double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, bool qcnt_zeroed,
+                    hipStream_t s);
 int launch_zero_u64(unsigned long long *p, int n, hipStream_t s);
 bool screen_supported(const Dims &dm, int dtype);
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);
@@ -156,9 +171,11 @@ bool msel_pays(const Dims &dm, int n_cu, int lo, int hi, int count);
 int launch_select_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const uint8_t *skip_mask, int lo,
                          int hi, int count, int prefix, int gap, int suffix, int32_t *out, int out_stride,
                          hipStream_t s);
+// cleared: the words of msel_zero_words have been set to zero by an earlier kernel on the stream
 int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *qd,
                        const unsigned long long *knorm, int32_t *band_idx, int32_t *band_cnt, int *above_band,
-                       int *list_ok, hipStream_t s);
+                       int *list_ok, bool cleared, hipStream_t s);
+void msel_zero_words(const Dims &dm, const MSelBufs &mb, ZeroList &z);
 // The middle pick on screened scores whose band lists are still there: the
 // threshold is one of the listed columns, so no sweep is needed to find it.
 int launch_select_from_band(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const uint8_t *skip_mask,
