@@ -438,20 +438,40 @@ __global__ __launch_bounds__(1024) void mband_close_kernel(const double *__restr
   __shared__ int s_n[MSEL_MAX_SLICES];   // one trip to memory for all counts
   if (tid < mb.S) s_n[tid] = mb.counts[counts_at(unit, tid)];
   __syncthreads();
-  int total = s_n[0];
-  for (int s = 1; s < mb.S; ++s) {
-    const int c = s_n[s];
-    const int32_t *src = row + min(N, s * seg);
-    int32_t *dst = row + total;
-    if (dst != src) {
-      for (int off = 0; off < c; off += 1024) {
-        const int32_t v = off + tid < c ? src[off + tid] : 0;
-        __syncthreads();
-        if (off + tid < c) dst[off + tid] = v;
-        __syncthreads();
-      }
+  int total = 0;
+  for (int s = 0; s < mb.S; ++s) total += s_n[s];
+  constexpr int CLOSE_U = 8;
+  if (total <= 1024 * CLOSE_U) {
+    // the usual case, a few thousand columns: every thread reads its entries of
+    // the closed list from wherever their slices put them, then all write
+    int32_t v[CLOSE_U];
+#pragma unroll
+    for (int i = 0; i < CLOSE_U; ++i) {
+      const int p = tid + 1024 * i;
+      int s = 0, before = 0;
+      while (s < mb.S - 1 && p >= before + s_n[s]) before += s_n[s++];
+      v[i] = p < total ? row[min(N, s * seg) + (p - before)] : 0;
     }
-    total += c;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < CLOSE_U; ++i)
+      if (tid + 1024 * i < total) row[tid + 1024 * i] = v[i];
+  } else {
+    total = s_n[0];
+    for (int s = 1; s < mb.S; ++s) {
+      const int c = s_n[s];
+      const int32_t *src = row + min(N, s * seg);
+      int32_t *dst = row + total;
+      if (dst != src) {
+        for (int off = 0; off < c; off += 1024) {
+          const int32_t v = off + tid < c ? src[off + tid] : 0;
+          __syncthreads();
+          if (off + tid < c) dst[off + tid] = v;
+          __syncthreads();
+        }
+      }
+      total += c;
+    }
   }
   if (tid == 0) band_cnt[unit] = total;
 }

@@ -315,12 +315,14 @@ def test_statistics_engines_agree():
 
 
 # ------------------------------------------------------------------ ties
-def test_all_equal_scores_take_lowest_positions():
+@pytest.mark.parametrize("ctx_len", [900, 33000])
+def test_all_equal_scores_take_lowest_positions(ctx_len):
     """K == 0 makes every score before the window equal: the tie rule alone
-    decides the top-t set and the middle pick."""
+    decides the top-t set and the middle pick.  (The long context is one whose
+    selections several blocks share: every column lands in the screening band.)"""
     def zero_k(ld):
         ld.k.zero_()
-    wl = small_workload(name="ties", wid=152, ctx_len=900, n_hetero=1)
+    wl = small_workload(name="ties", wid=152, ctx_len=ctx_len, n_hetero=1, batch=2 if ctx_len < 1000 else 1)
     bufs, refs = run_layer(wl, mutate=zero_k)
     kept = bufs.kept_idx.cpu().numpy()
     h = int(np.flatnonzero(refs[0]["mask"] == 0)[0])
