@@ -445,10 +445,10 @@ __global__ __launch_bounds__(1024) void mband_close_kernel(const double *__restr
     // the usual case, a few thousand columns: every thread reads its entries of
     // the closed list from wherever their slices put them, then all write
     int32_t v[CLOSE_U];
+    int s = 0, before = 0;   // slice of the thread's current entry (its entries ascend)
 #pragma unroll
     for (int i = 0; i < CLOSE_U; ++i) {
       const int p = tid + 1024 * i;
-      int s = 0, before = 0;
       while (s < mb.S - 1 && p >= before + s_n[s]) before += s_n[s++];
       v[i] = p < total ? row[min(N, s * seg) + (p - before)] : 0;
     }
