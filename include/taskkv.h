@@ -84,7 +84,8 @@ typedef struct taskkv_layer_cfg {
 
 /*
  * Create a context on `device_id` with `workspace_bytes` of scratch (see
- * taskkv_workspace_bytes).  Allocates; the only call besides destroy that does. */
+ * taskkv_workspace_bytes).  Allocates device memory; the only call that does
+ * (the first taskkv_profile_enable creates HIP events, nothing else allocates). */
 int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes);
 void taskkv_destroy(taskkv_ctx *ctx);
 const char *taskkv_strerror(int status);
