@@ -137,14 +137,14 @@ __global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restri
   int a, b;
   slice_of(N, s, mb.S, a, b);
   if (a >= b) return;
-  __shared__ unsigned h[2][4096];
+  __shared__ unsigned h[2 * 4096];   // one histogram per threshold
   const bool two = mb.nsel > 1;
   for (int j0 = a; j0 < b; j0 += SLICE_U * 1024) {
     uint64_t key[SLICE_U];
 #pragma unroll
     for (int r = 0; r < SLICE_U; ++r) key[r] = score_key(sc[min(j0 + r * 1024 + tid, b - 1)]);
     if (j0 == a) {   // with the first loads in flight
-      for (int i = tid; i < 2 * 4096; i += 1024) h[0][i] = 0;
+      for (int i = tid; i < 2 * 4096; i += 1024) h[i] = 0;
       __syncthreads();
     }
 #pragma unroll
@@ -152,8 +152,8 @@ __global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restri
       const int j = j0 + r * 1024 + tid;
       if (j < b) {
         const int d = digit1(key[r]);
-        if (j >= mb.lo[0] && j < mb.hi[0]) atomicAdd(&h[0][d], 1u);
-        if (two && j >= mb.lo[1] && j < mb.hi[1]) atomicAdd(&h[1][d], 1u);
+        if (j >= mb.lo[0] && j < mb.hi[0]) atomicAdd(&h[d], 1u);
+        if (two && j >= mb.lo[1] && j < mb.hi[1]) atomicAdd(&h[4096 + d], 1u);
       }
     }
   }
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restri
   for (int sel = 0; sel < mb.nsel; ++sel) {
     unsigned *g = mb.hist + hist_at(0, sel, unit, units);
     for (int i = tid; i < 4096; i += 1024)
-      if (h[sel][i]) atomicAdd(&g[i], h[sel][i]);
+      if (h[sel * 4096 + i]) atomicAdd(&g[i], h[sel * 4096 + i]);
   }
 }
 
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(1024) void msel_hist2_kernel(const double *__restri
   const int s = blockIdx.x, unit = blockIdx.y, units = gridDim.y, tid = threadIdx.x;
   if (skip && skip[unit]) return;
   __shared__ PickScratch ps;
-  __shared__ unsigned h[2][4096];
+  __shared__ unsigned h[2 * 4096];
   Wanted w[2];
   w[0] = wanted_level1(mb, 0, unit, units, ps);
   w[1] = w[0];
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(1024) void msel_hist2_kernel(const double *__restri
   int a, b;
   slice_of(N, s, mb.S, a, b);
   if (a >= b) return;
-  for (int i = tid; i < 2 * 4096; i += 1024) h[0][i] = 0;
+  for (int i = tid; i < 2 * 4096; i += 1024) h[i] = 0;
   __syncthreads();
   for (int j0 = a; j0 < b; j0 += SWEEP_U * 1024) {
     uint64_t key[SWEEP_U];
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(1024) void msel_hist2_kernel(const double *__restri
 #pragma unroll
         for (int sel = 0; sel < 2; ++sel)
           if (w[sel].level2 && j >= mb.lo[sel] && j < mb.hi[sel] && (key[r] & w[sel].known) == w[sel].pat)
-            atomicAdd(&h[sel][digit2(key[r])], 1u);
+            atomicAdd(&h[sel * 4096 + digit2(key[r])], 1u);
       }
     }
   }
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(1024) void msel_hist2_kernel(const double *__restri
     if (sel >= mb.nsel || !w[sel].level2) continue;
     unsigned *g = mb.hist + hist_at(1, sel, unit, units);
     for (int i = tid; i < 4096; i += 1024)
-      if (h[sel][i]) atomicAdd(&g[i], h[sel][i]);
+      if (h[sel * 4096 + i]) atomicAdd(&g[i], h[sel * 4096 + i]);
   }
 }
 
