@@ -233,15 +233,21 @@ def test_softmax_scale_override():
     run_layer(small_workload(name="scale", wid=150), cfg_override=dict(softmax_scale=0.05))
 
 
-@pytest.mark.parametrize("dtype,ctx_len", [("bf16", 6000), ("f32", 1500)])
-@pytest.mark.parametrize("scale", [3.0, 1.0, 1e-3, 1e-6])
+@pytest.mark.parametrize("dtype,ctx_len,scale", [(d, n, s) for d, n in (("bf16", 6000), ("f32", 1500))
+                                                 for s in (3.0, 1.0, 1e-3, 1e-6)] +
+                         # (weights this uniform over 33000 columns leave margins below 1e-9: no 1e-6 there)
+                         [("bf16", 33000, s) for s in (10.0, 3.0, 1.0, 1e-3)])
 def test_peaky_and_flat_softmax(dtype, ctx_len, scale):
     """Logits of the order of +-100 (a softmax that is nearly one-hot) down to
     1e-4 (nearly uniform weights, decision margins near the 1e-9 limit): the
     statistics, the selections and the attention outputs hold their bars.  (In
     fp32 arithmetic the error of a logit grows with its size; at scale 3 the
-    attention error reaches 6.5e-6 of the 1e-5 allowed.)"""
-    run_layer(small_workload(name=f"peaky-{dtype}-{scale}", wid=240, dtype=dtype, ctx_len=ctx_len, n_hetero=2),
+    attention error reaches 6.5e-6 of the 1e-5 allowed.)  The longest context
+    is one whose selections several blocks share, with a middle budget deep
+    inside the scores that a peaky softmax flushes to zero in fp32."""
+    long_ctx = ctx_len > 32768
+    run_layer(small_workload(name=f"peaky-{dtype}-{scale}", wid=240, dtype=dtype, ctx_len=ctx_len, n_hetero=2,
+                             batch=1 if long_ctx else 2, n_middle=20000 if long_ctx else 64),
               cfg_override=dict(softmax_scale=scale))
 
 
