@@ -133,22 +133,42 @@ __global__ __launch_bounds__(256) void decode_bf16_kernel(
   }
 }
 
-// fp32 cache, vector-ALU path (plain rows).  Small workloads only; accuracy
-// first: fp32 FMA dot products, expf, fp32 accumulation.
+// fp32 cache, vector-ALU path (plain rows); accuracy first: fp32 FMA dot
+// products, expf, fp32 accumulation.  With k_new given (only when one head
+// slice covers the query group, so that this block is the sole reader of the
+// row it writes) the block that owns slot len of its unit stores the new
+// token before reading, and eff_len takes the length the step works with.
 template <int D>
 __global__ __launch_bounds__(256) void decode_f32_kernel(
-    const float *__restrict__ q, const float *__restrict__ kc, const float *__restrict__ vc,
-    const int64_t *__restrict__ offsets, const int32_t *__restrict__ lens, float *__restrict__ pm,
-    float *__restrict__ pl, float *__restrict__ po, int n_units, int Hq, int Hkv, int G, float scale) {
+    const float *__restrict__ q, const float *__restrict__ k_new, const float *__restrict__ v_new, float *kc,
+    float *vc, const int64_t *__restrict__ offsets, const int32_t *__restrict__ lens,
+    int32_t *__restrict__ eff_len, int *__restrict__ d_err, float *__restrict__ pm, float *__restrict__ pl,
+    float *__restrict__ po, int n_units, int Hq, int Hkv, int G, float scale) {
   const int chunk = blockIdx.x, hg = blockIdx.y;
   const int64_t tok0 = (int64_t)chunk * CHUNK;
   const int u = find_unit(offsets, n_units, tok0);
   if (u < 0) return;
-  const int local0 = (int)(tok0 - offsets[u]);
-  const int len = lens[u];
-  if (local0 >= len) return;
-  const int n_tok = min(CHUNK, len - local0);
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int64_t base = offsets[u];
+  const int local0 = (int)(tok0 - base);
+  const int len_old = lens[u];
+  const bool want_app = k_new != nullptr;
+  const bool can_app = want_app && len_old < (int)(offsets[u + 1] - base);
+  const int len = len_old + (can_app ? 1 : 0);
+  if (want_app && local0 == 0 && hg == 0 && tid == 0) {
+    eff_len[u] = len;
+    if (!can_app) atomicOr(d_err, 1);
+  }
+  if (local0 >= len) return;
+  if (can_app && len_old >= local0 && len_old < local0 + CHUNK) {
+    if (tid < D) {
+      kc[((size_t)base + len_old) * D + tid] = k_new[(size_t)u * D + tid];
+      vc[((size_t)base + len_old) * D + tid] = v_new[(size_t)u * D + tid];
+    }
+    __threadfence_block();
+    __syncthreads();
+  }
+  const int n_tok = min(CHUNK, len - local0);
   const int b = u / Hkv, h = u % Hkv;
   const int nh = min(16, G - hg * 16);
 
@@ -160,6 +180,40 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(
     qs[hh][dd] = q[((size_t)b * Hq + (size_t)h * G + hg * 16 + hh) * D + dd];
   }
   __syncthreads();
+  if (nh <= 4) {
+    // few query heads per KV head (multi-head attention: one): D/4 lanes share a
+    // token, one float4 of its row each, so that a wave's load covers whole rows
+    // of 64/(D/4) consecutive tokens (fully coalesced, eight loads in flight);
+    // the lanes' partial dot products are added across the token's lanes.
+    constexpr int QL = D / 4, TPW = 64 / QL, U = 8;
+    const int ql = lane % QL, tl = lane / QL;
+    float4 qf[4];
+#pragma unroll
+    for (int hh = 0; hh < 4; ++hh)
+      qf[hh] = hh < nh ? *reinterpret_cast<const float4 *>(&qs[hh][4 * ql]) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int t0 = w * TPW; t0 < n_tok; t0 += 4 * TPW * U) {
+      float4 kv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int t = t0 + u * 4 * TPW + tl;
+        kv[u] = t < n_tok ? *reinterpret_cast<const float4 *>(kc + ((size_t)tok0 + t) * D + 4 * ql)
+                          : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int t = t0 + u * 4 * TPW + tl;
+#pragma unroll
+        for (int hh = 0; hh < 4; ++hh) {
+          if (hh < nh) {   // the same for all lanes
+            float d = fmaf(qf[hh].x, kv[u].x, fmaf(qf[hh].y, kv[u].y, fmaf(qf[hh].z, kv[u].z, qf[hh].w * kv[u].w)));
+#pragma unroll
+            for (int off = QL / 2; off >= 1; off >>= 1) d += __shfl_xor(d, off);
+            if (ql == 0 && t < n_tok) ps[hh][t] = d * scale;
+          }
+        }
+      }
+    }
+  } else {
   for (int t = tid; t < n_tok; t += 256) {
     const float4 *kr = reinterpret_cast<const float4 *>(kc + ((size_t)tok0 + t) * D);
     float dot[16];
@@ -181,6 +235,21 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(
     for (int hh = 0; hh < 16; ++hh)
       if (hh < nh) ps[hh][t] = dot[hh] * scale;
   }
+  }
+  // p.V: NTL token lanes x D/4 channel lanes; every thread walks its tokens with
+  // float4 loads of V (8 in flight), then the token lanes are added in lane order.
+  // The first eight rows of every thread are requested here, ahead of the
+  // softmax of the chunk, which needs no memory.
+  constexpr int DL = D / 4, NTL = 256 / DL, PRE = 8;
+  __shared__ float4 red[NTL][DL];
+  const int dl = tid % DL, tl = tid / DL;
+  float4 vpre[PRE];
+#pragma unroll
+  for (int i = 0; i < PRE; ++i) {
+    const int t = tl + i * NTL;
+    vpre[i] = t < n_tok ? *reinterpret_cast<const float4 *>(vc + ((size_t)tok0 + t) * D + 4 * dl)
+                        : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
   __syncthreads();
   for (int hh = w; hh < nh; hh += 4) {
     float mx = -INFINITY;
@@ -198,15 +267,17 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(
     if (lane == 0) { sm[hh] = mx; sl[hh] = sum; }
   }
   __syncthreads();
-  // p.V: NTL token lanes x D/4 channel lanes; every thread walks its tokens with
-  // float4 loads of V (8 in flight), then the token lanes are added in lane order.
-  constexpr int DL = D / 4, NTL = 256 / DL;
-  __shared__ float4 red[NTL][DL];
-  const int dl = tid % DL, tl = tid / DL;
   for (int hh = 0; hh < nh; ++hh) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < PRE; ++i) {
+      const int t = tl + i * NTL;
+      const float p = t < n_tok ? ps[hh][t] : 0.f;
+      acc.x = fmaf(p, vpre[i].x, acc.x); acc.y = fmaf(p, vpre[i].y, acc.y);
+      acc.z = fmaf(p, vpre[i].z, acc.z); acc.w = fmaf(p, vpre[i].w, acc.w);
+    }
 #pragma unroll 8
-    for (int t = tl; t < n_tok; t += NTL) {
+    for (int t = tl + PRE * NTL; t < n_tok; t += NTL) {
       const float p = ps[hh][t];
       const float4 vv = *reinterpret_cast<const float4 *>(vc + ((size_t)tok0 + t) * D + 4 * dl);
       acc.x = fmaf(p, vv.x, acc.x); acc.y = fmaf(p, vv.y, acc.y);
@@ -318,23 +389,31 @@ int launch_decode(taskkv_ctx *ctx, const Dims &dm, int dtype, const void *q, con
   const dim3 grid((unsigned)(capacity / CHUNK), (dm.G + 15) / 16), block(256);
   const dim3 cgrid(dm.B * dm.Hq), cblock(1024);
   if (dtype == TASKKV_F32) {
-    if (k_new) {
+    // the append is fused into the attention kernel when one head slice covers
+    // the query group; otherwise it runs as its own kernel first
+    const bool fused = k_new != nullptr && grid.y == 1;
+    if (k_new && !fused) {
       int rc = launch_append(dm, dtype, k_new, v_new, k_cache, v_cache, offsets, lens, ctx->d_err, s);
       if (rc) return rc;
     }
     auto qq = static_cast<const float *>(q);
-    auto kc = static_cast<const float *>(k_cache), vc = static_cast<const float *>(v_cache);
+    auto kn = fused ? static_cast<const float *>(k_new) : nullptr;
+    auto vn = fused ? static_cast<const float *>(v_new) : nullptr;
+    auto kc = static_cast<float *>(k_cache), vc = static_cast<float *>(v_cache);
     const float scale = (float)dm.scale;
     if (dm.D == 64)
-      launch_attention(ctx, decode_f32_kernel<64>, grid, block, s, qq, kc, vc, offsets, lens, pm, pl, po, dm.units,
-                       dm.Hq, dm.Hkv, dm.G, scale);
+      launch_attention(ctx, decode_f32_kernel<64>, grid, block, s, qq, kn, vn, kc, vc, offsets, lens, eff_len,
+                       ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale);
     else
-      launch_attention(ctx, decode_f32_kernel<128>, grid, block, s, qq, kc, vc, offsets, lens, pm, pl, po, dm.units,
-                       dm.Hq, dm.Hkv, dm.G, scale);
+      launch_attention(ctx, decode_f32_kernel<128>, grid, block, s, qq, kn, vn, kc, vc, offsets, lens, eff_len,
+                       ctx->d_err, pm, pl, po, dm.units, dm.Hq, dm.Hkv, dm.G, scale);
+    const int32_t *len_src = fused ? eff_len : lens;
     if (dm.D == 64)
-      combine_kernel<64, false><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
+      combine_kernel<64, false><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, len_src, fused ? lens : nullptr, out,
+                                                        dm.Hq, dm.Hkv, dm.G);
     else
-      combine_kernel<128, false><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, lens, nullptr, out, dm.Hq, dm.Hkv, dm.G);
+      combine_kernel<128, false><<<cgrid, cblock, 0, s>>>(pm, pl, po, offsets, len_src, fused ? lens : nullptr, out,
+                                                         dm.Hq, dm.Hkv, dm.G);
     return hip_ok(hipGetLastError());
   }
   // bf16: the append is fused into the attention kernel when one head slice
