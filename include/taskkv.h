@@ -177,7 +177,9 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
  * switch screening off to compress one set of scores under several budgets, or
  * to edit them between the two calls (when no other call on the ctx came in
  * between, the middle pick reuses the column lists that call left in the
- * workspace and relies on `scores` being unchanged).
+ * workspace and relies on `scores` being unchanged; under stream capture only
+ * when both calls are recorded into the same graph, since a replay runs
+ * without the library's host-side bookkeeping).
  * Middle tokens are the n_middle best of the pooled
  * scores inside [s1, N - s2), ties to the lower index; rows are copied
  * bit-for-bit; slots past a unit's length are zero-filled.  In

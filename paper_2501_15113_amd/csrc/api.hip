@@ -94,6 +94,20 @@ static void carve_screen_state(Carver &cv, const Dims &d, ScreenBufs &scr) {
   scr.list_ok = cv.take<int>((size_t)d.units);
 }
 
+// Id of the capture `s` is recording into, 0 when work on it runs at once.  What
+// a call leaves in the workspace for the next one can only be relied on when
+// both run at once or both are recorded into the same graph: a graph is
+// replayed without the host-side bookkeeping of this file.
+static unsigned long long capture_id(hipStream_t s) {
+  hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+  unsigned long long id = 0;
+  if (hipStreamGetCaptureInfo(s, &status, &id) != hipSuccess) {
+    (void)hipGetLastError();
+    return ~0ull;   // unknown: matches nothing
+  }
+  return status == hipStreamCaptureStatusActive ? id : 0ull;
+}
+
 static size_t ws_separate(const Dims &d) {
   const int n_chunks = score_parts(d);
   size_t b = ws_screen_state(d);
@@ -231,6 +245,7 @@ int taskkv_create(taskkv_ctx **out, int device_id, size_t workspace_bytes) {
   for (int i = 0; i < 4; ++i) c->stream_wg[i] = 0;
   c->screened_scores = nullptr;
   c->screened_list = 0;
+  c->screened_capture = 0;
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) {
     delete c;
@@ -342,6 +357,7 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   if (scores_screened(d, cfg->dtype, &scr)) {
     ctx->screened_scores = scores;
     ctx->screened_list = band_is_sliced(d, &scr) ? 1 : 0;
+    ctx->screened_capture = capture_id(s);
     const int sel[8] = {cfg->ctx_len, cfg->n_sink, cfg->n_recent, cfg->n_middle, cfg->pack_mode, cfg->pool_kernel,
                         cfg->batch, cfg->n_kv_heads};
     for (int i = 0; i < 8; ++i) ctx->screened_sel[i] = sel[i];
@@ -386,7 +402,9 @@ int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k,
   Carver cv(ctx->ws, ctx->ws_bytes);
   ScreenBufs scr;
   carve_screen_state(cv, d, scr);   // still as the separator left it, if this call follows it
-  const bool from_band = scores == ctx->screened_scores && ctx->screened_list;
+  const unsigned long long cap = capture_id(s);
+  const bool from_band = scores == ctx->screened_scores && ctx->screened_list && cap != ~0ull &&
+                         cap == ctx->screened_capture;
   ctx->screened_list = 0;           // the rest of the workspace is reused below
   const double *sel_scores = scores;
   int rc = TASKKV_OK;
@@ -471,6 +489,7 @@ int taskkv_decode_attn_static(const taskkv_layer_cfg *cfg, const void *q, const 
     for (int i = 0; i < 4; ++i) c.stream_wg[i] = 0;
     c.screened_scores = nullptr;
     c.screened_list = 0;
+    c.screened_capture = 0;
     st.own_flag = c.d_err;
     st.ready = true;
   }

@@ -333,10 +333,12 @@ __device__ __forceinline__ int list_ascending(SC sc, int lo, int hi, int take_eq
 // 1024 * SWEEP_U entries that the block holds in registers between counting
 // and writing (two barriers per chunk; every wave owns a contiguous sixteenth
 // of the chunk).  For blocks that list one slice of a unit.  Returns the number
-// of entries this call listed; n_class2: the class-2 entries it met.
+// of entries this call listed; n_class2: the class-2 entries it met.  Nothing is
+// written at or past out[limit], whatever the bases claim.
 template <typename SC, typename F>
 __device__ __forceinline__ int list_chunked(SC sc, int lo, int hi, int take_equal, int32_t *__restrict__ out,
-                                            int *s_cnt, F classify, int base1, int base2, int &n_class2) {
+                                            int limit, int *s_cnt, F classify, int base1, int base2,
+                                            int &n_class2) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const uint64_t below = (1ull << lane) - 1ull;
   int run1 = base1, run2 = base2;   // the same in every thread
@@ -374,8 +376,8 @@ __device__ __forceinline__ int list_chunked(SC sc, int lo, int hi, int take_equa
     for (int r = 0; r < SWEEP_U; ++r) {
       const bool m1 = (b1[r] >> lane) & 1ull, m2 = (b2[r] >> lane) & 1ull;
       const int before1 = w1 + __popcll(b1[r] & below), before2 = w2 + __popcll(b2[r] & below);
-      if (m1 || (m2 && before2 < take_equal))
-        out[before1 + min(before2, take_equal)] = position_of(sc, jw + 64 * r + lane);
+      const int at = before1 + min(before2, take_equal);
+      if ((m1 || (m2 && before2 < take_equal)) && at < limit) out[at] = position_of(sc, jw + 64 * r + lane);
       w1 += __popcll(b1[r]);
       w2 += __popcll(b2[r]);
     }

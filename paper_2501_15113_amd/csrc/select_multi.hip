@@ -382,8 +382,8 @@ __global__ __launch_bounds__(1024) void msel_write_kernel(const double *__restri
   a = max(a, mb.lo[0]);
   b = min(b, mb.hi[0]);
   int unused;
-  list_chunked(scores + (size_t)unit * N, a, b, mb.take_final[unit], orow + prefix, s_cnt, AboveOrAt{mb.pat[unit]},
-               base1, base2, unused);
+  list_chunked(scores + (size_t)unit * N, a, b, mb.take_final[unit], orow + prefix, mb.count[0], s_cnt,
+               AboveOrAt{mb.pat[unit]}, base1, base2, unused);
   if (s == 0) {
     const int count = mb.count[0];
     for (int i = tid; i < prefix; i += 1024) orow[i] = i;
@@ -408,8 +408,8 @@ __global__ __launch_bounds__(1024) void mband_write_kernel(const double *__restr
   int a, b;
   slice_of(dm.N, s, mb.S, a, b);
   int n_above;
-  const int n = list_chunked(scores + (size_t)unit * dm.N, a, b, 0, band_idx + (size_t)unit * dm.N + a, s_cnt, band, 0,
-                             0, n_above);
+  const int n = list_chunked(scores + (size_t)unit * dm.N, a, b, 0, band_idx + (size_t)unit * dm.N + a, b - a, s_cnt,
+                             band, 0, 0, n_above);
   if (tid == 0) {
     mb.counts[counts_at(unit, s)] = n;
     above_band[(size_t)unit * MSEL_MAX_SLICES + s] = n_above;
@@ -593,6 +593,19 @@ __global__ __launch_bounds__(1024) void mlist_settle_kernel(const double *__rest
   const double *sc = scores + (size_t)unit * N;
   const int32_t *list = band_idx + (size_t)unit * N;
   const int n = band_cnt[unit];
+  {
+    // the list indexes the scores: it has to be what the band kernels write
+    // (ascending columns inside the row), or the full selection decides
+    bool bad = n < 0 || n > N;
+    for (int i = tid; i < n && !bad; i += 1024) {
+      const int v = list[i];
+      bad = v < 0 || v >= N || (i > 0 && list[i - 1] >= v);
+    }
+    if (__syncthreads_or(bad)) {
+      if (tid == 0) mb.flag[unit] = 1;
+      return;
+    }
+  }
   // the listed columns of the middle: entries [ia, ib) of the ascending list
   int ia = 0, ib = 0;
   {

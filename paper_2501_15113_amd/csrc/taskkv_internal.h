@@ -55,6 +55,7 @@ struct taskkv_ctx {
   // columns they are fp32 values, good only for this selection
   const double *screened_scores;
   int screened_list;     // the band lists of that call are still in the workspace, with per-slice counts
+  unsigned long long screened_capture;   // id of the stream capture that call was recorded in, 0 = it ran at once
   int screened_sel[8];   // ctx_len, n_sink, n_recent, n_middle, pack_mode, pool_kernel, batch, n_kv_heads
 };
 

@@ -90,3 +90,46 @@ def test_graph_replays_match_eager_calls(dtype, ctx_len):
                                  f"{what}, step {s}")
         assert taskkv_last_async_error(ctx.handle) == 0
         assert np.isfinite(outs[-1].cpu().numpy()).all()
+
+
+@pytest.mark.parametrize("whole", [True, False])
+def test_graph_of_a_long_screened_layer(whole):
+    """On a long screened layer the compressor takes its middle threshold from
+    column lists that the separator leaves in the workspace, and whether they
+    are still there is bookkeeping on the host.  A graph is replayed without
+    that bookkeeping: recorded together, separator and compressor may share the
+    lists; a compressor recorded alone must not count on them, whatever ran
+    before the recording -- here the separator of another layer leaves its own
+    lists in the workspace before every replay."""
+    from paper_2501_15113_amd import session as ses
+    wl = small_workload(name="graph-long", wid=231, batch=1, ctx_len=34000, n_middle=1200, top_t=256,
+                        decode_steps=STEPS)
+    ld, other_ld = make_layer(wl, 0, "cuda:0"), make_layer(wl, 1, "cuda:0")
+    cfg = ses.cfg_from_workload(wl)
+    with ses.Context([cfg], STEPS, screening=2) as ctx:
+        want, _ = _eager(ses, ctx, cfg, ld)
+        bufs, other = ses.LayerBuffers(cfg, STEPS), ses.LayerBuffers(cfg, STEPS)
+
+        def record():
+            if whole:
+                bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+            bufs.compress(ctx, ld.k, ld.v)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            bufs.separate(ctx, ld.q_win, ld.k, ld.v)
+            bufs.compress(ctx, ld.k, ld.v)             # warm-up outside the capture
+            bufs.separate(ctx, ld.q_win, ld.k, ld.v)   # the lists are in the workspace when the recording starts
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            record()
+        for rep in range(3):
+            other.separate(ctx, other_ld.q_win, other_ld.k, other_ld.v)   # another layer's lists, valid ones
+            bufs.kept_idx.fill_(-7)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(bufs.kept_idx, want.kept_idx), f"replay {rep}"
+            assert torch.equal(bufs.mask, want.mask), f"replay {rep}"
