@@ -99,9 +99,12 @@ struct ZeroList {
   size_t n[6];   // 32-bit words
   int count;
   ZeroList() : count(0) {}
-  void add(void *ptr, size_t words) {
+  // at most five pieces are ever listed; a sixth would be refused rather than written past the arrays
+  bool add(void *ptr, size_t words) {
+    if (count >= 6) return false;
     p[count] = static_cast<uint32_t *>(ptr);
     n[count++] = words;
+    return true;
   }
 };
 
