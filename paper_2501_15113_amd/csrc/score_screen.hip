@@ -10,6 +10,8 @@
 //      thresholds among them and lists the columns that could matter -- every
 //      column at or above (1 - 3 eps) x the top-t threshold, and every middle
 //      column within 3 eps of the middle threshold;
+//      (on long contexts the same list comes from the sliced kernels of
+//      select_multi.hip, which bracket the thresholds instead of finding them);
 //   3. the fp64 scorer recomputes exactly the listed columns.
 // Unlisted columns keep their fp32 value; each is provably on the same side of
 // both thresholds as its exact value.
