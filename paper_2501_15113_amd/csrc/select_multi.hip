@@ -137,7 +137,11 @@ __global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restri
   int a, b;
   slice_of(N, s, mb.S, a, b);
   if (a >= b) return;
-  __shared__ unsigned h[2 * 4096];   // one histogram per threshold
+  // Two thresholds: the second one's range lies inside the first one's (the
+  // middle of the context inside the whole of it), so an entry is counted once,
+  // in the lower half if only the first range holds it, else in the upper half,
+  // and the first threshold's histogram is the sum of the two.
+  __shared__ unsigned h[2 * 4096];
   const bool two = mb.nsel > 1;
   for (int j0 = a; j0 < b; j0 += SLICE_U * 1024) {
     uint64_t key[SLICE_U];
@@ -152,16 +156,17 @@ __global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restri
       const int j = j0 + r * 1024 + tid;
       if (j < b) {
         const int d = digit1(key[r]);
-        if (j >= mb.lo[0] && j < mb.hi[0]) atomicAdd(&h[d], 1u);
         if (two && j >= mb.lo[1] && j < mb.hi[1]) atomicAdd(&h[4096 + d], 1u);
+        else if (j >= mb.lo[0] && j < mb.hi[0]) atomicAdd(&h[d], 1u);
       }
     }
   }
   __syncthreads();
-  for (int sel = 0; sel < mb.nsel; ++sel) {
-    unsigned *g = mb.hist + hist_at(0, sel, unit, units);
-    for (int i = tid; i < 4096; i += 1024)
-      if (h[sel * 4096 + i]) atomicAdd(&g[i], h[sel * 4096 + i]);
+  unsigned *g0 = mb.hist + hist_at(0, 0, unit, units), *g1 = mb.hist + hist_at(0, 1, unit, units);
+  for (int i = tid; i < 4096; i += 1024) {
+    const unsigned inner = h[4096 + i], all = h[i] + inner;
+    if (all) atomicAdd(&g0[i], all);
+    if (inner) atomicAdd(&g1[i], inner);   // only with two thresholds
   }
 }
 
@@ -372,10 +377,14 @@ __global__ __launch_bounds__(1024) void msel_write_kernel(const double *__restri
                      out_stride, nullptr, 0, rs, s_cnt);
     return;
   }
+  // picks of the slices before mine: all counts in one trip to memory
+  __shared__ int s_n[2 * MSEL_MAX_SLICES];
+  if (tid < 2 * s) s_n[tid] = mb.counts[counts_at(unit, tid >> 1) + (tid & 1)];
+  __syncthreads();
   int base1 = 0, base2 = 0;
   for (int x = 0; x < s; ++x) {
-    base1 += mb.counts[counts_at(unit, x)];
-    base2 += mb.counts[counts_at(unit, x) + 1];
+    base1 += s_n[2 * x];
+    base2 += s_n[2 * x + 1];
   }
   int a, b;
   slice_of(N, s, mb.S, a, b);
