@@ -246,11 +246,15 @@ __global__ void zero_i32_kernel(int32_t *p, int n) {
 }
 
 // part[unit][n_parts][Rpad][2] <- (row maximum, denominator) over the keys of
-// this block; grid = (key ranges, units, groups of 32 NW window rows).  NW
+// this block; grid = (key ranges, units, groups of 32 NW / WPR window rows).  NW
 // waves per block, one 32-row block each: 8, or 4 when the window has at most
 // 128 rows (two such blocks share a compute unit, so that every SIMD still
 // holds two waves with rows to work on).
-template <int D, int NW>
+// Windows of 32 or 64 rows (one query head per KV head with the usual window
+// of 32) have fewer 32-row blocks than a block has waves: there WPR = 2 waves
+// share a row block and take one of the two 32-key tiles of a step each, and
+// each writes a partial record of its own.
+template <int D, int NW, int WPR>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void score_i8_stats_kernel(
     const uint16_t *__restrict__ k, const v4i *__restrict__ qdig, const double *__restrict__ gq,
     const double *__restrict__ qd, const QTiny *__restrict__ qtiny, const int32_t *__restrict__ qcnt,
@@ -276,7 +280,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   for (int i = tid; i < EXP_TAB; i += THREADS) s_pow[i] = exp2((double)i * (1.0 / EXP_TAB));
 
   // my 32-row block: operands, factor, statistics (lane: row c32)
-  const int rb = blockIdx.z * NW + w;
+  constexpr int RBB = NW / WPR;   // row blocks per block
+  const int rb = blockIdx.z * RBB + w % RBB, sub = w / RBB;
   const bool have = rb < n_rb;
   const int row = (have ? rb : 0) * 32 + c32;
   v4i qv[KS][4];
@@ -423,6 +428,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
       for (int tile = 0; tile < I8_KEYS / 32; ++tile) {
         const int j0 = jstep + tile * 32;
         if (j0 >= kend) break;
+        if (WPR == 2 && tile != sub) continue;
         double t16[16];
         if (!plain) {
           // Key digits of the tile.  Blocks of eight waves name them where they are
@@ -616,7 +622,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     if (mn > -INFINITY) ls = ls * exp2((m - mn) * (1.0 / 256)) + lo * exp2((mo - mn) * (1.0 / 256));
     m = mn;
     if (half == 0) {
-      double *pp = part + ((size_t)unit * gridDim.x + blockIdx.x) * Rpad * 2;
+      double *pp = part + (((size_t)unit * gridDim.x + blockIdx.x) * WPR + sub) * Rpad * 2;
       pp[2 * row] = m * (1.0 / EXP_UNITS);   // back to natural units
       pp[2 * row + 1] = ls;
     }
@@ -631,27 +637,31 @@ bool i8_stats_supported(const Dims &dm, int dtype) {
 // statistics partials; n_wg key ranges of keys_per_wg keys each.
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
                     double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, bool qcnt_zeroed,
-                    hipStream_t s) {
+                    int *n_parts, hipStream_t s) {
   const int n_rb = dm.Rpad / 32;
   auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
   auto qdig = static_cast<v4i *>(bufs.qdig);
   if (!qcnt_zeroed) zero_i32_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(bufs.qcnt, dm.units);
-  const bool small = n_rb <= 4;   // at most 128 window rows: blocks of four waves
-  const int rows_per_block = small ? 128 : 256;
+  // waves per block, waves per row block: 8 x 1 for windows above 128 rows, 4 x 1
+  // down to 96 rows, 4 x 2 for 64 rows, 2 x 2 for 32
+  const int nw = n_rb > 4 ? 8 : (n_rb == 1 ? 2 : 4), wpr = n_rb <= 2 ? 2 : 1;
+  const int rows_per_block = 32 * nw / wpr;
   const dim3 grid(n_wg, dm.units, (dm.Rpad + rows_per_block - 1) / rows_per_block);
-  auto launch = [&](auto kernel, int threads) {
-    launch_profiled(bufs.prof, 2, kernel, grid, dim3(threads), s, kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, part,
+  *n_parts = n_wg * wpr;
+  auto launch = [&](auto kernel) {
+    launch_profiled(bufs.prof, 2, kernel, grid, dim3(64 * nw), s, kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, part,
                     knorm, dm, keys_per_wg);
   };
-  if (dm.D == 64) {
-    q_digits_kernel<64><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
-    if (small) launch(score_i8_stats_kernel<64, 4>, 256);
-    else launch(score_i8_stats_kernel<64, 8>, 512);
-  } else {
-    q_digits_kernel<128><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
-    if (small) launch(score_i8_stats_kernel<128, 4>, 256);
-    else launch(score_i8_stats_kernel<128, 8>, 512);
-  }
+  auto pick = [&](auto d) {
+    constexpr int DD = decltype(d)::value;
+    q_digits_kernel<DD><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
+    if (nw == 8) launch(score_i8_stats_kernel<DD, 8, 1>);
+    else if (wpr == 1) launch(score_i8_stats_kernel<DD, 4, 1>);
+    else if (nw == 4) launch(score_i8_stats_kernel<DD, 4, 2>);
+    else launch(score_i8_stats_kernel<DD, 2, 2>);
+  };
+  if (dm.D == 64) pick(std::integral_constant<int, 64>{});
+  else pick(std::integral_constant<int, 128>{});
   return hip_ok(hipGetLastError());
 }
 

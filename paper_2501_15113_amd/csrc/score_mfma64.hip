@@ -391,9 +391,11 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     const dim3 grid(n_wg, dm.units), block(64 * SNW);
     if (i8) {
       // bf16 inputs: exact integer dot products on the int8 matrix cores
-      int rc = launch_i8_stats(dm, q_win, k, qd, *i8b, part, screen ? scr->knorm : nullptr, n_wg, cpw * SKC, grp == 0, s);
+      int n_recs = n_wg;
+      int rc = launch_i8_stats(dm, q_win, k, qd, *i8b, part, screen ? scr->knorm : nullptr, n_wg, cpw * SKC, grp == 0,
+                               &n_recs, s);
       if (rc) return rc;
-      merge_stats_kernel<<<dim3(dm.units, (dm.Rpad + 15) / 16), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_wg);
+      merge_stats_kernel<<<dim3(dm.units, (dm.Rpad + 15) / 16), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_recs);
     } else {
       score_mfma64_kernel<T, D, 0, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
                                                                 nullptr);

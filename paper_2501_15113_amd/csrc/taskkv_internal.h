@@ -138,9 +138,10 @@ struct I8Bufs {
 };
 bool i8_stats_supported(const Dims &dm, int dtype);
 // qcnt_zeroed: bufs.qcnt has been set to zero by an earlier kernel on the stream
+// n_parts: partial records per row the kernel leaves in `part` (n_wg or twice that)
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
                     double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, bool qcnt_zeroed,
-                    hipStream_t s);
+                    int *n_parts, hipStream_t s);
 int launch_zero_u64(unsigned long long *p, int n, hipStream_t s);
 bool screen_supported(const Dims &dm, int dtype);
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);
