@@ -279,6 +279,23 @@ def test_int8_statistics_with_elements_outside_the_window(rate_q, rate_k, what):
     run_layer(wl, mutate=tiny, check_batches=(0, 1))
 
 
+@pytest.mark.parametrize("group,window", [(1, 32), (1, 16), (2, 32), (1, 64), (3, 32), (4, 32), (5, 32)])
+@pytest.mark.parametrize("outliers", [False, True])
+def test_int8_statistics_of_narrow_and_wide_windows(group, window, outliers):
+    """The int8 statistics kernel has a block shape per window size: two waves
+    per 32-row block for windows of 32 and 64 rows (one query head per KV head
+    is the common case), one wave per block of rows up to 128 rows, blocks of
+    eight waves above.  Each of them, with and without elements that leave the
+    integer window (remainder lists of both sides), on a context that ends in
+    a ragged tile."""
+    def tiny(ld):
+        _shrink(ld.q_win, 0.004, 21)
+        _shrink(ld.k, 0.001, 22)
+    wl = small_workload(name=f"i8win-{group}-{window}", wid=197, ctx_len=2101, n_q_heads=3 * group, n_kv_heads=3,
+                        obs_window=window, n_hetero=1, decode_steps=1)
+    run_layer(wl, mutate=tiny if outliers else None, check_batches=(0, 1))
+
+
 @pytest.mark.parametrize("side", ["window rows", "keys", "both"])
 def test_int8_statistics_when_the_remainders_carry_the_logits(side):
     """One channel 2^30 times larger than the rest pushes every other element
