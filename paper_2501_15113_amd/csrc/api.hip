@@ -92,6 +92,7 @@ static void carve_screen_state(Carver &cv, const Dims &d, ScreenBufs &scr) {
   scr.band_cnt = cv.take<int32_t>((size_t)d.units * 2);
   scr.above_band = cv.take<int>((size_t)d.units * MSEL_MAX_SLICES);
   scr.list_ok = cv.take<int>((size_t)d.units);
+  scr.pooled = nullptr;
 }
 
 // Id of the capture `s` is recording into, 0 when work on it runs at once.  What
@@ -121,6 +122,7 @@ static size_t ws_separate(const Dims &d) {
   b += al((size_t)d.units * I8_QCAP * sizeof(QTiny));                 //   remainders that do not fit
   b += al((size_t)d.units * sizeof(int32_t));                         //   their count
   b += msel_workspace_bytes(d);                                       // sliced selections
+  if (d.pool > 1) b += al((size_t)d.units * d.N * sizeof(double));    // pooled scores of the screening pass
   return b;
 }
 static size_t ws_compress(const Dims &d, int dtype) {
@@ -352,6 +354,7 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   MSelBufs mb;
   const bool sliced = msel_carve(cv, d, mb);
   scr.msel = sliced ? &mb : nullptr;
+  scr.pooled = d.pool > 1 ? cv.take<double>((size_t)d.units * d.N) : nullptr;
   if (!cv.ok) return TASKKV_EWORKSPACE;
   ctx->screened_list = 0;
   if (scores_screened(d, cfg->dtype, &scr)) {

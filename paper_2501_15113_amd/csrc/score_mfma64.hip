@@ -26,6 +26,7 @@
 // see and adds its share to C.
 #include <math.h>
 
+#include "band_common.h"
 #include "taskkv_internal.h"
 
 namespace taskkv {
@@ -410,8 +411,15 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     // part in a decision (any number of them: the grid covers all N)
     int rc = launch_screen(dm, q_win, k, stats, scores, cpw, s);
     if (rc) return rc;
+    // a middle pick that pools ranks by the pooled scores: the band follows it
+    const double *pooled = nullptr;
+    if (dm.pool > 1 && band_has_middle(dm)) {
+      rc = launch_pool(dm, scores, scr->pooled, s);
+      if (rc) return rc;
+      pooled = scr->pooled;
+    }
     if (sliced_band)
-      rc = launch_band_sliced(dm, scr->n_cu, *scr->msel, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt,
+      rc = launch_band_sliced(dm, scr->n_cu, *scr->msel, scores, pooled, qd, scr->knorm, scr->band_idx, scr->band_cnt,
                               scr->above_band, scr->list_ok, true, s);
     else
       rc = launch_band(dm, scores, qd, scr->knorm, scr->band_idx, scr->band_cnt, s);
@@ -439,7 +447,10 @@ bool band_is_sliced(const Dims &dm, const ScreenBufs *scr) {
 bool scores_screened(const Dims &dm, int dtype, const ScreenBufs *scr) {
   const int n_groups = (dm.Rtot + ROW_GROUP - 1) / ROW_GROUP;
   const bool big = (double)dm.units * dm.Rtot * dm.N >= 3e7;   // measured: loses at 8e6, wins at 7e7
-  return scr != nullptr && scr->mode != 0 && n_groups == 1 && screen_supported(dm, dtype) && (scr->mode == 2 || big);
+  // with pooling only the sliced band kernels list the neighbours a pooled score needs
+  const bool pool_ok = dm.pool == 1 || (band_is_sliced(dm, scr) && scr->pooled != nullptr);
+  return scr != nullptr && scr->mode != 0 && n_groups == 1 && screen_supported(dm, dtype) && pool_ok &&
+         (scr->mode == 2 || big);
 }
 
 int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, double *qd, double *part,

@@ -244,7 +244,7 @@ __global__ __launch_bounds__(256) void key_norm_kernel(const uint16_t *__restric
 }
 
 bool screen_supported(const Dims &dm, int dtype) {
-  return dtype == TASKKV_BF16 && dm.pool == 1 && dm.Rtot <= 64 * MAXQ;
+  return dtype == TASKKV_BF16 && dm.Rtot <= 64 * MAXQ;
 }
 
 int launch_zero_u64(unsigned long long *p, int n, hipStream_t s) {

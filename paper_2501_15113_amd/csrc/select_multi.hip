@@ -131,7 +131,10 @@ __global__ void msel_clear_kernel(MSelBufs mb, int units) {
   if (i < (size_t)units) mb.flag[i] = 0;
 }
 
+// scores1: what the second threshold ranks by when that is not `scores` (the
+// pooled scores of a middle pick that pools), else null.
 __global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restrict__ scores,
+                                                          const double *__restrict__ scores1,
                                                           const uint8_t *__restrict__ skip, MSelBufs mb, int N) {
   const int s = blockIdx.x, unit = blockIdx.y, units = gridDim.y, tid = threadIdx.x;
   if (skip && skip[unit]) return;
@@ -139,16 +142,22 @@ __global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restri
   int a, b;
   slice_of(N, s, mb.S, a, b);
   if (a >= b) return;
-  // Two thresholds: the second one's range lies inside the first one's (the
-  // middle of the context inside the whole of it), so an entry is counted once,
-  // in the lower half if only the first range holds it, else in the upper half,
-  // and the first threshold's histogram is the sum of the two.
+  // Two thresholds on the same scores: the second one's range lies inside the
+  // first one's (the middle of the context inside the whole of it), so an entry
+  // is counted once, in the lower half if only the first range holds it, else
+  // in the upper half, and the first threshold's histogram is the sum of the
+  // two.  On different scores each half is a histogram of its own.
   __shared__ unsigned h[2 * 4096];
-  const bool two = mb.nsel > 1;
+  const bool two = mb.nsel > 1, split = two && scores1 != nullptr;
+  const double *sc1 = split ? scores1 + (size_t)unit * N : sc;
   for (int j0 = a; j0 < b; j0 += SLICE_U * 1024) {
-    uint64_t key[SLICE_U];
+    uint64_t key[SLICE_U], key1[SLICE_U];
 #pragma unroll
     for (int r = 0; r < SLICE_U; ++r) key[r] = score_key(sc[min(j0 + r * 1024 + tid, b - 1)]);
+    if (split) {
+#pragma unroll
+      for (int r = 0; r < SLICE_U; ++r) key1[r] = score_key(sc1[min(j0 + r * 1024 + tid, b - 1)]);
+    }
     if (j0 == a) {   // with the first loads in flight
       for (int i = tid; i < 2 * 4096; i += 1024) h[i] = 0;
       __syncthreads();
@@ -158,21 +167,29 @@ __global__ __launch_bounds__(1024) void msel_hist1_kernel(const double *__restri
       const int j = j0 + r * 1024 + tid;
       if (j < b) {
         const int d = digit1(key[r]);
-        if (two && j >= mb.lo[1] && j < mb.hi[1]) atomicAdd(&h[4096 + d], 1u);
-        else if (j >= mb.lo[0] && j < mb.hi[0]) atomicAdd(&h[d], 1u);
+        const bool in1 = two && j >= mb.lo[1] && j < mb.hi[1], in0 = j >= mb.lo[0] && j < mb.hi[0];
+        if (split) {
+          if (in1) atomicAdd(&h[4096 + digit1(key1[r])], 1u);
+          if (in0) atomicAdd(&h[d], 1u);
+        } else if (in1) {
+          atomicAdd(&h[4096 + d], 1u);
+        } else if (in0) {
+          atomicAdd(&h[d], 1u);
+        }
       }
     }
   }
   __syncthreads();
   unsigned *g0 = mb.hist + hist_at(0, 0, unit, units), *g1 = mb.hist + hist_at(0, 1, unit, units);
   for (int i = tid; i < 4096; i += 1024) {
-    const unsigned inner = h[4096 + i], all = h[i] + inner;
+    const unsigned inner = h[4096 + i], all = split ? h[i] : h[i] + inner;
     if (all) atomicAdd(&g0[i], all);
     if (inner) atomicAdd(&g1[i], inner);   // only with two thresholds
   }
 }
 
 __global__ __launch_bounds__(1024) void msel_hist2_kernel(const double *__restrict__ scores,
+                                                          const double *__restrict__ scores1,
                                                           const uint8_t *__restrict__ skip, MSelBufs mb, int N) {
   const int s = blockIdx.x, unit = blockIdx.y, units = gridDim.y, tid = threadIdx.x;
   if (skip && skip[unit]) return;
@@ -191,18 +208,22 @@ __global__ __launch_bounds__(1024) void msel_hist2_kernel(const double *__restri
   if (a >= b) return;
   for (int i = tid; i < 2 * 4096; i += 1024) h[i] = 0;
   __syncthreads();
+  const bool split = mb.nsel > 1 && scores1 != nullptr;
+  const double *sc1 = split ? scores1 + (size_t)unit * N : sc;
   for (int j0 = a; j0 < b; j0 += SWEEP_U * 1024) {
-    uint64_t key[SWEEP_U];
+    uint64_t key[2][SWEEP_U];
 #pragma unroll
-    for (int r = 0; r < SWEEP_U; ++r) key[r] = score_key(sc[min(j0 + r * 1024 + tid, b - 1)]);
+    for (int r = 0; r < SWEEP_U; ++r) key[0][r] = score_key(sc[min(j0 + r * 1024 + tid, b - 1)]);
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) key[1][r] = split ? score_key(sc1[min(j0 + r * 1024 + tid, b - 1)]) : key[0][r];
 #pragma unroll
     for (int r = 0; r < SWEEP_U; ++r) {
       const int j = j0 + r * 1024 + tid;
       if (j < b) {
 #pragma unroll
         for (int sel = 0; sel < 2; ++sel)
-          if (w[sel].level2 && j >= mb.lo[sel] && j < mb.hi[sel] && (key[r] & w[sel].known) == w[sel].pat)
-            atomicAdd(&h[sel * 4096 + digit2(key[r])], 1u);
+          if (w[sel].level2 && j >= mb.lo[sel] && j < mb.hi[sel] && (key[sel][r] & w[sel].known) == w[sel].pat)
+            atomicAdd(&h[sel * 4096 + digit2(key[sel][r])], 1u);
       }
     }
   }
@@ -403,8 +424,30 @@ __global__ __launch_bounds__(1024) void msel_write_kernel(const double *__restri
   }
 }
 
+// The band of a middle pick that pools: its threshold is one of the pooled
+// scores, and a pooled score that has to be decided exactly needs the exact
+// scores of all the columns under its pooling window.  Lists the columns at or
+// above lo_t and those within `radius` of a middle column whose pooled score
+// lies inside [lo_k, hi_k].
+struct InBandPooled {
+  InBand b;
+  const double *pooled;   // the unit's row
+  int radius;
+  __device__ __forceinline__ int operator()(int j, double x) const {
+    if (x >= b.lo_t) return 1;
+    int hit = 0;
+    const int i0 = max(j - radius, b.m0), i1 = min(j + radius, b.m1 - 1);
+    for (int i = i0; i <= i1; ++i) {
+      const double p = pooled[i];
+      hit |= (p >= b.lo_k && p <= b.hi_k) ? 1 : 0;
+    }
+    return hit;
+  }
+};
+
 // The band's columns of a slice, listed from the slice's first slot of the row.
 __global__ __launch_bounds__(1024) void mband_write_kernel(const double *__restrict__ scores,
+                                                           const double *__restrict__ pooled,
                                                            const unsigned long long *__restrict__ knorm, MSelBufs mb,
                                                            Dims dm, int32_t *__restrict__ band_idx,
                                                            int *__restrict__ above_band) {
@@ -418,9 +461,14 @@ __global__ __launch_bounds__(1024) void mband_write_kernel(const double *__restr
                   tau_k, __longlong_as_double((long long)(score_key(tau_k) | rest)));
   int a, b;
   slice_of(dm.N, s, mb.S, a, b);
-  int n_above;
-  const int n = list_chunked(scores + (size_t)unit * dm.N, a, b, 0, band_idx + (size_t)unit * dm.N + a, b - a, s_cnt,
-                             band, 0, 0, n_above);
+  int n_above = 0, n;
+  const double *sc = scores + (size_t)unit * dm.N;
+  int32_t *out = band_idx + (size_t)unit * dm.N + a;
+  if (pooled != nullptr && mb.nsel > 1)
+    n = list_chunked(sc, a, b, 0, out, b - a, s_cnt, InBandPooled{band, pooled + (size_t)unit * dm.N, dm.pool / 2}, 0,
+                     0, n_above);
+  else
+    n = list_chunked(sc, a, b, 0, out, b - a, s_cnt, band, 0, 0, n_above);
   if (tid == 0) {
     mb.counts[counts_at(unit, s)] = n;
     above_band[(size_t)unit * MSEL_MAX_SLICES + s] = n_above;
@@ -433,13 +481,21 @@ __global__ __launch_bounds__(1024) void mband_close_kernel(const double *__restr
                                                            const double *__restrict__ qd,
                                                            const unsigned long long *__restrict__ knorm, MSelBufs mb,
                                                            Dims dm, int32_t *__restrict__ band_idx,
-                                                           int32_t *__restrict__ band_cnt, int *__restrict__ list_ok) {
+                                                           int32_t *__restrict__ band_cnt, int *__restrict__ list_ok,
+                                                           int pooled) {
   const int unit = blockIdx.x, tid = threadIdx.x, N = dm.N;
   if (tid == 0) list_ok[unit] = mb.flag[unit] ? 0 : 1;
   if (mb.flag[unit]) {   // the sliced kernels gave up on this unit: one block lists its band, without slice counts
     __shared__ RadixScratch rs;
     __shared__ int s_cnt[32];
     __shared__ double s_q[16];
+    if (pooled) {
+      // with pooling the one-block band has no list of neighbours to offer:
+      // every column of such a unit (degenerate scores) is recomputed
+      for (int i = tid; i < N; i += 1024) band_idx[(size_t)unit * N + i] = i;
+      if (tid == 0) band_cnt[unit] = N;
+      return;
+    }
     band_of_unit(scores + (size_t)unit * N, qd, __longlong_as_double((long long)knorm[unit]), unit, dm,
                  band_idx + (size_t)unit * N, band_cnt + unit, rs, s_cnt, s_q);
     return;
@@ -538,12 +594,12 @@ void msel_zero_words(const Dims &dm, const MSelBufs &mb, ZeroList &z) {
 }
 
 static void msel_histograms(const Dims &dm, const double *scores, const uint8_t *skip, const MSelBufs &mb,
-                            hipStream_t s, bool cleared = false) {
+                            hipStream_t s, bool cleared = false, const double *scores1 = nullptr) {
   const size_t n = (size_t)4 * dm.units * 4096;
   if (!cleared) msel_clear_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(mb, dm.units);
   const dim3 grid(mb.S, dm.units), block(1024);
-  msel_hist1_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
-  msel_hist2_kernel<<<grid, block, 0, s>>>(scores, skip, mb, dm.N);
+  msel_hist1_kernel<<<grid, block, 0, s>>>(scores, scores1, skip, mb, dm.N);
+  msel_hist2_kernel<<<grid, block, 0, s>>>(scores, scores1, skip, mb, dm.N);
 }
 static void msel_candidates(const Dims &dm, const double *scores, const uint8_t *skip, const MSelBufs &mb,
                             hipStream_t s) {
@@ -566,18 +622,20 @@ int launch_select_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *sc
   return hip_ok(hipGetLastError());
 }
 
-int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *qd,
-                       const unsigned long long *knorm, int32_t *band_idx, int32_t *band_cnt, int *above_band,
+int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *pooled,
+                       const double *qd, const unsigned long long *knorm, int32_t *band_idx, int32_t *band_cnt, int *above_band,
                        int *list_ok, bool cleared, hipStream_t s) {
   mb.S = msel_slices(dm, n_cu);
   mb.nsel = band_has_middle(dm) ? 2 : 1;
   mb.lo[0] = 0; mb.hi[0] = dm.N; mb.count[0] = dm.T;
   mb.lo[1] = dm.s1; mb.hi[1] = dm.N - dm.s2; mb.count[1] = dm.k;
   mb.bracket = 1;
-  msel_histograms(dm, scores, nullptr, mb, s, cleared);
+  if (mb.nsel < 2) pooled = nullptr;   // pooling only concerns the middle pick
+  msel_histograms(dm, scores, nullptr, mb, s, cleared, pooled);
   mband_brackets_kernel<<<dim3(dm.units, 3), dim3(1024), 0, s>>>(mb, dm, qd);
-  mband_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, knorm, mb, dm, band_idx, above_band);
-  mband_close_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, mb, dm, band_idx, band_cnt, list_ok);
+  mband_write_kernel<<<dim3(mb.S, dm.units), dim3(1024), 0, s>>>(scores, pooled, knorm, mb, dm, band_idx, above_band);
+  mband_close_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, qd, knorm, mb, dm, band_idx, band_cnt, list_ok,
+                                                         pooled != nullptr ? 1 : 0);
   return hip_ok(hipGetLastError());
 }
 

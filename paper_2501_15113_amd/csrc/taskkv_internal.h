@@ -122,6 +122,7 @@ struct ScreenBufs {
   // what the sliced band kernels leave for the middle pick of the compressor:
   int *above_band;             // [units][MSEL_MAX_SLICES] middle columns of a slice above the band
   int *list_ok;                // [units] 1 = the unit's list and counts come from the sliced kernels
+  double *pooled;              // [units][N] pooled fp32 scores when the middle pick pools (else null)
 };
 // Buffers of the int8 row-statistics pass (see score_i8.hip).
 constexpr int I8_QCAP = 4096;   // listed window-row remainders per unit
@@ -177,8 +178,9 @@ int launch_select_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *sc
                          int hi, int count, int prefix, int gap, int suffix, int32_t *out, int out_stride,
                          hipStream_t s);
 // cleared: the words of msel_zero_words have been set to zero by an earlier kernel on the stream
-int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *qd,
-                       const unsigned long long *knorm, int32_t *band_idx, int32_t *band_cnt, int *above_band,
+// pooled: the pooled scores the middle pick ranks by when it pools (width dm.pool), else null
+int launch_band_sliced(const Dims &dm, int n_cu, MSelBufs mb, const double *scores, const double *pooled,
+                       const double *qd, const unsigned long long *knorm, int32_t *band_idx, int32_t *band_cnt, int *above_band,
                        int *list_ok, bool cleared, hipStream_t s);
 void msel_zero_words(const Dims &dm, const MSelBufs &mb, ZeroList &z);
 // The middle pick on screened scores whose band lists are still there: the

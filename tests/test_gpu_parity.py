@@ -483,7 +483,12 @@ def test_empty_units_give_zero_output():
 @pytest.mark.parametrize("kw", [dict(), dict(recipe="zipf", ctx_len=5000, n_middle=300, top_t=200),
                                 dict(ctx_len=9000, n_q_heads=32, n_kv_heads=4, obs_window=32, n_middle=500),
                                 # long enough for the selections that several blocks share
-                                dict(batch=1, ctx_len=34000, n_middle=900, top_t=256)])
+                                dict(batch=1, ctx_len=34000, n_middle=900, top_t=256),
+                                # pooled middle pick: the band lists the columns under a pooled score's window
+                                dict(batch=1, ctx_len=34000, n_middle=900, top_t=256, pool_kernel=7),
+                                dict(batch=1, ctx_len=33100, n_q_heads=16, n_kv_heads=16, obs_window=32, n_middle=2500,
+                                     n_sink=4, n_recent=64, top_t=300, pool_kernel=3),
+                                dict(recipe="zipf", ctx_len=40000, n_middle=300, top_t=200, pool_kernel=7)])
 def test_screening_changes_no_decision(kw):
     """With and without the fp32 screening pass: identical mask, kept indices and
     top-t vectors; without it every score is fp64-exact."""
