@@ -553,7 +553,10 @@ static bool msel_sized(const Dims &dm) { return dm.N >= MSEL_MIN_RANGE && dm.uni
 // Long ranges on few units; elsewhere the extra launches cost more than the
 // idle compute units.
 bool msel_pays(const Dims &dm, int n_cu, int lo, int hi, int count) {
-  return msel_sized(dm) && hi - lo >= MSEL_MIN_RANGE && count > 0 && count < hi - lo && msel_slices(dm, n_cu) >= 2;
+  // (one block per unit leaves most of the chip idle on 16 units or fewer: there half the range pays,
+  // 8 units of 32496 scores measured 52 us in one block each, 40 us as six sliced kernels)
+  const int min_range = dm.units <= 16 ? MSEL_MIN_RANGE / 2 : MSEL_MIN_RANGE;
+  return msel_sized(dm) && hi - lo >= min_range && count > 0 && count < hi - lo && msel_slices(dm, n_cu) >= 2;
 }
 
 static size_t al256(size_t b) { return (b + 255) & ~size_t(255); }
