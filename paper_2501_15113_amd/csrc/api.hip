@@ -433,7 +433,7 @@ int taskkv_compress(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *k,
     MSelBufs mb;
     const bool sliced = msel_carve(cv, d, mb);
     if (!cv.ok) return TASKKV_EWORKSPACE;
-    if (sliced && from_band && d.pool == 1 && !d.keep_all && count > 0 && count < d.N - d.s1 - d.s2)
+    if (sliced && from_band && !d.keep_all && count > 0 && count < d.N - d.s1 - d.s2)
       rc = launch_select_from_band(d, ctx->n_cu, mb, sel_scores, hetero_mask, scr.band_idx, scr.band_cnt,
                                    scr.above_band, scr.list_ok, kept_idx, s);
     else if (sliced && !d.keep_all && msel_pays(d, ctx->n_cu, d.s1, d.N - d.s2, count))

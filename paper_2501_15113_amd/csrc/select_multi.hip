@@ -428,20 +428,23 @@ __global__ __launch_bounds__(1024) void msel_write_kernel(const double *__restri
 // scores, and a pooled score that has to be decided exactly needs the exact
 // scores of all the columns under its pooling window.  Lists the columns at or
 // above lo_t and those within `radius` of a middle column whose pooled score
-// lies inside [lo_k, hi_k].
+// lies inside [lo_k, hi_k] (1); 2 = a middle column that is not listed and
+// whose pooled score is above the band.  (A listed column outside the band
+// keeps a pooled score that is only fp32-accurate, and still on the same side
+// of the middle threshold as its exact value.)
 struct InBandPooled {
   InBand b;
   const double *pooled;   // the unit's row
   int radius;
   __device__ __forceinline__ int operator()(int j, double x) const {
-    if (x >= b.lo_t) return 1;
-    int hit = 0;
+    int hit = x >= b.lo_t ? 1 : 0, above = 0;
     const int i0 = max(j - radius, b.m0), i1 = min(j + radius, b.m1 - 1);
     for (int i = i0; i <= i1; ++i) {
       const double p = pooled[i];
       hit |= (p >= b.lo_k && p <= b.hi_k) ? 1 : 0;
+      above |= (i == j && p > b.hi_k) ? 1 : 0;
     }
-    return hit;
+    return hit ? 1 : (above ? 2 : 0);
   }
 };
 
