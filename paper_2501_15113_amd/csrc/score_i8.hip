@@ -78,6 +78,17 @@ __device__ __forceinline__ bool fits_window(int M, int e, int E) {
   return sh >= 0 || (((uint32_t)M >> back) << back) == (uint32_t)M;
 }
 __device__ __forceinline__ double bf16_to_double(uint32_t b) { return (double)__uint_as_float(b << 16); }
+// The bf16 element b in a row with exponent E: false if it fits the row's
+// window, else its remainder (the element minus the part inside the window).
+__device__ __forceinline__ bool remainder_of(uint32_t b, int E, double &rem) {
+  int e, M;
+  bool neg;
+  bf16_fields(b, e, M, neg);
+  if (fits_window(M, e, E)) return false;
+  const double kept = ldexp((double)window_part(M, e, E), E - I8_GRID);
+  rem = bf16_to_double(b) - (neg ? -kept : kept);
+  return true;
+}
 
 // Exponentials of the row statistics.  Logits are kept in units of ln 2 / 256
 // (the factor is folded into the rows' scale factors), so that for an argument
@@ -132,22 +143,27 @@ __device__ __forceinline__ double exp_sum17(double carry, double x0, const doubl
 // below 2^30 in magnitude, so the scaling and the conversion to an integer S
 // (towards zero: the magnitude keeps window_part's bits) are exact float
 // operations, and the element fits when converting back returns the scaled
-// value.  The four balanced digits of S are the bytes of
+// value.  That test is only made when the quick one fails: a scaled magnitude
+// of 128 or more has all eight mantissa bits on the grid, so if the smallest of
+// the sixteen is that large everything fits (a zero, or an element 2^22 below
+// its row's largest, sends the sixteen through the exact test).  The four
+// balanced digits of S are the bytes of
 // (S + 0x00808080) ^ 0x00808080; two rounds of byte permutes turn the four
 // elements' digit bytes into one dword per digit.
+__device__ __forceinline__ float scaled_element(const uint32_t (&w)[8], int x, int E) {
+  const float val = __uint_as_float((x & 1) ? (w[x >> 1] & 0xffff0000u) : (w[x >> 1] << 16));
+  return ldexpf(val, I8_GRID - E);
+}
 __device__ __forceinline__ bool digits_of(const uint32_t (&w)[8], int E, v4i (&dig)[4]) {
-  bool all_fit = true;
+  float smallest = INFINITY;
 #pragma unroll
   for (int x4 = 0; x4 < 4; ++x4) {
     uint32_t dd[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int x = 4 * x4 + i;
-      const float val = __uint_as_float((x & 1) ? (w[x >> 1] & 0xffff0000u) : (w[x >> 1] << 16));
-      const float scaled = ldexpf(val, I8_GRID - E);
-      const int S = (int)scaled;
-      all_fit = all_fit && (float)S == scaled;
-      dd[i] = (uint32_t)(S + 0x00808080) ^ 0x00808080u;
+      const float scaled = scaled_element(w, 4 * x4 + i, E);
+      smallest = __builtin_fminf(smallest, __builtin_fabsf(scaled));
+      dd[i] = (uint32_t)((int)scaled + 0x00808080) ^ 0x00808080u;
     }
     // byte t of dd[i] -> byte i of digit t (v_perm_b32: selectors 0-3 take bytes of the second operand, 4-7 of the first)
     const uint32_t a01 = __builtin_amdgcn_perm(dd[1], dd[0], 0x05010400u), b01 = __builtin_amdgcn_perm(dd[1], dd[0], 0x07030602u);
@@ -156,6 +172,13 @@ __device__ __forceinline__ bool digits_of(const uint32_t (&w)[8], int E, v4i (&d
     dig[1][x4] = (int)__builtin_amdgcn_perm(a23, a01, 0x07060302u);
     dig[2][x4] = (int)__builtin_amdgcn_perm(b23, b01, 0x05040100u);
     dig[3][x4] = (int)__builtin_amdgcn_perm(b23, b01, 0x07060302u);
+  }
+  if (smallest >= 128.f) return true;
+  bool all_fit = true;
+#pragma unroll
+  for (int x = 0; x < 16; ++x) {
+    const float scaled = scaled_element(w, x, E);
+    all_fit = all_fit && (float)(int)scaled == scaled;
   }
   return all_fit;
 }
@@ -219,13 +242,8 @@ __global__ __launch_bounds__(64) void q_digits_kernel(const uint16_t *__restrict
     if (!ok) {
       // the remainders of the elements that do not fit go on the unit's list
       for (int x = 0; x < 16; ++x) {
-        const uint32_t b = (x & 1) ? (w[ks][x >> 1] >> 16) : (w[ks][x >> 1] & 0xffffu);
-        int e, M;
-        bool neg;
-        bf16_fields(b, e, M, neg);
-        if (fits_window(M, e, E)) continue;
-        const double kept = ldexp((double)window_part(M, e, E), E - I8_GRID);
-        const double rem = bf16_to_double(b) - (neg ? -kept : kept);
+        double rem;
+        if (!remainder_of((x & 1) ? (w[ks][x >> 1] >> 16) : (w[ks][x >> 1] & 0xffffu), E, rem)) continue;
         const int at = atomicAdd(qcnt + unit, 1);
         if (at < I8_QCAP) {
           QTiny ent;
@@ -245,15 +263,194 @@ __global__ void zero_i32_kernel(int32_t *p, int n) {
   if (i < n) p[i] = 0;
 }
 
+// ---- pieces of a 32-key x 32-row tile that the kernels below share
+
+// t16[v] <- sum_{a,b} 256^(a+b) sum_c dk_a[c] dq_b[c] for the lane's sixteen
+// (key, row) pairs; ka(ks, a) gives the key digits a of channel block ks.
+// Classes a + b = 6 ... 0: Horner from the top class down, two classes
+// joined in int32 (256 x a class sum plus the next stays below 2^31) before every fp64 step.
+// (Interleaving the instructions of two classes, so that no two
+// consecutive ones accumulate into the same registers, was measured
+// 4 % slower: the second register block costs more than it hides.)
+// KZ / QZ: the tile's lowest key digits / the row block's lowest
+// digits are all zero, so the products with digit 0 on that side drop out.
+template <int KS, bool KZ, bool QZ, typename KA>
+__device__ __forceinline__ void digit_classes(KA ka, const v4i (&qv)[KS][4], double (&t16)[16]) {
+  // acc += the digit products of class cls
+  auto class_sum = [&](int cls, v16i acc) {
+#pragma unroll
+    for (int a = KZ ? 1 : 0; a < 4; ++a) {
+      const int b = cls - a;
+      if (b < (QZ ? 1 : 0) || b > 3) continue;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(ka(ks, a), qv[ks][b], acc, 0, 0, 0);
+    }
+    return acc;
+  };
+  v16i zero;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) zero[v] = 0;
+  {
+    const v16i top = class_sum(6, zero);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) t16[v] = (double)top[v];
+  }
+#pragma unroll
+  for (int cls = 5; cls >= 1; cls -= 2) {
+    if (KZ && QZ && cls == 1) {
+      // classes 1 and 0 are empty
+#pragma unroll
+      for (int v = 0; v < 16; ++v) t16[v] *= 65536.0;
+    } else if ((KZ || QZ) && cls == 1) {
+      const v16i hi = class_sum(1, zero);   // class 0 is empty
+#pragma unroll
+      for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 65536.0, (double)(hi[v] * 256));
+    } else {
+      // the lower class is accumulated on top of 256 x the upper one: one
+      // accumulator block instead of two
+      v16i acc = class_sum(cls, zero);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] *= 256;
+      acc = class_sum(cls - 1, acc);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 65536.0, (double)acc[v]);
+    }
+  }
+}
+
+// Four straight-line variants of digit_classes, chosen once per tile.  The
+// matrix phase runs at raised priority: when both waves of a SIMD are ready,
+// the one with matrix instructions to issue goes first and the other one's
+// vector work fills the gaps behind them (-2.5 %).
+template <int KS, typename KA>
+__device__ __forceinline__ void contract_tile(KA ka, const v4i (&qv)[KS][4], bool k_low_zero, bool q_low_zero,
+                                              double (&t16)[16]) {
+  __builtin_amdgcn_s_setprio(1);
+  if (k_low_zero) {
+    if (q_low_zero) digit_classes<KS, true, true>(ka, qv, t16);
+    else digit_classes<KS, true, false>(ka, qv, t16);
+  } else {
+    if (q_low_zero) digit_classes<KS, false, true>(ka, qv, t16);
+    else digit_classes<KS, false, false>(ka, qv, t16);
+  }
+  __builtin_amdgcn_s_setprio(0);
+}
+
+// Key of the tile that register v of a lane in key half `half` belongs to.
+__device__ __forceinline__ int tile_key(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
+
+// Remainders of this row's elements that did not fit: t16 += r * scale * k[c].
+template <int D>
+__device__ __forceinline__ void add_row_remainders(const QTiny *__restrict__ tiny, int n_tiny, int row, int j0, int half,
+                                                   int NK, double unit_scale, const uint16_t *__restrict__ kb,
+                                                   double (&t16)[16]) {
+  for (int e = 0; e < n_tiny; ++e) {
+    const QTiny ent = tiny[e];
+    if (ent.row != row) continue;
+    // the key indices are formed inside the loop on purpose: hoisted, their
+    // sixteen addresses and compares would be paid by every tile
+    int jl = j0 + 4 * half;
+    asm volatile("" : "+v"(jl));
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int j = jl + 8 * (v >> 2) + (v & 3);
+      if (j < NK) t16[v] += ent.r * unit_scale * bf16_to_double(kb[(size_t)j * D + ent.c]);
+    }
+  }
+}
+
+// Remainder of one key element that did not fit (ent.c: channel, ent.r: the
+// remainder; kk: the key within the tile): t16 += qh[c] * r * scale, with qh
+// the part of the row's element inside its window.
+template <int D>
+__device__ __forceinline__ void add_key_remainder(const QTiny &ent, int kk, int half, int row,
+                                                  const double *__restrict__ qdu, const QTiny *__restrict__ tiny,
+                                                  int n_tiny, double unit_scale, double (&t16)[16]) {
+  if (kk < 0 || kk >= 32 || ((kk >> 2) & 1) != half) return;
+  double qh = qdu[(size_t)row * D + ent.c];
+  for (int e2 = 0; e2 < n_tiny; ++e2) {
+    const QTiny q2 = tiny[e2];
+    if (q2.row == row && q2.c == ent.c) qh -= q2.r;
+  }
+  const int vv = 4 * (kk >> 3) + (kk & 3);
+  const double add = qh * ent.r * unit_scale;
+#pragma unroll
+  for (int v = 0; v < 16; ++v)
+    if (v == vv) t16[v] += add;
+}
+
+// Plain fp64 dot products for the lane's sixteen keys.
+template <int D>
+__device__ __forceinline__ void plain_logits(const double *__restrict__ q_row, const uint16_t *__restrict__ kb, int j0,
+                                             int half, int NK, double unit_scale, double (&t16)[16]) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) t16[v] = 0.0;
+  for (int cc = 0; cc < D; ++cc) {
+    const double qe = q_row[cc];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int j = j0 + tile_key(v, half);
+      t16[v] += qe * bf16_to_double(kb[(size_t)(j < NK ? j : 0) * D + cc]);
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) t16[v] *= unit_scale;
+}
+
+// The tile's visible logits join the running statistics (m, ls) of the lane's
+// row at once: seventeen exponentials for sixteen logits, no per-logit selects.
+__device__ __forceinline__ void join_statistics(double (&t16)[16], int j0, int half, int row, const Dims &dm,
+                                                const double *pow_tab, double &m, double &ls) {
+  const int N = dm.N, NK = dm.n_keys, L = dm.L;
+  double mx = m;
+  if (j0 + 31 < NK && j0 + 31 <= N - L) {
+    // a tile before the window: every key is visible to every row (rows
+    // past R carry zero digits; their statistics are never read), so the
+    // maximum and all sixteen arguments are finite
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mx = fmax(mx, t16[v]);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) t16[v] -= mx;
+    ls = exp_sum17<false>(ls, m - mx, t16, pow_tab);
+    m = mx;
+  } else {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int j = j0 + tile_key(v, half);
+      const bool vis = j < NK && row < dm.R && j <= N - L + (dm.row0 + row) % L;
+      t16[v] = vis ? t16[v] : -INFINITY;
+      mx = fmax(mx, t16[v]);
+    }
+    if (mx > -INFINITY) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) t16[v] -= mx;
+      ls = exp_sum17<true>(ls, m - mx, t16, pow_tab);
+      m = mx;
+    }
+  }
+}
+
+// Merges the two key halves of every row (lanes l and l ^ 32) and writes the
+// wave's partial record.
+__device__ __forceinline__ void write_partial(double m, double ls, int half, int row, double *__restrict__ pp) {
+  const double mo = __shfl_xor(m, 32), lo = __shfl_xor(ls, 32);
+  const double mn = fmax(m, mo);
+  if (mn > -INFINITY) ls = ls * exp2((m - mn) * (1.0 / 256)) + lo * exp2((mo - mn) * (1.0 / 256));
+  if (half == 0) {
+    pp[2 * row] = mn * (1.0 / EXP_UNITS);   // back to natural units
+    pp[2 * row + 1] = ls;
+  }
+}
+
 // part[unit][n_parts][Rpad][2] <- (row maximum, denominator) over the keys of
 // this block; grid = (key ranges, units, groups of 32 NW / WPR window rows).  NW
 // waves per block, one 32-row block each: 8, or 4 when the window has at most
 // 128 rows (two such blocks share a compute unit, so that every SIMD still
 // holds two waves with rows to work on).
-// Windows of 32 or 64 rows (one query head per KV head with the usual window
-// of 32) have fewer 32-row blocks than a block has waves: there WPR = 2 waves
-// share a row block and take one of the two 32-key tiles of a step each, and
-// each writes a partial record of its own.
+// Windows of 64 rows have fewer 32-row blocks than a block has waves: there
+// WPR = 2 waves share a row block and take one of the two 32-key tiles of a
+// step each, and each writes a partial record of its own.  (Windows of at most
+// 32 rows: score_i8_direct_kernel.)
 template <int D, int NW, int WPR>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void score_i8_stats_kernel(
     const uint16_t *__restrict__ k, const v4i *__restrict__ qdig, const double *__restrict__ gq,
@@ -370,17 +567,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
         bad &= bad - 1;
         if (l == src) {
           for (int x = 0; x < 16; ++x) {
-            const uint32_t b = (x & 1) ? (raw[it][x >> 1] >> 16) : (raw[it][x >> 1] & 0xffffu);
-            int e, M;
-            bool neg;
-            bf16_fields(b, e, M, neg);
-            if (fits_window(M, e, E)) continue;
+            double rem;
+            if (!remainder_of((x & 1) ? (raw[it][x >> 1] >> 16) : (raw[it][x >> 1] & 0xffffu), E, rem)) continue;
             if (cnt < I8_KCAP) {
-              const double kept = ldexp((double)window_part(M, e, E), E - I8_GRID);
               QTiny ent;
               ent.row = ck;
               ent.c = cseg * 16 + x;
-              ent.r = bf16_to_double(b) - (neg ? -kept : kept);
+              ent.r = rem;
               s_ktiny[buf][w][cnt] = ent;
             }
             ++cnt;
@@ -443,72 +636,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
               for (int t = 0; t < 4; ++t) ka[ks][t] = s_dig[buf][tile][ks][t][l];
           }
-          // classes a + b = 6 ... 0: Horner from the top class down, two classes
-          // joined in int32 (256 x a class sum plus the next stays below 2^31) before every fp64 step.
-          // (Interleaving the instructions of two classes, so that no two
-          // consecutive ones accumulate into the same registers, was measured
-          // 4 % slower: the second register block costs more than it hides.)
-          // KZ / QZ: the tile's lowest key digits / the row block's lowest
-          // digits are all zero, so the products with digit 0 on that side drop
-          // out; four straight-line variants, chosen once per tile.
-          auto contract = [&](auto kz, auto qz) {
-            constexpr bool KZ = decltype(kz)::value, QZ = decltype(qz)::value;
-            // acc += the digit products of class cls
-            auto class_sum = [&](int cls, v16i acc) {
-#pragma unroll
-              for (int a = KZ ? 1 : 0; a < 4; ++a) {
-                const int b = cls - a;
-                if (b < (QZ ? 1 : 0) || b > 3) continue;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                  acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(PRELOAD ? ka[ks][a] : s_dig[buf][tile][ks][a][l], qv[ks][b],
-                                                              acc, 0, 0, 0);
-              }
-              return acc;
-            };
-            v16i zero;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) zero[v] = 0;
-            {
-              const v16i top = class_sum(6, zero);
-#pragma unroll
-              for (int v = 0; v < 16; ++v) t16[v] = (double)top[v];
-            }
-#pragma unroll
-            for (int cls = 5; cls >= 1; cls -= 2) {
-              if (KZ && QZ && cls == 1) {
-                // classes 1 and 0 are empty
-#pragma unroll
-                for (int v = 0; v < 16; ++v) t16[v] *= 65536.0;
-              } else if ((KZ || QZ) && cls == 1) {
-                const v16i hi = class_sum(1, zero);   // class 0 is empty
-#pragma unroll
-                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 65536.0, (double)(hi[v] * 256));
-              } else {
-                // the lower class is accumulated on top of 256 x the upper one: one
-                // accumulator block instead of two
-                v16i acc = class_sum(cls, zero);
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] *= 256;
-                acc = class_sum(cls - 1, acc);
-#pragma unroll
-                for (int v = 0; v < 16; ++v) t16[v] = fma(t16[v], 65536.0, (double)acc[v]);
-              }
-            }
-          };
           const bool k_low_zero = !((knz >> tile) & 1);
-          // The matrix phase runs at raised priority: when both waves of a SIMD
-          // are ready, the one with matrix instructions to issue goes first and
-          // the other one's vector work fills the gaps behind them (-2.5 %).
-          __builtin_amdgcn_s_setprio(1);
-          if (k_low_zero) {
-            if (q_low_zero) contract(std::true_type{}, std::true_type{});
-            else contract(std::true_type{}, std::false_type{});
-          } else {
-            if (q_low_zero) contract(std::false_type{}, std::true_type{});
-            else contract(std::false_type{}, std::false_type{});
-          }
-          __builtin_amdgcn_s_setprio(0);
+          if (PRELOAD) contract_tile<KS>([&](int ks, int a) { return ka[ks][a]; }, qv, k_low_zero, q_low_zero, t16);
+          else contract_tile<KS>([&](int ks, int a) { return s_dig[buf][tile][ks][a][l]; }, qv, k_low_zero, q_low_zero, t16);
           {
             // exponents of the lane's sixteen keys (read late: sixteen registers
             // fewer across the matrix phase keep most temporaries out of scratch memory)
@@ -522,84 +652,21 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
             for (int v = 0; v < 16; ++v) t16[v] = ldexp(t16[v] * gqr, ek[v]);
           }
-          // remainders of this row's elements that did not fit: r * k[c]
-          for (int e = 0; e < n_tiny; ++e) {
-            const QTiny ent = tiny[e];
-            if (ent.row != row) continue;
-            // the key indices are formed inside the loop on purpose: hoisted, their
-            // sixteen addresses and compares would be paid by every tile
-            int jl = j0 + 4 * half;
-            asm volatile("" : "+v"(jl));
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int j = jl + 8 * (v >> 2) + (v & 3);
-              if (j < NK) t16[v] += ent.r * unit_scale * bf16_to_double(kb[(size_t)j * D + ent.c]);
-            }
-          }
+          add_row_remainders<D>(tiny, n_tiny, row, j0, half, NK, unit_scale, kb, t16);
           // remainders of key elements that did not fit: qh[c] * r
           if (k_listed) {
             for (int ww = 0; ww < NW; ++ww) {
               const int cw = s_kcnt[buf][ww];
               for (int e = 0; e < cw; ++e) {
                 const QTiny ent = s_ktiny[buf][ww][e];
-                const int kk = ent.row - tile * 32;          // key within the tile
-                if (kk < 0 || kk >= 32 || ((kk >> 2) & 1) != half) continue;
-                double qh = qdu[(size_t)row * D + ent.c];
-                for (int e2 = 0; e2 < n_tiny; ++e2) {
-                  const QTiny q2 = tiny[e2];
-                  if (q2.row == row && q2.c == ent.c) qh -= q2.r;
-                }
-                const int vv = 4 * (kk >> 3) + (kk & 3);
-                const double add = qh * ent.r * unit_scale;
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                  if (v == vv) t16[v] += add;
+                add_key_remainder<D>(ent, ent.row - tile * 32, half, row, qdu, tiny, n_tiny, unit_scale, t16);
               }
             }
           }
         } else {
-          // plain fp64 dot products for the lane's sixteen keys
-#pragma unroll
-          for (int v = 0; v < 16; ++v) t16[v] = 0.0;
-          for (int cc = 0; cc < D; ++cc) {
-            const double qe = qdu[(size_t)row * D + cc];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int j = j0 + 8 * (v >> 2) + 4 * half + (v & 3);
-              t16[v] += qe * bf16_to_double(kb[(size_t)(j < NK ? j : 0) * D + cc]);
-            }
-          }
-#pragma unroll
-          for (int v = 0; v < 16; ++v) t16[v] *= unit_scale;
+          plain_logits<D>(qdu + (size_t)row * D, kb, j0, half, NK, unit_scale, t16);
         }
-        // the tile's visible logits join the running statistics at once:
-        // seventeen exponentials for sixteen logits, no per-logit selects
-        double mx = m;
-        if (j0 + 31 < NK && j0 + 31 <= N - L) {
-          // a tile before the window: every key is visible to every row (rows
-          // past R carry zero digits; their statistics are never read), so the
-          // maximum and all sixteen arguments are finite
-#pragma unroll
-          for (int v = 0; v < 16; ++v) mx = fmax(mx, t16[v]);
-#pragma unroll
-          for (int v = 0; v < 16; ++v) t16[v] -= mx;
-          ls = exp_sum17<false>(ls, m - mx, t16, s_pow);
-          m = mx;
-        } else {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int j = j0 + 8 * (v >> 2) + 4 * half + (v & 3);
-            const bool vis = j < NK && row < R && j <= N - L + (row0 + row) % L;
-            t16[v] = vis ? t16[v] : -INFINITY;
-            mx = fmax(mx, t16[v]);
-          }
-          if (mx > -INFINITY) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) t16[v] -= mx;
-            ls = exp_sum17<true>(ls, m - mx, t16, s_pow);
-            m = mx;
-          }
-        }
+        join_statistics(t16, j0, half, row, dm, s_pow, m, ls);
       }
     }
     if (!convert_first) {
@@ -615,18 +682,179 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     if (l == 0 && norm_best > 0.f)
       atomicMax(knorm + unit, (unsigned long long)__double_as_longlong((double)norm_best * 1.001));
   }
-  // merge the two key halves of every row and write the block's partial
-  if (have) {
-    const double mo = __shfl_xor(m, 32), lo = __shfl_xor(ls, 32);
-    const double mn = fmax(m, mo);
-    if (mn > -INFINITY) ls = ls * exp2((m - mn) * (1.0 / 256)) + lo * exp2((mo - mn) * (1.0 / 256));
-    m = mn;
-    if (half == 0) {
-      double *pp = part + (((size_t)unit * gridDim.x + blockIdx.x) * WPR + sub) * Rpad * 2;
-      pp[2 * row] = m * (1.0 / EXP_UNITS);   // back to natural units
-      pp[2 * row + 1] = ls;
+  if (have) write_partial(m, ls, half, row, part + (((size_t)unit * gridDim.x + blockIdx.x) * WPR + sub) * Rpad * 2);
+}
+
+// Windows of at most 32 rows (one query head per KV head with the usual window
+// of 32): the key digits of a tile are used by one wave only, so there is
+// nothing to share.  Every wave converts its own tiles straight into operand
+// layout -- lane (key c32, half) loads and converts the 16-channel segments
+// [32 ks + 16 half, + 16) of its key, which is what it holds of the operand --
+// with no staging through other waves and no barrier between the waves; the
+// staged kernel's 64 KB of double-buffered digits would leave such a block's two
+// waves alone on their SIMDs.
+// grid = (key ranges, units); wave w of a block takes the tiles w, w + NW, ...
+// of the block's range and writes a partial record of its own:
+// part[unit][range][w][32][2].
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void score_i8_direct_kernel(
+    const uint16_t *__restrict__ k, const v4i *__restrict__ qdig, const double *__restrict__ gq,
+    const double *__restrict__ qd, const QTiny *__restrict__ qtiny, const int32_t *__restrict__ qcnt,
+    double *__restrict__ part, unsigned long long *__restrict__ knorm, Dims dm, int keys_per_wg) {
+  constexpr int KS = D / 32, THREADS = 64 * NW;
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, half = l >> 5;
+  const int N = dm.N, NK = dm.n_keys;
+  const double unit_scale = dm.scale * EXP_UNITS;   // logits are kept in units of ln 2 / 256
+  const uint16_t *kb = k + (size_t)unit * N * D;
+  const double *qdu = qd + (size_t)unit * 32 * D;
+  const int n_tiny_all = qcnt[unit];
+  const bool q_overflow = n_tiny_all > I8_QCAP;   // then every logit takes the plain fp64 route
+  const int n_tiny = q_overflow ? 0 : n_tiny_all;
+  const QTiny *tiny = qtiny + (size_t)unit * I8_QCAP;
+
+  __shared__ double s_pow[EXP_TAB];         // 2^(j/256)
+  __shared__ QTiny s_ktiny[NW][I8_KCAP];    // a wave's listed key remainders of its tile; .row = key of the tile
+  __shared__ int s_ek[NW][32];              // key factors of a wave's tile
+  // A wave's digits wait in LDS of its own for the matrix instructions that
+  // use them: held in registers (64 of them) they push others into scratch
+  // memory, and a reload from there waits, in order, for the key loads of the
+  // next tile that are meant to stay in flight behind the arithmetic.
+  __shared__ v4i s_dig[NW][KS][4][64];
+  for (int i = tid; i < EXP_TAB; i += THREADS) s_pow[i] = exp2((double)i * (1.0 / EXP_TAB));
+  __syncthreads();
+
+  const int row = c32;
+  v4i qv[KS][4];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) qv[ks][t] = qdig[((((size_t)unit) * KS + ks) * 4 + t) * 64 + l];
+  const double gqr = gq[(size_t)unit * 32 + row];
+  double m = -INFINITY, ls = 0.0;
+  bool q_low = false;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) q_low = q_low || (qv[ks][0][0] | qv[ks][0][1] | qv[ks][0][2] | qv[ks][0][3]) != 0;
+  const bool q_low_zero = __ballot(q_low) == 0ull;
+
+  const int kbase = blockIdx.x * keys_per_wg;
+  const int kend = min(kbase + keys_per_wg, NK);
+  const int n_tiles = kend > kbase ? (kend - kbase + 31) / 32 : 0;
+  uint32_t raw[KS][8];
+  auto fetch = [&](int tile) {
+    const int j = kbase + tile * 32 + c32;
+    if (tile < n_tiles && j < kend) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const uint4 lo = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + ks * 32 + half * 16);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + ks * 32 + half * 16 + 8);
+        raw[ks][0] = lo.x; raw[ks][1] = lo.y; raw[ks][2] = lo.z; raw[ks][3] = lo.w;
+        raw[ks][4] = hi.x; raw[ks][5] = hi.y; raw[ks][6] = hi.z; raw[ks][7] = hi.w;
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int x = 0; x < 8; ++x) raw[ks][x] = 0u;
     }
+  };
+  const bool want_norm = knorm != nullptr;   // the screening pass wants the largest squared key norm (over-estimated)
+  float norm_best = 0.f;
+
+  fetch(w);
+  for (int tile = w; tile < n_tiles; tile += NW) {
+    const int j0 = kbase + tile * 32;
+    // the tile's digits, in operand layout as they are converted
+    int E = 1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) E = max(E, row_exponent_of(raw[ks]));
+    E = max(E, __shfl_xor(E, 32));
+    if (want_norm) {
+      float ss = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const float lo = __uint_as_float(raw[ks][x] << 16), hi = __uint_as_float(raw[ks][x] & 0xffff0000u);
+          ss = fmaf(lo, lo, ss);
+          ss = fmaf(hi, hi, ss);
+        }
+      ss += __shfl_xor(ss, 32);
+      norm_best = fmaxf(norm_best, ss);
+    }
+    bool ok = true, k_low = false;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      v4i dig[4];
+      ok = digits_of(raw[ks], E, dig) && ok;
+      k_low = k_low || (dig[0][0] | dig[0][1] | dig[0][2] | dig[0][3]) != 0;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) s_dig[w][ks][t][l] = dig[t];
+    }
+    const bool k_low_zero = __ballot(k_low) == 0ull;
+    // remainders of the elements that do not fit go on the wave's short list,
+    // filled lane by lane; a count above its capacity sends the tile down the plain route
+    int cnt = 0;
+    unsigned long long bad = __ballot(!ok);
+    while (bad) {
+      const int src = __ffsll((long long)bad) - 1;
+      bad &= bad - 1;
+      if (l == src) {
+        // (the lane's 16-channel segments, read again: indexing the registers
+        // by a loop counter would move them to scratch memory)
+#pragma unroll 1
+        for (int i = 0; i < 16 * KS; ++i) {
+          const int c = (i >> 4) * 32 + half * 16 + (i & 15);
+          double rem;
+          if (!remainder_of(kb[(size_t)(j0 + c32) * D + c], E, rem)) continue;
+          if (cnt < I8_KCAP) {
+            QTiny ent;
+            ent.row = c32;
+            ent.c = c;
+            ent.r = rem;
+            s_ktiny[w][cnt] = ent;
+          }
+          ++cnt;
+        }
+      }
+      cnt = __shfl(cnt, src);
+    }
+    if (half == 0) s_ek[w][c32] = E - (2 * I8_GRID - 126);   // with the row factor: 2^(Eq - I8_GRID) 2^(Ek - I8_GRID)
+    fetch(tile + NW);   // the next tile's keys travel during this tile's arithmetic
+    __builtin_amdgcn_wave_barrier();   // the wave's own LDS writes above are read below, in program order
+
+    double t16[16];
+    if (!q_overflow && cnt <= I8_KCAP) {
+      contract_tile<KS>([&](int ks, int a) { return s_dig[w][ks][a][l]; }, qv, k_low_zero, q_low_zero, t16);
+      {
+        int ek[16];
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+          const v4i e4 = *reinterpret_cast<const v4i *>(&s_ek[w][8 * v4 + 4 * half]);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) ek[4 * v4 + x] = e4[x];
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t16[v] = ldexp(t16[v] * gqr, ek[v]);
+      }
+      add_row_remainders<D>(tiny, n_tiny, row, j0, half, NK, unit_scale, kb, t16);
+      for (int e = 0; e < cnt; ++e) {
+        const QTiny ent = s_ktiny[w][e];
+        add_key_remainder<D>(ent, ent.row, half, row, qdu, tiny, n_tiny, unit_scale, t16);
+      }
+    } else {
+      plain_logits<D>(qdu + (size_t)row * D, kb, j0, half, NK, unit_scale, t16);
+    }
+    join_statistics(t16, j0, half, row, dm, s_pow, m, ls);
+    __builtin_amdgcn_wave_barrier();   // the lists are rewritten by the next tile
   }
+
+  if (want_norm) {
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) norm_best = fmaxf(norm_best, __shfl_xor(norm_best, off));
+    if (l == 0 && norm_best > 0.f)
+      atomicMax(knorm + unit, (unsigned long long)__double_as_longlong((double)norm_best * 1.001));
+  }
+  write_partial(m, ls, half, row, part + (((size_t)unit * gridDim.x + blockIdx.x) * NW + w) * 32 * 2);
 }
 
 bool i8_stats_supported(const Dims &dm, int dtype) {
@@ -643,8 +871,32 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
   auto qdig = static_cast<v4i *>(bufs.qdig);
   if (!qcnt_zeroed) zero_i32_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(bufs.qcnt, dm.units);
   // waves per block, waves per row block: 8 x 1 for windows above 128 rows, 4 x 1
-  // down to 96 rows, 4 x 2 for 64 rows, 2 x 2 for 32
-  const int nw = n_rb > 4 ? 8 : (n_rb == 1 ? 2 : 4), wpr = n_rb <= 2 ? 2 : 1;
+  // down to 96 rows, 4 x 2 for 64 rows
+  if (n_rb == 1) {
+    // one row block: every wave for itself.  Enough tiles per wave to pay for
+    // its set-up (the row block's operands, the table), few enough for two
+    // waves on every SIMD, and no more partial records than the caller's
+    // split allows for (n_wg x 8 for one row block).
+    constexpr int DNW = 4;
+    const int tiles = (dm.n_keys + 31) / 32, n_cu = bufs.prof ? bufs.prof->n_cu : 256;
+    int per_wave = (int)(((int64_t)tiles * dm.units + n_cu * 8 - 1) / (n_cu * 8));
+    per_wave = per_wave < 4 ? 4 : per_wave;
+    int n_blk = (tiles + DNW * per_wave - 1) / (DNW * per_wave);
+    while (n_blk * DNW > n_wg * 8 && n_blk > 1) n_blk = (n_blk + 1) / 2;
+    const int keys_per_blk = ((tiles + n_blk - 1) / n_blk) * 32;
+    n_blk = (dm.n_keys + keys_per_blk - 1) / keys_per_blk;
+    *n_parts = n_blk * DNW;
+    auto go = [&](auto d) {
+      constexpr int DD = decltype(d)::value;
+      q_digits_kernel<DD><<<dim3(dm.units), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
+      launch_profiled(bufs.prof, 2, score_i8_direct_kernel<DD, DNW>, dim3(n_blk, dm.units), dim3(64 * DNW), s, kk, qdig,
+                      bufs.gq, qd, bufs.qtiny, bufs.qcnt, part, knorm, dm, keys_per_blk);
+    };
+    if (dm.D == 64) go(std::integral_constant<int, 64>{});
+    else go(std::integral_constant<int, 128>{});
+    return hip_ok(hipGetLastError());
+  }
+  const int nw = n_rb > 4 ? 8 : 4, wpr = n_rb <= 2 ? 2 : 1;
   const int rows_per_block = 32 * nw / wpr;
   const dim3 grid(n_wg, dm.units, (dm.Rpad + rows_per_block - 1) / rows_per_block);
   *n_parts = n_wg * wpr;
@@ -657,8 +909,7 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
     q_digits_kernel<DD><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
     if (nw == 8) launch(score_i8_stats_kernel<DD, 8, 1>);
     else if (wpr == 1) launch(score_i8_stats_kernel<DD, 4, 1>);
-    else if (nw == 4) launch(score_i8_stats_kernel<DD, 4, 2>);
-    else launch(score_i8_stats_kernel<DD, 2, 2>);
+    else launch(score_i8_stats_kernel<DD, 4, 2>);
   };
   if (dm.D == 64) pick(std::integral_constant<int, 64>{});
   else pick(std::integral_constant<int, 128>{});

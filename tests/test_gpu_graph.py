@@ -92,8 +92,9 @@ def test_graph_replays_match_eager_calls(dtype, ctx_len):
         assert np.isfinite(outs[-1].cpu().numpy()).all()
 
 
+@pytest.mark.parametrize("pool", [1, 7])
 @pytest.mark.parametrize("whole", [True, False])
-def test_graph_of_a_long_screened_layer(whole):
+def test_graph_of_a_long_screened_layer(whole, pool):
     """On a long screened layer the compressor takes its middle threshold from
     column lists that the separator leaves in the workspace, and whether they
     are still there is bookkeeping on the host.  A graph is replayed without
@@ -103,7 +104,7 @@ def test_graph_of_a_long_screened_layer(whole):
     lists in the workspace before every replay."""
     from paper_2501_15113_amd import session as ses
     wl = small_workload(name="graph-long", wid=231, batch=1, ctx_len=34000, n_middle=1200, top_t=256,
-                        decode_steps=STEPS)
+                        decode_steps=STEPS, pool_kernel=pool)
     ld, other_ld = make_layer(wl, 0, "cuda:0"), make_layer(wl, 1, "cuda:0")
     cfg = ses.cfg_from_workload(wl)
     with ses.Context([cfg], STEPS, screening=2) as ctx:
