@@ -409,7 +409,7 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     }
     // fp32 screening of every column, then fp64 for the columns that can take
     // part in a decision (any number of them: the grid covers all N)
-    int rc = launch_screen(dm, q_win, k, stats, scores, cpw, s);
+    int rc = launch_screen(dm, q_win, k, stats, scores, cpw, scr->n_cu, s);
     if (rc) return rc;
     // a middle pick that pools ranks by the pooled scores: the band follows it
     const double *pooled = nullptr;

@@ -41,6 +41,79 @@ union Frag16 {
   bf16x8 b;
 };
 
+// Softmax weights of one 16-key tile summed over the RB 16-row blocks a wave
+// holds (A operands a, row statistics m2 / inv in accumulator layout): the
+// 16 RB x 16 logits with RB x d/32 matrix instructions, issued together ahead
+// of the exponentials; returns the lane's share of its key's column sum (lane
+// (c, kg): key j0 + c, rows 4 kg .. 4 kg + 3 of every block), to be added over kg.
+template <int D, int RB>
+__device__ __forceinline__ float tile_column_sums(const Frag16 (&a)[RB][D / 32], const Frag16 (&bk)[D / 32],
+                                                  const float (&m2)[RB][4], const float (&inv)[RB][4],
+                                                  float scale_log2, int j0, int c, int kg, int rq, const Dims &dm) {
+  constexpr int KS = D / 32;
+  const int N = dm.N, L = dm.L, R = dm.R;
+  floatx4 acc[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) acc[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+      acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][kk].b, bk[kk].b, acc[rb], 0, 0, 0);
+  float colsum = 0.f;
+  if (j0 + 15 <= N - L) {
+    // before the window: no causal mask inside the tile.  Rows past R have
+    // inv = 0; keys past N are dropped when the sums are stored
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[rb][v], scale_log2, -m2[rb][v])), inv[rb][v], colsum);
+  } else {
+    const int j = j0 + c;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r2 = 64 * rq + 16 * rb + 4 * kg + v;
+        const bool vis = j < N && r2 < R && j <= N - L + r2 % L;
+        const float p = __builtin_amdgcn_exp2f(fmaf(acc[rb][v], scale_log2, -m2[rb][v])) * inv[rb][v];
+        colsum += vis ? p : 0.f;
+      }
+  }
+  return colsum;
+}
+
+// A operands and row statistics of the 16-row blocks [64 rq + 16 rb, + 16),
+// rb < RB, of a unit's window: lane (c, kg) holds Q[row 64 rq + 16 rb + c][(d/4) kg + 8 kk .. +8]
+// and, in accumulator layout, m (in units of ln 2) and 1 / l of rows 4 kg .. 4 kg + 3.
+template <int D, int RB>
+__device__ __forceinline__ void load_window_rows(const uint16_t *__restrict__ q_win, const double *__restrict__ st,
+                                                 int unit, int rq, int c, int kg, const Dims &dm,
+                                                 Frag16 (&a)[RB][D / 32], float (&m2)[RB][4], float (&inv)[RB][4]) {
+  constexpr int KS = D / 32;
+  const int b = unit / dm.Hkv, h = unit % dm.Hkv, L = dm.L, R = dm.R;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int row = 64 * rq + 16 * rb + c;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = make_uint4(0, 0, 0, 0);
+    if (row < R) {
+      const int g = row / L, i = row % L;
+      const uint16_t *qp = q_win + (((size_t)b * dm.Hq + (size_t)h * dm.G + g) * L + i) * D + (D / 4) * kg;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = *reinterpret_cast<const uint4 *>(qp + 8 * kk);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int r2 = 64 * rq + 16 * rb + 4 * kg + v;   // row of accumulator register v
+      const bool ok = r2 < R;
+      m2[rb][v] = ok ? (float)(st[2 * r2] * 1.4426950408889634) : 0.f;
+      inv[rb][v] = ok ? (float)(1.0 / st[2 * r2 + 1]) : 0.f;
+    }
+  }
+}
+
 // One block = 4 waves.  A wave owns a quad of four 16-row blocks of the window
 // (A operands in registers) and a slice of the chunk's keys; for every 16-key
 // tile it forms the 64 x 16 logits with 4 x d/32 MFMAs, turns them into softmax
@@ -80,25 +153,7 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
   auto load_rows = [&](int rq) {
     if (rq == cur_rq) return;
     cur_rq = rq;
-#pragma unroll
-    for (int rb = 0; rb < 4; ++rb) {
-      const int row = 64 * rq + 16 * rb + c;
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = make_uint4(0, 0, 0, 0);
-      if (row < R) {
-        const int g = row / L, i = row % L;
-        const uint16_t *qp = q_win + (((size_t)b * dm.Hq + (size_t)h * dm.G + g) * L + i) * D + (D / 4) * kg;
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk) a[rb][kk].u = *reinterpret_cast<const uint4 *>(qp + 8 * kk);
-      }
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int r2 = 64 * rq + 16 * rb + 4 * kg + v;   // row of accumulator register v
-        const bool ok = r2 < R;
-        m2[rb][v] = ok ? (float)(st[2 * r2] * 1.4426950408889634) : 0.f;
-        inv[rb][v] = ok ? (float)(1.0 / st[2 * r2 + 1]) : 0.f;
-      }
-    }
+    load_window_rows<D, 4>(q_win, st, unit, rq, c, kg, dm, a, m2, inv);
   };
 
   for (int ch = 0; ch < chunks_per_wg; ++ch) {
@@ -144,36 +199,8 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
       if (jc < jend) read_tile(jc, bk);
       for (int j0 = jc; j0 < jend; j0 += 16) {
         const int j = j0 + c;
-        const bool valid = j < N;
         if (j0 + 16 < jend) read_tile(j0 + 16, bk_next);
-        floatx4 acc[4];
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) acc[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-#pragma unroll
-          for (int rb = 0; rb < 4; ++rb)
-            acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][kk].b, bk[kk].b, acc[rb], 0, 0, 0);
-        float colsum = 0.f;
-        if (j0 + 15 <= N - L) {
-          // before the window: no causal mask inside the tile.  Rows past R have
-          // inv = 0; keys past N are dropped when the sums are stored
-#pragma unroll
-          for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-              colsum = fmaf(__builtin_amdgcn_exp2f(fmaf(acc[rb][v], scale_log2, -m2[rb][v])), inv[rb][v], colsum);
-        } else {
-#pragma unroll
-          for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              const int r2 = 64 * rq + 16 * rb + 4 * kg + v;
-              const bool vis = valid && r2 < R && j <= N - L + r2 % L;
-              const float p = __builtin_amdgcn_exp2f(fmaf(acc[rb][v], scale_log2, -m2[rb][v])) * inv[rb][v];
-              colsum += vis ? p : 0.f;
-            }
-        }
+        float colsum = tile_column_sums<D, 4>(a, bk, m2, inv, scale_log2, j0, c, kg, rq, dm);
         colsum = sum_lanes_16_32(colsum);
         if (kg == 0) cs[rq][j - jchunk] = colsum;
 #pragma unroll
@@ -190,6 +217,51 @@ __global__ __launch_bounds__(256) void score_screen_kernel(const uint16_t *__res
       }
     }
     __syncthreads();
+  }
+}
+
+// Windows of at most 64 rows are one row quad: a key's column sum is complete
+// inside one wave, and a chunk of keys staged for four waves would be used by
+// one.  Every wave streams a run of keys of its own straight from memory into
+// operand layout (lane (c, kg) holds key c's channels (d/4) kg .. + d/4: four
+// lanes read a key's row between them), two tiles ahead of the one it works on,
+// and writes its sums itself: no LDS, no barriers.  RB: 16-row blocks in use.
+template <int D, int RB>
+__global__ __launch_bounds__(256) void score_screen_direct_kernel(const uint16_t *__restrict__ q_win,
+                                                                  const uint16_t *__restrict__ k,
+                                                                  const double *__restrict__ stats,
+                                                                  double *__restrict__ scores, Dims dm,
+                                                                  int keys_per_wave) {
+  constexpr int KS = D / 32;
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c = l & 15, kg = l >> 4;
+  const int N = dm.N;
+  const uint16_t *kb = k + (size_t)unit * N * D;
+  const float scale_log2 = (float)(dm.scale * 1.4426950408889634);
+  const float inv_rows = 1.f / (float)dm.Rtot;
+  Frag16 a[RB][KS];
+  float m2[RB][4], inv[RB][4];
+  load_window_rows<D, RB>(q_win, stats + (size_t)unit * dm.Rpad * 2, unit, 0, c, kg, dm, a, m2, inv);
+  const int jbeg = (blockIdx.x * 4 + w) * keys_per_wave, jend = min(jbeg + keys_per_wave, N);
+  auto read_tile = [&](int j0, Frag16 (&bk)[KS]) {
+    const int j = min(j0 + c, N - 1);
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk)
+      bk[kk].u = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + (D / 4) * kg + 8 * kk);
+  };
+  Frag16 bk[3][KS];
+  if (jbeg < jend) read_tile(jbeg, bk[0]);
+  if (jbeg + 16 < jend) read_tile(jbeg + 16, bk[1]);
+  for (int j0 = jbeg; j0 < jend; j0 += 16) {
+    if (j0 + 32 < jend) read_tile(j0 + 32, bk[2]);
+    float colsum = tile_column_sums<D, RB>(a, bk[0], m2, inv, scale_log2, j0, c, kg, 0, dm);
+    colsum = sum_lanes_16_32(colsum);
+    const int j = j0 + c;
+    if (kg == 0 && j < N) scores[(size_t)unit * N + j] = (double)(colsum * inv_rows);
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      bk[0][kk] = bk[1][kk];
+      bk[1][kk] = bk[2][kk];
+    }
   }
 }
 
@@ -264,10 +336,26 @@ int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, h
 }
 
 int launch_screen(const Dims &dm, const void *q_win, const void *k, const double *stats, double *scores,
-                  int chunks_per_wg, hipStream_t s) {
+                  int chunks_per_wg, int n_cu, hipStream_t s) {
+  auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
+  if (dm.Rpad <= 64) {
+    // one row quad: runs of keys per wave, some sixteen waves per compute unit in all
+    const int tiles = (dm.N + 15) / 16;
+    int per_wave = (int)(((int64_t)tiles * dm.units + n_cu * 16 - 1) / (n_cu * 16));
+    per_wave = per_wave < 8 ? 8 : per_wave;
+    const int keys_per_wave = per_wave * 16;
+    const dim3 grid((dm.N + 4 * keys_per_wave - 1) / (4 * keys_per_wave), dm.units), block(256);
+    if (dm.D == 64) {
+      if (dm.Rpad <= 32) score_screen_direct_kernel<64, 2><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, keys_per_wave);
+      else score_screen_direct_kernel<64, 4><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, keys_per_wave);
+    } else {
+      if (dm.Rpad <= 32) score_screen_direct_kernel<128, 2><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, keys_per_wave);
+      else score_screen_direct_kernel<128, 4><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, keys_per_wave);
+    }
+    return hip_ok(hipGetLastError());
+  }
   const int n_chunks = (dm.N + QKC - 1) / QKC;
   const dim3 grid((n_chunks + chunks_per_wg - 1) / chunks_per_wg, dm.units), block(256);
-  auto qq = static_cast<const uint16_t *>(q_win), kk = static_cast<const uint16_t *>(k);
   if (dm.D == 64) score_screen_kernel<64><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, chunks_per_wg);
   else score_screen_kernel<128><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, chunks_per_wg);
   return hip_ok(hipGetLastError());

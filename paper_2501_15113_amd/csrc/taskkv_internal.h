@@ -147,7 +147,7 @@ int launch_zero_u64(unsigned long long *p, int n, hipStream_t s);
 bool screen_supported(const Dims &dm, int dtype);
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);
 int launch_screen(const Dims &dm, const void *q_win, const void *k, const double *stats, double *scores,
-                  int chunks_per_wg, hipStream_t s);
+                  int chunks_per_wg, int n_cu, hipStream_t s);
 // Buffers of the selections whose sweeps are cut into slices (see select_multi.hip).
 constexpr int MSEL_MAX_SLICES = 32;    // blocks that share a unit
 constexpr int MSEL_MAX_UNITS = 256;    // beyond this one block per unit fills the chip anyway

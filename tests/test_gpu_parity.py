@@ -492,7 +492,14 @@ def test_empty_units_give_zero_output():
                                 dict(batch=1, ctx_len=34000, n_middle=900, top_t=256, pool_kernel=7),
                                 dict(batch=1, ctx_len=33100, n_q_heads=16, n_kv_heads=16, obs_window=32, n_middle=2500,
                                      n_sink=4, n_recent=64, top_t=300, pool_kernel=3),
-                                dict(recipe="zipf", ctx_len=40000, n_middle=300, top_t=200, pool_kernel=7)])
+                                dict(recipe="zipf", ctx_len=40000, n_middle=300, top_t=200, pool_kernel=7),
+                                # windows of at most 64 rows: every wave screens a run of keys of its own
+                                dict(ctx_len=5003, n_q_heads=4, n_kv_heads=4, obs_window=16, n_middle=300),
+                                dict(ctx_len=4100, n_q_heads=6, n_kv_heads=3, obs_window=32, n_middle=300, head_dim=64),
+                                dict(ctx_len=3000, n_q_heads=9, n_kv_heads=3, obs_window=16, n_middle=200),
+                                dict(ctx_len=2500, n_q_heads=3, n_kv_heads=3, obs_window=5, n_middle=200, n_hetero=1),
+                                dict(batch=1, ctx_len=2000, n_q_heads=4, n_kv_heads=4, obs_window=64, top_t=500,
+                                     n_middle=200)])
 def test_screening_changes_no_decision(kw):
     """With and without the fp32 screening pass: identical mask, kept indices and
     top-t vectors; without it every score is fp64-exact."""
