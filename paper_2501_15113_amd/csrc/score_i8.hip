@@ -898,7 +898,18 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
   }
   const int nw = n_rb > 4 ? 8 : 4, wpr = n_rb <= 2 ? 2 : 1;
   const int rows_per_block = 32 * nw / wpr;
-  const dim3 grid(n_wg, dm.units, (dm.Rpad + rows_per_block - 1) / rows_per_block);
+  const int nz = (dm.Rpad + rows_per_block - 1) / rows_per_block;
+  // A block's set-up (operands of its row blocks, the table, filling the key
+  // pipeline) is worth several 64-key steps: ranges of up to 1024 keys while
+  // the blocks still fill the chip once (measured on 8 and 32 units of 128 rows
+  // x 32768 and 65536 keys: 3-5 % of the whole compression against ranges of
+  // 256 keys, 2048 keys a little slower again)
+  const int slots = (bufs.prof ? bufs.prof->n_cu : 256) * (nw == 8 ? 1 : 2);
+  while ((int64_t)((n_wg + 1) / 2) * dm.units * nz >= slots && keys_per_wg < 1024) {
+    keys_per_wg *= 2;
+    n_wg = (dm.n_keys + keys_per_wg - 1) / keys_per_wg;
+  }
+  const dim3 grid(n_wg, dm.units, nz);
   *n_parts = n_wg * wpr;
   auto launch = [&](auto kernel) {
     launch_profiled(bufs.prof, 2, kernel, grid, dim3(64 * nw), s, kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, part,
