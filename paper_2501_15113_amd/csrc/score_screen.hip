@@ -355,6 +355,8 @@ int launch_screen(const Dims &dm, const void *q_win, const void *k, const double
     return hip_ok(hipGetLastError());
   }
   const int n_chunks = (dm.N + QKC - 1) / QKC;
+  while ((int64_t)((n_chunks + 2 * chunks_per_wg - 1) / (2 * chunks_per_wg)) * dm.units >= 2 * n_cu && chunks_per_wg < 16)
+    chunks_per_wg *= 2;
   const dim3 grid((n_chunks + chunks_per_wg - 1) / chunks_per_wg, dm.units), block(256);
   if (dm.D == 64) score_screen_kernel<64><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, chunks_per_wg);
   else score_screen_kernel<128><<<grid, block, 0, s>>>(qq, kk, stats, scores, dm, chunks_per_wg);
