@@ -668,35 +668,38 @@ __global__ __launch_bounds__(1024) void mlist_settle_kernel(const double *__rest
   const double *sc = scores + (size_t)unit * N;
   const int32_t *list = band_idx + (size_t)unit * N;
   const int n = band_cnt[unit];
+  // The list indexes the scores: it has to be what the band kernels write
+  // (ascending columns inside the row), or the full selection decides.  The
+  // same pass counts the entries before the middle and before its end: the
+  // listed columns of the middle are entries [ia, ib) of the ascending list
+  // (a binary search would be two dozen dependent trips to memory).
+  __shared__ int s_below[2];
+  if (tid < 2) s_below[tid] = 0;
+  __syncthreads();
   {
-    // the list indexes the scores: it has to be what the band kernels write
-    // (ascending columns inside the row), or the full selection decides
     bool bad = n < 0 || n > N;
+    int b1 = 0, b2 = 0;
     for (int i = tid; i < n && !bad; i += 1024) {
       const int v = list[i];
       bad = v < 0 || v >= N || (i > 0 && list[i - 1] >= v);
+      b1 += v < dm.s1 ? 1 : 0;
+      b2 += v < N - dm.s2 ? 1 : 0;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      b1 += __shfl_xor(b1, off);
+      b2 += __shfl_xor(b2, off);
+    }
+    if ((tid & 63) == 0 && (b1 | b2)) {
+      atomicAdd(&s_below[0], b1);
+      atomicAdd(&s_below[1], b2);
     }
     if (__syncthreads_or(bad)) {
       if (tid == 0) mb.flag[unit] = 1;
       return;
     }
   }
-  // the listed columns of the middle: entries [ia, ib) of the ascending list
-  int ia = 0, ib = 0;
-  {
-    int lo = 0, hi = n;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (list[mid] < dm.s1) lo = mid + 1; else hi = mid;
-    }
-    ia = lo;
-    hi = n;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (list[mid] < N - dm.s2) lo = mid + 1; else hi = mid;
-    }
-    ib = lo;
-  }
+  const int ia = s_below[0], ib = s_below[1];
   int above = 0;
   for (int x = 0; x < mb.S; ++x) above += above_band[(size_t)unit * MSEL_MAX_SLICES + x];
   const int need = dm.k - above;
