@@ -286,18 +286,41 @@ def test_int8_statistics_with_elements_outside_the_window(rate_q, rate_k, what):
 @pytest.mark.parametrize("group,window", [(1, 32), (1, 16), (2, 32), (1, 64), (3, 32), (4, 32), (5, 32)])
 @pytest.mark.parametrize("outliers", [False, True])
 def test_int8_statistics_of_narrow_and_wide_windows(group, window, outliers):
-    """The int8 statistics kernel has a block shape per window size: two waves
-    per 32-row block for windows of 32 and 64 rows (one query head per KV head
-    is the common case), one wave per block of rows up to 128 rows, blocks of
-    eight waves above.  Each of them, with and without elements that leave the
-    integer window (remainder lists of both sides), on a context that ends in
-    a ragged tile."""
+    """The int8 statistics pass has a kernel shape per window size: every wave for
+    itself for windows of at most 32 rows (one query head per KV head is the
+    common case), two waves per 32-row block for 64 rows, one wave per block of
+    rows up to 128 rows, blocks of eight waves above.  Each of them, with and
+    without elements that leave the integer window (remainder lists of both
+    sides), on a context that ends in a ragged tile."""
     def tiny(ld):
         _shrink(ld.q_win, 0.004, 21)
         _shrink(ld.k, 0.001, 22)
     wl = small_workload(name=f"i8win-{group}-{window}", wid=197, ctx_len=2101, n_q_heads=3 * group, n_kv_heads=3,
                         obs_window=window, n_hetero=1, decode_steps=1)
     run_layer(wl, mutate=tiny if outliers else None, check_batches=(0, 1))
+
+
+@pytest.mark.parametrize("head_dim", [64, 128])
+@pytest.mark.parametrize("rate_q,rate_k,what", [
+    (0.0, 0.0, "no remainders"),
+    (0.002, 0.0005, "a few remainders on both lists"),
+    (0.0, 0.02, "key lists overflow: plain fp64 dot products for those tiles"),
+    (0.7, 0.001, "window-row list overflows: plain fp64 dot products everywhere"),
+    (0.01, 0.004, "many remainders, same channels on both sides"),
+])
+def test_int8_statistics_of_single_block_windows_on_every_route(rate_q, rate_k, what, head_dim):
+    """Windows of at most 32 rows go through the kernel in which every wave
+    converts its own key tiles: its remainder lists (one per wave and tile) and
+    its plain route, for both head sizes, with the screening pass of narrow
+    windows behind it."""
+    def tiny(ld):
+        if rate_q:
+            _shrink(ld.q_win, rate_q, 31)
+        if rate_k:
+            _shrink(ld.k, rate_k, 32)
+    wl = small_workload(name="i8direct", wid=199, ctx_len=2333, n_q_heads=5, n_kv_heads=5, obs_window=32,
+                        head_dim=head_dim, n_hetero=2, decode_steps=1)
+    run_layer(wl, mutate=tiny, check_batches=(0, 1), screening=2)
 
 
 @pytest.mark.parametrize("side", ["window rows", "keys", "both"])
@@ -319,6 +342,8 @@ def test_int8_statistics_when_the_remainders_carry_the_logits(side):
             ld.q_win[..., 1] = 0
     wl = small_workload(name="i8rem", wid=198, ctx_len=1200, n_q_heads=16, n_kv_heads=4)
     run_layer(wl, mutate=shape, check_batches=(0, 1), steps=0)
+    narrow = small_workload(name="i8rem-narrow", wid=198, ctx_len=1200, n_q_heads=4, n_kv_heads=4, obs_window=32)
+    run_layer(narrow, mutate=shape, check_batches=(0, 1), steps=0)
 
 
 def test_statistics_engines_agree():
