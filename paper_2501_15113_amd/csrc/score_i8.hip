@@ -138,6 +138,28 @@ __device__ __forceinline__ double exp_sum17(double carry, double x0, const doubl
   return sum;
 }
 
+// The same exponential for N finite arguments one by one, in place: x[v] <- 2^(x[v] / 256).
+template <int N>
+__device__ __forceinline__ void exp_each(double (&x)[N], const double *tab) {
+  double y[N];
+  int ki[N];
+#pragma unroll
+  for (int v = 0; v < N; ++v) {
+    const double kf = rint(x[v]);
+    x[v] -= kf;
+    ki[v] = (int)kf;
+  }
+#pragma unroll
+  for (int v = 0; v < N; ++v) y[v] = tab[ki[v] & (EXP_TAB - 1)];
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int v = 0; v < N; ++v) {
+    const double q = fma(x[v], 3.308302680541371e-09, 3.665565596910106e-06);
+    const double p = fma(q, x[v], 0.0027076061740622863) * x[v];
+    x[v] = ldexp(fma(y[v], p, y[v]), ki[v] >> 8);
+  }
+}
+
 // 16 elements (8 dwords of bf16 pairs) -> four 16-byte digit vectors; returns
 // whether every element fits the window.  An element times 2^(I8_GRID - E) is
 // below 2^30 in magnitude, so the scaling and the conversion to an integer S
@@ -340,24 +362,33 @@ __device__ __forceinline__ void contract_tile(KA ka, const v4i (&qv)[KS][4], boo
 __device__ __forceinline__ int tile_key(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
 
 // Remainders of this row's elements that did not fit: t16 += r * scale * k[c].
-template <int D>
-__device__ __forceinline__ void add_row_remainders(const QTiny *__restrict__ tiny, int n_tiny, int row, int j0, int half,
-                                                   int NK, double unit_scale, const uint16_t *__restrict__ kb,
+// key_at(v): the key of register v, or a negative number for none.
+template <int D, typename KEY>
+__device__ __forceinline__ void add_row_remainders(const QTiny *__restrict__ tiny, int n_tiny, int row, KEY key_at,
+                                                   double unit_scale, const uint16_t *__restrict__ kb,
                                                    double (&t16)[16]) {
   for (int e = 0; e < n_tiny; ++e) {
     const QTiny ent = tiny[e];
     if (ent.row != row) continue;
-    // the key indices are formed inside the loop on purpose: hoisted, their
-    // sixteen addresses and compares would be paid by every tile
-    int jl = j0 + 4 * half;
-    asm volatile("" : "+v"(jl));
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int j = jl + 8 * (v >> 2) + (v & 3);
-      if (j < NK) t16[v] += ent.r * unit_scale * bf16_to_double(kb[(size_t)j * D + ent.c]);
+      const int j = key_at(v);
+      if (j >= 0) t16[v] += ent.r * unit_scale * bf16_to_double(kb[(size_t)j * D + ent.c]);
     }
   }
 }
+// The keys of a tile of 32 consecutive ones from j0 on, for a lane in key half
+// `half`.  (The indices are formed where they are used on purpose: hoisted,
+// their sixteen addresses and compares would be paid by every tile.)
+struct ConsecutiveKeys {
+  int j0, half, n_keys;
+  __device__ __forceinline__ int operator()(int v) const {
+    int jl = j0 + 4 * half;
+    asm volatile("" : "+v"(jl));
+    const int j = jl + 8 * (v >> 2) + (v & 3);
+    return j < n_keys ? j : -1;
+  }
+};
 
 // Remainder of one key element that did not fit (ent.c: channel, ent.r: the
 // remainder; kk: the key within the tile): t16 += qh[c] * r * scale, with qh
@@ -379,18 +410,19 @@ __device__ __forceinline__ void add_key_remainder(const QTiny &ent, int kk, int 
     if (v == vv) t16[v] += add;
 }
 
-// Plain fp64 dot products for the lane's sixteen keys.
-template <int D>
-__device__ __forceinline__ void plain_logits(const double *__restrict__ q_row, const uint16_t *__restrict__ kb, int j0,
-                                             int half, int NK, double unit_scale, double (&t16)[16]) {
+// Plain fp64 dot products for the lane's sixteen keys (key_at as above; a
+// register without a key gets the first key's product, which nobody reads).
+template <int D, typename KEY>
+__device__ __forceinline__ void plain_logits(const double *__restrict__ q_row, const uint16_t *__restrict__ kb,
+                                             KEY key_at, double unit_scale, double (&t16)[16]) {
 #pragma unroll
   for (int v = 0; v < 16; ++v) t16[v] = 0.0;
   for (int cc = 0; cc < D; ++cc) {
     const double qe = q_row[cc];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int j = j0 + tile_key(v, half);
-      t16[v] += qe * bf16_to_double(kb[(size_t)(j < NK ? j : 0) * D + cc]);
+      const int j = key_at(v);
+      t16[v] += qe * bf16_to_double(kb[(size_t)(j >= 0 ? j : 0) * D + cc]);
     }
   }
 #pragma unroll
@@ -652,7 +684,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
             for (int v = 0; v < 16; ++v) t16[v] = ldexp(t16[v] * gqr, ek[v]);
           }
-          add_row_remainders<D>(tiny, n_tiny, row, j0, half, NK, unit_scale, kb, t16);
+          add_row_remainders<D>(tiny, n_tiny, row, ConsecutiveKeys{j0, half, NK}, unit_scale, kb, t16);
           // remainders of key elements that did not fit: qh[c] * r
           if (k_listed) {
             for (int ww = 0; ww < NW; ++ww) {
@@ -664,7 +696,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
             }
           }
         } else {
-          plain_logits<D>(qdu + (size_t)row * D, kb, j0, half, NK, unit_scale, t16);
+          plain_logits<D>(qdu + (size_t)row * D, kb, ConsecutiveKeys{j0, half, NK}, unit_scale, t16);
         }
         join_statistics(t16, j0, half, row, dm, s_pow, m, ls);
       }
@@ -836,13 +868,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
         for (int v = 0; v < 16; ++v) t16[v] = ldexp(t16[v] * gqr, ek[v]);
       }
-      add_row_remainders<D>(tiny, n_tiny, row, j0, half, NK, unit_scale, kb, t16);
+      add_row_remainders<D>(tiny, n_tiny, row, ConsecutiveKeys{j0, half, NK}, unit_scale, kb, t16);
       for (int e = 0; e < cnt; ++e) {
         const QTiny ent = s_ktiny[w][e];
         add_key_remainder<D>(ent, ent.row, half, row, qdu, tiny, n_tiny, unit_scale, t16);
       }
     } else {
-      plain_logits<D>(qdu + (size_t)row * D, kb, j0, half, NK, unit_scale, t16);
+      plain_logits<D>(qdu + (size_t)row * D, kb, ConsecutiveKeys{j0, half, NK}, unit_scale, t16);
     }
     join_statistics(t16, j0, half, row, dm, s_pow, m, ls);
     __builtin_amdgcn_wave_barrier();   // the lists are rewritten by the next tile
@@ -855,6 +887,183 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
       atomicMax(knorm + unit, (unsigned long long)__double_as_longlong((double)norm_best * 1.001));
   }
   write_partial(m, ls, half, row, part + (((size_t)unit * gridDim.x + blockIdx.x) * NW + w) * 32 * 2);
+}
+
+// Exact column means (Eq. 13) of the columns a unit's list names, after the
+// screening pass: score[j] = (1 / rows) sum_i exp(x_ij - m_i) / l_i with the
+// logits of the integer contraction above and the row statistics it produced.
+// A tile is 32 listed keys; every wave converts its own tiles as in
+// score_i8_direct_kernel, then goes through the window's 32-row blocks with
+// the tile's digits in LDS of its own: logits, exponentials against the rows'
+// maxima, a running sum per key and lane.  The lanes of a key half hold the
+// same sixteen keys for 32 different rows: their sums meet in LDS, one lane per
+// key adds the rows up and writes the score.  grid = (blocks per unit, units);
+// tiles are dealt to the waves of a unit's blocks in turn.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void score_i8_columns_kernel(
+    const uint16_t *__restrict__ k, const v4i *__restrict__ qdig, const double *__restrict__ gq,
+    const double *__restrict__ qd, const QTiny *__restrict__ qtiny, const int32_t *__restrict__ qcnt,
+    const double *__restrict__ stats, const int32_t *__restrict__ band_idx, const int32_t *__restrict__ band_cnt,
+    double *__restrict__ scores, Dims dm) {
+  constexpr int KS = D / 32, THREADS = 64 * NW;
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, half = l >> 5;
+  const int N = dm.N, L = dm.L, R = dm.R, Rpad = dm.Rpad, n_rb = Rpad / 32;
+  const int n_listed = band_cnt[unit];
+  const int32_t *cols = band_idx + (size_t)unit * N;
+  const double unit_scale = dm.scale * EXP_UNITS;
+  const uint16_t *kb = k + (size_t)unit * N * D;
+  const double *qdu = qd + (size_t)unit * Rpad * D;
+  const double *st = stats + (size_t)unit * Rpad * 2;
+  const int n_tiny_all = qcnt[unit];
+  const bool q_overflow = n_tiny_all > I8_QCAP;
+  const int n_tiny = q_overflow ? 0 : n_tiny_all;
+  const QTiny *tiny = qtiny + (size_t)unit * I8_QCAP;
+
+  __shared__ double s_pow[EXP_TAB];
+  __shared__ QTiny s_ktiny[NW][I8_KCAP];
+  __shared__ int s_ek[NW][32];
+  __shared__ int s_col[NW][32];              // columns of the tile's keys, -1 past the list's end
+  __shared__ v4i s_dig[NW][KS][4][64];
+  // a lane's sums of its sixteen keys over the row blocks, [16][64] doubles in
+  // the place of the wave's digits, which are done with by then
+  static_assert(sizeof(v4i) * KS * 4 * 64 >= sizeof(double) * 16 * 64, "the sums fit the digits' place");
+  double(*s_sum)[64] = reinterpret_cast<double(*)[64]>(&s_dig[w][0][0][0]);
+  for (int i = tid; i < EXP_TAB; i += THREADS) s_pow[i] = exp2((double)i * (1.0 / EXP_TAB));
+  __syncthreads();
+
+  const int n_tiles = (n_listed + 31) / 32;
+  for (int tile = blockIdx.x * NW + w; tile < n_tiles; tile += gridDim.x * NW) {
+    const int pos = tile * 32 + c32;
+    const int col = pos < n_listed ? cols[pos] : -1;
+    // the key's two halves of every 32-channel block, as score_i8_direct_kernel reads them
+    uint32_t raw[KS][8];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
+      if (col >= 0) {
+        lo = *reinterpret_cast<const uint4 *>(kb + (size_t)col * D + ks * 32 + half * 16);
+        hi = *reinterpret_cast<const uint4 *>(kb + (size_t)col * D + ks * 32 + half * 16 + 8);
+      }
+      raw[ks][0] = lo.x; raw[ks][1] = lo.y; raw[ks][2] = lo.z; raw[ks][3] = lo.w;
+      raw[ks][4] = hi.x; raw[ks][5] = hi.y; raw[ks][6] = hi.z; raw[ks][7] = hi.w;
+    }
+    int E = 1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) E = max(E, row_exponent_of(raw[ks]));
+    E = max(E, __shfl_xor(E, 32));
+    bool ok = true, k_low = false;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      v4i dig[4];
+      ok = digits_of(raw[ks], E, dig) && ok;
+      k_low = k_low || (dig[0][0] | dig[0][1] | dig[0][2] | dig[0][3]) != 0;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) s_dig[w][ks][t][l] = dig[t];
+    }
+    const bool k_low_zero = __ballot(k_low) == 0ull;
+    int cnt = 0;
+    unsigned long long bad = __ballot(!ok);
+    while (bad) {
+      const int src = __ffsll((long long)bad) - 1;
+      bad &= bad - 1;
+      if (l == src) {
+#pragma unroll 1
+        for (int i = 0; i < 16 * KS; ++i) {
+          const int c = (i >> 4) * 32 + half * 16 + (i & 15);
+          double rem;
+          if (!remainder_of(kb[(size_t)col * D + c], E, rem)) continue;
+          if (cnt < I8_KCAP) {
+            QTiny ent;
+            ent.row = c32;
+            ent.c = c;
+            ent.r = rem;
+            s_ktiny[w][cnt] = ent;
+          }
+          ++cnt;
+        }
+      }
+      cnt = __shfl(cnt, src);
+    }
+    if (half == 0) {
+      s_ek[w][c32] = E - (2 * I8_GRID - 126);
+      s_col[w][c32] = col;
+    }
+    __builtin_amdgcn_wave_barrier();   // the wave's own LDS writes above are read below, in program order
+
+    // the lane's sixteen keys: their columns (and factors) are read from the
+    // wave's LDS where they are used, not held in registers across the row blocks
+    const auto key_at = [&](int v) { return s_col[w][tile_key(v, half)]; };
+    const bool plain = q_overflow || cnt > I8_KCAP;
+    double sum16[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sum16[v] = 0.0;
+#pragma unroll 1
+    for (int rb = 0; rb < n_rb; ++rb) {
+      const int row = rb * 32 + c32;
+      double t16[16];
+      if (!plain) {
+        v4i qv[KS][4];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+          for (int t = 0; t < 4; ++t) qv[ks][t] = qdig[((((size_t)unit * n_rb + rb) * KS + ks) * 4 + t) * 64 + l];
+        bool q_low = false;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) q_low = q_low || (qv[ks][0][0] | qv[ks][0][1] | qv[ks][0][2] | qv[ks][0][3]) != 0;
+        contract_tile<KS>([&](int ks, int a) { return s_dig[w][ks][a][l]; }, qv, k_low_zero, __ballot(q_low) == 0ull, t16);
+        const double gqr = gq[(size_t)unit * Rpad + row];
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+          const v4i e4 = *reinterpret_cast<const v4i *>(&s_ek[w][8 * v4 + 4 * half]);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) t16[4 * v4 + x] = ldexp(t16[4 * v4 + x] * gqr, e4[x]);
+        }
+        add_row_remainders<D>(tiny, n_tiny, row, key_at, unit_scale, kb, t16);
+        for (int e = 0; e < cnt; ++e) {
+          const QTiny ent = s_ktiny[w][e];
+          add_key_remainder<D>(ent, ent.row, half, row, qdu, tiny, n_tiny, unit_scale, t16);
+        }
+      } else {
+        plain_logits<D>(qdu + (size_t)row * D, kb, key_at, unit_scale, t16);
+      }
+      // weights against the row's statistics (in table units), masked where the
+      // key lies behind the row's own position or there is no row or key
+      const bool row_ok = row < R;
+      const double m_units = row_ok ? st[2 * row] * EXP_UNITS : 0.0;
+      const double inv = row_ok ? 1.0 / st[2 * row + 1] : 0.0;
+      const int last_visible = N - L + (dm.row0 + row) % L;
+#pragma unroll
+      for (int h8 = 0; h8 < 2; ++h8) {
+        double x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = fmin(t16[8 * h8 + i] - m_units, 0.0);
+        exp_each<8>(x, s_pow);
+#pragma unroll
+        for (int v4 = 0; v4 < 2; ++v4) {
+          const v4i c4 = *reinterpret_cast<const v4i *>(&s_col[w][8 * (2 * h8 + v4) + 4 * half]);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const bool vis = c4[i] >= 0 && c4[i] <= last_visible;
+            sum16[8 * h8 + 4 * v4 + i] += vis ? x[4 * v4 + i] * inv : 0.0;
+          }
+        }
+      }
+    }
+    // rows of a key half meet in LDS; lane t < 32 adds up key t
+    __builtin_amdgcn_wave_barrier();   // (all reads of the digits come before)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s_sum[v][l] = sum16[v];
+    __builtin_amdgcn_wave_barrier();
+    if (l < 32) {
+      const int v = 4 * (l >> 3) + (l & 3), hf = (l >> 2) & 1;
+      double total = 0.0;
+#pragma unroll 8
+      for (int r = 0; r < 32; ++r) total += s_sum[v][32 * hf + r];
+      const int out_col = s_col[w][l];
+      if (out_col >= 0) scores[(size_t)unit * N + out_col] = total / (double)dm.Rtot;
+    }
+    __builtin_amdgcn_wave_barrier();   // the wave's LDS is rewritten by its next tile
+  }
 }
 
 bool i8_stats_supported(const Dims &dm, int dtype) {
@@ -924,6 +1133,25 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
   };
   if (dm.D == 64) pick(std::integral_constant<int, 64>{});
   else pick(std::integral_constant<int, 128>{});
+  return hip_ok(hipGetLastError());
+}
+
+// Exact scores of the listed columns of every unit (see score_i8_columns_kernel).
+// The window rows' digits, factors and remainder lists are those launch_i8_stats
+// left in `bufs` for the same rows.
+int launch_i8_columns(const Dims &dm, const void *k, const double *qd, const I8Bufs &bufs, const double *stats,
+                      const int32_t *band_idx, const int32_t *band_cnt, double *scores, int blocks_per_unit,
+                      hipStream_t s) {
+  auto kk = static_cast<const uint16_t *>(k);
+  auto qdig = static_cast<const v4i *>(bufs.qdig);
+  constexpr int CNW = 4;
+  const dim3 grid(blocks_per_unit < 1 ? 1 : blocks_per_unit, dm.units), block(64 * CNW);
+  if (dm.D == 64)
+    score_i8_columns_kernel<64, CNW><<<grid, block, 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, stats, band_idx,
+                                                            band_cnt, scores, dm);
+  else
+    score_i8_columns_kernel<128, CNW><<<grid, block, 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, stats, band_idx,
+                                                             band_cnt, scores, dm);
   return hip_ok(hipGetLastError());
 }
 

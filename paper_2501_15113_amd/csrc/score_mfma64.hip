@@ -431,6 +431,13 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
     // from queueing: measured 134 -> 60 us at 64 units, 69 -> 35 us at 32.
     int band_grid = scr->n_cu / dm.units;
     band_grid = band_grid < 1 ? 1 : (band_grid > 64 ? 64 : band_grid);
+    if (i8) {
+      // bf16 inputs: the listed columns from the integer contraction too (the
+      // fp64 matrix instruction makes 6 us of a 16-key task's 11)
+      rc = launch_i8_columns(dm, k, qd, *i8b, stats, scr->band_idx, scr->band_cnt, scores, 2 * band_grid, s);
+      if (rc) return rc;
+      continue;
+    }
     score_mfma64_kernel<T, D, 1, true><<<dim3(band_grid, dm.units), block, 0, s>>>(k, qd, stats, part, scores, dm,
                                                                            cpw, scr->band_idx, scr->band_cnt);
   }

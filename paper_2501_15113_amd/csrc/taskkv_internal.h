@@ -143,6 +143,10 @@ bool i8_stats_supported(const Dims &dm, int dtype);
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
                     double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, bool qcnt_zeroed,
                     int *n_parts, hipStream_t s);
+// exact scores of the listed columns from the digits launch_i8_stats left in bufs
+int launch_i8_columns(const Dims &dm, const void *k, const double *qd, const I8Bufs &bufs, const double *stats,
+                      const int32_t *band_idx, const int32_t *band_cnt, double *scores, int blocks_per_unit,
+                      hipStream_t s);
 int launch_zero_u64(unsigned long long *p, int n, hipStream_t s);
 bool screen_supported(const Dims &dm, int dtype);
 int launch_key_norms(const Dims &dm, const void *k, unsigned long long *knorm, hipStream_t s);
