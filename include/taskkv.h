@@ -297,7 +297,8 @@ int taskkv_set_screening(taskkv_ctx *ctx, int mode);
 
 /* Row maxima and softmax denominators of the window scores (Eq. 12) are needed
  * to fp64 accuracy.  For bf16 inputs they come from exact integer dot products
- * on the int8 matrix cores (engine 1, default); engine 0 uses the fp64 matrix
+ * on the int8 matrix cores (engine 1, default), and so do the scores of the
+ * columns that a screening separator recomputes; engine 0 uses the fp64 matrix
  * instruction, as fp32 inputs always do.  Engine 1 evaluates its exponentials
  * from a table and a cubic (relative error 2e-13), so the two engines' scores
  * agree to about 1e-13 relative, not to the last bit; decisions (top-t, middle
