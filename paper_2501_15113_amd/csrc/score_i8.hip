@@ -656,21 +656,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
         if (WPR == 2 && tile != sub) continue;
         double t16[16];
         if (!plain) {
-          // Key digits of the tile.  Blocks of eight waves name them where they are
-          // used (the compiler then reads each from LDS once per variant and places
-          // the reads itself, which leaves it fewer registers to spill: -1.5 %);
-          // blocks of four waves run 1.5 % faster with all sixteen read up front.
-          constexpr bool PRELOAD = NW != 8;
-          v4i ka[KS][4];
-          if (PRELOAD) {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-              for (int t = 0; t < 4; ++t) ka[ks][t] = s_dig[buf][tile][ks][t][l];
-          }
+          // The tile's key digits are named where they are used: the compiler
+          // then reads each from LDS once per variant and places the reads
+          // itself, which leaves it fewer registers to spill than sixteen vectors
+          // read up front (1-2 % of the whole compression for every block shape).
           const bool k_low_zero = !((knz >> tile) & 1);
-          if (PRELOAD) contract_tile<KS>([&](int ks, int a) { return ka[ks][a]; }, qv, k_low_zero, q_low_zero, t16);
-          else contract_tile<KS>([&](int ks, int a) { return s_dig[buf][tile][ks][a][l]; }, qv, k_low_zero, q_low_zero, t16);
+          contract_tile<KS>([&](int ks, int a) { return s_dig[buf][tile][ks][a][l]; }, qv, k_low_zero, q_low_zero, t16);
           {
             // exponents of the lane's sixteen keys (read late: sixteen registers
             // fewer across the matrix phase keep most temporaries out of scratch memory)
