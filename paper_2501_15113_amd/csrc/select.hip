@@ -50,43 +50,48 @@ __device__ __forceinline__ double elem_to_double(uint16_t x) {
   return (double)__uint_as_float(uint32_t(x) << 16);
 }
 
-// Eq. 15: v'[unit] = sum over the picked tokens of C[j] * V[j, :] in fp64.  One
-// block per unit: 1024 / D groups of D channel threads; group g adds the picks
-// g, g + groups, ... (independent loads instead of one chain of t dependent
-// ones), and the group sums are added in group order.
+// Eq. 15: v' = sum over the t picked tokens of C_j v_j, one block per unit.  A
+// wave takes sixteen picks at a time, a lane the channels c and c + 64 of every
+// one of them: the sixteen index loads, then the sixteen score and value loads
+// behind them, are in flight together, and a block's sixteen waves cover 256
+// picks per round -- the usual t in one.  Picks are added in index order inside a
+// wave and the waves' partial vectors in wave order: the same sum every time.
 template <typename T>
 __global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__ scores, const T *__restrict__ v,
                                                       const int32_t *__restrict__ top_idx,
                                                       double *__restrict__ sem, Dims dm) {
-  const int unit = blockIdx.x, D = dm.D;
-  const int c = threadIdx.x % D, grp = threadIdx.x / D, n_grp = 1024 / D;
+  const int unit = blockIdx.x, D = dm.D, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const double *sc = scores + (size_t)unit * dm.N;
   const T *vb = v + (size_t)unit * dm.N * D;
   const int32_t *idx = top_idx + (size_t)unit * dm.T;
   __shared__ double red[16][128];
-  double acc = 0.0;
   constexpr int U = 16;
-  for (int n0 = grp; n0 < dm.T; n0 += U * n_grp) {
-    // sixteen picks of the group at a time: their index, score and value loads
-    // overlap instead of forming one chain per pick
+  const bool second = D > 64;   // head sizes 64 and 128: one or two channels per lane
+  double acc0 = 0.0, acc1 = 0.0;
+  for (int n0 = wv * U; n0 < dm.T; n0 += 16 * U) {
     int j[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) j[u] = n0 + u * n_grp < dm.T ? idx[n0 + u * n_grp] : -1;
-    double w[U], x[U];
+    for (int u = 0; u < U; ++u) j[u] = n0 + u < dm.T ? idx[n0 + u] : -1;
+    double w[U], x0[U], x1[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       w[u] = j[u] >= 0 ? sc[j[u]] : 0.0;
-      x[u] = j[u] >= 0 ? elem_to_double(vb[(size_t)j[u] * D + c]) : 0.0;
+      x0[u] = j[u] >= 0 ? elem_to_double(vb[(size_t)j[u] * D + lane]) : 0.0;
+      x1[u] = j[u] >= 0 && second ? elem_to_double(vb[(size_t)j[u] * D + 64 + lane]) : 0.0;
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) acc += w[u] * x[u];   // same order as one pick at a time
+    for (int u = 0; u < U; ++u) {
+      acc0 += w[u] * x0[u];
+      acc1 += w[u] * x1[u];
+    }
   }
-  red[grp][c] = acc;
+  red[wv][lane] = acc0;
+  red[wv][64 + lane] = acc1;
   __syncthreads();
-  if (grp == 0) {
+  if (threadIdx.x < D) {
     double sum = 0.0;
-    for (int g = 0; g < n_grp; ++g) sum += red[g][c];
-    sem[(size_t)unit * D + c] = sum;
+    for (int g = 0; g < 16; ++g) sum += red[g][threadIdx.x];
+    sem[(size_t)unit * D + threadIdx.x] = sum;
   }
 }
 
