@@ -96,7 +96,7 @@ __global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__
 }
 
 // Eq. 7-8 and the ranking rule: one block per batch element.
-__global__ __launch_bounds__(256) void dist_mask_kernel(const double *__restrict__ sem,
+__global__ __launch_bounds__(1024) void dist_mask_kernel(const double *__restrict__ sem,
                                                         double *__restrict__ dist,
                                                         uint8_t *__restrict__ mask, Dims dm) {
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void dist_mask_kernel(const double *__restrict
     centre[tid] = acc / (double)H;
   }
   __syncthreads();
-  for (int h = wv; h < H; h += 4) {
+  for (int h = wv; h < H; h += 16) {
     double acc = 0.0;
     for (int c = lane; c < D; c += 64) {
       const double dl = sb[(size_t)h * D + c] - centre[c];
@@ -174,7 +174,7 @@ int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const vo
   else
     semvec_kernel<uint16_t><<<dim3(dm.units), dim3(1024), 0, s>>>(
         scores, static_cast<const uint16_t *>(v), top_idx, sem_vec, dm);
-  dist_mask_kernel<<<dim3(dm.B), dim3(256), 0, s>>>(sem_vec, dist, mask, dm);
+  dist_mask_kernel<<<dim3(dm.B), dim3(1024), 0, s>>>(sem_vec, dist, mask, dm);
   return hip_ok(hipGetLastError());
 }
 
