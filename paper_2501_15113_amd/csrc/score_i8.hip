@@ -708,6 +708,110 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   if (have) write_partial(m, ls, half, row, part + (((size_t)unit * gridDim.x + blockIdx.x) * WPR + sub) * Rpad * 2);
 }
 
+// ---- a wave that converts its own tile of 32 keys (the two kernels below)
+
+// The pieces of a key's row that lane (key, half) holds of the operand: the two
+// 16-channel segments [32 ks + 16 half, + 16) of every 32-channel block; zeros
+// without a row.
+template <int D>
+__device__ __forceinline__ void fetch_key_pieces(const uint16_t *__restrict__ key_row, int half,
+                                                 uint32_t (&raw)[D / 32][8]) {
+  constexpr int KS = D / 32;
+  if (key_row != nullptr) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const uint4 lo = *reinterpret_cast<const uint4 *>(key_row + ks * 32 + half * 16);
+      const uint4 hi = *reinterpret_cast<const uint4 *>(key_row + ks * 32 + half * 16 + 8);
+      raw[ks][0] = lo.x; raw[ks][1] = lo.y; raw[ks][2] = lo.z; raw[ks][3] = lo.w;
+      raw[ks][4] = hi.x; raw[ks][5] = hi.y; raw[ks][6] = hi.z; raw[ks][7] = hi.w;
+    }
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int x = 0; x < 8; ++x) raw[ks][x] = 0u;
+  }
+}
+
+// The tile's digits in operand layout into the wave's LDS (dig), the keys'
+// factors (ek[key] with f_k = 2^ek, the row factor's grid folded in) and the
+// remainders of the elements that do not fit on the wave's short list, filled
+// lane by lane (.row = key of the tile); returns their number: above I8_KCAP
+// the tile takes the plain route.  key_row: the lane's key in memory (its
+// elements are read again for the list: indexing the registers by a loop
+// counter would move them to scratch memory).  norm_best (or null): running
+// maximum of the keys' squared norms.
+template <int D>
+__device__ __forceinline__ int convert_own_tile(const uint32_t (&raw)[D / 32][8], const uint16_t *__restrict__ key_row,
+                                                int l, v4i (&dig_out)[D / 32][4][64], int (&ek)[32],
+                                                QTiny (&list)[I8_KCAP], bool &k_low_zero, float *norm_best) {
+  constexpr int KS = D / 32;
+  const int c32 = l & 31, half = l >> 5;
+  int E = 1;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) E = max(E, row_exponent_of(raw[ks]));
+  E = max(E, __shfl_xor(E, 32));
+  if (norm_best != nullptr) {
+    float ss = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const float lo = __uint_as_float(raw[ks][x] << 16), hi = __uint_as_float(raw[ks][x] & 0xffff0000u);
+        ss = fmaf(lo, lo, ss);
+        ss = fmaf(hi, hi, ss);
+      }
+    ss += __shfl_xor(ss, 32);
+    *norm_best = fmaxf(*norm_best, ss);
+  }
+  bool ok = true, k_low = false;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    v4i dig[4];
+    ok = digits_of(raw[ks], E, dig) && ok;
+    k_low = k_low || (dig[0][0] | dig[0][1] | dig[0][2] | dig[0][3]) != 0;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) dig_out[ks][t][l] = dig[t];
+  }
+  k_low_zero = __ballot(k_low) == 0ull;
+  int cnt = 0;
+  unsigned long long bad = __ballot(!ok);
+  while (bad) {
+    const int src = __ffsll((long long)bad) - 1;
+    bad &= bad - 1;
+    if (l == src) {
+#pragma unroll 1
+      for (int i = 0; i < 16 * KS; ++i) {
+        const int c = (i >> 4) * 32 + half * 16 + (i & 15);
+        double rem;
+        if (!remainder_of(key_row[c], E, rem)) continue;
+        if (cnt < I8_KCAP) {
+          QTiny ent;
+          ent.row = c32;
+          ent.c = c;
+          ent.r = rem;
+          list[cnt] = ent;
+        }
+        ++cnt;
+      }
+    }
+    cnt = __shfl(cnt, src);
+  }
+  if (half == 0) ek[c32] = E - (2 * I8_GRID - 126);   // with the row factor: 2^(Eq - I8_GRID) 2^(Ek - I8_GRID)
+  return cnt;
+}
+
+// Class sums -> logits in table units: the row's factor and the factors of the
+// lane's sixteen keys.
+__device__ __forceinline__ void scale_logits(double (&t16)[16], double gqr, const int (&ek)[32], int half) {
+#pragma unroll
+  for (int v4 = 0; v4 < 4; ++v4) {
+    const v4i e4 = *reinterpret_cast<const v4i *>(&ek[8 * v4 + 4 * half]);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) t16[4 * v4 + x] = ldexp(t16[4 * v4 + x] * gqr, e4[x]);
+  }
+}
+
 // Windows of at most 32 rows (one query head per KV head with the usual window
 // of 32): the key digits of a tile are used by one wave only, so there is
 // nothing to share.  Every wave converts its own tiles straight into operand
@@ -765,20 +869,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   uint32_t raw[KS][8];
   auto fetch = [&](int tile) {
     const int j = kbase + tile * 32 + c32;
-    if (tile < n_tiles && j < kend) {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const uint4 lo = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + ks * 32 + half * 16);
-        const uint4 hi = *reinterpret_cast<const uint4 *>(kb + (size_t)j * D + ks * 32 + half * 16 + 8);
-        raw[ks][0] = lo.x; raw[ks][1] = lo.y; raw[ks][2] = lo.z; raw[ks][3] = lo.w;
-        raw[ks][4] = hi.x; raw[ks][5] = hi.y; raw[ks][6] = hi.z; raw[ks][7] = hi.w;
-      }
-    } else {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int x = 0; x < 8; ++x) raw[ks][x] = 0u;
-    }
+    fetch_key_pieces<D>(tile < n_tiles && j < kend ? kb + (size_t)j * D : nullptr, half, raw);
   };
   const bool want_norm = knorm != nullptr;   // the screening pass wants the largest squared key norm (over-estimated)
   float norm_best = 0.f;
@@ -787,78 +878,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   for (int tile = w; tile < n_tiles; tile += NW) {
     const int j0 = kbase + tile * 32;
     // the tile's digits, in operand layout as they are converted
-    int E = 1;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) E = max(E, row_exponent_of(raw[ks]));
-    E = max(E, __shfl_xor(E, 32));
-    if (want_norm) {
-      float ss = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-          const float lo = __uint_as_float(raw[ks][x] << 16), hi = __uint_as_float(raw[ks][x] & 0xffff0000u);
-          ss = fmaf(lo, lo, ss);
-          ss = fmaf(hi, hi, ss);
-        }
-      ss += __shfl_xor(ss, 32);
-      norm_best = fmaxf(norm_best, ss);
-    }
-    bool ok = true, k_low = false;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      v4i dig[4];
-      ok = digits_of(raw[ks], E, dig) && ok;
-      k_low = k_low || (dig[0][0] | dig[0][1] | dig[0][2] | dig[0][3]) != 0;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) s_dig[w][ks][t][l] = dig[t];
-    }
-    const bool k_low_zero = __ballot(k_low) == 0ull;
-    // remainders of the elements that do not fit go on the wave's short list,
-    // filled lane by lane; a count above its capacity sends the tile down the plain route
-    int cnt = 0;
-    unsigned long long bad = __ballot(!ok);
-    while (bad) {
-      const int src = __ffsll((long long)bad) - 1;
-      bad &= bad - 1;
-      if (l == src) {
-        // (the lane's 16-channel segments, read again: indexing the registers
-        // by a loop counter would move them to scratch memory)
-#pragma unroll 1
-        for (int i = 0; i < 16 * KS; ++i) {
-          const int c = (i >> 4) * 32 + half * 16 + (i & 15);
-          double rem;
-          if (!remainder_of(kb[(size_t)(j0 + c32) * D + c], E, rem)) continue;
-          if (cnt < I8_KCAP) {
-            QTiny ent;
-            ent.row = c32;
-            ent.c = c;
-            ent.r = rem;
-            s_ktiny[w][cnt] = ent;
-          }
-          ++cnt;
-        }
-      }
-      cnt = __shfl(cnt, src);
-    }
-    if (half == 0) s_ek[w][c32] = E - (2 * I8_GRID - 126);   // with the row factor: 2^(Eq - I8_GRID) 2^(Ek - I8_GRID)
+    bool k_low_zero;
+    const int cnt = convert_own_tile<D>(raw, kb + (size_t)min(j0 + c32, NK - 1) * D, l, s_dig[w], s_ek[w], s_ktiny[w],
+                                        k_low_zero, want_norm ? &norm_best : nullptr);
     fetch(tile + NW);   // the next tile's keys travel during this tile's arithmetic
     __builtin_amdgcn_wave_barrier();   // the wave's own LDS writes above are read below, in program order
 
     double t16[16];
     if (!q_overflow && cnt <= I8_KCAP) {
       contract_tile<KS>([&](int ks, int a) { return s_dig[w][ks][a][l]; }, qv, k_low_zero, q_low_zero, t16);
-      {
-        int ek[16];
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-          const v4i e4 = *reinterpret_cast<const v4i *>(&s_ek[w][8 * v4 + 4 * half]);
-#pragma unroll
-          for (int x = 0; x < 4; ++x) ek[4 * v4 + x] = e4[x];
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) t16[v] = ldexp(t16[v] * gqr, ek[v]);
-      }
+      scale_logits(t16, gqr, s_ek[w], half);
       add_row_remainders<D>(tiny, n_tiny, row, ConsecutiveKeys{j0, half, NK}, unit_scale, kb, t16);
       for (int e = 0; e < cnt; ++e) {
         const QTiny ent = s_ktiny[w][e];
@@ -926,59 +955,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   for (int tile = blockIdx.x * NW + w; tile < n_tiles; tile += gridDim.x * NW) {
     const int pos = tile * 32 + c32;
     const int col = pos < n_listed ? cols[pos] : -1;
-    // the key's two halves of every 32-channel block, as score_i8_direct_kernel reads them
     uint32_t raw[KS][8];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
-      if (col >= 0) {
-        lo = *reinterpret_cast<const uint4 *>(kb + (size_t)col * D + ks * 32 + half * 16);
-        hi = *reinterpret_cast<const uint4 *>(kb + (size_t)col * D + ks * 32 + half * 16 + 8);
-      }
-      raw[ks][0] = lo.x; raw[ks][1] = lo.y; raw[ks][2] = lo.z; raw[ks][3] = lo.w;
-      raw[ks][4] = hi.x; raw[ks][5] = hi.y; raw[ks][6] = hi.z; raw[ks][7] = hi.w;
-    }
-    int E = 1;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) E = max(E, row_exponent_of(raw[ks]));
-    E = max(E, __shfl_xor(E, 32));
-    bool ok = true, k_low = false;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      v4i dig[4];
-      ok = digits_of(raw[ks], E, dig) && ok;
-      k_low = k_low || (dig[0][0] | dig[0][1] | dig[0][2] | dig[0][3]) != 0;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) s_dig[w][ks][t][l] = dig[t];
-    }
-    const bool k_low_zero = __ballot(k_low) == 0ull;
-    int cnt = 0;
-    unsigned long long bad = __ballot(!ok);
-    while (bad) {
-      const int src = __ffsll((long long)bad) - 1;
-      bad &= bad - 1;
-      if (l == src) {
-#pragma unroll 1
-        for (int i = 0; i < 16 * KS; ++i) {
-          const int c = (i >> 4) * 32 + half * 16 + (i & 15);
-          double rem;
-          if (!remainder_of(kb[(size_t)col * D + c], E, rem)) continue;
-          if (cnt < I8_KCAP) {
-            QTiny ent;
-            ent.row = c32;
-            ent.c = c;
-            ent.r = rem;
-            s_ktiny[w][cnt] = ent;
-          }
-          ++cnt;
-        }
-      }
-      cnt = __shfl(cnt, src);
-    }
-    if (half == 0) {
-      s_ek[w][c32] = E - (2 * I8_GRID - 126);
-      s_col[w][c32] = col;
-    }
+    const uint16_t *key_row = kb + (size_t)max(col, 0) * D;
+    fetch_key_pieces<D>(col >= 0 ? key_row : nullptr, half, raw);
+    bool k_low_zero;
+    const int cnt = convert_own_tile<D>(raw, key_row, l, s_dig[w], s_ek[w], s_ktiny[w], k_low_zero, nullptr);
+    if (half == 0) s_col[w][c32] = col;
     __builtin_amdgcn_wave_barrier();   // the wave's own LDS writes above are read below, in program order
 
     // the lane's sixteen keys: their columns (and factors) are read from the
@@ -1002,13 +984,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) q_low = q_low || (qv[ks][0][0] | qv[ks][0][1] | qv[ks][0][2] | qv[ks][0][3]) != 0;
         contract_tile<KS>([&](int ks, int a) { return s_dig[w][ks][a][l]; }, qv, k_low_zero, __ballot(q_low) == 0ull, t16);
-        const double gqr = gq[(size_t)unit * Rpad + row];
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-          const v4i e4 = *reinterpret_cast<const v4i *>(&s_ek[w][8 * v4 + 4 * half]);
-#pragma unroll
-          for (int x = 0; x < 4; ++x) t16[4 * v4 + x] = ldexp(t16[4 * v4 + x] * gqr, e4[x]);
-        }
+        scale_logits(t16, gq[(size_t)unit * Rpad + row], s_ek[w], half);
         add_row_remainders<D>(tiny, n_tiny, row, key_at, unit_scale, kb, t16);
         for (int e = 0; e < cnt; ++e) {
           const QTiny ent = s_ktiny[w][e];
