@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtaskkv.so")
-SOURCES = ["api.hip", "score_mfma64.hip", "score_screen.hip", "score_i8.hip", "select.hip", "select_multi.hip", "cache.hip", "decode.hip", "decode_stream.hip"]
+SOURCES = ["api.hip", "score_mfma64.hip", "score_screen.hip", "score_i8.hip", "score_i8_own.hip", "select.hip", "select_multi.hip", "cache.hip", "decode.hip", "decode_stream.hip"]
 # packed-fp32 instructions are switched off on purpose (device pass only; the
 # host pass prints a harmless "not a recognized feature" note)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature",

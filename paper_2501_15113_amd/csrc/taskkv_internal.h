@@ -143,6 +143,9 @@ bool i8_stats_supported(const Dims &dm, int dtype);
 int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const double *qd, const I8Bufs &bufs,
                     double *part, unsigned long long *knorm, int n_wg, int keys_per_wg, bool qcnt_zeroed,
                     int *n_parts, hipStream_t s);
+// row statistics of a window of at most 32 rows from the digits in bufs (launch_i8_stats calls it)
+int launch_i8_direct(const Dims &dm, const void *k, const double *qd, const I8Bufs &bufs, double *part,
+                     unsigned long long *knorm, int max_parts, int *n_parts, hipStream_t s);
 // exact scores of the listed columns from the digits launch_i8_stats left in bufs
 int launch_i8_columns(const Dims &dm, const void *k, const double *qd, const I8Bufs &bufs, const double *stats,
                       const int32_t *band_idx, const int32_t *band_cnt, double *scores, int blocks_per_unit,
