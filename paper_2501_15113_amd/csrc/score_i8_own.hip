@@ -6,6 +6,15 @@
 
 namespace taskkv {
 
+// Lanes of one wave hand data to each other through LDS without a block
+// barrier: the wave's LDS operations execute in program order, so all it takes
+// is that the compiler keeps them in that order, for memory (the fence) and in
+// its instruction schedule (the barrier).
+__device__ __forceinline__ void wave_lds_handover() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 // ---- a wave that converts its own tile of 32 keys (the two kernels below)
 
 // The pieces of a key's row that lane (key, half) holds of the operand: the two
@@ -180,7 +189,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     const int cnt = convert_own_tile<D>(raw, kb + (size_t)min(j0 + c32, NK - 1) * D, l, s_dig[w], s_ek[w], s_ktiny[w],
                                         k_low_zero, want_norm ? &norm_best : nullptr);
     fetch(tile + NW);   // the next tile's keys travel during this tile's arithmetic
-    __builtin_amdgcn_wave_barrier();   // the wave's own LDS writes above are read below, in program order
+    wave_lds_handover();   // the wave's own LDS writes above are read below, in program order
 
     double t16[16];
     if (!q_overflow && cnt <= I8_KCAP) {
@@ -195,7 +204,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
       plain_logits<D>(qdu + (size_t)row * D, kb, ConsecutiveKeys{j0, half, NK}, unit_scale, t16);
     }
     join_statistics(t16, j0, half, row, dm, s_pow, m, ls);
-    __builtin_amdgcn_wave_barrier();   // the lists are rewritten by the next tile
+    wave_lds_handover();   // the lists are rewritten by the next tile
   }
 
   if (want_norm) {
@@ -241,11 +250,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   __shared__ QTiny s_ktiny[NW][I8_KCAP];
   __shared__ int s_ek[NW][32];
   __shared__ int s_col[NW][32];              // columns of the tile's keys, -1 past the list's end
-  __shared__ v4i s_dig[NW][KS][4][64];
-  // a lane's sums of its sixteen keys over the row blocks, [16][64] doubles in
-  // the place of the wave's digits, which are done with by then
+  // a wave's digits, and in their place, when they are done with, a lane's sums
+  // of its sixteen keys over the row blocks
+  union TileLds {
+    v4i dig[KS][4][64];
+    double sum[16][64];
+  };
   static_assert(sizeof(v4i) * KS * 4 * 64 >= sizeof(double) * 16 * 64, "the sums fit the digits' place");
-  double(*s_sum)[64] = reinterpret_cast<double(*)[64]>(&s_dig[w][0][0][0]);
+  __shared__ TileLds s_tile[NW];
+  auto &s_dig_w = s_tile[w].dig;
+  auto &s_sum = s_tile[w].sum;
   for (int i = tid; i < EXP_TAB; i += THREADS) s_pow[i] = exp2((double)i * (1.0 / EXP_TAB));
   __syncthreads();
 
@@ -257,9 +271,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
     const uint16_t *key_row = kb + (size_t)max(col, 0) * D;
     fetch_key_pieces<D>(col >= 0 ? key_row : nullptr, half, raw);
     bool k_low_zero;
-    const int cnt = convert_own_tile<D>(raw, key_row, l, s_dig[w], s_ek[w], s_ktiny[w], k_low_zero, nullptr);
+    const int cnt = convert_own_tile<D>(raw, key_row, l, s_dig_w, s_ek[w], s_ktiny[w], k_low_zero, nullptr);
     if (half == 0) s_col[w][c32] = col;
-    __builtin_amdgcn_wave_barrier();   // the wave's own LDS writes above are read below, in program order
+    wave_lds_handover();   // the wave's own LDS writes above are read below, in program order
 
     // the lane's sixteen keys: their columns (and factors) are read from the
     // wave's LDS where they are used, not held in registers across the row blocks
@@ -281,7 +295,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
         bool q_low = false;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) q_low = q_low || (qv[ks][0][0] | qv[ks][0][1] | qv[ks][0][2] | qv[ks][0][3]) != 0;
-        contract_tile<KS>([&](int ks, int a) { return s_dig[w][ks][a][l]; }, qv, k_low_zero, __ballot(q_low) == 0ull, t16);
+        contract_tile<KS>([&](int ks, int a) { return s_dig_w[ks][a][l]; }, qv, k_low_zero, __ballot(q_low) == 0ull, t16);
         scale_logits(t16, gq[(size_t)unit * Rpad + row], s_ek[w], half);
         add_row_remainders<D>(tiny, n_tiny, row, key_at, unit_scale, kb, t16);
         for (int e = 0; e < cnt; ++e) {
@@ -315,10 +329,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
       }
     }
     // rows of a key half meet in LDS; lane t < 32 adds up key t
-    __builtin_amdgcn_wave_barrier();   // (all reads of the digits come before)
+    wave_lds_handover();   // (all reads of the digits come before)
 #pragma unroll
     for (int v = 0; v < 16; ++v) s_sum[v][l] = sum16[v];
-    __builtin_amdgcn_wave_barrier();
+    wave_lds_handover();
     if (l < 32) {
       const int v = 4 * (l >> 3) + (l & 3), hf = (l >> 2) & 1;
       double total = 0.0;
@@ -327,7 +341,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
       const int out_col = s_col[w][l];
       if (out_col >= 0) scores[(size_t)unit * N + out_col] = total / (double)dm.Rtot;
     }
-    __builtin_amdgcn_wave_barrier();   // the wave's LDS is rewritten by its next tile
+    wave_lds_handover();   // the wave's LDS is rewritten by its next tile
   }
 }
 
