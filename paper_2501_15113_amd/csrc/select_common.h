@@ -2,6 +2,8 @@
 // selection kernels): unsigned integer order equals numeric order.
 #pragma once
 
+#include <type_traits>
+
 #include "taskkv_internal.h"
 
 namespace taskkv {
@@ -329,6 +331,15 @@ __device__ __forceinline__ int list_ascending(SC sc, int lo, int hi, int take_eq
   return tot1 + min(base2 + tot2, take_equal) - min(base2, take_equal);
 }
 
+// A classifier may class the SWEEP_U x 64 consecutive entries a wave holds at
+// once -- wave_masks(first entry, lane, the lane's scores, hi, class-1 masks,
+// class-2 masks), one mask per run of 64 -- instead of entry by entry: for
+// tests that look at an entry's neighbours.
+template <typename F, typename = void>
+struct classifies_by_wave : std::false_type {};
+template <typename F>
+struct classifies_by_wave<F, std::void_t<decltype(F::BY_WAVE)>> : std::true_type {};
+
 // list_ascending with every score read once: the range is taken in chunks of
 // 1024 * SWEEP_U entries that the block holds in registers between counting
 // and writing (two barriers per chunk; every wave owns a contiguous sixteenth
@@ -349,12 +360,19 @@ __device__ __forceinline__ int list_chunked(SC sc, int lo, int hi, int take_equa
     for (int r = 0; r < SWEEP_U; ++r) x[r] = sc[min(jw + 64 * r + lane, hi - 1)];
     uint64_t b1[SWEEP_U], b2[SWEEP_U];
     int n1 = 0, n2 = 0;
+    if constexpr (classifies_by_wave<F>::value) {
+      classify.wave_masks(jw, lane, x, hi, b1, b2);
+    } else {
+#pragma unroll
+      for (int r = 0; r < SWEEP_U; ++r) {
+        const int j = jw + 64 * r + lane;
+        const int cls = j < hi ? classify(j, x[r]) : 0;
+        b1[r] = __ballot(cls == 1);
+        b2[r] = __ballot(cls == 2);
+      }
+    }
 #pragma unroll
     for (int r = 0; r < SWEEP_U; ++r) {
-      const int j = jw + 64 * r + lane;
-      const int cls = j < hi ? classify(j, x[r]) : 0;
-      b1[r] = __ballot(cls == 1);
-      b2[r] = __ballot(cls == 2);
       n1 += __popcll(b1[r]);
       n2 += __popcll(b2[r]);
     }

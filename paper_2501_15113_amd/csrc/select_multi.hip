@@ -448,6 +448,59 @@ struct InBandPooled {
   }
 };
 
+// The same test for a whole wave's SWEEP_U x 64 consecutive columns: every
+// column's own pooled score gives one bit (in the band or not), and "within
+// `radius` of a set bit" is shifts and ors of the 64-bit masks, with the
+// neighbouring runs' bits carried in and `radius` columns of halo on either
+// side of the wave's span -- one read of the pooled scores per column, all of
+// them in flight together, where the test column by column makes 2 radius + 1
+// dependent trips.  radius <= 31.
+struct InBandPooledWave {
+  static constexpr bool BY_WAVE = true;
+  InBand b;
+  const double *pooled;   // the unit's row
+  int radius;
+  __device__ __forceinline__ bool in_band(int i) const {
+    if (i < b.m0 || i >= b.m1) return false;
+    const double p = pooled[i];
+    return p >= b.lo_k && p <= b.hi_k;
+  }
+  __device__ __forceinline__ void wave_masks(int jw, int lane, const double (&x)[SWEEP_U], int hi,
+                                             uint64_t (&b1)[SWEEP_U], uint64_t (&b2)[SWEEP_U]) const {
+    uint64_t kb[SWEEP_U], live[SWEEP_U];
+    double p[SWEEP_U];
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) {
+      const int j = jw + 64 * r + lane;
+      p[r] = pooled[min(max(j, b.m0), b.m1 - 1)];
+    }
+    // halo, one load: lanes [0, radius) take the columns before the span, lanes
+    // [32, 32 + radius) those behind it; bit u of `left` is column
+    // jw - radius + u, bit u of `right` column jw + 64 SWEEP_U + u
+    const int hl = lane & 31, hcol = lane < 32 ? jw - radius + hl : jw + 64 * SWEEP_U + hl;
+    const uint64_t halo = __ballot(hl < radius && in_band(hcol));
+    const uint64_t left = halo & 0xffffffffull, right = halo >> 32;
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) {
+      const int j = jw + 64 * r + lane;
+      const bool mid = j >= b.m0 && j < b.m1;
+      live[r] = __ballot(j < hi);
+      kb[r] = __ballot(mid && p[r] >= b.lo_k && p[r] <= b.hi_k);
+      b1[r] = __ballot(x[r] >= b.lo_t);
+      b2[r] = __ballot(mid && p[r] > b.hi_k);
+    }
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) {
+      const uint64_t prev = r > 0 ? kb[r - 1] : left << (64 - radius);
+      const uint64_t next = r < SWEEP_U - 1 ? kb[r + 1] : right;
+      uint64_t d = kb[r];
+      for (int u = 1; u <= radius; ++u) d |= (kb[r] << u) | (kb[r] >> u) | (prev >> (64 - u)) | (next << (64 - u));
+      b1[r] = (b1[r] | d) & live[r];
+      b2[r] = b2[r] & ~b1[r] & live[r];
+    }
+  }
+};
+
 // The band's columns of a slice, listed from the slice's first slot of the row.
 __global__ __launch_bounds__(1024) void mband_write_kernel(const double *__restrict__ scores,
                                                            const double *__restrict__ pooled,
@@ -467,7 +520,10 @@ __global__ __launch_bounds__(1024) void mband_write_kernel(const double *__restr
   int n_above = 0, n;
   const double *sc = scores + (size_t)unit * dm.N;
   int32_t *out = band_idx + (size_t)unit * dm.N + a;
-  if (pooled != nullptr && mb.nsel > 1)
+  if (pooled != nullptr && mb.nsel > 1 && dm.pool / 2 <= 31)
+    n = list_chunked(sc, a, b, 0, out, b - a, s_cnt, InBandPooledWave{band, pooled + (size_t)unit * dm.N, dm.pool / 2},
+                     0, 0, n_above);
+  else if (pooled != nullptr && mb.nsel > 1)
     n = list_chunked(sc, a, b, 0, out, b - a, s_cnt, InBandPooled{band, pooled + (size_t)unit * dm.N, dm.pool / 2}, 0,
                      0, n_above);
   else
@@ -547,8 +603,15 @@ __global__ __launch_bounds__(1024) void mband_close_kernel(const double *__restr
 }
 
 // ---- launchers
+// The sliced kernels hold one 1024-thread block per compute unit at a time
+// (registers), and a block's fixed costs -- a few dependent trips to memory,
+// two barriers -- are most of what it takes on a slice of a few thousand
+// scores: one block per compute unit in all, two where a slice would otherwise
+// exceed two sweeps of a block (32 units of 32768 scores: the band and the
+// selections together 20 us faster with 8 slices than with 16).
 static int msel_slices(const Dims &dm, int n_cu) {
-  const int S = 2 * n_cu / dm.units;
+  int S = n_cu / dm.units;
+  if (S >= 1 && dm.N / S > 2 * 1024 * SWEEP_U) S *= 2;
   return S < 1 ? 1 : (S > MSEL_MAX_SLICES ? MSEL_MAX_SLICES : S);
 }
 static bool msel_sized(const Dims &dm) { return dm.N >= MSEL_MIN_RANGE && dm.units <= MSEL_MAX_UNITS; }
