@@ -42,7 +42,7 @@ __device__ __forceinline__ int position_of(const ListedScores &v, int j) { retur
 constexpr int SWEEP_U = 8;
 
 // Candidates the radix select keeps in LDS once few enough remain.
-constexpr int RADIX_CAND = 4096;
+constexpr int RADIX_CAND = 8192;
 struct RadixScratch {
   uint64_t found;
   int bin, rem, n_bin, n;
