@@ -460,11 +460,6 @@ struct InBandPooledWave {
   InBand b;
   const double *pooled;   // the unit's row
   int radius;
-  __device__ __forceinline__ bool in_band(int i) const {
-    if (i < b.m0 || i >= b.m1) return false;
-    const double p = pooled[i];
-    return p >= b.lo_k && p <= b.hi_k;
-  }
   __device__ __forceinline__ void wave_masks(int jw, int lane, const double (&x)[SWEEP_U], int hi,
                                              uint64_t (&b1)[SWEEP_U], uint64_t (&b2)[SWEEP_U]) const {
     uint64_t kb[SWEEP_U], live[SWEEP_U];
@@ -478,7 +473,8 @@ struct InBandPooledWave {
     // [32, 32 + radius) those behind it; bit u of `left` is column
     // jw - radius + u, bit u of `right` column jw + 64 SWEEP_U + u
     const int hl = lane & 31, hcol = lane < 32 ? jw - radius + hl : jw + 64 * SWEEP_U + hl;
-    const uint64_t halo = __ballot(hl < radius && in_band(hcol));
+    const double hp = pooled[min(max(hcol, b.m0), b.m1 - 1)];   // (no branch around it: it travels with the loads above)
+    const uint64_t halo = __ballot(hl < radius && hcol >= b.m0 && hcol < b.m1 && hp >= b.lo_k && hp <= b.hi_k);
     const uint64_t left = halo & 0xffffffffull, right = halo >> 32;
 #pragma unroll
     for (int r = 0; r < SWEEP_U; ++r) {
