@@ -93,10 +93,12 @@ __device__ __forceinline__ void pick_bin12(const unsigned *hist, RS &rs, int rem
 // and the wanted one is the remaining-th largest of those.  All 1024 threads.
 template <typename SC>
 __device__ __forceinline__ uint64_t radix_finish(SC sc, int lo, int hi, RadixScratch &rs, uint64_t pat, uint64_t known,
-                                                 int shift, int remaining, int n_match, int &take_equal) {
+                                                 int shift, int remaining, int n_match, int &take_equal,
+                                                 int n_in_lds = 0) {
   const int tid = threadIdx.x, lane = tid & 63;
-  bool in_lds = false;
-  int n_cand = 0;
+  // n_in_lds > 0: the caller has put all hi - lo keys into rs.cand already
+  bool in_lds = n_in_lds > 0;
+  int n_cand = n_in_lds;
   if (tid == 0) rs.n = 0;
   __syncthreads();
   for (; shift >= 0; shift -= 12) {
@@ -198,6 +200,9 @@ __device__ __forceinline__ uint64_t radix_threshold(SC sc, int lo, int hi, int c
   int remaining = count;
   int n_match = hi - lo;   // entries that share all known digits
   int shift = 36;
+  // a range that fits the candidate buffer is read from memory once: its keys
+  // stay in LDS for all the digits
+  const bool keep = hi - lo <= RADIX_CAND;
   {
     for (int i = tid; i < 4096; i += 1024) rs.hist12[i] = 0;
     if (tid == 0) rs.top_and = 15u, rs.top_or = 0u;
@@ -210,6 +215,7 @@ __device__ __forceinline__ uint64_t radix_threshold(SC sc, int lo, int hi, int c
 #pragma unroll
       for (int r = 0; r < SWEEP_U; ++r) {
         if (j0 + r * 1024 + tid < hi) {
+          if (keep) rs.cand[j0 + r * 1024 + tid - lo] = key[r];
           atomicAdd(&rs.hist12[(unsigned)(key[r] >> 48) & 4095u], 1u);
           const unsigned top = (unsigned)(key[r] >> 60);
           t_and &= top;
@@ -256,7 +262,7 @@ __device__ __forceinline__ uint64_t radix_threshold(SC sc, int lo, int hi, int c
     n_match = rs.n_bin;
     __syncthreads();
   }
-  return radix_finish(sc, lo, hi, rs, pat, known, shift, remaining, n_match, take_equal);
+  return radix_finish(sc, lo, hi, rs, pat, known, shift, remaining, n_match, take_equal, keep ? hi - lo : 0);
 }
 
 // Ascending list of the indices j in [lo, hi) that `classify(j, sc[j])` marks: 1 = listed,
