@@ -11,18 +11,49 @@ namespace taskkv {
 
 // Average pooling of the selection scores: stride 1, zero padding, fixed
 // divisor (Sec. 5.4 names only the kernel size).
-__global__ void pool_kernel(const double *__restrict__ c, double *__restrict__ p, int N, int width) {
-  const int unit = blockIdx.y;
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= N) return;
+// A block of 256 threads stages 1024 scores and the halo on either side in LDS
+// (coalesced loads, all in flight), then every thread adds up the windows of
+// four outputs from there, left to right.
+constexpr int POOL_SPAN = 1024, POOL_MAX_HALO = 64;
+__global__ __launch_bounds__(256) void pool_kernel(const double *__restrict__ c, double *__restrict__ p, int N,
+                                                   int width) {
+  const int unit = blockIdx.y, tid = threadIdx.x;
+  const int j0 = blockIdx.x * POOL_SPAN;
   const double *row = c + (size_t)unit * N;
   const int r = (width - 1) / 2;
-  double acc = 0.0;
-  for (int u = -r; u <= r; ++u) {
-    const int jj = j + u;
-    if (jj >= 0 && jj < N) acc += row[jj];
+  if (r > POOL_MAX_HALO) {   // windows wider than the staged halo: straight from memory
+    for (int j = j0 + tid; j < min(j0 + POOL_SPAN, N); j += 256) {
+      double acc = 0.0;
+      for (int u = -r; u <= r; ++u) {
+        const int jj = j + u;
+        if (jj >= 0 && jj < N) acc += row[jj];
+      }
+      p[(size_t)unit * N + j] = acc / (double)width;
+    }
+    return;
   }
-  p[(size_t)unit * N + j] = acc / (double)width;
+  __shared__ double s[POOL_SPAN + 2 * POOL_MAX_HALO];
+  // s[i] = row[j0 - r + i], zero outside the row
+  double x[5];
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    const int at = tid + 256 * i, jj = j0 - r + at;
+    x[i] = at < POOL_SPAN + 2 * r && jj >= 0 && jj < N ? row[jj] : 0.0;
+  }
+#pragma unroll
+  for (int i = 0; i < 5; ++i) {
+    const int at = tid + 256 * i;
+    if (at < POOL_SPAN + 2 * r) s[at] = x[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int at = tid + 256 * i, j = j0 + at;
+    if (j >= N) break;
+    double acc = 0.0;
+    for (int u = 0; u <= 2 * r; ++u) acc += s[at + u];
+    p[(size_t)unit * N + j] = acc / (double)width;
+  }
 }
 
 // One block per unit (see select_of_unit).  Units flagged in `skip` get an all
@@ -103,11 +134,25 @@ __global__ __launch_bounds__(1024) void dist_mask_kernel(const double *__restric
   const int H = dm.Hkv, D = dm.D;
   const double *sb = sem + (size_t)b * H * D;
   __shared__ double centre[128];
+  __shared__ double part[8][128];
   __shared__ double sd[256];
   __shared__ uint8_t smask[256];
+  // the centre: eight groups of threads take every eighth head each (their
+  // loads are in flight together), the groups' sums are added in a fixed order
+  {
+    const int c = tid & 127, hg = tid >> 7;
+    double acc = 0.0;
+    if (c < D) {
+#pragma unroll 4
+      for (int h = hg; h < H; h += 8) acc += sb[(size_t)h * D + c];
+    }
+    part[hg][c] = acc;
+  }
+  __syncthreads();
   if (tid < D) {
     double acc = 0.0;
-    for (int h = 0; h < H; ++h) acc += sb[(size_t)h * D + tid];
+#pragma unroll
+    for (int g = 0; g < 8; ++g) acc += part[g][tid];
     centre[tid] = acc / (double)H;
   }
   __syncthreads();
@@ -132,12 +177,20 @@ __global__ __launch_bounds__(1024) void dist_mask_kernel(const double *__restric
     smask[tid] = rank < dm.n_het ? 1 : 0;
   }
   __syncthreads();
-  if (dm.add_centre && tid == 0) {
-    int best = -1;
-    for (int h = 0; h < H; ++h)
-      if (!smask[h] && (best < 0 || sd[h] < sd[best])) best = h;
-    if (best >= 0) smask[best] = 1;
+  // the unmarked head nearest to the centre (lowest index among equals):
+  // every unmarked head counts the unmarked ones that come before it
+  bool nearest = false;
+  if (dm.add_centre && tid < H) {
+    const double mine = sd[tid];
+    int before = 0;
+    for (int o = 0; o < H; ++o) {
+      const double other = sd[o];
+      before += !smask[o] && ((other < mine) || (other == mine && o < tid));
+    }
+    nearest = !smask[tid] && before == 0;
   }
+  __syncthreads();
+  if (nearest) smask[tid] = 1;
   __syncthreads();
   if (tid < H) {
     dist[(size_t)b * H + tid] = sd[tid];
@@ -161,7 +214,7 @@ int launch_select_listed(const Dims &dm, const double *scores, const int32_t *li
 }
 
 int launch_pool(const Dims &dm, const double *scores, double *pooled, hipStream_t s) {
-  pool_kernel<<<dim3((dm.N + 255) / 256, dm.units), dim3(256), 0, s>>>(scores, pooled, dm.N, dm.pool);
+  pool_kernel<<<dim3((dm.N + POOL_SPAN - 1) / POOL_SPAN, dm.units), dim3(256), 0, s>>>(scores, pooled, dm.N, dm.pool);
   return hip_ok(hipGetLastError());
 }
 

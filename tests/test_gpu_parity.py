@@ -97,6 +97,9 @@ SWEEP = [
     dict(n_sink=300, n_recent=300, ctx_len=512, top_t=1000),           # sinks+recent cover N; t > N
     dict(n_middle=5000, ctx_len=900),                                  # k larger than the middle
     dict(pool_kernel=7, ctx_len=1300),                                 # pooled selection scores
+    dict(pool_kernel=129, ctx_len=2500, n_middle=200),                 # the widest window staged in LDS
+    dict(pool_kernel=131, ctx_len=2500, n_middle=200),                 # wider: windows straight from memory
+    dict(pool_kernel=31, ctx_len=1024, n_middle=100),                  # the context ends with a pooling block
     dict(recipe="zipf", ctx_len=3000, n_middle=200, top_t=128),
     dict(obs_window=1, ctx_len=520),
     dict(obs_window=50, ctx_len=50, n_sink=2, n_recent=3, n_middle=4, top_t=10),   # L = N
