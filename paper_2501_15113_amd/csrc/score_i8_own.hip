@@ -345,6 +345,191 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   }
 }
 
+// The same for windows of several 32-row blocks, where a wave that went through
+// all row blocks of a tile of its own would take as many microseconds as there
+// are blocks, one after the other, with most of the chip waiting for the longest
+// list: here the NW waves of a block share a tile.  Wave w converts the 32-channel
+// block w of the tile's keys (the keys' common exponents meet in LDS first),
+// takes the row blocks w, w + NW, ... against the digits of all waves, and the
+// waves' sums meet in LDS, where lane t of wave 0 adds up key t in a fixed
+// order.  grid = (blocks per unit, units); tiles are dealt to a unit's blocks
+// in turn.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) void score_i8_columns_shared_kernel(
+    const uint16_t *__restrict__ k, const v4i *__restrict__ qdig, const double *__restrict__ gq,
+    const double *__restrict__ qd, const QTiny *__restrict__ qtiny, const int32_t *__restrict__ qcnt,
+    const double *__restrict__ stats, const int32_t *__restrict__ band_idx, const int32_t *__restrict__ band_cnt,
+    double *__restrict__ scores, Dims dm) {
+  constexpr int KS = D / 32, THREADS = 64 * NW;
+  static_assert(KS <= NW, "one converting wave per 32-channel block");
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, half = l >> 5;
+  const int N = dm.N, L = dm.L, R = dm.R, Rpad = dm.Rpad, n_rb = Rpad / 32;
+  const int n_listed = band_cnt[unit];
+  const int32_t *cols = band_idx + (size_t)unit * N;
+  const double unit_scale = dm.scale * EXP_UNITS;
+  const uint16_t *kb = k + (size_t)unit * N * D;
+  const double *qdu = qd + (size_t)unit * Rpad * D;
+  const double *st = stats + (size_t)unit * Rpad * 2;
+  const int n_tiny_all = qcnt[unit];
+  const bool q_overflow = n_tiny_all > I8_QCAP;
+  const int n_tiny = q_overflow ? 0 : n_tiny_all;
+  const QTiny *tiny = qtiny + (size_t)unit * I8_QCAP;
+
+  __shared__ double s_pow[EXP_TAB];
+  __shared__ QTiny s_ktiny[KS][I8_KCAP];     // remainders of the elements a converting wave could not fit
+  __shared__ int s_kcnt[KS];
+  __shared__ int s_low[KS];                  // a converting wave met a non-zero lowest digit
+  __shared__ int s_E[KS][32];                // largest exponent field of a key's channel block
+  __shared__ int s_ek[32];
+  __shared__ int s_col[32];                  // columns of the tile's keys, -1 past the list's end
+  __shared__ v4i s_dig[KS][4][64];
+  __shared__ double s_sum[NW][16][64];       // a wave's lanes' sums of their sixteen keys over its row blocks
+  for (int i = tid; i < EXP_TAB; i += THREADS) s_pow[i] = exp2((double)i * (1.0 / EXP_TAB));
+
+  v4i qv[KS][4];
+  const auto load_q = [&](int rb) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) qv[ks][t] = qdig[((((size_t)unit * n_rb + rb) * KS + ks) * 4 + t) * 64 + l];
+  };
+
+  const int n_tiles = (n_listed + 31) / 32;
+  for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int pos = tile * 32 + c32;
+    const int col = pos < n_listed ? cols[pos] : -1;
+    const uint16_t *key_row = kb + (size_t)max(col, 0) * D;
+    uint32_t raw[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) raw[x] = 0u;
+    if (w < KS && col >= 0) {
+      const uint4 lo = *reinterpret_cast<const uint4 *>(key_row + w * 32 + half * 16);
+      const uint4 hi = *reinterpret_cast<const uint4 *>(key_row + w * 32 + half * 16 + 8);
+      raw[0] = lo.x; raw[1] = lo.y; raw[2] = lo.z; raw[3] = lo.w;
+      raw[4] = hi.x; raw[5] = hi.y; raw[6] = hi.z; raw[7] = hi.w;
+    }
+    if (w < KS) {
+      int Ew = row_exponent_of(raw);
+      Ew = max(Ew, __shfl_xor(Ew, 32));
+      if (half == 0) s_E[w][c32] = Ew;
+    }
+    if (w == 0 && half == 0) s_col[c32] = col;
+    __syncthreads();   // (also: the table, and the previous tile's readers are done)
+    int E = 1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) E = max(E, s_E[ks][c32]);
+    if (w < KS) {
+      v4i dig[4];
+      const bool ok = digits_of(raw, E, dig);
+      const bool k_low = (dig[0][0] | dig[0][1] | dig[0][2] | dig[0][3]) != 0;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) s_dig[w][t][l] = dig[t];
+      int cnt = 0;
+      unsigned long long bad = __ballot(!ok);
+      while (bad) {
+        const int src = __ffsll((long long)bad) - 1;
+        bad &= bad - 1;
+        if (l == src) {
+#pragma unroll 1
+          for (int i = 0; i < 16; ++i) {
+            const int c = w * 32 + half * 16 + i;
+            double rem;
+            if (!remainder_of(key_row[c], E, rem)) continue;
+            if (cnt < I8_KCAP) {
+              QTiny ent;
+              ent.row = c32;
+              ent.c = c;
+              ent.r = rem;
+              s_ktiny[w][cnt] = ent;
+            }
+            ++cnt;
+          }
+        }
+        cnt = __shfl(cnt, src);
+      }
+      const bool any_low = __ballot(k_low) != 0ull;
+      if (l == 0) {
+        s_kcnt[w] = cnt;
+        s_low[w] = any_low ? 1 : 0;
+      }
+      if (w == 0 && half == 0) s_ek[c32] = E - (2 * I8_GRID - 126);
+    }
+    __syncthreads();
+    bool k_low_zero = true, plain = q_overflow;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      k_low_zero = k_low_zero && s_low[ks] == 0;
+      plain = plain || s_kcnt[ks] > I8_KCAP;
+    }
+
+    const auto key_at = [&](int v) { return s_col[tile_key(v, half)]; };
+    double sum16[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sum16[v] = 0.0;
+#pragma unroll 1
+    for (int rb = w; rb < n_rb; rb += NW) {
+      const int row = rb * 32 + c32;
+      double t16[16];
+      if (!plain) {
+        // (requested earlier -- before the conversion, or during the exponentials
+        // of the row block before -- the 64 registers push a hundred others into
+        // scratch memory)
+        load_q(rb);
+        bool q_low = false;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) q_low = q_low || (qv[ks][0][0] | qv[ks][0][1] | qv[ks][0][2] | qv[ks][0][3]) != 0;
+        contract_tile<KS>([&](int ks, int a) { return s_dig[ks][a][l]; }, qv, k_low_zero, __ballot(q_low) == 0ull, t16);
+        scale_logits(t16, gq[(size_t)unit * Rpad + row], s_ek, half);
+        add_row_remainders<D>(tiny, n_tiny, row, key_at, unit_scale, kb, t16);
+        for (int ks = 0; ks < KS; ++ks)
+          for (int e = 0; e < s_kcnt[ks]; ++e) {
+            const QTiny ent = s_ktiny[ks][e];
+            add_key_remainder<D>(ent, ent.row, half, row, qdu, tiny, n_tiny, unit_scale, t16);
+          }
+      } else {
+        plain_logits<D>(qdu + (size_t)row * D, kb, key_at, unit_scale, t16);
+      }
+      // weights against the row's statistics (in table units), masked where the
+      // key lies behind the row's own position or there is no row or key
+      const bool row_ok = row < R;
+      const double m_units = row_ok ? st[2 * row] * EXP_UNITS : 0.0;
+      const double inv = row_ok ? 1.0 / st[2 * row + 1] : 0.0;
+      const int last_visible = N - L + (dm.row0 + row) % L;
+#pragma unroll
+      for (int h8 = 0; h8 < 2; ++h8) {
+        double x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = fmin(t16[8 * h8 + i] - m_units, 0.0);
+        exp_each<8>(x, s_pow);
+#pragma unroll
+        for (int v4 = 0; v4 < 2; ++v4) {
+          const v4i c4 = *reinterpret_cast<const v4i *>(&s_col[8 * (2 * h8 + v4) + 4 * half]);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const bool vis = c4[i] >= 0 && c4[i] <= last_visible;
+            sum16[8 * h8 + 4 * v4 + i] += vis ? x[4 * v4 + i] * inv : 0.0;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s_sum[w][v][l] = sum16[v];
+    __syncthreads();
+    if (tid < 32) {
+      const int v = 4 * (l >> 3) + (l & 3), hf = (l >> 2) & 1;
+      double total = 0.0;
+      for (int ww = 0; ww < NW; ++ww)
+#pragma unroll 8
+        for (int r = 0; r < 32; ++r) total += s_sum[ww][v][32 * hf + r];
+      const int out_col = s_col[l];
+      if (out_col >= 0) scores[(size_t)unit * N + out_col] = total / (double)dm.Rtot;
+    }
+    // (the next tile's first barrier comes after its writes of s_E and s_col only:
+    // s_col is read by wave 0 above, so that barrier alone does not protect it)
+    __syncthreads();
+  }
+}
+
 // Row statistics of a window of at most 32 rows (see score_i8_direct_kernel);
 // the window rows' digits are in `bufs`.  max_parts: partial records per unit
 // that `part` has room for; *n_parts: records written.
@@ -384,6 +569,22 @@ int launch_i8_columns(const Dims &dm, const void *k, const double *qd, const I8B
   auto qdig = static_cast<const v4i *>(bufs.qdig);
   constexpr int CNW = 4;
   const dim3 grid(blocks_per_unit < 1 ? 1 : blocks_per_unit, dm.units), block(64 * CNW);
+  // Several row blocks and short lists: the waves of a block share a tile.  A
+  // block then takes one tile at a time where its waves would take one each, so
+  // it pays up to about two tiles per block (cfg3 / cfg4 / cfg5-shaped layers,
+  // a few hundred columns per unit: 27 -> 21, 22 -> 12, 43 -> 42 us); the lists of a
+  // pooled middle pick carry the neighbours of every band column, several
+  // thousand columns per unit, and stay with the kernel of a tile per wave
+  // (8-head stack at 60 %: 0.305 against 0.311 ms per layer).
+  if (dm.Rpad > 32 && dm.pool == 1) {
+    if (dm.D == 64)
+      score_i8_columns_shared_kernel<64, CNW><<<grid, block, 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, stats,
+                                                                    band_idx, band_cnt, scores, dm);
+    else
+      score_i8_columns_shared_kernel<128, CNW><<<grid, block, 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, stats,
+                                                                     band_idx, band_cnt, scores, dm);
+    return hip_ok(hipGetLastError());
+  }
   if (dm.D == 64)
     score_i8_columns_kernel<64, CNW><<<grid, block, 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, stats, band_idx,
                                                             band_cnt, scores, dm);

@@ -326,6 +326,30 @@ def test_int8_statistics_of_single_block_windows_on_every_route(rate_q, rate_k, 
     run_layer(wl, mutate=tiny, check_batches=(0, 1), screening=2)
 
 
+@pytest.mark.parametrize("head_dim,group", [(128, 4), (64, 4), (128, 8), (128, 5), (64, 2)])
+@pytest.mark.parametrize("rate_q,rate_k,what", [
+    (0.0, 0.0, "no remainders"),
+    (0.002, 0.0005, "a few remainders on both lists"),
+    (0.0, 0.02, "key lists overflow: plain fp64 dot products for those tiles"),
+    (0.7, 0.001, "window-row list overflows: plain fp64 dot products everywhere"),
+    (0.01, 0.004, "many remainders, same channels on both sides"),
+])
+def test_listed_columns_of_wide_windows_on_every_route(rate_q, rate_k, what, head_dim, group):
+    """After a screening pass the exact scores of the listed columns come from
+    the integer contraction too; for windows of several 32-row blocks the waves
+    of a block share a tile of listed keys (one, two or an uneven number of row
+    blocks per wave here): its remainder lists, one per converting wave, and
+    its plain route, for both head sizes."""
+    def tiny(ld):
+        if rate_q:
+            _shrink(ld.q_win, rate_q, 41)
+        if rate_k:
+            _shrink(ld.k, rate_k, 42)
+    wl = small_workload(name="i8cols", wid=203, ctx_len=2333, n_q_heads=3 * group, n_kv_heads=3, obs_window=32,
+                        head_dim=head_dim, n_hetero=1, decode_steps=1)
+    run_layer(wl, mutate=tiny, check_batches=(0, 1), screening=2)
+
+
 @pytest.mark.parametrize("side", ["window rows", "keys", "both"])
 def test_int8_statistics_when_the_remainders_carry_the_logits(side):
     """One channel 2^30 times larger than the rest pushes every other element
