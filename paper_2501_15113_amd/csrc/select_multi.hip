@@ -738,11 +738,24 @@ __global__ __launch_bounds__(1024) void mlist_settle_kernel(const double *__rest
   {
     bool bad = n < 0 || n > N;
     int b1 = 0, b2 = 0;
-    for (int i = tid; i < n && !bad; i += 1024) {
-      const int v = list[i];
-      bad = v < 0 || v >= N || (i > 0 && list[i - 1] >= v);
-      b1 += v < dm.s1 ? 1 : 0;
-      b2 += v < N - dm.s2 ? 1 : 0;
+    // (SWEEP_U entries of a thread in flight at once: a loop that looks at one
+    // entry per trip is a chain of memory latencies, eight of them for a list
+    // of 8192 columns)
+    for (int i0 = tid; i0 < n && !bad; i0 += 1024 * SWEEP_U) {
+      int v[SWEEP_U], before[SWEEP_U];
+#pragma unroll
+      for (int r = 0; r < SWEEP_U; ++r) {
+        const int i = min(i0 + 1024 * r, n - 1);
+        v[r] = list[i];
+        before[r] = i > 0 ? list[i - 1] : -1;
+      }
+#pragma unroll
+      for (int r = 0; r < SWEEP_U; ++r) {
+        if (i0 + 1024 * r >= n) continue;
+        bad = bad || v[r] < 0 || v[r] >= N || before[r] >= v[r];
+        b1 += v[r] < dm.s1 ? 1 : 0;
+        b2 += v[r] < N - dm.s2 ? 1 : 0;
+      }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -759,9 +772,18 @@ __global__ __launch_bounds__(1024) void mlist_settle_kernel(const double *__rest
     }
   }
   const int ia = s_below[0], ib = s_below[1];
-  int above = 0;
-  for (int x = 0; x < mb.S; ++x) above += above_band[(size_t)unit * MSEL_MAX_SLICES + x];
-  const int need = dm.k - above;
+  // the slices' counts of middle columns above the band: one lane each (a loop
+  // over them in every thread is a chain of up to 64 memory latencies)
+  static_assert(MSEL_MAX_SLICES <= 64, "one wave adds up the slices' counts");
+  __shared__ int s_above;
+  if (tid < 64) {
+    int a = tid < mb.S ? above_band[(size_t)unit * MSEL_MAX_SLICES + tid] : 0;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) a += __shfl_xor(a, off);
+    if (tid == 0) s_above = a;
+  }
+  __syncthreads();
+  const int need = dm.k - s_above;
   if (need < 1 || need > ib - ia) {   // not while the band's bound holds; the full selection decides then
     if (tid == 0) mb.flag[unit] = 1;
     return;
@@ -774,11 +796,19 @@ __global__ __launch_bounds__(1024) void mlist_settle_kernel(const double *__rest
   if (tid < 2 * MSEL_MAX_SLICES) c[tid] = 0;
   __syncthreads();
   const int seg = slice_len(N, mb.S);
-  for (int i = ia + tid; i < ib; i += 1024) {
-    const int j = list[i];
-    const uint64_t key = score_key(sc[j]);
-    if (key > pat) atomicAdd(&c[j / seg], 1);
-    else if (key == pat) atomicAdd(&c[MSEL_MAX_SLICES + j / seg], 1);
+  for (int i0 = ia + tid; i0 < ib; i0 += 1024 * SWEEP_U) {
+    int j[SWEEP_U];
+    uint64_t key[SWEEP_U];
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) j[r] = list[min(i0 + 1024 * r, ib - 1)];
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) key[r] = score_key(sc[j[r]]);
+#pragma unroll
+    for (int r = 0; r < SWEEP_U; ++r) {
+      if (i0 + 1024 * r >= ib) continue;
+      if (key[r] > pat) atomicAdd(&c[j[r] / seg], 1);
+      else if (key[r] == pat) atomicAdd(&c[MSEL_MAX_SLICES + j[r] / seg], 1);
+    }
   }
   __syncthreads();
   if (tid < mb.S) {
