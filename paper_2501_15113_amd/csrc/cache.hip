@@ -29,29 +29,62 @@ __device__ __forceinline__ double elem_as_double(uint16_t x) {
 // cannot be laid out in `capacity` tokens: the units that do not fit are left
 // empty (no region, length 0), so that nothing downstream reads or writes past
 // the buffer, and bit 2 of the sticky flag reports it.
-__global__ void layout_kernel(const uint8_t *__restrict__ mask, int64_t *__restrict__ offsets,
-                              int32_t *__restrict__ lens, int *__restrict__ d_err, Dims dm,
-                              int reserve, int64_t capacity) {
+// The usual case -- everything fits -- is a block-wide prefix sum of the units'
+// regions (every thread takes a run of consecutive units); only a layout that
+// overflows is walked unit by unit, by one thread.
+__global__ __launch_bounds__(256) void layout_kernel(const uint8_t *__restrict__ mask, int64_t *__restrict__ offsets,
+                                                     int32_t *__restrict__ lens, int *__restrict__ d_err, Dims dm,
+                                                     int reserve, int64_t capacity) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int short_len = dm.s1 + dm.k + dm.s2;
-  for (int u = threadIdx.x; u < dm.units; u += blockDim.x)
-    lens[u] = (dm.keep_all || mask[u]) ? dm.N : short_len;
+  const auto len_of = [&](int u) { return (dm.keep_all || mask[u]) ? dm.N : short_len; };
+  const auto region_of = [&](int len) {
+    const int64_t cap = ((int64_t)len + reserve + CHUNK - 1) / CHUNK * CHUNK;
+    return cap < CHUNK ? (int64_t)CHUNK : cap;   // every unit owns at least one chunk
+  };
+  const int upt = (dm.units + 255) / 256, first = tid * upt;
+  int64_t own = 0;
+  for (int i = 0; i < upt; ++i)
+    if (first + i < dm.units) own += region_of(len_of(first + i));
+  int64_t incl = own;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int64_t t = __shfl_up(incl, off);
+    if (lane >= off) incl += t;
+  }
+  __shared__ int64_t s_wave[4];
+  if (lane == 63) s_wave[wv] = incl;
   __syncthreads();
-  if (threadIdx.x == 0) {
+  int64_t run = incl - own;
+  for (int w = 0; w < wv; ++w) run += s_wave[w];
+  const int64_t total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+  if (total <= capacity) {
+    for (int i = 0; i < upt; ++i) {
+      const int u = first + i;
+      if (u >= dm.units) break;
+      const int len = len_of(u);
+      lens[u] = len;
+      offsets[u] = run;
+      run += region_of(len);
+    }
+    if (tid == 0) offsets[dm.units] = total;
+    return;
+  }
+  if (tid == 0) {
     int64_t off = 0;
-    bool overflow = false;
     for (int u = 0; u < dm.units; ++u) {
       offsets[u] = off;
-      int64_t cap = ((int64_t)lens[u] + reserve + CHUNK - 1) / CHUNK * CHUNK;
-      if (cap < CHUNK) cap = CHUNK;  // every unit owns at least one chunk
+      int len = len_of(u);
+      int64_t cap = region_of(len);
       if (off + cap > capacity) {
-        lens[u] = 0;
+        len = 0;
         cap = 0;
-        overflow = true;
       }
+      lens[u] = len;
       off += cap;
     }
     offsets[dm.units] = off;
-    if (overflow) atomicOr(d_err, 2);
+    atomicOr(d_err, 2);
   }
 }
 
