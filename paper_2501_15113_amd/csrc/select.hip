@@ -103,17 +103,24 @@ __global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__
     int j[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) j[u] = n0 + u < dm.T ? idx[n0 + u] : -1;
-    double w[U], x0[U], x1[U];
+    // every load unconditional (a pick past the end reads token 0 with weight
+    // zero) and converted only after all are requested: a load under a branch
+    // is waited for where it stands, sixteen memory latencies one after the other
+    double w[U];
+    T r0[U], r1[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      w[u] = j[u] >= 0 ? sc[j[u]] : 0.0;
-      x0[u] = j[u] >= 0 ? elem_to_double(vb[(size_t)j[u] * D + lane]) : 0.0;
-      x1[u] = j[u] >= 0 && second ? elem_to_double(vb[(size_t)j[u] * D + 64 + lane]) : 0.0;
+      const size_t row = (size_t)max(j[u], 0) * D;
+      w[u] = sc[max(j[u], 0)];
+      r0[u] = vb[row + lane];
+      r1[u] = vb[row + (second ? 64 : 0) + lane];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      acc0 += w[u] * x0[u];
-      acc1 += w[u] * x1[u];
+      const bool on = j[u] >= 0;
+      const double wu = on ? w[u] : 0.0;
+      acc0 += wu * (on ? elem_to_double(r0[u]) : 0.0);
+      acc1 += wu * (on && second ? elem_to_double(r1[u]) : 0.0);
     }
   }
   red[wv][lane] = acc0;
