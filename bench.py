@@ -12,7 +12,8 @@ len * d * 2 * sizeof) divided by the GPU time of the decode calls.
 The default run reports the load-imbalance stress workload (cfg5) as `value`
 and adds short measurements of the other bf16 workloads as `also_cfg2`,
 `also_cfg4` and `also_cfg3` (the 32-layer stack, with one decode call per
-layer and with one call for the whole stack); `--only` leaves them out.
+layer and with one call for the whole stack), and of two 32-layer stacks on
+the paper's layer schedule as `also_schedules`; `--only` leaves them out.
 
 Prints ONE JSON line.
 """
@@ -187,6 +188,12 @@ def main():
         out["also_cfg4"] = pick(measure(args, "cfg4", False, False, k_extra, w_extra))
         out["also_cfg3"] = {"per_layer": pick(measure(args, "cfg3", False, False, min(k_extra, 3), w_extra)),
                             "stacked": pick(measure(args, "cfg3", False, True, min(k_extra, 3), w_extra))}
+        # The 32-layer stacks on the paper's layer schedule (Eq. 16-17) at a 40 % budget, Llama- and
+        # Mistral-shaped: heterogeneous head counts and middle budgets differ from layer to layer.
+        out["also_schedules"] = {
+            name: {"per_layer": pick(measure(args, name, False, False, min(k_extra, 2), w_extra)),
+                   "stacked": pick(measure(args, name, False, True, min(k_extra, 2), w_extra))}
+            for name in ("llama40", "mistral40")}
         out["exact_semantic_vector"] = exact_vector_leg()
     print(json.dumps(out))
 
