@@ -374,11 +374,11 @@ int taskkv_separate(taskkv_ctx *ctx, const taskkv_layer_cfg *cfg, const void *q_
   // unlisted column is provably below the threshold): a few hundred candidates
   // instead of N.
   if (ctx->screening && scores_screened(d, cfg->dtype, &scr))
-    rc = launch_select_listed(d, scores, scr.band_idx, scr.band_cnt, d.T, top_idx, s);
-  else if (sliced && msel_pays(d, ctx->n_cu, 0, d.N, d.T))
-    rc = launch_select_sliced(d, ctx->n_cu, mb, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, s);
-  else
-    rc = launch_select(d, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, 0, s);
+    return launch_topt_semvec_mask(d, cfg->dtype, scores, scr.band_idx, scr.band_cnt, v, top_idx, sem_vec, dist,
+                                   hetero_mask, s);
+  if (!(sliced && msel_pays(d, ctx->n_cu, 0, d.N, d.T)))
+    return launch_topt_semvec_mask(d, cfg->dtype, scores, nullptr, nullptr, v, top_idx, sem_vec, dist, hetero_mask, s);
+  rc = launch_select_sliced(d, ctx->n_cu, mb, scores, nullptr, 0, d.N, d.T, 0, 0, 0, top_idx, d.T, s);
   if (rc) return rc;
   return launch_semvec_mask(d, cfg->dtype, scores, v, top_idx, sem_vec, dist, hetero_mask, s);
 }

@@ -62,8 +62,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__
                                                       const uint8_t *__restrict__ skip, int skip_all,
                                                       int N, int lo, int hi, int count, int prefix,
                                                       int gap, int suffix, int32_t *__restrict__ out,
-                                                      int out_stride, const int32_t *__restrict__ listed,
-                                                      const int32_t *__restrict__ n_listed) {
+                                                      int out_stride) {
   const int unit = blockIdx.x, tid = threadIdx.x;
   int32_t *orow = out + (size_t)unit * out_stride;
   if (skip_all || (skip && skip[unit])) {
@@ -72,8 +71,8 @@ __global__ __launch_bounds__(1024) void select_kernel(const double *__restrict__
   }
   __shared__ RadixScratch rs;
   __shared__ int s_cnt[32];
-  select_of_unit(scores + (size_t)unit * N, orow, N, lo, hi, count, prefix, gap, suffix, out_stride,
-                 listed ? listed + (size_t)unit * N : nullptr, listed ? n_listed[unit] : 0, rs, s_cnt);
+  select_of_unit(scores + (size_t)unit * N, orow, N, lo, hi, count, prefix, gap, suffix, out_stride, nullptr, 0, rs,
+                 s_cnt);
 }
 
 __device__ __forceinline__ double elem_to_double(float x) { return (double)x; }
@@ -81,28 +80,25 @@ __device__ __forceinline__ double elem_to_double(uint16_t x) {
   return (double)__uint_as_float(uint32_t(x) << 16);
 }
 
-// Eq. 15: v' = sum over the t picked tokens of C_j v_j, one block per unit.  A
-// wave takes sixteen picks at a time, a lane the channels c and c + 64 of every
-// one of them: the sixteen index loads, then the sixteen score and value loads
-// behind them, are in flight together, and a block's sixteen waves cover 256
-// picks per round -- the usual t in one.  Picks are added in index order inside a
-// wave and the waves' partial vectors in wave order: the same sum every time.
+// Eq. 15: v' = sum over the t picked tokens of C_j v_j, all 1024 threads of a
+// unit's block.  A wave takes sixteen picks at a time, a lane the channels c and
+// c + 64 of every one of them: the sixteen index loads, then the sixteen score
+// and value loads behind them, are in flight together, and a block's sixteen
+// waves cover 256 picks per round -- the usual t in one.  Picks are added in
+// index order inside a wave and the waves' partial vectors in wave order: the
+// same sum every time.  idx: the unit's picks (-1 = none); red: LDS.
 template <typename T>
-__global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__ scores, const T *__restrict__ v,
-                                                      const int32_t *__restrict__ top_idx,
-                                                      double *__restrict__ sem, Dims dm) {
-  const int unit = blockIdx.x, D = dm.D, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const double *sc = scores + (size_t)unit * dm.N;
-  const T *vb = v + (size_t)unit * dm.N * D;
-  const int32_t *idx = top_idx + (size_t)unit * dm.T;
-  __shared__ double red[16][128];
+__device__ __forceinline__ void semvec_of_unit(const double *__restrict__ sc, const T *__restrict__ vb,
+                                               const int32_t *__restrict__ idx, double *__restrict__ sem_row,
+                                               int n_picks, int D, double (&red)[16][128]) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   constexpr int U = 16;
   const bool second = D > 64;   // head sizes 64 and 128: one or two channels per lane
   double acc0 = 0.0, acc1 = 0.0;
-  for (int n0 = wv * U; n0 < dm.T; n0 += 16 * U) {
+  for (int n0 = wv * U; n0 < n_picks; n0 += 16 * U) {
     int j[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) j[u] = n0 + u < dm.T ? idx[n0 + u] : -1;
+    for (int u = 0; u < U; ++u) j[u] = n0 + u < n_picks ? idx[n0 + u] : -1;
     // every load unconditional (a pick past the end reads token 0 with weight
     // zero) and converted only after all are requested: a load under a branch
     // is waited for where it stands, sixteen memory latencies one after the other
@@ -129,8 +125,42 @@ __global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__
   if (threadIdx.x < D) {
     double sum = 0.0;
     for (int g = 0; g < 16; ++g) sum += red[g][threadIdx.x];
-    sem[(size_t)unit * D + threadIdx.x] = sum;
+    sem_row[threadIdx.x] = sum;
   }
+}
+
+// One block per unit: the semantic vector from picks that are in memory.
+template <typename T>
+__global__ __launch_bounds__(1024) void semvec_kernel(const double *__restrict__ scores, const T *__restrict__ v,
+                                                      const int32_t *__restrict__ top_idx,
+                                                      double *__restrict__ sem, Dims dm) {
+  const int unit = blockIdx.x;
+  __shared__ double red[16][128];
+  semvec_of_unit(scores + (size_t)unit * dm.N, v + (size_t)unit * dm.N * dm.D, top_idx + (size_t)unit * dm.T,
+                 sem + (size_t)unit * dm.D, dm.T, dm.D, red);
+}
+
+// One block per unit: the top-t pick (Eq. 14; among all columns, or among the
+// columns a list names) and the semantic vector of the picks behind it -- the
+// two are a chain inside one unit, and as two kernels they paid two launches
+// for it.  The picks go through memory (they are an output of their own); the
+// barrier between the halves makes the block's writes visible to its readers.
+template <typename T>
+__global__ __launch_bounds__(1024) void topt_semvec_kernel(const double *__restrict__ scores,
+                                                           const int32_t *__restrict__ listed,
+                                                           const int32_t *__restrict__ n_listed,
+                                                           const T *__restrict__ v, int32_t *__restrict__ top_idx,
+                                                           double *__restrict__ sem, Dims dm) {
+  const int unit = blockIdx.x;
+  __shared__ RadixScratch rs;
+  __shared__ int s_cnt[32];
+  __shared__ double red[16][128];
+  int32_t *picks = top_idx + (size_t)unit * dm.T;
+  select_of_unit(scores + (size_t)unit * dm.N, picks, dm.N, 0, dm.N, dm.T, 0, 0, 0, dm.T,
+                 listed ? listed + (size_t)unit * dm.N : nullptr, listed ? n_listed[unit] : 0, rs, s_cnt);
+  __syncthreads();
+  semvec_of_unit(scores + (size_t)unit * dm.N, v + (size_t)unit * dm.N * dm.D, picks, sem + (size_t)unit * dm.D,
+                 dm.T, dm.D, red);
 }
 
 // Eq. 7-8 and the ranking rule: one block per batch element.
@@ -209,19 +239,25 @@ int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask
                   int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
                   hipStream_t s) {
   select_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, skip_mask, skip_all, dm.N, lo, hi, count, prefix, gap,
-                                                     suffix, out, out_stride, nullptr, nullptr);
-  return hip_ok(hipGetLastError());
-}
-
-int launch_select_listed(const Dims &dm, const double *scores, const int32_t *listed, const int32_t *n_listed,
-                         int count, int32_t *out, hipStream_t s) {
-  select_kernel<<<dim3(dm.units), dim3(1024), 0, s>>>(scores, nullptr, 0, dm.N, 0, 0, count, 0, 0, 0, out, count,
-                                                     listed, n_listed);
+                                                     suffix, out, out_stride);
   return hip_ok(hipGetLastError());
 }
 
 int launch_pool(const Dims &dm, const double *scores, double *pooled, hipStream_t s) {
   pool_kernel<<<dim3((dm.N + POOL_SPAN - 1) / POOL_SPAN, dm.units), dim3(256), 0, s>>>(scores, pooled, dm.N, dm.pool);
+  return hip_ok(hipGetLastError());
+}
+
+int launch_topt_semvec_mask(const Dims &dm, int dtype, const double *scores, const int32_t *listed,
+                            const int32_t *n_listed, const void *v, int32_t *top_idx, double *sem_vec, double *dist,
+                            uint8_t *mask, hipStream_t s) {
+  if (dtype == TASKKV_F32)
+    topt_semvec_kernel<float><<<dim3(dm.units), dim3(1024), 0, s>>>(scores, listed, n_listed,
+                                                                  static_cast<const float *>(v), top_idx, sem_vec, dm);
+  else
+    topt_semvec_kernel<uint16_t><<<dim3(dm.units), dim3(1024), 0, s>>>(
+        scores, listed, n_listed, static_cast<const uint16_t *>(v), top_idx, sem_vec, dm);
+  dist_mask_kernel<<<dim3(dm.B), dim3(1024), 0, s>>>(sem_vec, dist, mask, dm);
   return hip_ok(hipGetLastError());
 }
 

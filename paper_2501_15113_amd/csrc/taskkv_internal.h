@@ -204,10 +204,12 @@ int launch_scores(const Dims &dm, int dtype, const void *q_win, const void *k, d
 int launch_select(const Dims &dm, const double *scores, const uint8_t *skip_mask, int lo, int hi,
                   int count, int prefix, int gap, int suffix, int32_t *out, int out_stride, int skip_all,
                   hipStream_t s);
-// top `count` among the columns an ascending per-unit list names ([units][N] entries, n_listed[unit] used)
-int launch_select_listed(const Dims &dm, const double *scores, const int32_t *listed, const int32_t *n_listed,
-                         int count, int32_t *out, hipStream_t s);
 int launch_pool(const Dims &dm, const double *scores, double *pooled, hipStream_t s);
+// top-t pick (among the columns an ascending per-unit list names -- [units][N] entries, n_listed[unit] used -- or
+// among all when listed is null), semantic vectors, distances, mask
+int launch_topt_semvec_mask(const Dims &dm, int dtype, const double *scores, const int32_t *listed,
+                            const int32_t *n_listed, const void *v, int32_t *top_idx, double *sem_vec, double *dist,
+                            uint8_t *mask, hipStream_t s);
 int launch_semvec_mask(const Dims &dm, int dtype, const double *scores, const void *v,
                        const int32_t *top_idx, double *sem_vec, double *dist, uint8_t *mask,
                        hipStream_t s);
