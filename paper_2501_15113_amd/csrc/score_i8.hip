@@ -324,14 +324,19 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
   auto qdig = static_cast<v4i *>(bufs.qdig);
   if (!qcnt_zeroed) zero_i32_kernel<<<dim3((dm.units + 255) / 256), dim3(256), 0, s>>>(bufs.qcnt, dm.units);
   // waves per block, waves per row block: 8 x 1 for windows above 128 rows, 4 x 1
-  // down to 96 rows, 4 x 2 for 64 rows
+  // down to 96 rows (8 x 2 on few keys), 4 x 2 for 64 rows
   if (n_rb == 1) {
     // one row block: every wave for itself (score_i8_own.hip)
     if (dm.D == 64) q_digits_kernel<64><<<dim3(dm.units), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
     else q_digits_kernel<128><<<dim3(dm.units), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
     return launch_i8_direct(dm, k, qd, bufs, part, knorm, n_wg * 8, n_parts, s);
   }
-  const int nw = n_rb > 4 ? 8 : 4, wpr = n_rb <= 2 ? 2 : 1;
+  // (96- and 128-row windows on few keys in all -- a layer of 8 units x 8192
+  // keys -- leave most of the chip idle as blocks of four waves: there eight
+  // waves, two per row block, measured 164 -> 159 us for the whole compression;
+  // from 8 units x 32768 keys on, the same shape is 3-8 % slower than 4 x 1)
+  const bool few_keys = n_rb > 2 && n_rb <= 4 && (int64_t)dm.units * dm.n_keys <= 131072;
+  const int nw = n_rb > 4 || few_keys ? 8 : 4, wpr = n_rb <= 2 || few_keys ? 2 : 1;
   const int rows_per_block = 32 * nw / wpr;
   const int nz = (dm.Rpad + rows_per_block - 1) / rows_per_block;
   // A block's set-up (operands of its row blocks, the table, filling the key
@@ -353,7 +358,8 @@ int launch_i8_stats(const Dims &dm, const void *q_win, const void *k, const doub
   auto pick = [&](auto d) {
     constexpr int DD = decltype(d)::value;
     q_digits_kernel<DD><<<dim3(dm.units * n_rb), dim3(64), 0, s>>>(qq, qdig, bufs.gq, bufs.qtiny, bufs.qcnt, dm);
-    if (nw == 8) launch(score_i8_stats_kernel<DD, 8, 1>);
+    if (nw == 8 && wpr == 1) launch(score_i8_stats_kernel<DD, 8, 1>);
+    else if (nw == 8) launch(score_i8_stats_kernel<DD, 8, 2>);
     else if (wpr == 1) launch(score_i8_stats_kernel<DD, 4, 1>);
     else launch(score_i8_stats_kernel<DD, 4, 2>);
   };

@@ -292,7 +292,8 @@ def test_int8_statistics_of_narrow_and_wide_windows(group, window, outliers):
     """The int8 statistics pass has a kernel shape per window size: every wave for
     itself for windows of at most 32 rows (one query head per KV head is the
     common case), two waves per 32-row block for 64 rows, one wave per block of
-    rows up to 128 rows, blocks of eight waves above.  Each of them, with and
+    rows up to 128 rows (two waves per block of rows while the layer has few
+    keys in all, as here), blocks of eight waves above.  Each of them, with and
     without elements that leave the integer window (remainder lists of both
     sides), on a context that ends in a ragged tile."""
     def tiny(ld):
@@ -301,6 +302,19 @@ def test_int8_statistics_of_narrow_and_wide_windows(group, window, outliers):
     wl = small_workload(name=f"i8win-{group}-{window}", wid=197, ctx_len=2101, n_q_heads=3 * group, n_kv_heads=3,
                         obs_window=window, n_hetero=1, decode_steps=1)
     run_layer(wl, mutate=tiny if outliers else None, check_batches=(0, 1))
+
+
+@pytest.mark.parametrize("group", [3, 4])
+def test_int8_statistics_of_wide_windows_on_many_keys(group):
+    """Windows of 96 and 128 rows take blocks of eight waves while a layer has
+    few keys in all and blocks of four waves from 131072 keys on: the larger
+    shape, with elements that leave the integer window on both sides."""
+    def tiny(ld):
+        _shrink(ld.q_win, 0.004, 51)
+        _shrink(ld.k, 0.001, 52)
+    wl = small_workload(name=f"i8many-{group}", wid=204, batch=2, ctx_len=23000, n_q_heads=3 * group, n_kv_heads=3,
+                        obs_window=32, n_hetero=1, n_middle=300, decode_steps=1)
+    run_layer(wl, mutate=tiny, check_batches=(1,))
 
 
 @pytest.mark.parametrize("head_dim", [64, 128])
