@@ -453,7 +453,8 @@ bool band_is_sliced(const Dims &dm, const ScreenBufs *scr) {
 
 bool scores_screened(const Dims &dm, int dtype, const ScreenBufs *scr) {
   const int n_groups = (dm.Rtot + ROW_GROUP - 1) / ROW_GROUP;
-  const bool big = (double)dm.units * dm.Rtot * dm.N >= 3e7;   // measured: loses at 8e6, wins at 7e7
+  // measured on 8 KV heads x 128 rows: 11 us slower at 8.4e6 (8192 keys), 33-70 us faster at 1.7e7-2.5e7
+  const bool big = (double)dm.units * dm.Rtot * dm.N >= 1.2e7;
   // with pooling only the sliced band kernels list the neighbours a pooled score needs
   const bool pool_ok = dm.pool == 1 || (band_is_sliced(dm, scr) && scr->pooled != nullptr);
   return scr != nullptr && scr->mode != 0 && n_groups == 1 && screen_supported(dm, dtype) && pool_ok &&
