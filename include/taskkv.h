@@ -292,7 +292,7 @@ int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream);
  * identical either way.  mode 0: never (every score in fp64); 1 (default): when
  * the layer is large enough for it to pay; 2: whenever the inputs allow
  * (bf16, at most 512 window rows per KV head; with pool_kernel > 1 only
- * contexts of 32768 tokens and more, on at most 256 (batch, KV head) units). */
+ * contexts of 12288 tokens and more, on at most 256 (batch, KV head) units). */
 int taskkv_set_screening(taskkv_ctx *ctx, int mode);
 
 /* Row maxima and softmax denominators of the window scores (Eq. 12) are needed

@@ -613,12 +613,11 @@ static int msel_slices(const Dims &dm, int n_cu) {
 static bool msel_sized(const Dims &dm) { return dm.N >= MSEL_MIN_RANGE && dm.units <= MSEL_MAX_UNITS; }
 
 // Long ranges on few units; elsewhere the extra launches cost more than the
-// idle compute units.
+// idle compute units.  Measured on 8 and 32 units, separator and compressor
+// together: sliced 7-36 us slower at 8192 scores, 4-5 us faster at 12288, 7-16 us
+// at 16384, 14-19 us at 24000.
 bool msel_pays(const Dims &dm, int n_cu, int lo, int hi, int count) {
-  // (one block per unit leaves most of the chip idle on 16 units or fewer: there half the range pays,
-  // 8 units of 32496 scores measured 52 us in one block each, 40 us as six sliced kernels)
-  const int min_range = dm.units <= 16 ? MSEL_MIN_RANGE / 2 : MSEL_MIN_RANGE;
-  return msel_sized(dm) && hi - lo >= min_range && count > 0 && count < hi - lo && msel_slices(dm, n_cu) >= 2;
+  return msel_sized(dm) && hi - lo >= MSEL_MIN_RANGE && count > 0 && count < hi - lo && msel_slices(dm, n_cu) >= 2;
 }
 
 static size_t al256(size_t b) { return (b + 255) & ~size_t(255); }

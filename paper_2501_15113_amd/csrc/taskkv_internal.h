@@ -158,7 +158,7 @@ int launch_screen(const Dims &dm, const void *q_win, const void *k, const double
 // Buffers of the selections whose sweeps are cut into slices (see select_multi.hip).
 constexpr int MSEL_MAX_SLICES = 32;    // blocks that share a unit
 constexpr int MSEL_MAX_UNITS = 256;    // beyond this one block per unit fills the chip anyway
-constexpr int MSEL_MIN_RANGE = 32768;  // shorter ranges do not pay for the extra launches (half of it on 16 units or fewer)
+constexpr int MSEL_MIN_RANGE = 12288;  // shorter ranges do not pay for the extra launches
 constexpr int MSEL_CAND = 4096;        // entries of the wanted bin a unit's candidate list takes
 struct MSelBufs {
   unsigned *hist;                // [2 levels][2][units][4096] digit histograms

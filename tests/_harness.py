@@ -69,7 +69,7 @@ def check_compression(ld, cfg, bufs, k_rows, v_rows, b, ref):
     Hkv, N = cfg.n_kv_heads, cfg.ctx_len
     scores = bufs.scores[b].cpu().numpy()
     # (with pooling, only contexts long enough for the band kernels that list a pooled column's neighbours)
-    screened = (cfg.dtype == 1 and (cfg.pool_kernel == 1 or cfg.ctx_len >= 32768) and
+    screened = (cfg.dtype == 1 and (cfg.pool_kernel == 1 or cfg.ctx_len >= 12288) and
                 (cfg.n_q_heads // cfg.n_kv_heads) * cfg.obs_window <= 512 and getattr(bufs, "screening", True))
     if screened:
         # fp32-accurate everywhere, fp64-exact on every column that can decide something

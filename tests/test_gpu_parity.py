@@ -116,6 +116,11 @@ SWEEP = [
     dict(n_q_heads=192, n_kv_heads=3, n_hetero=1, obs_window=8, ctx_len=520, batch=1, head_dim=64),   # 512 window rows
     dict(n_q_heads=12, n_kv_heads=3, n_hetero=1, obs_window=32, ctx_len=40000, n_middle=2000, n_recent=1000,
          batch=1, decode_steps=2),                                     # a long context, budgets in the thousands
+    # the shortest context whose selections several blocks share, and a middle below that length
+    dict(ctx_len=12288, n_middle=300, decode_steps=1),
+    dict(ctx_len=12290, n_recent=100, n_middle=900, decode_steps=1, pool_kernel=7, batch=1),
+    dict(ctx_len=13000, n_recent=2000, n_middle=700, decode_steps=1, dtype="f32", batch=1),
+    dict(ctx_len=12287, n_middle=300, decode_steps=1, batch=1),
     # few units, a middle between half and the whole of the shortest range several blocks share
     dict(ctx_len=33000, n_recent=9000, n_middle=700, decode_steps=1),
     dict(ctx_len=33000, n_recent=9000, n_middle=700, decode_steps=1, pool_kernel=7, batch=1),
