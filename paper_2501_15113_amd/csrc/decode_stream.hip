@@ -37,7 +37,11 @@ __device__ __forceinline__ int64_t range_start(int i, int64_t T, int W, int skew
   const int r = i & 7;
   const int64_t c = (int64_t)(i - r) * 1024 +
                     (r <= 4 ? r * (1024 + skew) : 4 * (1024 + skew) + (r - 4) * (1024 - skew));
-  return c * T / ((int64_t)W * 1024);
+  // c T < 2^53 and the quotient, when it is not an integer, lies at least
+  // 1 / (1024 W) from the next one: the correctly rounded fp64 quotient has the
+  // same floor as the 64-bit integer division, which costs a wave ten times as
+  // many instructions at the head of every launch
+  return (int64_t)((double)c * (double)T / ((double)W * 1024.0));
 }
 // What the decode kernel leaves behind for the combine kernel, after the
 // units + 1 page prefixes: the first page of every wave's range (W + 1
