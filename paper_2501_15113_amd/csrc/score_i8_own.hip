@@ -571,8 +571,9 @@ int launch_i8_columns(const Dims &dm, const void *k, const double *qd, const I8B
   const dim3 grid(blocks_per_unit < 1 ? 1 : blocks_per_unit, dm.units), block(64 * CNW);
   // Several row blocks and short lists: the waves of a block share a tile.  A
   // block then takes one tile at a time where its waves would take one each, so
-  // it pays up to about two tiles per block (cfg3 / cfg4 / cfg5-shaped layers,
-  // a few hundred columns per unit: 27 -> 21, 22 -> 12, 43 -> 42 us); the lists of a
+  // it pays up to about two tiles per block (a few hundred listed columns per
+  // unit: 32 units of 128 rows 27 -> 21 us, 8 units of 128 rows 22 -> 12 us,
+  // 64 units of 256 rows 43 -> 42 us); the lists of a
   // pooled middle pick carry the neighbours of every band column, several
   // thousand columns per unit, and stay with the kernel of a tile per wave
   // (8-head stack at 60 %: 0.305 against 0.311 ms per layer).
