@@ -343,17 +343,38 @@ __global__ __launch_bounds__(1024) void combine_stream_kernel(
       m_run = m_new;
     }
   }
-  red_o[cl][dl] = acc;
-  if (dl == 0) { red_m[cl] = m_run; red_l[cl] = l_run; }
+  // the slot lanes of a wave (64 / DL of them) merge through lane exchanges
+  // first -- both partners form the same sum -- so that the serial part below
+  // goes over the block's sixteen waves instead of over all slot lanes
+#pragma unroll
+  for (int off = DL; off < 64; off <<= 1) {
+    const float m_o = __shfl_xor(m_run, off), l_o = __shfl_xor(l_run, off);
+    float4 a_o;
+    a_o.x = __shfl_xor(acc.x, off); a_o.y = __shfl_xor(acc.y, off);
+    a_o.z = __shfl_xor(acc.z, off); a_o.w = __shfl_xor(acc.w, off);
+    const float m_new = fmaxf(m_run, m_o);
+    const float a = m_run > -INFINITY ? __builtin_amdgcn_exp2f(m_run - m_new) : 0.f;
+    const float b = m_o > -INFINITY ? __builtin_amdgcn_exp2f(m_o - m_new) : 0.f;
+    acc.x = acc.x * a + a_o.x * b; acc.y = acc.y * a + a_o.y * b;
+    acc.z = acc.z * a + a_o.z * b; acc.w = acc.w * a + a_o.w * b;
+    l_run = l_run * a + l_o * b;
+    m_run = m_new;
+  }
+  constexpr int NWV = 16;   // waves per block
+  const int wv = tid >> 6;
+  if ((tid & 63) < DL) {
+    red_o[wv][dl] = acc;
+    if (dl == 0) { red_m[wv] = m_run; red_l[wv] = l_run; }
+  }
   __syncthreads();
   if (tid < DL) {
     float M = red_m[0];
 #pragma unroll
-    for (int cc = 1; cc < NCL; ++cc) M = fmaxf(M, red_m[cc]);
+    for (int cc = 1; cc < NWV; ++cc) M = fmaxf(M, red_m[cc]);
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     float L = 0.f;
 #pragma unroll
-    for (int cc = 0; cc < NCL; ++cc) {
+    for (int cc = 0; cc < NWV; ++cc) {
       const float wgt = __builtin_amdgcn_exp2f(red_m[cc] - M);   // 0 for lanes that saw no slot
       const float4 x = red_o[cc][tid];
       o.x += x.x * wgt; o.y += x.y * wgt; o.z += x.z * wgt; o.w += x.w * wgt;
