@@ -280,8 +280,9 @@ void decode_stream_kernel(
 // whose page ranges meet the unit.  One block of 1024 threads = NCL slot lanes x
 // D/4 channel lanes; slot lane c owns slots c, c+NCL, ... and requests UN of
 // them at once (the partials sit in L2; the kernel is latency bound), reduces
-// them with its own running maximum, and the NCL lane results are merged in
-// lane order -- one trip to memory, fixed summation order, reproducible.
+// them with its own running maximum, and the NCL lane results are merged first
+// inside each wave (lane exchanges), then over the waves in wave order -- one
+// trip to memory, fixed summation order, reproducible.
 template <int D>
 __global__ __launch_bounds__(1024) void combine_stream_kernel(
     const float *__restrict__ pm, const float *__restrict__ pl, const float *__restrict__ po,
