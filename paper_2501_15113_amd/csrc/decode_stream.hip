@@ -75,9 +75,49 @@ void decode_stream_kernel(
   __shared__ int s_len[MAXU];        // length used by this step, bit 31 = a token is appended
   __shared__ int s_off[MAXU];        // offsets / CHUNK
   __shared__ int s_wtot[4];
+  const bool publish = blockIdx.x == 0 && hg == 0;
+  int64_t T;
+  if (n_units <= 64) {
+    // Few units: every wave builds the whole table by itself, a lane per unit,
+    // so that no wave waits for another (the four waves write the same values
+    // to the same words of LDS; a wave reads back what it wrote itself or the
+    // identical word of a neighbour).
+    int len = 0, pages = 0;
+    if (l < n_units) {
+      const int len_old = lens[l];
+      const int64_t o0 = offsets[l], o1 = offsets[l + 1];
+      const bool can = want_app && len_old < (int)(o1 - o0);
+      len = len_old + (can ? 1 : 0);
+      pages = (len + PAGE - 1) / PAGE;
+      s_len[l] = len | (can ? (int)0x80000000 : 0);
+      s_off[l] = (int)(o0 / CHUNK);
+      if (publish && w == 0) {
+        eff_len[l] = len;
+        if (want_app && !can) atomicOr(d_err, 1);
+      }
+    }
+    int incl = pages;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(incl, off);
+      if (l >= off) incl += t;
+    }
+    const int total = __shfl(incl, 63);
+    if (l < n_units) {
+      s_pref[l] = incl - pages;
+      if (publish && w == 0) page_prefix[l] = incl - pages;
+    }
+    if (l == 0) {
+      s_pref[n_units] = total;
+      if (publish && w == 0) page_prefix[n_units] = total;
+    }
+    T = total;
+    // the wave's LDS writes above are read below, in program order
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  } else {
   const int upt = (n_units + 255) / 256;
   const int first = tid * upt;
-  const bool publish = blockIdx.x == 0 && hg == 0;
   int sum = 0;
   for (int i = 0; i < upt; ++i) {
     const int u = first + i;
@@ -118,7 +158,8 @@ void decode_stream_kernel(
     if (publish) page_prefix[n_units] = run;
   }
   __syncthreads();
-  const int64_t T = s_pref[n_units];
+  T = s_pref[n_units];
+  }
   const int W = gridDim.x * 4;
   const int wid = blockIdx.x * 4 + w;
   const int p0 = (int)range_start(wid, T, W, skew), p1 = (int)range_start(wid + 1, T, W, skew);
