@@ -77,6 +77,7 @@ void decode_stream_kernel(
   __shared__ int s_wtot[4];
   const bool publish = blockIdx.x == 0 && hg == 0;
   int64_t T;
+  int lane_pref = 0x7fffffff;   // with at most 64 units: the first page of the lane's unit
   if (n_units <= 64) {
     // Few units: every wave builds the whole table by itself, a lane per unit,
     // so that no wave waits for another (the four waves write the same values
@@ -104,8 +105,9 @@ void decode_stream_kernel(
     }
     const int total = __shfl(incl, 63);
     if (l < n_units) {
-      s_pref[l] = incl - pages;
-      if (publish && w == 0) page_prefix[l] = incl - pages;
+      lane_pref = incl - pages;
+      s_pref[l] = lane_pref;
+      if (publish && w == 0) page_prefix[l] = lane_pref;
     }
     if (l == 0) {
       s_pref[n_units] = total;
@@ -173,7 +175,10 @@ void decode_stream_kernel(
 
   // first unit of my range: largest u with s_pref[u] <= p0
   int u0;
-  {
+  if (n_units <= 64) {
+    // the lanes hold the prefixes: one vote instead of a chain of LDS reads
+    u0 = __popcll(__ballot(lane_pref <= p0)) - 1;
+  } else {
     int lo = 0, hi = n_units - 1;
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
