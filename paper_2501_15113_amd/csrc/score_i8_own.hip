@@ -235,8 +235,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   constexpr int KS = D / 32, THREADS = 64 * NW;
   const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, half = l >> 5;
   const int N = dm.N, L = dm.L, R = dm.R, Rpad = dm.Rpad, n_rb = Rpad / 32;
-  const int n_listed = band_cnt[unit];
-  const int32_t *cols = band_idx + (size_t)unit * N;
+  // without a list: every column of the unit
+  const int n_listed = band_idx != nullptr ? band_cnt[unit] : N;
+  const int32_t *cols = band_idx != nullptr ? band_idx + (size_t)unit * N : nullptr;
   const double unit_scale = dm.scale * EXP_UNITS;
   const uint16_t *kb = k + (size_t)unit * N * D;
   const double *qdu = qd + (size_t)unit * Rpad * D;
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int n_tiles = (n_listed + 31) / 32;
   for (int tile = blockIdx.x * NW + w; tile < n_tiles; tile += gridDim.x * NW) {
     const int pos = tile * 32 + c32;
-    const int col = pos < n_listed ? cols[pos] : -1;
+    const int col = pos < n_listed ? (cols != nullptr ? cols[pos] : pos) : -1;
     uint32_t raw[KS][8];
     const uint16_t *key_row = kb + (size_t)max(col, 0) * D;
     fetch_key_pieces<D>(col >= 0 ? key_row : nullptr, half, raw);
@@ -559,7 +560,8 @@ int launch_i8_direct(const Dims &dm, const void *k, const double *qd, const I8Bu
   return hip_ok(hipGetLastError());
 }
 
-// Exact scores of the listed columns of every unit (see score_i8_columns_kernel).
+// Exact scores of the listed columns of every unit (see score_i8_columns_kernel);
+// band_idx == nullptr: of all columns (the pass of a layer that does not screen).
 // The window rows' digits, factors and remainder lists are those launch_i8_stats
 // left in `bufs` for the same rows.
 int launch_i8_columns(const Dims &dm, const void *k, const double *qd, const I8Bufs &bufs, const double *stats,
@@ -577,7 +579,7 @@ int launch_i8_columns(const Dims &dm, const void *k, const double *qd, const I8B
   // pooled middle pick carry the neighbours of every band column, several
   // thousand columns per unit, and stay with the kernel of a tile per wave
   // (8-head stack at 60 %: 0.305 against 0.311 ms per layer).
-  if (dm.Rpad > 32 && dm.pool == 1) {
+  if (dm.Rpad > 32 && dm.pool == 1 && band_idx != nullptr) {
     if (dm.D == 64)
       score_i8_columns_shared_kernel<64, CNW><<<grid, block, 0, s>>>(kk, qdig, bufs.gq, qd, bufs.qtiny, bufs.qcnt, stats,
                                                                     band_idx, band_cnt, scores, dm);

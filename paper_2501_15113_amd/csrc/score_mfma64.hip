@@ -403,6 +403,17 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
       merge_stats_kernel<<<dim3(dm.units, (dm.Rpad + 15) / 16), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_parts);
     }
     if (!screen) {
+      if (i8 && n_groups == 1) {
+        // bf16 inputs: all columns from the integer contraction, a tile of 32
+        // columns per wave (8 units x 128 rows x 8192 keys: 61 us as the fp64
+        // column pass)
+        const int n_cu = i8b->prof ? i8b->prof->n_cu : 256;
+        int per_unit = 2 * n_cu / dm.units;
+        per_unit = per_unit < 1 ? 1 : (per_unit > 256 ? 256 : per_unit);
+        const int rc = launch_i8_columns(dm, k, qd, *i8b, stats, nullptr, nullptr, scores, per_unit, s);
+        if (rc) return rc;
+        continue;
+      }
       score_mfma64_kernel<T, D, 1, false><<<grid, block, 0, s>>>(k, qd, stats, part, scores, dm, cpw, nullptr,
                                                                 nullptr);
       continue;
