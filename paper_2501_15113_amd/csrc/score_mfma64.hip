@@ -464,9 +464,14 @@ bool band_is_sliced(const Dims &dm, const ScreenBufs *scr) {
 
 bool scores_screened(const Dims &dm, int dtype, const ScreenBufs *scr) {
   const int n_groups = (dm.Rtot + ROW_GROUP - 1) / ROW_GROUP;
-  // measured on 8 KV heads x 128 rows: 11 us slower at 8.4e6 (8192 keys), 33-70 us faster at 1.7e7-2.5e7;
-  // on 32 KV heads x 32 rows (the kernels for narrow windows): level at 4.2e6, 24 us faster at 8.4e6
-  const bool big = (double)dm.units * dm.Rtot * dm.N >= (dm.Rtot <= 32 ? 6e6 : 1.2e7);
+  // Measured against the integer form of the full column pass, separator and
+  // compressor together, W = units x rows x keys: below 12288 keys the band is
+  // one block per unit and screening wins only on large layers (32 units x 128
+  // rows x 8192 keys, W = 3.4e7: 22 us faster; 16 x 128 x 8192, 1.7e7: 12 us
+  // slower); from 12288 keys on it wins from W = 1.26e7 for windows of 32 rows
+  // (16 us) and from 1.7e7 for 128 rows (5 us; 11 us slower at 1.26e7).
+  const double W = (double)dm.units * dm.Rtot * dm.N;
+  const bool big = W >= 3e7 || (dm.N >= MSEL_MIN_RANGE && W >= (dm.Rtot <= 32 ? 1.2e7 : 1.6e7));
   // with pooling only the sliced band kernels list the neighbours a pooled score needs
   const bool pool_ok = dm.pool == 1 || (band_is_sliced(dm, scr) && scr->pooled != nullptr);
   return scr != nullptr && scr->mode != 0 && n_groups == 1 && screen_supported(dm, dtype) && pool_ok &&
