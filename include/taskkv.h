@@ -289,7 +289,7 @@ int taskkv_last_async_error(taskkv_ctx *ctx, void *hip_stream);
 
 /* Screening lets taskkv_separate score bf16 inputs on the bf16 matrix cores
  * first and recompute in fp64 only the columns that can matter; decisions are
- * identical either way.  mode 0: never (every score in fp64); 1 (default): when
+ * identical either way.  mode 0: never (every score exact); 1 (default): when
  * the layer is large enough for it to pay; 2: whenever the inputs allow
  * (bf16, at most 512 window rows per KV head; with pool_kernel > 1 only
  * contexts of 12288 tokens and more, on at most 256 (batch, KV head) units). */
@@ -298,7 +298,8 @@ int taskkv_set_screening(taskkv_ctx *ctx, int mode);
 /* Row maxima and softmax denominators of the window scores (Eq. 12) are needed
  * to fp64 accuracy.  For bf16 inputs they come from exact integer dot products
  * on the int8 matrix cores (engine 1, default), and so do the scores of the
- * columns that a screening separator recomputes; engine 0 uses the fp64 matrix
+ * columns that a screening separator recomputes, and of all columns of a layer
+ * that does not screen (windows of at most 512 rows); engine 0 uses the fp64 matrix
  * instruction, as fp32 inputs always do.  Engine 1 evaluates its exponentials
  * from a table and a cubic (relative error 2e-13), so the two engines' scores
  * agree to about 1e-13 relative, not to the last bit; decisions (top-t, middle
