@@ -340,7 +340,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll 8
       for (int r = 0; r < 32; ++r) total += s_sum[v][32 * hf + r];
       const int out_col = s_col[w][l];
-      if (out_col >= 0) scores[(size_t)unit * N + out_col] = total / (double)dm.Rtot;
+      // (a window of several row groups, all columns: the groups' launches add
+      // up in the scores, which were cleared before the first)
+      if (out_col >= 0) {
+        double *dst = scores + (size_t)unit * N + out_col;
+        const double part_mean = total / (double)dm.Rtot;
+        *dst = cols == nullptr && dm.R != dm.Rtot ? *dst + part_mean : part_mean;
+      }
     }
     wave_lds_handover();   // the wave's LDS is rewritten by its next tile
   }

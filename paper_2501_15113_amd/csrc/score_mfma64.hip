@@ -403,7 +403,7 @@ static int run_scores(const Dims &dm_all, int dtype, const T *q_win, const T *k,
       merge_stats_kernel<<<dim3(dm.units, (dm.Rpad + 15) / 16), dim3(1024), 0, s>>>(part, stats, dm.Rpad, n_parts);
     }
     if (!screen) {
-      if (i8 && n_groups == 1) {
+      if (i8) {
         // bf16 inputs: all columns from the integer contraction, a tile of 32
         // columns per wave (8 units x 128 rows x 8192 keys: 61 us as the fp64
         // column pass)
